@@ -1,0 +1,269 @@
+"""Pins of the CPU oracle's cache format, salient selection and decode attention (Sections II-A, III-B,
+III-C of arXiv 2501.15021).  No GPU needed."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+from paper_2501_15021_amd import synth
+
+D = 128
+
+
+def _gen(w, seed=11):
+    d = synth.generate(w, seed=seed)
+    return {k: (v.numpy() if hasattr(v, "numpy") else v) for k, v in d.items()}
+
+
+# ----------------------------------------------------------------------------- byte format
+def test_code_positions_are_bijections(orc):
+    L = orc.lib()
+    w_, b_ = C.c_size_t(), C.c_int()
+    for fn in (L.orc_k_code_pos, L.orc_v_code_pos):
+        seen = set()
+        for t in range(64, 128):                      # two whole token blocks, not the first ones
+            for e in range(D):
+                fn(t, e, C.byref(w_), C.byref(b_))
+                assert 0 <= b_.value <= 30 and b_.value % 2 == 0
+                seen.add((w_.value, b_.value))
+        words = {w for w, _ in seen}
+        assert len(seen) == 64 * D                    # no two codes share a position
+        assert words == set(range(2 * 256, 4 * 256))  # and the two blocks are filled exactly
+    seen = {L.orc_vsal_pos(s, e) for s in range(32, 96) for e in range(D)}
+    assert seen == set(range(4096, 3 * 4096))
+
+
+def test_code_positions_hand_cases(orc):
+    L = orc.lib()
+    w_, b_ = C.c_size_t(), C.c_int()
+    # K: token 37 = block 1, second... (37 % 32 = 5 -> half 0, n 5); channel 77 = m 2, j 1, i 5
+    L.orc_k_code_pos(37, 77, C.byref(w_), C.byref(b_))
+    assert (w_.value, b_.value) == (256 + (16 * 1 + 5) * 4 + (0 + 1), 2 * (0 + 5))
+    # K: token 31 -> half 1, n 15; channel 0
+    L.orc_k_code_pos(31, 0, C.byref(w_), C.byref(b_))
+    assert (w_.value, b_.value) == ((0 + 15) * 4 + 2, 0)
+    # V: token 22 -> half 1, r 6 -> q 1, ii 2; channel 101 -> nb 6, n 5 -> word 2*(6%2)+6/4 = 1, XY = 1
+    L.orc_v_code_pos(22, 101, C.byref(w_), C.byref(b_))
+    assert (w_.value, b_.value) == ((16 * 1 + 5) * 4 + 1, 16 + 2 * (4 + 2))
+    # V overlay: slot 45 -> blk 1, (13) half 0, r 13 -> q 3, ii 1; channel 18 -> nb 1, n 2
+    assert L.orc_vsal_pos(45, 18) == 4096 + 512 + (48 + 2) * 8 + 2
+
+
+def test_pack_round_trip_and_clean_rmw(orc):
+    w = synth.small("rt", B=1, Hq=2, Hkv=2, T=70, G=64)
+    d = _gen(w)
+    for fill in (0x00, 0xFF):
+        c = orc.OracleCache(1, 2, 64, 128, 64, fill=fill)
+        c.select_tsa(d["is_text"])
+        c.quantize_append(d["k"], d["v"], 0.8)
+        for h in range(2):
+            for t in (0, 1, 15, 16, 31, 32, 69):
+                for tensor, src in ((0, d["k"]), (1, d["v"])):
+                    codes, sb, z, ybf = orc.quantize_row(src[0, h, t], 64, 0.8)
+                    got = [c.get_code(tensor, 0, h, t, e) for e in range(D)]
+                    assert got == list(codes)
+                    meta = (c.k_meta, c.v_meta)[tensor][0, h, t]
+                    sal = bool(d["is_text"][0, t])
+                    for g in range(2):
+                        assert meta[g] == (int(sb[g]) | (0x8000 if sal else 0) | ((int(z[g]) & 0xFFFF) << 16))
+    # positions beyond T_len keep the fill pattern (appending never touches other tokens' bits)
+    c0 = orc.OracleCache(1, 2, 64, 128, 64, fill=0x00); c0.select_tsa(d["is_text"]); c0.quantize_append(d["k"], d["v"], 0.8)
+    c1 = orc.OracleCache(1, 2, 64, 128, 64, fill=0xFF); c1.select_tsa(d["is_text"]); c1.quantize_append(d["k"], d["v"], 0.8)
+    diff = c0.k_codes ^ c1.k_codes
+    assert int(np.unpackbits(diff.view(np.uint8)).sum()) == 2 * (128 - 70) * D * 2
+    diff = c0.v_codes ^ c1.v_codes
+    assert int(np.unpackbits(diff.view(np.uint8)).sum()) == 2 * (128 - 70) * D * 2
+    # appending in two pieces gives the same bytes as appending at once
+    c2 = orc.OracleCache(1, 2, 64, 128, 64, fill=0x00); c2.select_tsa(d["is_text"])
+    c2.quantize_append(d["k"][:, :, :41], d["v"][:, :, :41], 0.8)
+    c2.quantize_append(d["k"][:, :, 41:], d["v"][:, :, 41:], 0.8)
+    for name in ("k_codes", "v_codes", "k_meta", "v_meta", "k_sal", "v_sal"):
+        assert np.array_equal(getattr(c0, name), getattr(c2, name)), name
+
+
+# ----------------------------------------------------------------------------- salient selection (III-B)
+def test_tsa_equals_text_mask(orc):
+    w = synth.small("tsa", B=2, Hq=4, Hkv=2, T=100, n_text_head=7, n_text_tail=9)
+    d = _gen(w)
+    c = orc.OracleCache(2, 2, 128, 128, 64)
+    c.select_tsa(d["is_text"])
+    expect = np.nonzero(d["is_text"][0])[0]
+    for b in range(2):
+        for h in range(2):
+            assert c.sal_cnt[b, h] == 16
+            assert np.array_equal(c.sal_idx[b, h, :16], expect)
+
+
+def test_psa_mass_invariants_and_topk(orc):
+    w = synth.small("psa", B=2, Hq=4, Hkv=2, T=96, W=8, top_k=6)
+    d = _gen(w)
+    c = orc.OracleCache(2, 2, 128, 128, 64)
+    mass = c.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale, want_mass=True)
+    # every softmax row sums to 1 -> total mass = W * (Hq/Hkv)
+    assert np.allclose(mass.sum(axis=-1), w.W * 2, rtol=1e-12)
+    assert (mass >= 0).all()
+    # causal: the last key is seen only by the last row (of each of the 2 query heads of the group)
+    assert (mass[..., -1] <= 2.0).all()
+    # independent numpy evaluation of the definition (bf16-rounded operands, fp64 softmax)
+    import torch
+    rb = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    q, k = rb(d["q_tail"]), rb(d["k"])
+    for b in range(2):
+        for h in range(2):
+            ref = np.zeros(w.T)
+            for hq in (2 * h, 2 * h + 1):
+                for i in range(w.W):
+                    pos = w.T - w.W + i
+                    lg = w.sm_scale * (k[b, h, :pos + 1] @ q[b, hq, i])
+                    p = np.exp(lg - lg.max()); p /= p.sum()
+                    ref[:pos + 1] += p
+            assert np.allclose(mass[b, h], ref, rtol=1e-10, atol=1e-14)
+            order = sorted(range(w.T), key=lambda t: (-ref[t], t))[:w.top_k]
+            assert c.sal_cnt[b, h] == w.top_k
+            assert list(c.sal_idx[b, h, :w.top_k]) == sorted(order)
+            # planted high-norm keys attract the attention (Section III-A.3)
+            # (with only 16 scoring rows one of the four may be missed; the heaviest token is always a pivot)
+            assert len(set(d["pivots"][b].tolist()) & set(c.sal_idx[b, h, :w.top_k].tolist())) >= 3
+            assert int(np.argmax(ref)) in d["pivots"][b].tolist()
+
+
+def test_psa_single_row_by_hand(orc):
+    # W = 1, T = 3, one head: q = e0, keys k_t = a_t * e0 -> logits sm * a_t, mass = softmax(sm * a)
+    q = np.zeros((1, 1, 1, D), dtype=np.float16); q[..., 0] = 1.0
+    k = np.zeros((1, 1, 3, D), dtype=np.float16); k[0, 0, :, 0] = [0.0, 2.0, 1.0]
+    c = orc.OracleCache(1, 1, 128, 64, 64)
+    mass = c.select_psa(q, k, 2, 1.0, want_mass=True)
+    e = np.exp([0.0, 2.0, 1.0]); e /= e.sum()
+    assert np.allclose(mass[0, 0], e, rtol=1e-14)
+    assert list(c.sal_idx[0, 0, :2]) == [1, 2] and c.sal_cnt[0, 0] == 2
+    # equal masses: the lower position wins
+    k[0, 0, :, 0] = [1.0, 1.0, 1.0]
+    c.select_psa(q, k, 2, 1.0)
+    assert list(c.sal_idx[0, 0, :2]) == [0, 1]
+
+
+# ----------------------------------------------------------------------------- decode attention (II-A, III-C)
+def _dequant_rows_numpy(orc, c, tensor, b, h, T):
+    """Independent dequantization: codes through the position map, Eq. 4 in numpy."""
+    G = c.G
+    meta = (c.k_meta, c.v_meta)[tensor][b, h]
+    rows = np.zeros((T, D))
+    for t in range(T):
+        for e in range(D):
+            mw = int(meta[t, e // G])
+            s = float(np.array([mw & 0x7FFF], dtype=np.uint16).view(np.float16)[0])
+            z = ((mw >> 16) ^ 0x8000) - 0x8000
+            rows[t, e] = s * (c.get_code(tensor, b, h, t, e) - z)
+    n = min(int(c.sal_cnt[b, h]), c.S_cap)
+    L = orc.lib()
+    for s_, t in enumerate(c.sal_idx[b, h, :n]):
+        if tensor == 0:
+            rows[t] = orc.bf16_bits_to_f64(c.k_sal[b, h, s_])
+        else:
+            plane = c.v_sal[b, h].reshape(-1)
+            rows[t] = orc.bf16_bits_to_f64(np.array([plane[L.orc_vsal_pos(s_, e)] for e in range(D)], dtype=np.uint16))
+    return rows
+
+
+def _softmax_attention(q, K, V, sm):
+    lg = sm * (K @ q)
+    p = np.exp(lg - lg.max()); p /= p.sum()
+    return p @ V, lg.max() + np.log(np.exp(lg - lg.max()).sum())
+
+
+@pytest.mark.parametrize("mode,G,Hq,Hkv", [("tsa", 128, 2, 2), ("psa", 64, 4, 2), ("psa", 128, 6, 2)])
+def test_decode_matches_bruteforce(orc, mode, G, Hq, Hkv):
+    w = synth.small("dec", B=2, Hq=Hq, Hkv=Hkv, T=45, G=G, top_k=5)
+    d = _gen(w, seed=21)
+    c = orc.OracleCache(2, Hkv, G, 64, 64)
+    if mode == "tsa":
+        c.select_tsa(d["is_text"])
+    else:
+        c.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale)
+    c.quantize_append(d["k"], d["v"], 0.8)
+    out, lse = c.decode(d["q"], w.sm_scale)
+    H = orc.hadamard_dense(D)
+    r = Hq // Hkv
+    for b in range(2):
+        for hq in range(Hq):
+            Kh = _dequant_rows_numpy(orc, c, 0, b, hq // r, w.T)
+            Vh = _dequant_rows_numpy(orc, c, 1, b, hq // r, w.T)
+            qrot = d["q"][b, hq].astype(np.float64) @ H
+            o, l = _softmax_attention(qrot, Kh, Vh, w.sm_scale)
+            assert np.allclose(out[b, hq], o @ H, rtol=1e-10, atol=1e-12)
+            assert abs(lse[b, hq] - l) < 1e-10
+    # rotated-output mode differs by exactly one transform
+    out_rot, _ = c.decode(d["q"], w.sm_scale, unrotate=False)
+    assert np.allclose(out_rot @ H, out, rtol=1e-10, atol=1e-12)
+    # single-output entry agrees with the batched one
+    o1, l1 = c.decode_one(1, Hq - 1, Hq, d["q"][1, Hq - 1], w.sm_scale)
+    assert np.array_equal(o1, out[1, Hq - 1]) and l1 == lse[1, Hq - 1]
+
+
+def test_decode_special_cases(orc):
+    w = synth.small("spec", B=1, Hq=2, Hkv=1, T=40)
+    d = _gen(w, seed=22)
+    H = orc.hadamard_dense(D)
+    # T = 1: the output is the (dequantized) value row itself, whatever the query
+    c = orc.OracleCache(1, 1, 128, 64, 64)
+    c.quantize_append(d["k"][:, :, :1], d["v"][:, :, :1], 0.8)
+    out, _ = c.decode(d["q"], w.sm_scale)
+    v0 = _dequant_rows_numpy(orc, c, 1, 0, 0, 1)[0] @ H
+    assert np.allclose(out[0, 0], v0, atol=1e-12) and np.allclose(out[0, 1], v0, atol=1e-12)
+    # zero query: all scores equal -> mean of the value rows; sm_scale = 0 does the same
+    c = orc.OracleCache(1, 1, 128, 64, 64)
+    c.quantize_append(d["k"], d["v"], 0.8)
+    Vh = _dequant_rows_numpy(orc, c, 1, 0, 0, w.T)
+    out, lse = c.decode(np.zeros_like(d["q"]), w.sm_scale)
+    assert np.allclose(out[0, 0], Vh.mean(axis=0) @ H, atol=1e-12)
+    assert abs(lse[0, 0] - np.log(w.T)) < 1e-12
+    out2, _ = c.decode(d["q"], 0.0)
+    assert np.allclose(out2[0, 1], Vh.mean(axis=0) @ H, atol=1e-12)
+
+
+def test_all_salient_cache_is_plain_attention_up_to_bf16(orc):
+    """With every row kept 16-bit the method is attention on the original K,V (the rotation is an equivalent
+    transformation, Section III-C.2), up to the bfloat16 rounding of the stored rows."""
+    w = synth.small("allsal", B=1, Hq=2, Hkv=2, T=50)
+    d = _gen(w, seed=23)
+    c = orc.OracleCache(1, 2, 128, 64, 64)
+    c.select_tsa(np.ones((1, w.T), dtype=np.uint8))
+    c.quantize_append(d["k"], d["v"], 0.8)
+    out, _ = c.decode(d["q"], w.sm_scale)
+    for h in range(2):
+        o, _ = _softmax_attention(d["q"][0, h].astype(np.float64), d["k"][0, h].astype(np.float64),
+                                  d["v"][0, h].astype(np.float64), w.sm_scale)
+        # logits carry bf16 rounding of keys whose norm is large (outlier channels x20, pivots x10)
+        assert np.max(np.abs(out[0, h] - o)) <= 0.05 * np.max(np.abs(o)) + 0.02
+
+
+def test_gqa_equals_mha_with_repeated_kv(orc):
+    w = synth.small("gqa", B=1, Hq=6, Hkv=2, T=37, G=64)
+    d = _gen(w, seed=24)
+    c = orc.OracleCache(1, 2, 64, 64, 64)
+    c.select_psa(d["q_tail"], d["k"], 4, w.sm_scale)
+    c.quantize_append(d["k"], d["v"], 0.8)
+    out, _ = c.decode(d["q"], w.sm_scale)
+    rep = lambda a: np.repeat(a, 3, axis=1)
+    c2 = orc.OracleCache(1, 6, 64, 64, 64)
+    c2.sal_idx[:] = rep(c.sal_idx); c2.sal_cnt[:] = rep(c.sal_cnt)
+    c2.quantize_append(rep(d["k"]), rep(d["v"]), 0.8)
+    out2, _ = c2.decode(d["q"], w.sm_scale)
+    assert np.array_equal(out, out2)
+
+
+def test_workload_shapes_and_structure():
+    for name, w in synth.WORKLOADS.items():
+        m = synth.is_text_mask(w)
+        assert m.sum() == w.n_text and m[0] == 1
+    w = synth.WORKLOADS["cfg1"]
+    assert w.n_text == 64 and w.s_cap(0) == 64
+    w2 = synth.WORKLOADS["cfg2"]
+    assert w2.n_text == 640 and w2.mode(0) == "tsa" and w2.mode(2) == "psa" and w2.s_cap(0) == 640
+    d = synth.generate(synth.small("s", 2, 2, 2, 64), seed=5)
+    d2 = synth.generate(synth.small("s", 2, 2, 2, 64), seed=5)
+    assert all((d[k] == d2[k]).all() for k in d)
+    k = d["k"].float()
+    ch = d["outlier_channels"][0]
+    assert k[0, 0, 1:, ch].abs().mean() > 5 * k[0, 0, 1:, :].abs().mean() / 2
+    assert d["pivots"][:, 0].eq(0).all()
