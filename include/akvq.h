@@ -1,0 +1,133 @@
+/*
+ * akvq.h -- C ABI of the AKVQ-VL KV-cache hot path for AMD MI355X (gfx950).
+ *
+ * Method: arXiv 2501.15021 (AKVQ-VL).  Salient tokens (text tokens in Text-Salient-Attention layers,
+ * pivot tokens in Pivot-Token-Salient-Attention layers, Section III-B) stay 16-bit; every other cached
+ * Key/Value row is rotated by the 128-point Walsh-Hadamard matrix (Section III-C.2, Eq. 7) and stored as
+ * group-wise asymmetric 2-bit codes (Section III-C.1, Eq. 3-6).  Decode attention reads that cache directly.
+ *
+ * Conventions
+ *   - Every pointer named "device" is GPU memory owned by the caller.  The library allocates nothing,
+ *     frees nothing and never synchronises: each call validates its arguments on the host, enqueues
+ *     kernels on `stream` (a hipStream_t passed as void*, NULL = default stream) and returns.
+ *   - All device pointers must be 16-byte aligned.
+ *   - Return value: AKVQ_OK or a negative akvq_status.  Argument errors launch nothing.
+ *   - head_dim is fixed to 128, codes are 2-bit, the quantization group G is 64 or 128 channels of
+ *     the rotated head vector.
+ *
+ * Cache format (one layer; this library's own, MFMA-operand-native)
+ *   Tokens are stored in blocks of 32.  One block of one (batch, kv-head) plane is 1024 bytes =
+ *   64 chunks of 16 bytes (4 little-endian uint32 words); a 64-lane wavefront loads a block with one
+ *   128-bit load per lane and finds its matrix-core operand in its own registers.
+ *   k_codes [B][Hkv][T_cap/32][256 words]
+ *       token t: blk=t/32, half=(t%32)/16, n=t%16.  rotated channel e: m=e/32, j=(e%32)/8, i=e%8.
+ *       word = blk*256 + (16*j+n)*4 + 2*half + m/2;  bits [2s, 2s+2) with s = 8*(m%2) + i.
+ *   v_codes [B][Hkv][T_cap/32][256 words]   (token-transposed inside the block)
+ *       token t: blk, half as above, r=t%16, q=r/4, ii=r%4.  channel e: nb=e/16, n=e%16.
+ *       word = blk*256 + (16*q+n)*4 + 2*(nb%2) + nb/4;  bits [16*half + 2p, +2) with p = 4*((nb/2)%2) + ii.
+ *   k_meta, v_meta [B][Hkv][T_cap][128/G] uint32
+ *       bits 0-14 scale (IEEE binary16, positive), bit 15 = row is salient (its 2-bit copy is ignored
+ *       by decode), bits 16-31 zero-point (int16).  Dequantized value = scale * (code - zero)  (Eq. 4).
+ *   k_sal [B][Hkv][S_cap][128] bfloat16: rotated salient rows, natural channel order.
+ *   v_sal [B][Hkv][S_cap/32][4096] bfloat16: rotated salient rows, tiled: slot s: blk=s/32,
+ *       half=(s%32)/16, r=s%16, q=r/4, ii=r%4; channel e: nb=e/16, n=e%16;
+ *       index = blk*4096 + nb*512 + (16*q+n)*8 + 2*ii + half.
+ *   sal_idx [B][Hkv][S_cap] int32 ascending token positions; sal_cnt [B][Hkv] int32 (values above S_cap
+ *       mean "S_cap stored, more were found"; consumers clamp).
+ *   T_cap and S_cap must be multiples of 64.
+ */
+#ifndef AKVQ_H
+#define AKVQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AKVQ_OK = 0,
+  AKVQ_ERR_INVALID_ARG = -1, /* null / misaligned pointer, non-positive size, Hq not a multiple of Hkv, W > T ... */
+  AKVQ_ERR_UNSUPPORTED = -2, /* G not in {64,128}, Hq/Hkv > 8, W not a multiple of 16 ... */
+  AKVQ_ERR_CAPACITY = -3,    /* T_len + n_new > T_cap, top_k > S_cap */
+  AKVQ_ERR_WORKSPACE = -4,   /* workspace smaller than akvq_*_workspace_bytes() */
+  AKVQ_ERR_HIP = -5          /* a kernel launch failed; see akvq_last_hip_error() */
+} akvq_status;
+
+enum { AKVQ_MODE_TSA = 0, AKVQ_MODE_PSA = 1 };
+
+/* flags */
+enum {
+  AKVQ_V_PREROTATED = 1u, /* quantize_append: V rows arrive already rotated (H folded into W_V offline,
+                             Section III-C.2 / Fig. 7); skip the transform on V */
+  AKVQ_OUT_ROTATED = 2u   /* decode_attention: leave the output in the rotated domain (H folded into W_O) */
+};
+
+/* One layer's cache.  Plain data; every pointer is device memory owned by the caller (layout above).
+ * T_len is the number of valid rows; the caller advances it after akvq_quantize_append. */
+typedef struct akvq_cache {
+  int32_t B, Hkv, G, T_cap, S_cap, T_len;
+  uint32_t *k_codes, *v_codes; /* device */
+  uint32_t *k_meta, *v_meta;   /* device */
+  uint16_t *k_sal, *v_sal;     /* device */
+  int32_t *sal_idx, *sal_cnt;  /* device */
+} akvq_cache;
+
+const char *akvq_strerror(int status);
+int akvq_last_hip_error(void); /* hipError_t of the most recent failed launch in this thread, 0 if none */
+int akvq_version(void);
+
+/* Host helper: byte sizes of the eight device arrays of a cache with the given shape fields
+ * (order: k_codes, v_codes, k_meta, v_meta, k_sal, v_sal, sal_idx, sal_cnt).  Returns AKVQ_OK or an error. */
+int akvq_cache_bytes(const akvq_cache *shape, size_t out_bytes[8]);
+
+/* Host helpers: device workspace each call needs (bytes; 0 on invalid arguments). */
+size_t akvq_select_workspace_bytes(int B, int Hq, int Hkv, int T, int W);
+size_t akvq_decode_workspace_bytes(int B, int Hq, int n_split);
+/* Host helper: number of KV splits akvq_decode_attention uses when n_split <= 0 is passed. */
+int akvq_decode_default_splits(int B, int Hkv, int T_len);
+
+/*
+ * akvq_select_salient -- Section III-B: write the salient-token list of every (batch, kv-head).
+ *   mode AKVQ_MODE_TSA (III-B.1): salient = text positions.  Needs is_text (device, [B][T] uint8).
+ *   mode AKVQ_MODE_PSA (III-B.2): salient = the top_k positions by attention-column mass
+ *       mass[b][hkv][t] = sum over the Hq/Hkv query heads of the group and the W last prompt rows i of
+ *       softmax_t( sm_scale * q_i . k_t )[t], row i sitting at position T-W+i and seeing keys t <= T-W+i.
+ *       Operands are rounded to bfloat16, products accumulate in fp32 on the matrix cores, softmax in fp32.
+ *       Needs q_tail (device, [B][Hq][W][128] binary16, post-RoPE) and k (device, [B][Hkv][T][128] binary16,
+ *       post-RoPE, un-rotated).  Ties go to the lower position.  W must be a multiple of 16, W <= T, W <= 64.
+ *   Output: c->sal_idx (ascending) and c->sal_cnt.  mass_out (device, [B][Hkv][T] fp32) is optional (PSA).
+ *   workspace: device, akvq_select_workspace_bytes() bytes (PSA only; may be NULL for TSA).
+ */
+int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, const void *q_tail, int Hq,
+                        const void *k, int T, int W, int top_k, float sm_scale, float *mass_out,
+                        void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * akvq_quantize_append -- Section III-C write path for rows [T_len, T_len + n_new).
+ *   k_new, v_new: device, [B][Hkv][n_new][128] binary16 (K post-RoPE, un-rotated).
+ *   Each row is rotated (fp32 butterfly, stride 1..64, then 2^-3.5), its groups get scale / zero-point
+ *   (Eq. 5-6 with clipped_min = clip*min, clipped_max = clip*max; scale stored as binary16 rounded up) and
+ *   2-bit codes (Eq. 3, round-half-even of x/scale + zero).  Rows listed in c->sal_idx additionally get a
+ *   bfloat16 copy in the overlay at the slot equal to their rank in the list, and the salient bit in meta.
+ *   c->sal_idx / c->sal_cnt must already be final for these rows.  Does not modify c->T_len.
+ */
+int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_new, int n_new, float clip,
+                         uint32_t flags, void *stream);
+
+/*
+ * akvq_decode_attention -- read path: out[b][hq] = softmax_t( sm_scale * q~ . k^_t ) v^_t over the T_len cached rows
+ *   (Section II-A decode step with the Section III-C cache), q~ = q * H_128, k^/v^ = bfloat16 overlay row if the
+ *   row is salient else scale*(code - zero).  Split over T (n_split partial softmaxes merged exactly);
+ *   fp32 accumulation.  Output is rotated back by H_128 unless AKVQ_OUT_ROTATED.
+ *   q: device [B][Hq][128] binary16.  out: device [B][Hq][128] fp32.  lse_out: optional device [B][Hq] fp32.
+ *   n_split <= 0 picks akvq_decode_default_splits().  workspace: device, akvq_decode_workspace_bytes() bytes.
+ */
+int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+                          int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AKVQ_H */

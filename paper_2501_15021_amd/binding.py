@@ -1,0 +1,181 @@
+"""Thin ctypes binding of libakvq.so (C ABI in include/akvq.h).
+
+Argument marshalling only: torch supplies device memory and the current stream; every step of the
+method runs inside the library's HIP kernels.  There is no fallback: if the library is missing or a
+call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libakvq.so")
+
+D = 128
+MODE_TSA, MODE_PSA = 0, 1
+V_PREROTATED, OUT_ROTATED = 1, 2
+
+EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",
+           "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
+           "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention"]
+
+
+class AkvqError(RuntimeError):
+    pass
+
+
+class akvq_cache(C.Structure):
+    _fields_ = [("B", C.c_int32), ("Hkv", C.c_int32), ("G", C.c_int32), ("T_cap", C.c_int32),
+                ("S_cap", C.c_int32), ("T_len", C.c_int32),
+                ("k_codes", C.c_void_p), ("v_codes", C.c_void_p), ("k_meta", C.c_void_p), ("v_meta", C.c_void_p),
+                ("k_sal", C.c_void_p), ("v_sal", C.c_void_p), ("sal_idx", C.c_void_p), ("sal_cnt", C.c_void_p)]
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Load the library built by paper_2501_15021_amd.build (never builds, never falls back)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise AkvqError(f"{LIB_PATH} is missing: run `python -m paper_2501_15021_amd.build` "
+                            "(or __graft_entry__.build()) first; there is no CPU fallback")
+        L = C.CDLL(LIB_PATH)
+        L.akvq_strerror.restype = C.c_char_p
+        L.akvq_strerror.argtypes = [C.c_int]
+        L.akvq_last_hip_error.restype = C.c_int
+        L.akvq_version.restype = C.c_int
+        L.akvq_cache_bytes.restype = C.c_int
+        L.akvq_cache_bytes.argtypes = [C.POINTER(akvq_cache), C.POINTER(C.c_size_t)]
+        L.akvq_select_workspace_bytes.restype = C.c_size_t
+        L.akvq_select_workspace_bytes.argtypes = [C.c_int] * 5
+        L.akvq_decode_workspace_bytes.restype = C.c_size_t
+        L.akvq_decode_workspace_bytes.argtypes = [C.c_int] * 3
+        L.akvq_decode_default_splits.restype = C.c_int
+        L.akvq_decode_default_splits.argtypes = [C.c_int] * 3
+        L.akvq_select_salient.restype = C.c_int
+        L.akvq_select_salient.argtypes = [C.POINTER(akvq_cache), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                          C.c_int, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+                                          C.c_void_p]
+        L.akvq_quantize_append.restype = C.c_int
+        L.akvq_quantize_append.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_void_p, C.c_int, C.c_float,
+                                           C.c_uint32, C.c_void_p]
+        L.akvq_decode_attention.restype = C.c_int
+        L.akvq_decode_attention.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
+                                            C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+        _lib = L
+    return _lib
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        L = lib()
+        raise AkvqError(f"{what}: {L.akvq_strerror(status).decode()} (status {status}, hip {L.akvq_last_hip_error()})")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream() -> C.c_void_p:
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+class Cache:
+    """One layer's mixed-precision cache: device tensors plus the plain-C descriptor the library takes."""
+
+    def __init__(self, B: int, Hkv: int, G: int, T_cap: int, S_cap: int, device="cuda", fill: Optional[int] = None):
+        self.B, self.Hkv, self.G, self.T_cap, self.S_cap, self.T_len = B, Hkv, G, T_cap, S_cap, 0
+        shape = akvq_cache(B, Hkv, G, T_cap, S_cap, 0)
+        sizes = (C.c_size_t * 8)()
+        _check(lib().akvq_cache_bytes(C.byref(shape), sizes), "akvq_cache_bytes")
+        dev = torch.device(device)
+        mk = (lambda n: torch.empty(n, dtype=torch.uint8, device=dev)) if fill is None else \
+             (lambda n: torch.full((n,), fill, dtype=torch.uint8, device=dev))
+        self.k_codes = mk(sizes[0]).view(torch.int32).view(B, Hkv, T_cap // 32, 256)
+        self.v_codes = mk(sizes[1]).view(torch.int32).view(B, Hkv, T_cap // 32, 256)
+        self.k_meta = mk(sizes[2]).view(torch.int32).view(B, Hkv, T_cap, D // G)
+        self.v_meta = mk(sizes[3]).view(torch.int32).view(B, Hkv, T_cap, D // G)
+        # the overlay is zero-filled: decode masks unused slots, zeroing keeps them finite for other readers
+        self.k_sal = torch.zeros(sizes[4] // 2, dtype=torch.int16, device=dev).view(B, Hkv, S_cap, D)
+        self.v_sal = torch.zeros(sizes[5] // 2, dtype=torch.int16, device=dev).view(B, Hkv, S_cap // 32, 4096)
+        self.sal_idx = torch.full((B, Hkv, S_cap), -1, dtype=torch.int32, device=dev)
+        self.sal_cnt = torch.zeros(sizes[7] // 4, dtype=torch.int32, device=dev)
+        self._ws = {}
+
+    def struct(self) -> akvq_cache:
+        return akvq_cache(self.B, self.Hkv, self.G, self.T_cap, self.S_cap, self.T_len,
+                          self.k_codes.data_ptr(), self.v_codes.data_ptr(), self.k_meta.data_ptr(),
+                          self.v_meta.data_ptr(), self.k_sal.data_ptr(), self.v_sal.data_ptr(),
+                          self.sal_idx.data_ptr(), self.sal_cnt.data_ptr())
+
+    def workspace(self, key: str, nbytes: int) -> torch.Tensor:
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() < nbytes:
+            ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.k_codes.device)
+            self._ws[key] = ws
+        return ws
+
+    def counts(self) -> torch.Tensor:
+        return self.sal_cnt[: self.B * self.Hkv].view(self.B, self.Hkv)
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in (self.k_codes, self.v_codes, self.k_meta, self.v_meta,
+                                                          self.k_sal, self.v_sal, self.sal_idx, self.sal_cnt))
+
+
+def select_salient(cache: Cache, mode: int, *, is_text: Optional[torch.Tensor] = None,
+                   q_tail: Optional[torch.Tensor] = None, k: Optional[torch.Tensor] = None, top_k: int = 0,
+                   sm_scale: float = 0.0, mass_out: Optional[torch.Tensor] = None) -> None:
+    """akvq_select_salient: writes cache.sal_idx / cache.sal_cnt on the current stream."""
+    c = cache.struct()
+    if mode == MODE_TSA:
+        assert is_text.dtype == torch.uint8 and is_text.is_contiguous() and is_text.shape[0] == cache.B
+        st = lib().akvq_select_salient(C.byref(c), mode, _ptr(is_text), None, cache.Hkv, None, is_text.shape[1], 0, 0,
+                                       0.0, None, None, 0, _stream())
+    else:
+        assert q_tail.dtype == torch.float16 and k.dtype == torch.float16
+        assert q_tail.is_contiguous() and k.is_contiguous()
+        B, Hq, W, _ = q_tail.shape
+        T = k.shape[2]
+        nws = lib().akvq_select_workspace_bytes(B, Hq, cache.Hkv, T, W)
+        ws = cache.workspace("select", nws)
+        if mass_out is not None:
+            assert mass_out.dtype == torch.float32 and mass_out.is_contiguous()
+        st = lib().akvq_select_salient(C.byref(c), mode, None, _ptr(q_tail), Hq, _ptr(k), T, W, top_k, sm_scale,
+                                       _ptr(mass_out), _ptr(ws), ws.numel(), _stream())
+    _check(st, "akvq_select_salient")
+
+
+def quantize_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, clip: float, flags: int = 0) -> None:
+    """akvq_quantize_append for rows [T_len, T_len + n_new); advances cache.T_len."""
+    assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16
+    assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.shape == v_new.shape
+    n_new = k_new.shape[2]
+    c = cache.struct()
+    _check(lib().akvq_quantize_append(C.byref(c), _ptr(k_new), _ptr(v_new), n_new, clip, flags, _stream()),
+           "akvq_quantize_append")
+    cache.T_len += n_new
+
+
+def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: int = 0, flags: int = 0,
+                     out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None):
+    """akvq_decode_attention: returns (out [B,Hq,128] fp32, lse [B,Hq] fp32)."""
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    B, Hq, _ = q.shape
+    if n_split <= 0:
+        n_split = lib().akvq_decode_default_splits(cache.B, cache.Hkv, cache.T_len)
+    ws = cache.workspace("decode", lib().akvq_decode_workspace_bytes(B, Hq, n_split))
+    if out is None:
+        out = torch.empty(B, Hq, D, dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
+    c = cache.struct()
+    _check(lib().akvq_decode_attention(C.byref(c), _ptr(q), Hq, sm_scale, _ptr(out), _ptr(lse), n_split, _ptr(ws),
+                                       ws.numel(), flags, _stream()), "akvq_decode_attention")
+    return out, lse

@@ -1,0 +1,184 @@
+// C ABI of libakvq (declared in include/akvq.h): argument validation, size helpers, kernel dispatch.
+// Nothing here allocates, frees or synchronises; every call enqueues on the caller's stream and returns.
+#include "../../include/akvq.h"
+
+#include <hip/hip_runtime.h>
+
+#include "akvq_kernels.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int check_cache_shape(const akvq_cache *c) {
+  if (!c) return AKVQ_ERR_INVALID_ARG;
+  if (c->B <= 0 || c->Hkv <= 0 || c->T_cap <= 0 || c->S_cap <= 0 || c->T_len < 0) return AKVQ_ERR_INVALID_ARG;
+  if (c->G != 64 && c->G != 128) return AKVQ_ERR_UNSUPPORTED;
+  if (c->T_cap % 64 != 0 || c->S_cap % 64 != 0) return AKVQ_ERR_INVALID_ARG;
+  if (c->T_len > c->T_cap) return AKVQ_ERR_CAPACITY;
+  return AKVQ_OK;
+}
+
+int check_cache_pointers(const akvq_cache *c) {
+  const void *p[8] = {c->k_codes, c->v_codes, c->k_meta, c->v_meta, c->k_sal, c->v_sal, c->sal_idx, c->sal_cnt};
+  for (const void *x : p)
+    if (!x || !aligned16(x)) return AKVQ_ERR_INVALID_ARG;
+  return AKVQ_OK;
+}
+
+int hip_status(hipError_t e) {
+  if (e == hipSuccess) return AKVQ_OK;
+  g_last_hip_error = (int)e;
+  return AKVQ_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *akvq_strerror(int status) {
+  switch (status) {
+    case AKVQ_OK: return "ok";
+    case AKVQ_ERR_INVALID_ARG: return "invalid argument";
+    case AKVQ_ERR_UNSUPPORTED: return "unsupported configuration";
+    case AKVQ_ERR_CAPACITY: return "capacity exceeded";
+    case AKVQ_ERR_WORKSPACE: return "workspace too small";
+    case AKVQ_ERR_HIP: return "HIP launch failed";
+    default: return "unknown status";
+  }
+}
+
+int akvq_last_hip_error(void) { return g_last_hip_error; }
+
+int akvq_version(void) { return 100; }
+
+int akvq_cache_bytes(const akvq_cache *shape, size_t out_bytes[8]) {
+  int st = check_cache_shape(shape);
+  if (st != AKVQ_OK) return st;
+  if (!out_bytes) return AKVQ_ERR_INVALID_ARG;
+  const size_t bh = (size_t)shape->B * shape->Hkv;
+  const size_t codes = bh * (size_t)(shape->T_cap / 32) * 1024;
+  const size_t meta = bh * (size_t)shape->T_cap * (128 / shape->G) * 4;
+  const size_t sal = bh * (size_t)shape->S_cap * 128 * 2;
+  out_bytes[0] = codes; out_bytes[1] = codes;
+  out_bytes[2] = meta;  out_bytes[3] = meta;
+  out_bytes[4] = sal;   out_bytes[5] = sal;
+  out_bytes[6] = bh * (size_t)shape->S_cap * 4;
+  out_bytes[7] = round_up(bh * 4, 16);
+  return AKVQ_OK;
+}
+
+static int select_chunks(int T) { return (T + akvq::kScoreChunk - 1) / akvq::kScoreChunk; }
+
+size_t akvq_select_workspace_bytes(int B, int Hq, int Hkv, int T, int W) {
+  if (B <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || W <= 0) return 0;
+  const size_t stats = (size_t)B * Hq * select_chunks(T) * W * 2 * sizeof(float);
+  const size_t mass = (size_t)B * Hkv * T * sizeof(float);
+  return round_up(stats, 256) + round_up(mass, 256);
+}
+
+size_t akvq_decode_workspace_bytes(int B, int Hq, int n_split) {
+  if (B <= 0 || Hq <= 0 || n_split <= 0) return 0;
+  return round_up((size_t)B * Hq * n_split * akvq::kPartialStride * sizeof(float), 256);
+}
+
+int akvq_decode_default_splits(int B, int Hkv, int T_len) {
+  if (B <= 0 || Hkv <= 0 || T_len <= 0) return 1;
+  const long units = (long)B * Hkv;
+  const int tiles = (T_len + 63) / 64;
+  long want = (8192 + units - 1) / units;      // enough wavefronts to fill 256 CUs several times over
+  long cap = tiles / 4 > 1 ? tiles / 4 : 1;    // but keep at least four 64-token tiles per split
+  if (want > cap) want = cap;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  return (int)want;
+}
+
+int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, const void *q_tail, int Hq,
+                        const void *k, int T, int W, int top_k, float sm_scale, float *mass_out,
+                        void *workspace, size_t workspace_bytes, void *stream) {
+  int st = check_cache_shape(c);
+  if (st != AKVQ_OK) return st;
+  if (!c->sal_idx || !c->sal_cnt || !aligned16(c->sal_idx) || !aligned16(c->sal_cnt)) return AKVQ_ERR_INVALID_ARG;
+  if (T <= 0 || T > c->T_cap) return AKVQ_ERR_INVALID_ARG;
+  akvq::SelectArgs a{};
+  a.sal_idx = c->sal_idx; a.sal_cnt = c->sal_cnt;
+  a.B = c->B; a.Hkv = c->Hkv; a.T = T; a.S_cap = c->S_cap;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (mode == AKVQ_MODE_TSA) {
+    if (!is_text) return AKVQ_ERR_INVALID_ARG;
+    a.is_text = is_text;
+    a.Hq = c->Hkv;
+    return hip_status(akvq::launch_select_tsa(a, s));
+  }
+  if (mode != AKVQ_MODE_PSA) return AKVQ_ERR_INVALID_ARG;
+  if (!q_tail || !k || !aligned16(q_tail) || !aligned16(k)) return AKVQ_ERR_INVALID_ARG;
+  if (Hq <= 0 || Hq % c->Hkv != 0 || W <= 0 || W > T || top_k <= 0) return AKVQ_ERR_INVALID_ARG;
+  if (W % 16 != 0 || W > 64) return AKVQ_ERR_UNSUPPORTED;
+  if (top_k > c->S_cap) return AKVQ_ERR_CAPACITY;
+  if (mass_out && !aligned16(mass_out)) return AKVQ_ERR_INVALID_ARG;
+  if (!workspace || !aligned16(workspace)) return AKVQ_ERR_INVALID_ARG;
+  if (workspace_bytes < akvq_select_workspace_bytes(c->B, Hq, c->Hkv, T, W)) return AKVQ_ERR_WORKSPACE;
+  a.q_tail = static_cast<const uint16_t *>(q_tail);
+  a.k = static_cast<const uint16_t *>(k);
+  a.Hq = Hq; a.W = W; a.top_k = top_k; a.sm_scale = sm_scale;
+  a.n_chunk = select_chunks(T);
+  a.row_stats = static_cast<float *>(workspace);
+  const size_t stats = round_up((size_t)c->B * Hq * a.n_chunk * W * 2 * sizeof(float), 256);
+  a.mass = mass_out ? mass_out : reinterpret_cast<float *>(static_cast<char *>(workspace) + stats);
+  return hip_status(akvq::launch_select_psa(a, s));
+}
+
+int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_new, int n_new, float clip,
+                         uint32_t flags, void *stream) {
+  int st = check_cache_shape(c);
+  if (st != AKVQ_OK) return st;
+  st = check_cache_pointers(c);
+  if (st != AKVQ_OK) return st;
+  if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new <= 0) return AKVQ_ERR_INVALID_ARG;
+  if (!(clip > 0.0f) || clip > 1.0f) return AKVQ_ERR_INVALID_ARG;
+  if ((long)c->T_len + n_new > c->T_cap) return AKVQ_ERR_CAPACITY;
+  akvq::QuantArgs a{};
+  a.k_new = static_cast<const uint16_t *>(k_new);
+  a.v_new = static_cast<const uint16_t *>(v_new);
+  a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
+  a.k_sal = c->k_sal; a.v_sal = c->v_sal; a.sal_idx = c->sal_idx; a.sal_cnt = c->sal_cnt;
+  a.Hkv = c->Hkv; a.T_cap = c->T_cap; a.S_cap = c->S_cap; a.T_len = c->T_len; a.n_new = n_new;
+  a.first_blk = c->T_len / 32;
+  a.n_blk = (c->T_len + n_new - 1) / 32 - a.first_blk + 1;
+  a.clip = clip;
+  a.rotate_v = (flags & AKVQ_V_PREROTATED) ? 0 : 1;
+  return hip_status(akvq::launch_quantize_append(a, c->B, c->G, static_cast<hipStream_t>(stream)));
+}
+
+int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+                          int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
+  int st = check_cache_shape(c);
+  if (st != AKVQ_OK) return st;
+  st = check_cache_pointers(c);
+  if (st != AKVQ_OK) return st;
+  if (c->T_len <= 0) return AKVQ_ERR_INVALID_ARG;
+  if (!q || !out || !aligned16(q) || !aligned16(out)) return AKVQ_ERR_INVALID_ARG;
+  if (lse_out && !aligned16(lse_out)) return AKVQ_ERR_INVALID_ARG;
+  if (Hq <= 0 || Hq % c->Hkv != 0) return AKVQ_ERR_INVALID_ARG;
+  if (Hq / c->Hkv > 8) return AKVQ_ERR_UNSUPPORTED;
+  if (n_split <= 0) n_split = akvq_decode_default_splits(c->B, c->Hkv, c->T_len);
+  if (n_split > 1024) return AKVQ_ERR_INVALID_ARG;
+  if (!workspace || !aligned16(workspace)) return AKVQ_ERR_INVALID_ARG;
+  if (workspace_bytes < akvq_decode_workspace_bytes(c->B, Hq, n_split)) return AKVQ_ERR_WORKSPACE;
+  akvq::DecodeArgs a{};
+  a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
+  a.k_sal = c->k_sal; a.v_sal = c->v_sal; a.sal_idx = c->sal_idx; a.sal_cnt = c->sal_cnt;
+  a.q = static_cast<const uint16_t *>(q);
+  a.partial = static_cast<float *>(workspace);
+  a.out = out; a.lse = lse_out;
+  a.B = c->B; a.Hq = Hq; a.Hkv = c->Hkv; a.T_cap = c->T_cap; a.S_cap = c->S_cap; a.T_len = c->T_len;
+  a.n_split = n_split; a.sm_scale = sm_scale;
+  a.out_rotated = (flags & AKVQ_OUT_ROTATED) ? 1 : 0;
+  return hip_status(akvq::launch_decode_attention(a, c->G, static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

@@ -1,0 +1,711 @@
+// Read path of the AKVQ-VL cache: decode attention straight from the packed 2-bit + bfloat16 cache
+// (decode step of Section II-A over the cache of Section III-C, arXiv 2501.15021).
+//
+// One wavefront owns one (batch, kv-head, KV-split).  Both contractions run on the matrix cores with the
+// 2-bit codes expanded to bfloat16 integers in registers (one and-or per two codes, see akvq_device.h):
+//   scores  S = Q~ * C_K^T   : rows = the query vector split into bfloat16 terms, K-dim = 128 channels,
+//   output  O = W  * C_V     : rows = (softmax weight x scale) split into bfloat16 terms, K-dim = 32 tokens.
+// Scale, zero-point and the constants of the expansion are applied to the small side of each product
+// (per token for S, per channel-class for O), so the streamed bytes are touched once, by one and-or each.
+// The cache block layout makes each lane's 128-bit load its own matrix-core operand: no shuffles.
+#include "akvq_device.h"
+#include "akvq_kernels.h"
+
+namespace akvq {
+
+namespace {
+
+// ------------------------------------------------------------------------------------------------
+// Rotate the query (orthonormal 128-point Walsh-Hadamard, Section III-C.2) inside one wavefront, through LDS.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *qf, int lane) {
+  uint32_t two = reinterpret_cast<const uint32_t *>(q_row)[lane];
+  qf[2 * lane] = half_bits_to_float(two & 0xFFFFu);
+  qf[2 * lane + 1] = half_bits_to_float(two >> 16);
+  wave_lds_sync();
+#pragma unroll
+  for (int h = 1; h < kD; h *= 2) {
+    int i = ((lane / h) * 2 * h) + (lane % h);
+    float x = qf[i], y = qf[i + h];
+    wave_lds_sync();
+    qf[i] = x + y;
+    qf[i + h] = x - y;
+    wave_lds_sync();
+  }
+  qf[lane] *= inv_sqrt128();
+  qf[lane + 64] *= inv_sqrt128();
+  wave_lds_sync();
+}
+
+// exponent k of the 4^k factor that the expansion attaches to channel e of a K row (see the K block layout:
+// channel e sits in code pair e%8 of its word; pairs 0..3 are the X operand, 4..7 the Y operand)
+__device__ __forceinline__ int k_channel_exp(int e) { return pair_exp((e & 7) >> 2, e & 3); }
+__device__ __forceinline__ float pow4_neg(int k) { return k == 0 ? 1.0f : (k == 1 ? 0.25f : 0.0625f); }
+
+__device__ __forceinline__ uint32_t pack16(uint32_t lo, uint32_t hi) { return (lo & 0xFFFFu) | (hi << 16); }
+
+struct Meta {
+  float scale, zero;
+  bool salient;
+};
+__device__ __forceinline__ Meta unpack_meta(uint32_t w) {
+  Meta m;
+  m.scale = half_bits_to_float(w & 0x7FFFu);
+  m.zero = (float)((int)w >> 16);
+  m.salient = (w & 0x8000u) != 0;
+  return m;
+}
+
+// ------------------------------------------------------------------------------------------------
+// MHA (one query head per KV head).  A tile is 64 tokens = two cache blocks; the query's three bfloat16 terms
+// sit in rows 4g..4g+2 of the A operand used for token group g, so after the 16 products lane l holds the
+// three partial dot products of token l: one token per lane for the softmax.
+// ------------------------------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
+  constexpr int NG = kD / G;
+  __shared__ float qf[kD];
+  __shared__ uint16_t q_scaled[3][kD];   // terms of q~[e] * 4^-k(e): A operand for the code stream
+  __shared__ uint16_t q_plain[3][kD];    // terms of q~[e]: A operand for bfloat16 rows
+  __shared__ __attribute__((aligned(16))) uint16_t w_lds[2][NG][2][2][kTokBlock];  // [blk][group][xy][term][slot]
+  __shared__ __attribute__((aligned(16))) uint16_t zero16[8];
+
+  const int lane = threadIdx.x;
+  const int split = blockIdx.x;
+  const int bh = blockIdx.y;  // Hq == Hkv here
+  const int mrow = lane & 15, qd = lane >> 4;
+
+  if (lane < 8) zero16[lane] = 0;
+  rotate_query_lds(a.q + (size_t)bh * kD, qf, lane);
+
+  // ---- query terms, bias of the expansion constant, per-group sums ----
+  float bias_part[NG], qsum_part[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) bias_part[g] = qsum_part[g] = 0.0f;
+#pragma unroll
+  for (int rep = 0; rep < 2; ++rep) {
+    const int e = lane + 64 * rep;
+    const float v = qf[e];
+    uint32_t hi, mid, lo;
+    split3_bf16(v, hi, mid, lo);
+    q_plain[0][e] = (uint16_t)hi; q_plain[1][e] = (uint16_t)mid; q_plain[2][e] = (uint16_t)lo;
+    const float vs = v * pow4_neg(k_channel_exp(e));
+    split3_bf16(vs, hi, mid, lo);
+    q_scaled[0][e] = (uint16_t)hi; q_scaled[1][e] = (uint16_t)mid; q_scaled[2][e] = (uint16_t)lo;
+    const float rs = bf16_bits_to_f32(hi) + bf16_bits_to_f32(mid) + bf16_bits_to_f32(lo);
+    const int g = (NG == 2) ? rep : 0;  // e < 64 -> group 0
+    bias_part[g] += rs;
+    qsum_part[g] += v;
+  }
+  float qbias[NG], qsum[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    qbias[g] = kCodeBias * wave_sum(bias_part[g]);
+    qsum[g] = wave_sum(qsum_part[g]);
+  }
+  wave_lds_sync();
+
+  // ---- A operands for the code stream: [token group g][kc], row 4g+term, K-slot pair i ----
+  bf16x8 a_k[4][4];
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    const int term = mrow - 4 * g;
+    const bool live = term >= 0 && term < 3;
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) {
+      u32x4 r;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e_lo = 32 * (2 * (kc >> 1)) + 8 * qd + 4 * (kc & 1) + i;
+        const int e_hi = e_lo + 32;
+        r[i] = live ? pack16(q_scaled[term < 0 ? 0 : (term > 2 ? 2 : term)][e_lo],
+                             q_scaled[term < 0 ? 0 : (term > 2 ? 2 : term)][e_hi])
+                    : 0u;
+      }
+      a_k[g][kc] = __builtin_bit_cast(bf16x8, r);
+    }
+  }
+
+  f32x4 acc_o[8];
+#pragma unroll
+  for (int nb = 0; nb < 8; ++nb) acc_o[nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.0f;
+  float sx[NG], sy[NG], sz[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) sx[g] = sy[g] = sz[g] = 0.0f;
+
+  const int r16 = lane & 15, half = (lane >> 4) & 1, blk_of_lane = lane >> 5;
+  const int slot = 2 * r16 + half, ii = r16 & 3;
+  const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
+
+  // online-softmax bookkeeping shared by the code stream and the bfloat16 rows
+  auto softmax_step = [&](float score, bool ok, float &p) -> bool {
+    const float tile_max = wave_max(ok ? score : -INFINITY);
+    const float m_new = fmaxf(m_run, tile_max);
+    if (m_new == -INFINITY) { p = 0.0f; return false; }
+    if (m_new > m_run) {
+      const float alpha = (m_run == -INFINITY) ? 0.0f : __expf(m_run - m_new);
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) acc_o[nb] *= alpha;
+      l_run *= alpha;
+#pragma unroll
+      for (int g = 0; g < NG; ++g) { sx[g] *= alpha; sy[g] *= alpha; sz[g] *= alpha; }
+      m_run = m_new;
+    }
+    p = ok ? __expf(score - m_new) : 0.0f;
+    l_run += p;
+    return true;
+  };
+
+  // ================= code stream =================
+  const int n_tiles = (a.T_len + 63) / 64;
+  const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
+  const int tile_begin = split * tiles_per_split;
+  const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
+  const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
+  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords;
+  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords;
+  const uint32_t *km_base = a.k_meta + (size_t)bh * a.T_cap * NG;
+  const uint32_t *vm_base = a.v_meta + (size_t)bh * a.T_cap * NG;
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int t = tile * 64 + lane;
+    u32x4 kcv[2], vcv[2];
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+      kcv[b2] = *reinterpret_cast<const u32x4 *>(kc_base + ((size_t)(2 * tile + b2) * kBlockWords) + lane * 4);
+      vcv[b2] = *reinterpret_cast<const u32x4 *>(vc_base + ((size_t)(2 * tile + b2) * kBlockWords) + lane * 4);
+    }
+    uint32_t kmw[NG], vmw[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      kmw[g] = km_base[(size_t)t * NG + g];
+      vmw[g] = vm_base[(size_t)t * NG + g];
+    }
+
+    // scores: lane l ends up with the terms of token l in acc[0..2]
+    f32x4 acc[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) acc[g] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf) {
+        const int tg = 2 * b2 + hf;
+        const uint32_t w0 = kcv[b2][2 * hf], w1 = kcv[b2][2 * hf + 1];
+        acc[0] = mfma_bf16(a_k[tg][0], expand_x(w0), acc[0]);
+        acc[0] = mfma_bf16(a_k[tg][1], expand_y(w0), acc[0]);
+        acc[NG - 1] = mfma_bf16(a_k[tg][2], expand_x(w1), acc[NG - 1]);
+        acc[NG - 1] = mfma_bf16(a_k[tg][3], expand_y(w1), acc[NG - 1]);
+      }
+    float score = 0.0f;
+    bool salient = false;
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const Meta mk = unpack_meta(kmw[g]);
+      salient = salient || mk.salient;
+      const float raw = (acc[g][0] + acc[g][1] + acc[g][2]) - qbias[g];
+      score += mk.scale * (raw - mk.zero * qsum[g]);
+    }
+    score *= a.sm_scale;
+    const bool ok = (t < a.T_len) && !salient;
+    float p;
+    if (!softmax_step(score, ok, p)) continue;
+
+    // weights for the value contraction: w = p * scale_V, as two bfloat16 terms, pre-divided by the 4^k of their slot
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const Meta mv = unpack_meta(vmw[g]);
+      const float wv = ok ? p * mv.scale : 0.0f;
+      const uint32_t hi = f32_to_bf16_rne(wv);
+      const float hif = bf16_bits_to_f32(hi);
+      const uint32_t lo = f32_to_bf16_rne(wv - hif);
+      const float lof = bf16_bits_to_f32(lo);
+      const float wr = hif + lof;
+      w_lds[blk_of_lane][g][0][0][slot] = (uint16_t)(__float_as_uint(hif * cx) >> 16);
+      w_lds[blk_of_lane][g][0][1][slot] = (uint16_t)(__float_as_uint(lof * cx) >> 16);
+      w_lds[blk_of_lane][g][1][0][slot] = (uint16_t)(__float_as_uint(hif * cy) >> 16);
+      w_lds[blk_of_lane][g][1][1][slot] = (uint16_t)(__float_as_uint(lof * cy) >> 16);
+      sx[g] += wr * cx;
+      sy[g] += wr * cy;
+      sz[g] += wr * mv.zero;
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+      bf16x8 a_v[NG][2];
+#pragma unroll
+      for (int g = 0; g < NG; ++g)
+#pragma unroll
+        for (int xy = 0; xy < 2; ++xy) {
+          const uint16_t *src = mrow < 2 ? &w_lds[b2][g][xy][mrow][8 * qd] : zero16;
+          a_v[g][xy] = *reinterpret_cast<const bf16x8 *>(src);
+        }
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const int g = (NG == 2) ? (w & 1) : 0;
+        const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
+        acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(vcv[b2][w]), acc_o[nbx]);
+        acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(vcv[b2][w]), acc_o[nby]);
+      }
+    }
+    wave_lds_sync();
+  }
+
+  // ================= bfloat16 (salient) rows: units of 64 overlay slots, dealt round-robin to the splits =========
+  int cnt = a.sal_cnt[bh];
+  cnt = min(max(cnt, 0), a.S_cap);
+  const int n_units = (cnt + 63) / 64;
+  if (split < n_units) {
+    bf16x8 a_s[4][4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int term = mrow - 4 * g;
+      const bool live = term >= 0 && term < 3;
+      const int tc = term < 0 ? 0 : (term > 2 ? 2 : term);
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc) {
+        u32x4 r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int e = 32 * kc + 8 * qd + 2 * i;
+          r[i] = live ? pack16(q_plain[tc][e], q_plain[tc][e + 1]) : 0u;
+        }
+        a_s[g][kc] = __builtin_bit_cast(bf16x8, r);
+      }
+    }
+    const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
+    const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
+    const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+    for (int unit = split; unit < n_units; unit += a.n_split) {
+      const int s_lane = unit * 64 + lane;
+      f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc) {
+          const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(
+              ks_base + (size_t)(unit * 64 + 16 * g + mrow) * kD + 32 * kc + 8 * qd);
+          acc = mfma_bf16(a_s[g][kc], kb, acc);
+        }
+      const float score = a.sm_scale * (acc[0] + acc[1] + acc[2]);
+      const bool ok = (s_lane < cnt) && (sidx[min(s_lane, a.S_cap - 1)] < a.T_len);
+      float p;
+      if (!softmax_step(score, ok, p)) continue;
+      {
+        const float wv = ok ? p : 0.0f;
+        const uint32_t hi = f32_to_bf16_rne(wv);
+        const uint32_t lo = f32_to_bf16_rne(wv - bf16_bits_to_f32(hi));
+        w_lds[blk_of_lane][0][0][0][slot] = (uint16_t)hi;
+        w_lds[blk_of_lane][0][0][1][slot] = (uint16_t)lo;
+      }
+      wave_lds_sync();
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        const uint16_t *src = mrow < 2 ? &w_lds[b2][0][0][mrow][8 * qd] : zero16;
+        const bf16x8 a_v = *reinterpret_cast<const bf16x8 *>(src);
+        // which of this lane's 8 K-slots (pair i, half) are real rows: mask the others (unwritten memory)
+        uint32_t keep[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int s0 = unit * 64 + 32 * b2 + 4 * qd + i;  // half 0; half 1 is 16 slots further
+          keep[i] = (s0 < cnt ? 0x0000FFFFu : 0u) | (s0 + 16 < cnt ? 0xFFFF0000u : 0u);
+        }
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) {
+          u32x4 vb = *reinterpret_cast<const u32x4 *>(
+              vs_base + (size_t)(unit * 2 + b2) * 4096 + nb * 512 + (16 * qd + mrow) * 8);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) vb[i] &= keep[i];
+          acc_o[nb] = mfma_bf16(a_v, __builtin_bit_cast(bf16x8, vb), acc_o[nb]);
+        }
+      }
+      wave_lds_sync();
+    }
+  }
+
+  // ================= partial result of this split =================
+  const float l_tot = wave_sum(l_run);
+  float corr_x[NG], corr_y[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) {
+    const float z = wave_sum(sz[g]);
+    corr_x[g] = kCodeBias * wave_sum(sx[g]) + z;
+    corr_y[g] = kCodeBias * wave_sum(sy[g]) + z;
+  }
+  float *dst = a.partial + ((size_t)bh * a.n_split + split) * kPartialStride;
+  if (lane == 0) { dst[0] = m_run; dst[1] = l_tot; }
+  if (lane < 16) {
+#pragma unroll
+    for (int nb = 0; nb < 8; ++nb) {
+      const int g = (NG == 2) ? (nb >> 2) : 0;
+      const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
+      dst[4 + 16 * nb + lane] = (acc_o[nb][0] + acc_o[nb][1]) - corr;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// GQA (R = Hq/Hkv query heads share a KV head, 2 <= R <= 8; also valid for R = 1).  A tile is one cache block
+// (32 tokens, two token groups of 16).  Rows 2h+term of the A operand carry the two bfloat16 terms of head h,
+// so lane (n, q) receives heads 2q, 2q+1 of token n, and the same lanes own those heads' output rows.
+// ------------------------------------------------------------------------------------------------
+template <int G>
+__global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
+  constexpr int NG = kD / G;
+  __shared__ float qf[kD];
+  __shared__ uint16_t q_scaled[16][kD];  // row 2h+term
+  __shared__ uint16_t q_plain[16][kD];
+  __shared__ float qbias_lds[8][NG], qsum_lds[8][NG];
+  __shared__ __attribute__((aligned(16))) uint16_t w_lds[NG][2][16][kTokBlock];  // [group][xy][row][slot]
+
+  const int lane = threadIdx.x;
+  const int split = blockIdx.x;
+  const int bh = blockIdx.y;  // b * Hkv + hkv
+  const int R = a.Hq / a.Hkv;
+  const int b = bh / a.Hkv, hkv = bh % a.Hkv;
+  const int mrow = lane & 15, qd = lane >> 4;
+
+  for (int x = lane; x < 16 * kD; x += 64) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
+  for (int x = lane; x < NG * 2 * 16 * kTokBlock; x += 64) (&w_lds[0][0][0][0])[x] = 0;
+  wave_lds_sync();
+  for (int h = 0; h < R; ++h) {
+    rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf, lane);
+    float bias_part[NG], qsum_part[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) bias_part[g] = qsum_part[g] = 0.0f;
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const int e = lane + 64 * rep;
+      const float v = qf[e];
+      uint32_t hi = f32_to_bf16_rne(v);
+      uint32_t lo = f32_to_bf16_rne(v - bf16_bits_to_f32(hi));
+      q_plain[2 * h][e] = (uint16_t)hi; q_plain[2 * h + 1][e] = (uint16_t)lo;
+      const float vs = v * pow4_neg(k_channel_exp(e));
+      hi = f32_to_bf16_rne(vs);
+      lo = f32_to_bf16_rne(vs - bf16_bits_to_f32(hi));
+      q_scaled[2 * h][e] = (uint16_t)hi; q_scaled[2 * h + 1][e] = (uint16_t)lo;
+      const int g = (NG == 2) ? rep : 0;
+      bias_part[g] += bf16_bits_to_f32(hi) + bf16_bits_to_f32(lo);
+      qsum_part[g] += v;
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float bsum = kCodeBias * wave_sum(bias_part[g]);
+      const float qs = wave_sum(qsum_part[g]);
+      if (lane == 0) { qbias_lds[h][g] = bsum; qsum_lds[h][g] = qs; }
+    }
+    wave_lds_sync();
+  }
+
+  bf16x8 a_k[4];
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) {
+    u32x4 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e_lo = 32 * (2 * (kc >> 1)) + 8 * qd + 4 * (kc & 1) + i;
+      r[i] = pack16(q_scaled[mrow][e_lo], q_scaled[mrow][e_lo + 32]);
+    }
+    a_k[kc] = __builtin_bit_cast(bf16x8, r);
+  }
+  // this lane scores heads h0 = 2*qd and h0+1
+  const int h0 = 2 * qd;
+  float qbias[2][NG], qsum[2][NG];
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      qbias[hh][g] = (h0 + hh < R) ? qbias_lds[h0 + hh][g] : 0.0f;
+      qsum[hh][g] = (h0 + hh < R) ? qsum_lds[h0 + hh][g] : 0.0f;
+    }
+
+  f32x4 acc_o[8];
+#pragma unroll
+  for (int nb = 0; nb < 8; ++nb) acc_o[nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float sx[2][NG], sy[2][NG], sz[2][NG];
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) sx[hh][g] = sy[hh][g] = sz[hh][g] = 0.0f;
+
+  const int ii = mrow & 3;  // token n = mrow of its group: pair position
+  const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
+
+  auto row_max16 = [](float v) {
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+    return v;
+  };
+  auto row_sum16 = [](float v) {
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+    return v;
+  };
+
+  // scores sc[hh][tg] of heads h0+hh for tokens (16*tg + mrow) of the tile; ok[tg]; returns weights p[hh][tg]
+  auto softmax_step = [&](const float (&sc)[2][2], const bool (&ok)[2], float (&p)[2][2]) {
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      float mx = fmaxf(ok[0] ? sc[hh][0] : -INFINITY, ok[1] ? sc[hh][1] : -INFINITY);
+      mx = row_max16(mx);
+      const float m_new = fmaxf(m_run[hh], mx);
+      if (m_new > m_run[hh]) {
+        const float alpha = (m_run[hh] == -INFINITY) ? 0.0f : __expf(m_run[hh] - m_new);
+#pragma unroll
+        for (int nb = 0; nb < 8; ++nb) { acc_o[nb][2 * hh] *= alpha; acc_o[nb][2 * hh + 1] *= alpha; }
+        l_run[hh] *= alpha;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) { sx[hh][g] *= alpha; sy[hh][g] *= alpha; sz[hh][g] *= alpha; }
+        m_run[hh] = m_new;
+      }
+#pragma unroll
+      for (int tg = 0; tg < 2; ++tg) {
+        p[hh][tg] = (ok[tg] && m_new != -INFINITY) ? __expf(sc[hh][tg] - m_new) : 0.0f;
+        l_run[hh] += p[hh][tg];
+      }
+    }
+  };
+
+  // ================= code stream =================
+  const int n_tiles = (a.T_len + 31) / 32;
+  const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
+  const int tile_begin = split * tiles_per_split;
+  const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
+  const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
+  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords;
+  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords;
+  const uint32_t *km_base = a.k_meta + (size_t)bh * a.T_cap * NG;
+  const uint32_t *vm_base = a.v_meta + (size_t)bh * a.T_cap * NG;
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const u32x4 kcv = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)tile * kBlockWords + lane * 4);
+    const u32x4 vcv = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)tile * kBlockWords + lane * 4);
+    uint32_t kmw[2][NG], vmw[2][NG];
+#pragma unroll
+    for (int tg = 0; tg < 2; ++tg)
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const size_t t = (size_t)tile * 32 + 16 * tg + mrow;
+        kmw[tg][g] = km_base[t * NG + g];
+        vmw[tg][g] = vm_base[t * NG + g];
+      }
+    float sc[2][2];
+    bool ok[2];
+#pragma unroll
+    for (int tg = 0; tg < 2; ++tg) {
+      f32x4 acc[NG];
+#pragma unroll
+      for (int g = 0; g < NG; ++g) acc[g] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      const uint32_t w0 = kcv[2 * tg], w1 = kcv[2 * tg + 1];
+      acc[0] = mfma_bf16(a_k[0], expand_x(w0), acc[0]);
+      acc[0] = mfma_bf16(a_k[1], expand_y(w0), acc[0]);
+      acc[NG - 1] = mfma_bf16(a_k[2], expand_x(w1), acc[NG - 1]);
+      acc[NG - 1] = mfma_bf16(a_k[3], expand_y(w1), acc[NG - 1]);
+      bool salient = false;
+      float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+      for (int g = 0; g < NG; ++g) {
+        const Meta mk = unpack_meta(kmw[tg][g]);
+        salient = salient || mk.salient;
+        s0 += mk.scale * (((acc[g][0] + acc[g][1]) - qbias[0][g]) - mk.zero * qsum[0][g]);
+        s1 += mk.scale * (((acc[g][2] + acc[g][3]) - qbias[1][g]) - mk.zero * qsum[1][g]);
+      }
+      sc[0][tg] = s0 * a.sm_scale;
+      sc[1][tg] = s1 * a.sm_scale;
+      ok[tg] = (tile * 32 + 16 * tg + mrow < a.T_len) && !salient;
+    }
+    float p[2][2];
+    softmax_step(sc, ok, p);
+    // weights: rows 4*qd + {0,1,2,3} = (head h0: hi, lo; head h0+1: hi, lo); slots 2*mrow (+1 for the second group)
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        uint32_t hi[2], lo[2];
+        float hif[2], lof[2];
+#pragma unroll
+        for (int tg = 0; tg < 2; ++tg) {
+          const Meta mv = unpack_meta(vmw[tg][g]);
+          const float wv = ok[tg] ? p[hh][tg] * mv.scale : 0.0f;  // rows past T_len hold arbitrary meta
+          hi[tg] = f32_to_bf16_rne(wv);
+          hif[tg] = bf16_bits_to_f32(hi[tg]);
+          lo[tg] = f32_to_bf16_rne(wv - hif[tg]);
+          lof[tg] = bf16_bits_to_f32(lo[tg]);
+          const float wr = hif[tg] + lof[tg];
+          sx[hh][g] += wr * cx;
+          sy[hh][g] += wr * cy;
+          sz[hh][g] += wr * mv.zero;
+        }
+        const int row = 4 * qd + 2 * hh;
+        auto bits = [](float f) { return __float_as_uint(f) >> 16; };
+        reinterpret_cast<uint32_t *>(&w_lds[g][0][row][0])[mrow] = pack16(bits(hif[0] * cx), bits(hif[1] * cx));
+        reinterpret_cast<uint32_t *>(&w_lds[g][0][row + 1][0])[mrow] = pack16(bits(lof[0] * cx), bits(lof[1] * cx));
+        reinterpret_cast<uint32_t *>(&w_lds[g][1][row][0])[mrow] = pack16(bits(hif[0] * cy), bits(hif[1] * cy));
+        reinterpret_cast<uint32_t *>(&w_lds[g][1][row + 1][0])[mrow] = pack16(bits(lof[0] * cy), bits(lof[1] * cy));
+      }
+    wave_lds_sync();
+    bf16x8 a_v[NG][2];
+#pragma unroll
+    for (int g = 0; g < NG; ++g)
+#pragma unroll
+      for (int xy = 0; xy < 2; ++xy)
+        a_v[g][xy] = *reinterpret_cast<const bf16x8 *>(&w_lds[g][xy][mrow][8 * qd]);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const int g = (NG == 2) ? (w & 1) : 0;
+      const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
+      acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(vcv[w]), acc_o[nbx]);
+      acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(vcv[w]), acc_o[nby]);
+    }
+    wave_lds_sync();
+  }
+
+  // ================= bfloat16 (salient) rows: units of 32 overlay slots =================
+  int cnt = a.sal_cnt[bh];
+  cnt = min(max(cnt, 0), a.S_cap);
+  const int n_units = (cnt + 31) / 32;
+  if (split < n_units) {
+    bf16x8 a_s[4];
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) {
+      u32x4 r;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = 32 * kc + 8 * qd + 2 * i;
+        r[i] = pack16(q_plain[mrow][e], q_plain[mrow][e + 1]);
+      }
+      a_s[kc] = __builtin_bit_cast(bf16x8, r);
+    }
+    const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
+    const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
+    const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+    for (int unit = split; unit < n_units; unit += a.n_split) {
+      float sc[2][2];
+      bool ok[2];
+#pragma unroll
+      for (int tg = 0; tg < 2; ++tg) {
+        f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        const int s_lane = unit * 32 + 16 * tg + mrow;
+#pragma unroll
+        for (int kc = 0; kc < 4; ++kc) {
+          const bf16x8 kb =
+              *reinterpret_cast<const bf16x8 *>(ks_base + (size_t)s_lane * kD + 32 * kc + 8 * qd);
+          acc = mfma_bf16(a_s[kc], kb, acc);
+        }
+        sc[0][tg] = a.sm_scale * (acc[0] + acc[1]);
+        sc[1][tg] = a.sm_scale * (acc[2] + acc[3]);
+        ok[tg] = (s_lane < cnt) && (sidx[min(s_lane, a.S_cap - 1)] < a.T_len);
+      }
+      float p[2][2];
+      softmax_step(sc, ok, p);
+#pragma unroll
+      for (int hh = 0; hh < 2; ++hh) {
+        uint32_t hi[2], lo[2];
+#pragma unroll
+        for (int tg = 0; tg < 2; ++tg) {
+          hi[tg] = f32_to_bf16_rne(p[hh][tg]);
+          lo[tg] = f32_to_bf16_rne(p[hh][tg] - bf16_bits_to_f32(hi[tg]));
+        }
+        const int row = 4 * qd + 2 * hh;
+        reinterpret_cast<uint32_t *>(&w_lds[0][0][row][0])[mrow] = pack16(hi[0], hi[1]);
+        reinterpret_cast<uint32_t *>(&w_lds[0][0][row + 1][0])[mrow] = pack16(lo[0], lo[1]);
+      }
+      wave_lds_sync();
+      const bf16x8 a_v = *reinterpret_cast<const bf16x8 *>(&w_lds[0][0][mrow][8 * qd]);
+      uint32_t keep[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int s0 = unit * 32 + 4 * qd + i;
+        keep[i] = (s0 < cnt ? 0x0000FFFFu : 0u) | (s0 + 16 < cnt ? 0xFFFF0000u : 0u);
+      }
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) {
+        u32x4 vb = *reinterpret_cast<const u32x4 *>(vs_base + (size_t)unit * 4096 + nb * 512 + (16 * qd + mrow) * 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) vb[i] &= keep[i];
+        acc_o[nb] = mfma_bf16(a_v, __builtin_bit_cast(bf16x8, vb), acc_o[nb]);
+      }
+      wave_lds_sync();
+    }
+  }
+
+  // ================= partial results =================
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    const int h = h0 + hh;
+    const float l_tot = row_sum16(l_run[hh]);
+    float corr_x[NG], corr_y[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      const float z = row_sum16(sz[hh][g]);
+      corr_x[g] = kCodeBias * row_sum16(sx[hh][g]) + z;
+      corr_y[g] = kCodeBias * row_sum16(sy[hh][g]) + z;
+    }
+    if (h < R) {
+      float *dst = a.partial + (((size_t)b * a.Hq + hkv * R + h) * a.n_split + split) * kPartialStride;
+      if (mrow == 0) { dst[0] = m_run[hh]; dst[1] = l_tot; }
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) {
+        const int g = (NG == 2) ? (nb >> 2) : 0;
+        const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
+        dst[4 + 16 * nb + mrow] = (acc_o[nb][2 * hh] + acc_o[nb][2 * hh + 1]) - corr;
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Merge the KV splits (exact log-sum-exp merge), rotate the output back (H is its own inverse), write out.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
+  __shared__ float of[kD];
+  const int bhq = blockIdx.x;
+  const int d = threadIdx.x;
+  const float *part = a.partial + (size_t)bhq * a.n_split * kPartialStride;
+  float m_all = -INFINITY;
+  for (int s = 0; s < a.n_split; ++s) m_all = fmaxf(m_all, part[(size_t)s * kPartialStride]);
+  float l_all = 0.0f, o = 0.0f;
+  for (int s = 0; s < a.n_split; ++s) {
+    const float ms = part[(size_t)s * kPartialStride];
+    if (ms == -INFINITY) continue;
+    const float wgt = __expf(ms - m_all);
+    l_all += wgt * part[(size_t)s * kPartialStride + 1];
+    o += wgt * part[(size_t)s * kPartialStride + 4 + d];
+  }
+  o = o / l_all;
+  if (!a.out_rotated) {
+    of[d] = o;
+    __syncthreads();
+#pragma unroll
+    for (int h = 1; h < kD; h *= 2) {
+      const float mine = of[d], other = of[d ^ h];
+      __syncthreads();
+      of[d] = (d & h) ? (other - mine) : (mine + other);
+      __syncthreads();
+    }
+    o = of[d] * inv_sqrt128();
+  }
+  a.out[(size_t)bhq * kD + d] = o;
+  if (a.lse && d == 0) a.lse[bhq] = m_all + __logf(l_all);
+}
+
+}  // namespace
+
+hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream) {
+  dim3 grid(a.n_split, a.B * a.Hkv), block(64);
+  if (a.Hq == a.Hkv) {
+    if (G == 128) hipLaunchKernelGGL(decode_mha_kernel<128>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(decode_mha_kernel<64>, grid, block, 0, stream, a);
+  } else {
+    if (G == 128) hipLaunchKernelGGL(decode_gqa_kernel<128>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(decode_gqa_kernel<64>, grid, block, 0, stream, a);
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(decode_combine_kernel, dim3(a.B * a.Hq), dim3(128), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace akvq

@@ -1,0 +1,97 @@
+// Device-side helpers shared by the gfx950 kernels of libakvq (number formats, wave-level primitives,
+// matrix-core operand types, the 2-bit -> bfloat16 operand expansion).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace akvq {
+
+constexpr int kD = 128;          // head_dim
+constexpr int kWave = 64;        // wavefront width on CDNA4
+constexpr int kTokBlock = 32;    // tokens per cache block (1024 bytes of codes)
+constexpr int kBlockWords = 256; // uint32 words per block
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+// 2^-3.5: the normalisation of the 128-point Walsh-Hadamard matrix (seven levels of 1/sqrt(2), Eq. 7).
+__device__ __forceinline__ float inv_sqrt128() { return __uint_as_float(0x3DB504F3u); }
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t h16) {
+  return (float)__builtin_bit_cast(_Float16, (unsigned short)h16);
+}
+// float -> binary16 bits, round to nearest even (the conversion instruction's default mode)
+__device__ __forceinline__ uint32_t float_to_half_bits_rne(float f) {
+  return (uint32_t)__builtin_bit_cast(unsigned short, (_Float16)f);
+}
+
+// float -> bfloat16 bits, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// Split a float into up to three bfloat16 terms whose sum reproduces it to ~24 bits.
+__device__ __forceinline__ void split3_bf16(float v, uint32_t &hi, uint32_t &mid, uint32_t &lo) {
+  hi = f32_to_bf16_rne(v);
+  float r1 = v - bf16_bits_to_f32(hi);
+  mid = f32_to_bf16_rne(r1);
+  float r2 = r1 - bf16_bits_to_f32(mid);
+  lo = f32_to_bf16_rne(r2);
+}
+
+// ---- wave-level reductions (64 lanes) ----
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// LDS traffic between lanes of one wavefront only needs the wave's own memory ops to have landed.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// ---- 2-bit codes -> bfloat16 matrix-core operands --------------------------------------------------
+// A 32-bit code word holds 8 code pairs: pair p = (bits [2p,2p+2), bits [16+2p,16+2p+2)).
+// OR-ing a masked pair into 0x4300'4300 yields two bfloat16 numbers 128 + 4^k * code (k = the field's
+// position inside the 7-bit mantissa: 0, 1 or 2).  The constant 128 and the factor 4^k are undone on the
+// other operand of the contraction, so expansion costs one and-or per two codes (plus two shifts per word).
+// Pairs 0..3 form the "X" operand (factors 4^{0,1,2,0}), pairs 4..7 the "Y" operand (4^{1,2,0,1}).
+__device__ __forceinline__ uint32_t expand_pair(uint32_t w, int k) {
+  return (w & (0x00030003u << (2 * k))) | 0x43004300u;
+}
+__device__ __forceinline__ bf16x8 expand_x(uint32_t w) {
+  uint32_t w6 = w >> 6;
+  u32x4 r = {expand_pair(w, 0), expand_pair(w, 1), expand_pair(w, 2), expand_pair(w6, 0)};
+  return __builtin_bit_cast(bf16x8, r);
+}
+__device__ __forceinline__ bf16x8 expand_y(uint32_t w) {
+  uint32_t w6 = w >> 6, w12 = w >> 12;
+  u32x4 r = {expand_pair(w6, 1), expand_pair(w6, 2), expand_pair(w12, 0), expand_pair(w12, 1)};
+  return __builtin_bit_cast(bf16x8, r);
+}
+// exponent k (factor 4^k) carried by pair i of the X / Y operand
+__device__ __forceinline__ int pair_exp(int xy, int i) {
+  // X: {0,1,2,0}   Y: {1,2,0,1}
+  return xy == 0 ? (i == 3 ? 0 : i) : (i == 0 ? 1 : (i == 1 ? 2 : (i == 2 ? 0 : 1)));
+}
+constexpr float kCodeBias = 128.0f; // the 2^7 every expanded code carries
+
+__device__ __forceinline__ f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+
+} // namespace akvq

@@ -1,0 +1,51 @@
+// Host-side launch interfaces of the libakvq kernels (internal; the public ABI is include/akvq.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace akvq {
+
+struct QuantArgs {
+  const uint16_t *k_new, *v_new;  // [B][Hkv][n_new][128] binary16
+  uint32_t *k_codes, *v_codes, *k_meta, *v_meta;
+  uint16_t *k_sal, *v_sal;
+  const int32_t *sal_idx, *sal_cnt;
+  int Hkv, T_cap, S_cap, T_len, n_new;
+  int first_blk, n_blk;  // 32-token blocks touched by rows [T_len, T_len + n_new)
+  float clip;
+  int rotate_v;
+};
+hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream);
+
+struct DecodeArgs {
+  const uint32_t *k_codes, *v_codes, *k_meta, *v_meta;
+  const uint16_t *k_sal, *v_sal;
+  const int32_t *sal_idx, *sal_cnt;
+  const uint16_t *q;  // [B][Hq][128] binary16
+  float *partial;     // [B*Hq][n_split][kPartialStride] fp32
+  float *out;         // [B][Hq][128]
+  float *lse;         // optional [B][Hq]
+  int B, Hq, Hkv, T_cap, S_cap, T_len, n_split;
+  float sm_scale;
+  int out_rotated;
+};
+constexpr int kPartialStride = 132;  // m, l, 2 pad, 128 accumulators
+hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream);
+
+struct SelectArgs {
+  const uint8_t *is_text;    // [B][T]
+  const uint16_t *q_tail;    // [B][Hq][W][128] binary16
+  const uint16_t *k;         // [B][Hkv][T][128] binary16
+  int32_t *sal_idx, *sal_cnt;
+  float *mass;               // [B][Hkv][T] fp32 (user buffer or workspace)
+  float *row_stats;          // workspace: [B][Hq][n_chunk][W][2]
+  int B, Hq, Hkv, T, W, top_k, S_cap, n_chunk;
+  float sm_scale;
+};
+constexpr int kScoreChunk = 256;  // keys per scoring workgroup
+hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream);
+hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream);
+
+}  // namespace akvq

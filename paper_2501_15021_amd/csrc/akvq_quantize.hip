@@ -1,0 +1,336 @@
+// Write path of the AKVQ-VL cache (Section III-C of arXiv 2501.15021): rotate each new Key/Value head vector by
+// the 128-point Walsh-Hadamard matrix (Eq. 7), derive per-group scale and zero-point (Eq. 5-6, with clipping),
+// emit 2-bit codes (Eq. 3), pack them into the block layout decode reads, and keep salient rows as bfloat16.
+//
+// Mapping: one wavefront owns one 32-token block of one (batch, kv-head, tensor).  Four neighbouring lanes own a
+// token pair (t, t+16): lane (r, j) holds channels e = 32*m + 8*j + i (m<4, i<8) of tokens r and r+16 of the
+// block, so every global load is a 128-bit load and a quad covers 64 contiguous bytes of a row.  Butterfly
+// strides 1,2,4 and 32,64 stay in registers; strides 8,16 cross the quad with DPP quad_perm.
+#include "akvq_device.h"
+#include "akvq_kernels.h"
+
+namespace akvq {
+
+namespace {
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_move_u(uint32_t v) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
+}
+constexpr int kQuadXor1 = 0xB1;  // quad_perm [1,0,3,2]
+constexpr int kQuadXor2 = 0x4E;  // quad_perm [2,3,0,1]
+constexpr int kRowRor4 = 0x124;  // rotate right by 4 inside a row of 16 lanes
+constexpr int kRowRor8 = 0x128;
+
+// One cross-lane butterfly level: the lane whose index bit is clear keeps a+b, its partner keeps a-b.
+// sign_mask is 0 for the lower lane and 0x80000000 for the upper one; (own ^ sign) is exact, so the single
+// rounding is that of the add, as the specification of the transform requires.
+template <int CTRL>
+__device__ __forceinline__ float cross_butterfly(float own, uint32_t sign_mask) {
+  float partner = dpp_move<CTRL>(own);
+  float signed_own = __uint_as_float(__float_as_uint(own) ^ sign_mask);
+  return partner + signed_own;
+}
+
+// un-normalised 128-point butterfly over u[4][8] (m, i) with the j index spread over the quad
+__device__ __forceinline__ void wht128_quad(float (&u)[4][8], int j) {
+  // strides 1, 2, 4: inside i
+#pragma unroll
+  for (int h = 1; h < 8; h *= 2)
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        if ((i & h) == 0) {
+          float a = u[m][i], b = u[m][i + h];
+          u[m][i] = a + b;
+          u[m][i + h] = a - b;
+        }
+  // strides 8, 16: across the quad (j bit 0, j bit 1)
+  const uint32_t s1 = (j & 1) ? 0x80000000u : 0u;
+  const uint32_t s2 = (j & 2) ? 0x80000000u : 0u;
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) u[m][i] = cross_butterfly<kQuadXor1>(u[m][i], s1);
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) u[m][i] = cross_butterfly<kQuadXor2>(u[m][i], s2);
+  // strides 32, 64: inside m
+#pragma unroll
+  for (int h = 1; h < 4; h *= 2)
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+      if ((m & h) == 0)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float a = u[m][i], b = u[m + h][i];
+          u[m][i] = a + b;
+          u[m + h][i] = a - b;
+        }
+}
+
+struct GroupQ {
+  uint32_t meta;      // scale bits | zero << 16 (salient flag added by the caller)
+  float rcpu;         // kappa / scale
+  float magic_zero;   // 1.5 * 2^23 + zero
+};
+
+constexpr float kMagic = 12582912.0f;      // 1.5 * 2^23: adding it rounds to an integer in the low mantissa bits
+constexpr uint32_t kMagicBits = 0x4B400000u;
+
+// Eq. 5-6 for one group from the extrema of the un-normalised transform.
+__device__ __forceinline__ GroupQ group_params(float umin, float umax, float kappa, float clip) {
+  float gmin = __fmul_rn(umin, kappa), gmax = __fmul_rn(umax, kappa);
+  float cmin = __fmul_rn(clip, gmin), cmax = __fmul_rn(clip, gmax);
+  float range = __fsub_rn(cmax, cmin);
+  float s32 = __fmul_rn(range, __uint_as_float(0x3EAAAAABu));
+  uint32_t s16;
+  if (!(s32 > 0.0f)) {
+    s16 = 0x3C00u;
+  } else {
+    s16 = float_to_half_bits_rne(s32);
+    if (s16 >= 0x7C00u) s16 = 0x7BFFu;
+    else if (half_bits_to_float(s16) < s32) s16 += 1u;
+    if (s16 >= 0x7C00u) s16 = 0x7BFFu;
+  }
+  float s = half_bits_to_float(s16);
+  float rcp = __fdiv_rn(1.0f, s);
+  float zr = rintf(__fmul_rn(cmin, rcp));
+  int z = (zr != zr) ? 0 : -(int)fminf(fmaxf(zr, -40000.0f), 40000.0f);
+  z = min(32767, max(-32768, z));
+  GroupQ g;
+  g.meta = s16 | ((uint32_t)(z & 0xFFFF) << 16);
+  g.rcpu = __fmul_rn(rcp, kappa);
+  g.magic_zero = kMagic + (float)z;
+  return g;
+}
+
+// Eq. 3: clamp(round(x/scale + zero), 0, 3); the fused multiply-add rounds the exact sum once, to an integer.
+__device__ __forceinline__ uint32_t code_of(float u, const GroupQ &g) {
+  float t = __fmaf_rn(u, g.rcpu, g.magic_zero);
+  t = fminf(fmaxf(t, kMagic), kMagic + 3.0f);
+  return __float_as_uint(t) - kMagicBits;
+}
+
+template <int G>
+__global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
+  __shared__ int slot_of_lds[4][kTokBlock];
+  const int wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
+  const int blk_rel = blockIdx.x * 4 + wave;
+  if (blk_rel >= a.n_blk) return;  // whole wavefront leaves; no block-wide barrier is used below
+  const int blk = a.first_blk + blk_rel;
+  const int bh = blockIdx.y;
+  const int tensor = blockIdx.z;  // 0 = K, 1 = V
+  const int r = lane >> 2, j = lane & 3;
+  constexpr int NG = kD / G;
+
+  const uint16_t *src = tensor == 0 ? a.k_new : a.v_new;
+  const bool rotate = tensor == 0 ? true : (a.rotate_v != 0);
+  const float kappa = rotate ? inv_sqrt128() : 1.0f;
+  const int t0 = blk * kTokBlock;
+  const int t_end = a.T_len + a.n_new;
+
+  // ---- which tokens of this block are salient, and at which overlay slot (rank in the ascending list) ----
+  int *slot_of = slot_of_lds[wave];
+  int cnt = a.sal_cnt[bh];
+  cnt = min(max(cnt, 0), a.S_cap);
+  const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+  if (lane < kTokBlock) slot_of[lane] = -1;
+  int lb = 0;
+  {
+    int lo = 0, hi = cnt;  // first entry >= t0 (same value in every lane)
+    while (lo < hi) {
+      int mid = (lo + hi) >> 1;
+      if (sidx[mid] < t0) lo = mid + 1; else hi = mid;
+    }
+    lb = lo;
+  }
+  wave_lds_sync();
+  if (lane < kTokBlock && lb + lane < cnt) {
+    int e = sidx[lb + lane];
+    if (e >= t0 && e < t0 + kTokBlock) slot_of[e - t0] = lb + lane;
+  }
+  wave_lds_sync();
+
+  uint32_t kw[2][2];         // K words of token half h: [h][group-of-64 word]
+  uint32_t vcode[2][2][8];   // V: [mpair][xy... packed per (i)] built below
+  uint32_t vmask_part = 0;
+  bool valid[2];
+  uint32_t meta_out[2][NG];
+  int slots[2];
+
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int t = t0 + 16 * h + r;
+    valid[h] = (t >= a.T_len) && (t < t_end);
+    slots[h] = slot_of[16 * h + r];
+    float u[4][8];
+    if (valid[h]) {
+      const uint16_t *row = src + ((size_t)bh * a.n_new + (t - a.T_len)) * kD;
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        u32x4 raw = *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j);
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          u[m][2 * w] = half_bits_to_float(raw[w] & 0xFFFFu);
+          u[m][2 * w + 1] = half_bits_to_float(raw[w] >> 16);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) u[m][i] = 0.0f;
+    }
+    if (rotate) wht128_quad(u, j);
+
+    // ---- bfloat16 overlay for salient rows (Section III-C.1: salient tokens keep 16-bit precision) ----
+    if (valid[h] && slots[h] >= 0) {
+      const int slot = slots[h];
+      if (tensor == 0) {
+        uint16_t *dst = a.k_sal + ((size_t)bh * a.S_cap + slot) * kD;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          u32x4 o;
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            o[w] = f32_to_bf16_rne(__fmul_rn(u[m][2 * w], kappa)) |
+                   (f32_to_bf16_rne(__fmul_rn(u[m][2 * w + 1], kappa)) << 16);
+          *reinterpret_cast<u32x4 *>(dst + 32 * m + 8 * j) = o;
+        }
+      } else {
+        uint16_t *plane = a.v_sal + (size_t)bh * a.S_cap * kD;
+        const int sb = slot >> 5, sh = (slot & 31) >> 4, sr = slot & 15, sq = sr >> 2, sii = sr & 3;
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int e = 32 * m + 8 * j + i, nb = e >> 4, n = e & 15;
+            plane[(size_t)sb * 4096 + nb * 512 + (16 * sq + n) * 8 + 2 * sii + sh] =
+                (uint16_t)f32_to_bf16_rne(__fmul_rn(u[m][i], kappa));
+          }
+      }
+    }
+
+    // ---- group extrema (quad reduction), scale, zero-point ----
+    GroupQ gq[NG];
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      constexpr int MPG = 4 / NG;  // m-slices per group
+      float mn = u[g * MPG][0], mx = u[g * MPG][0];
+#pragma unroll
+      for (int m = g * MPG; m < (g + 1) * MPG; ++m)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          mn = fminf(mn, u[m][i]);
+          mx = fmaxf(mx, u[m][i]);
+        }
+      mn = fminf(mn, dpp_move<kQuadXor1>(mn));
+      mx = fmaxf(mx, dpp_move<kQuadXor1>(mx));
+      mn = fminf(mn, dpp_move<kQuadXor2>(mn));
+      mx = fmaxf(mx, dpp_move<kQuadXor2>(mx));
+      gq[g] = group_params(mn, mx, kappa, a.clip);
+      meta_out[h][g] = gq[g].meta | (slots[h] >= 0 ? 0x8000u : 0u);
+    }
+
+    // ---- codes ----
+    if (tensor == 0) {
+      // K word (m/2): slot 8*(m%2)+i at bits 2*slot
+#pragma unroll
+      for (int wq = 0; wq < 2; ++wq) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int m = 2 * wq + mm;
+            word |= code_of(u[m][i], gq[m / (4 / NG)]) << (2 * (8 * mm + i));
+          }
+        kw[h][wq] = word;
+      }
+    } else {
+      // V: byte lanes of a partial word: token half h, X (m even) / Y (m odd)
+#pragma unroll
+      for (int mp = 0; mp < 2; ++mp)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          uint32_t cx = code_of(u[2 * mp][i], gq[(2 * mp) / (4 / NG)]);
+          uint32_t cy = code_of(u[2 * mp + 1][i], gq[(2 * mp + 1) / (4 / NG)]);
+          uint32_t part = (cx | (cy << 8)) << (16 * h);
+          if (h == 0) vcode[0][mp][i] = part; else vcode[0][mp][i] |= part;
+        }
+      if (valid[h]) vmask_part |= 0x0303u << (16 * h);
+    }
+  }
+
+  // ---- meta ----
+  if (j == 0) {
+    uint32_t *meta = tensor == 0 ? a.k_meta : a.v_meta;
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+      if (valid[h]) {
+        uint32_t *dst = meta + ((size_t)bh * a.T_cap + t0 + 16 * h + r) * NG;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) dst[g] = meta_out[h][g];
+      }
+  }
+
+  const size_t blk_word = ((size_t)bh * (a.T_cap / kTokBlock) + blk) * kBlockWords;
+  if (tensor == 0) {
+    // chunk 16*j + r: words {2h, 2h+1} belong to token half h
+    uint32_t *chunk = a.k_codes + blk_word + (size_t)(16 * j + r) * 4;
+    if (valid[0] && valid[1]) {
+      u32x4 o = {kw[0][0], kw[0][1], kw[1][0], kw[1][1]};
+      *reinterpret_cast<u32x4 *>(chunk) = o;
+    } else if (valid[0]) {
+      u32x2 o = {kw[0][0], kw[0][1]};
+      *reinterpret_cast<u32x2 *>(chunk) = o;
+    } else if (valid[1]) {
+      u32x2 o = {kw[1][0], kw[1][1]};
+      *reinterpret_cast<u32x2 *>(chunk + 2) = o;
+    }
+  } else {
+    // shift the byte lanes to this token's pair position (ii = r%4), then OR over the four rows that share a chunk
+    const int ii = r & 3, q = r >> 2;
+    uint32_t mask = vmask_part << (2 * ii);
+    mask |= dpp_move_u<kRowRor4>(mask);
+    mask |= dpp_move_u<kRowRor8>(mask);
+    if (mask != 0u) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        uint32_t w0 = vcode[0][0][i] << (2 * ii), w1 = vcode[0][1][i] << (2 * ii);
+        w0 |= dpp_move_u<kRowRor4>(w0);
+        w1 |= dpp_move_u<kRowRor4>(w1);
+        w0 |= dpp_move_u<kRowRor8>(w0);
+        w1 |= dpp_move_u<kRowRor8>(w1);
+        if ((i >> 1) == ii) {  // each of the four rows stores two of the eight chunks
+          uint32_t *dst = a.v_codes + blk_word + (size_t)(16 * q + 8 * (j & 1) + i) * 4 + 2 * (j >> 1);
+          if (mask != 0xFFFFFFFFu) {  // block only partly new: keep the other tokens' bits
+            w0 = (dst[0] & ~mask) | (w0 & mask);
+            w1 = (dst[1] & ~mask) | (w1 & mask);
+          }
+          u32x2 o = {w0, w1};
+          *reinterpret_cast<u32x2 *>(dst) = o;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream) {
+  dim3 grid((a.n_blk + 3) / 4, B * a.Hkv, 2), block(256);
+  if (G == 128) hipLaunchKernelGGL(quantize_append_kernel<128>, grid, block, 0, stream, a);
+  else hipLaunchKernelGGL(quantize_append_kernel<64>, grid, block, 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace akvq

@@ -1,0 +1,344 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars: packed codes, meta words (scale / zero / salient bit), overlay rows and salient index sets bit-exact;
+attention output within 2e-3 of the oracle relative to the row's largest output magnitude (fp32 accumulation).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_15021_amd import binding as akvq
+from paper_2501_15021_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+D = 128
+ATTN_TOL = 2e-3
+
+
+def _np(d):
+    return {k: (v.cpu().numpy() if hasattr(v, "cpu") else v) for k, v in d.items()}
+
+
+def _dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).cuda()
+
+
+def _u32(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def _u16(t):
+    return t.cpu().numpy().view(np.uint16)
+
+
+def make_pair(orc, w, fill=0, t_cap=None, s_cap=None, layer=0):
+    t_cap = t_cap or (w.T + 63) // 64 * 64
+    s_cap = s_cap or w.s_cap(layer)
+    oc = orc.OracleCache(w.B, w.Hkv, w.G, t_cap, s_cap, fill=fill)
+    gc = akvq.Cache(w.B, w.Hkv, w.G, t_cap, s_cap, fill=fill)
+    return oc, gc
+
+
+def copy_salient_to_gpu(oc, gc):
+    gc.sal_idx.copy_(_dev(oc.sal_idx))
+    gc.counts().copy_(_dev(oc.sal_cnt))
+
+
+def assert_cache_equal(oc, gc, what=""):
+    T = oc.T_len
+    assert gc.T_len == T
+    torch.cuda.synchronize()
+    for name in ("k_codes", "v_codes"):
+        got, ref = _u32(getattr(gc, name)), getattr(oc, name)
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, f"{what} {name}: {len(bad)} words differ, first at {bad[0]}: " \
+                              f"{got[tuple(bad[0])]:#x} vs {ref[tuple(bad[0])]:#x}"
+    for name in ("k_meta", "v_meta"):
+        got, ref = _u32(getattr(gc, name))[:, :, :T], getattr(oc, name)[:, :, :T]
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, f"{what} {name}: {len(bad)} words differ, first at {bad[0]}: " \
+                              f"{got[tuple(bad[0])]:#x} vs {ref[tuple(bad[0])]:#x}"
+    for name in ("k_sal", "v_sal"):
+        got, ref = _u16(getattr(gc, name)), getattr(oc, name)
+        bad = np.argwhere(got != ref)
+        assert bad.size == 0, f"{what} {name}: {len(bad)} values differ, first at {bad[0]}"
+
+
+def assert_attention_close(out_gpu, lse_gpu, out_ref, lse_ref, what=""):
+    out_gpu = out_gpu.cpu().numpy().astype(np.float64)
+    err = np.abs(out_gpu - out_ref).max(axis=-1)
+    scale = np.maximum(np.abs(out_ref).max(axis=-1), 1e-6)
+    rel = err / scale
+    worst = np.unravel_index(np.argmax(rel), rel.shape)
+    assert rel.max() <= ATTN_TOL, f"{what}: worst relative error {rel.max():.3e} at (b,h)={worst}"
+    if lse_gpu is not None:
+        assert np.abs(lse_gpu.cpu().numpy() - lse_ref).max() <= 2e-3, what
+    return rel.max()
+
+
+# ------------------------------------------------------------------------------------------- write path
+@pytest.mark.parametrize("G,T,clip,fill", [(128, 70, 0.8, 0), (64, 70, 1.0, 0xFF), (128, 640, 0.8, 0),
+                                           (64, 193, 0.8, 0xA5), (128, 1, 0.8, 0)])
+def test_quantize_append_bit_exact(orc, G, T, clip, fill):
+    w = synth.small(f"q{G}_{T}", B=2, Hq=3, Hkv=3, T=max(T, 12), G=G, clip=clip)
+    d = _np(synth.generate(w, seed=101 + T))
+    k, v = d["k"][:, :, :T], d["v"][:, :, :T]
+    oc, gc = make_pair(orc, w, fill=fill, t_cap=(T + 63) // 64 * 64 + 64, s_cap=64)
+    oc.select_tsa(d["is_text"])
+    copy_salient_to_gpu(oc, gc)
+    oc.quantize_append(k, v, clip)
+    akvq.quantize_append(gc, _dev(k), _dev(v), clip)
+    assert_cache_equal(oc, gc, f"G={G} T={T}")
+
+
+def test_quantize_append_in_pieces_and_single_rows(orc):
+    w = synth.small("pieces", B=1, Hq=2, Hkv=2, T=100, G=64)
+    d = _np(synth.generate(w, seed=103))
+    oc, gc = make_pair(orc, w, fill=0x5A, t_cap=128, s_cap=64)
+    oc.select_psa(d["q_tail"], d["k"], 6, w.sm_scale)
+    copy_salient_to_gpu(oc, gc)
+    cuts = [0, 41, 42, 43, 64, 65, 97, 100]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        oc.quantize_append(d["k"][:, :, a:b], d["v"][:, :, a:b], 0.8)
+        akvq.quantize_append(gc, _dev(d["k"][:, :, a:b]), _dev(d["v"][:, :, a:b]), 0.8)
+        assert_cache_equal(oc, gc, f"rows {a}:{b}")
+
+
+def test_quantize_prerotated_values(orc):
+    w = synth.small("prerot", B=1, Hq=2, Hkv=2, T=64, G=128)
+    d = _np(synth.generate(w, seed=104))
+    oc, gc = make_pair(orc, w, t_cap=64, s_cap=64)
+    oc.quantize_append(d["k"], d["v"], 0.8, rotate_v=False)
+    akvq.quantize_append(gc, _dev(d["k"]), _dev(d["v"]), 0.8, flags=akvq.V_PREROTATED)
+    assert_cache_equal(oc, gc, "prerotated V")
+
+
+def test_quantize_adversarial_rows(orc):
+    """Constant rows, exact ties, tiny and huge magnitudes, zero rows."""
+    rng = np.random.default_rng(5)
+    T = 64
+    k = rng.standard_normal((1, 1, T, D)).astype(np.float16)
+    k[0, 0, 0] = 0.0
+    k[0, 0, 1] = 2.75
+    k[0, 0, 2] = np.float16(6e-8)
+    k[0, 0, 3] = 60000.0
+    k[0, 0, 4, ::2] = 1.0; k[0, 0, 4, 1::2] = -1.0
+    k[0, 0, 5] = (np.arange(D) % 4).astype(np.float16) - 1.5
+    k[0, 0, 6] = (rng.integers(-8, 9, D) * 0.5).astype(np.float16)
+    k[0, 0, 7] = np.where(np.arange(D) == 17, 1000.0, 1e-3).astype(np.float16)
+    v = k[:, :, ::-1].copy()
+    for G in (128, 64):
+        for clip in (1.0, 0.8, 0.5):
+            oc = orc.OracleCache(1, 1, G, 64, 64)
+            gc = akvq.Cache(1, 1, G, 64, 64, fill=0)
+            oc.quantize_append(k, v, clip)
+            akvq.quantize_append(gc, _dev(k), _dev(v), clip)
+            assert_cache_equal(oc, gc, f"adversarial G={G} clip={clip}")
+            oc2 = orc.OracleCache(1, 1, G, 64, 64)
+            gc2 = akvq.Cache(1, 1, G, 64, 64, fill=0)
+            oc2.quantize_append(k, v, clip, rotate_v=False)
+            akvq.quantize_append(gc2, _dev(k), _dev(v), clip, flags=akvq.V_PREROTATED)
+            assert_cache_equal(oc2, gc2, f"adversarial prerotated G={G} clip={clip}")
+
+
+# ------------------------------------------------------------------------------------------- selection
+def test_select_tsa_exact(orc):
+    w = synth.small("tsa", B=3, Hq=4, Hkv=2, T=700, n_text_head=37, n_text_tail=41)
+    d = _np(synth.generate(w, seed=105))
+    mask = d["is_text"].copy()
+    mask[1, 100:400:7] = 1       # a batch element with scattered text
+    mask[2] = 0                  # and one without any
+    oc, gc = make_pair(orc, w, t_cap=704, s_cap=128)
+    oc.select_tsa(mask)
+    akvq.select_salient(gc, akvq.MODE_TSA, is_text=_dev(mask))
+    torch.cuda.synchronize()
+    assert np.array_equal(gc.counts().cpu().numpy(), oc.sal_cnt)
+    for b in range(3):
+        for h in range(2):
+            n = min(oc.sal_cnt[b, h], 128)
+            assert np.array_equal(gc.sal_idx[b, h, :n].cpu().numpy(), oc.sal_idx[b, h, :n])
+    # capacity: more text than slots -> count reports the truth, first S_cap positions stored
+    oc2, gc2 = make_pair(orc, w, t_cap=704, s_cap=64)
+    oc2.select_tsa(mask)
+    akvq.select_salient(gc2, akvq.MODE_TSA, is_text=_dev(mask))
+    torch.cuda.synchronize()
+    assert np.array_equal(gc2.counts().cpu().numpy(), oc2.sal_cnt) and oc2.sal_cnt.max() > 64
+    assert np.array_equal(gc2.sal_idx.cpu().numpy()[:2], oc2.sal_idx[:2])
+
+
+def check_psa(orc, w, d, top_k, seed_note=""):
+    oc, gc = make_pair(orc, w, s_cap=max(64, (top_k + 63) // 64 * 64))
+    mass_ref = oc.select_psa(d["q_tail"], d["k"], top_k, w.sm_scale, want_mass=True)
+    mass = torch.zeros(w.B, w.Hkv, w.T, dtype=torch.float32, device="cuda")
+    akvq.select_salient(gc, akvq.MODE_PSA, q_tail=_dev(d["q_tail"]), k=_dev(d["k"]), top_k=top_k,
+                        sm_scale=w.sm_scale, mass_out=mass)
+    torch.cuda.synchronize()
+    mass = mass.cpu().numpy().astype(np.float64)
+    assert np.allclose(mass.sum(-1), w.W * (w.Hq // w.Hkv), rtol=1e-4), "softmax rows must sum to one"
+    assert np.abs(mass - mass_ref).max() <= 2e-4 * max(1.0, mass_ref.max()), np.abs(mass - mass_ref).max()
+    cnt = gc.counts().cpu().numpy()
+    assert (cnt == min(top_k, w.T)).all()
+    idx = gc.sal_idx.cpu().numpy()
+    n_loose = 0
+    for b in range(w.B):
+        for h in range(w.Hkv):
+            got, ref = idx[b, h, :top_k], oc.sal_idx[b, h, :top_k]
+            assert (np.diff(got) > 0).all(), "indices must be ascending and distinct"
+            # the GPU's own masses must make its set a correct top-k (ties to the lower position)
+            gm = mass[b, h]
+            order = sorted(range(w.T), key=lambda t: (-np.float32(gm[t]), t))[:top_k]
+            assert sorted(order) == list(got), f"top-k of the GPU masses wrong at {(b, h)}"
+            if not np.array_equal(got, ref):
+                # several results can be correct when masses at the k-th boundary differ by less than the
+                # fp32-vs-fp64 noise: every disagreeing element must sit within that noise of the boundary
+                n_loose += 1
+                mr = mass_ref[b, h]
+                kth = np.sort(mr)[::-1][top_k - 1]
+                for t in set(got) ^ set(ref):
+                    assert abs(mr[t] - kth) <= 2e-4 * max(1.0, mass_ref.max()), (b, h, t, mr[t], kth)
+    return n_loose
+
+
+def test_select_psa_small(orc):
+    w = synth.small("psa", B=2, Hq=4, Hkv=2, T=300, W=16, top_k=8)
+    d = _np(synth.generate(w, seed=106))
+    check_psa(orc, w, d, 8)
+
+
+def test_select_psa_cfg1(orc):
+    w = synth.WORKLOADS["cfg1"]
+    d = _np(synth.generate(w))
+    n_loose = check_psa(orc, w, d, w.top_k)
+    assert n_loose <= 2
+    # planted pivots attract the mass (Section III-A.3): all four are in every head's set
+    oc = orc.OracleCache(w.B, w.Hkv, w.G, 640, 64)
+    oc.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale)
+    hits = [len(set(d["pivots"][0].tolist()) & set(oc.sal_idx[0, h, :w.top_k].tolist())) for h in range(w.Hkv)]
+    assert min(hits) >= 3 and np.mean(hits) > 3.8
+
+
+# ------------------------------------------------------------------------------------------- decode attention
+def run_decode_case(orc, w, d, mode, top_k, n_splits=(0,), T=None, clip=0.8, flags=0):
+    T = T or w.T
+    k, v = d["k"][:, :, :T], d["v"][:, :, :T]
+    n_sal = T if mode == "all" else max(top_k, w.n_text)
+    oc, gc = make_pair(orc, w, t_cap=(T + 63) // 64 * 64, s_cap=max(64, (n_sal + 63) // 64 * 64))
+    if mode == "tsa":
+        oc.select_tsa(d["is_text"][:, :T])
+    elif mode == "psa":
+        oc.select_psa(d["q_tail"], k, top_k, w.sm_scale)
+    elif mode == "all":
+        oc.select_tsa(np.ones((w.B, T), dtype=np.uint8))
+    copy_salient_to_gpu(oc, gc)
+    oc.quantize_append(k, v, clip)
+    akvq.quantize_append(gc, _dev(k), _dev(v), clip)
+    assert_cache_equal(oc, gc, "decode case cache")
+    out_ref, lse_ref = oc.decode(d["q"], w.sm_scale, unrotate=not (flags & akvq.OUT_ROTATED))
+    q = _dev(d["q"])
+    worst = 0.0
+    for ns in n_splits:
+        out, lse = akvq.decode_attention(gc, q, w.sm_scale, n_split=ns, flags=flags)
+        torch.cuda.synchronize()
+        worst = max(worst, assert_attention_close(out, lse, out_ref, lse_ref, f"{w.name} {mode} T={T} n_split={ns}"))
+    return worst
+
+
+@pytest.mark.parametrize("mode", ["tsa", "psa", "none", "all"])
+@pytest.mark.parametrize("G", [128, 64])
+def test_decode_mha_small(orc, mode, G):
+    w = synth.small(f"dmha{G}", B=2, Hq=3, Hkv=3, T=200, G=G, n_text_head=20, n_text_tail=9, top_k=7, W=16)
+    d = _np(synth.generate(w, seed=107))
+    run_decode_case(orc, w, d, mode, 7, n_splits=(1, 2, 3))
+
+
+@pytest.mark.parametrize("T", [1, 2, 31, 33, 64, 65, 127, 129])
+def test_decode_ragged_lengths(orc, T):
+    w = synth.small("ragged", B=1, Hq=2, Hkv=2, T=140, G=128, n_text_head=3, n_text_tail=3, W=16)
+    d = _np(synth.generate(w, seed=108))
+    run_decode_case(orc, w, d, "tsa", 4, n_splits=(1, 2), T=T)
+
+
+@pytest.mark.parametrize("Hq,Hkv,G", [(4, 2, 128), (14, 2, 64), (8, 1, 64), (3, 1, 128)])
+@pytest.mark.parametrize("mode", ["tsa", "psa"])
+def test_decode_gqa_small(orc, Hq, Hkv, G, mode):
+    w = synth.small(f"dgqa{Hq}_{Hkv}", B=2, Hq=Hq, Hkv=Hkv, T=333, G=G, n_text_head=33, n_text_tail=12, top_k=9, W=16)
+    d = _np(synth.generate(w, seed=109))
+    run_decode_case(orc, w, d, mode, 9, n_splits=(1, 4, 5))
+
+
+def test_decode_rotated_output_flag(orc):
+    w = synth.small("rotout", B=1, Hq=2, Hkv=2, T=100, W=16)
+    d = _np(synth.generate(w, seed=110))
+    run_decode_case(orc, w, d, "psa", 4, n_splits=(2,), flags=akvq.OUT_ROTATED)
+
+
+@pytest.mark.parametrize("mode,clip", [("tsa", 0.8), ("psa", 0.8), ("tsa", 1.0), ("psa", 1.0)])
+def test_cfg1_end_to_end(orc, mode, clip):
+    """Config 1: one layer, 32 heads, 640 tokens (35 text + 576 vision + 29 text), both salient modes, whole path on
+    the GPU: select -> quantize -> decode."""
+    w = synth.WORKLOADS["cfg1"]
+    d = _np(synth.generate(w))
+    oc, gc = make_pair(orc, w)
+    k, v, q, qt = _dev(d["k"]), _dev(d["v"]), _dev(d["q"]), _dev(d["q_tail"])
+    if mode == "tsa":
+        oc.select_tsa(d["is_text"])
+        akvq.select_salient(gc, akvq.MODE_TSA, is_text=_dev(d["is_text"]))
+    else:
+        oc.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale)
+        akvq.select_salient(gc, akvq.MODE_PSA, q_tail=qt, k=k, top_k=w.top_k, sm_scale=w.sm_scale)
+    torch.cuda.synchronize()
+    same = np.array_equal(gc.sal_idx.cpu().numpy()[..., :w.top_k if mode == "psa" else 64],
+                          oc.sal_idx[..., :w.top_k if mode == "psa" else 64])
+    if not same:  # a near-tie at the k-th boundary: continue from the oracle's set so that the rest stays comparable
+        copy_salient_to_gpu(oc, gc)
+    oc.quantize_append(d["k"], d["v"], clip)
+    akvq.quantize_append(gc, k, v, clip)
+    assert_cache_equal(oc, gc, f"cfg1 {mode}")
+    out_ref, lse_ref = oc.decode(d["q"], w.sm_scale)
+    for ns in (0, 1, 5):
+        out, lse = akvq.decode_attention(gc, q, w.sm_scale, n_split=ns)
+        assert_attention_close(out, lse, out_ref, lse_ref, f"cfg1 {mode} n_split={ns}")
+
+
+def test_decode_then_append_then_decode(orc):
+    """Decode-phase use: one new row per step, some of them salient (listed by the caller)."""
+    w = synth.small("steps", B=1, Hq=2, Hkv=2, T=90, W=16)
+    d = _np(synth.generate(w, seed=111))
+    oc, gc = make_pair(orc, w, t_cap=128, s_cap=64)
+    oc.select_tsa(d["is_text"])               # tail text positions 87..89 arrive during decode and are salient
+    copy_salient_to_gpu(oc, gc)
+    oc.quantize_append(d["k"][:, :, :80], d["v"][:, :, :80], 0.8)
+    akvq.quantize_append(gc, _dev(d["k"][:, :, :80]), _dev(d["v"][:, :, :80]), 0.8)
+    for t in range(80, 90):
+        oc.quantize_append(d["k"][:, :, t:t + 1], d["v"][:, :, t:t + 1], 0.8)
+        akvq.quantize_append(gc, _dev(d["k"][:, :, t:t + 1]), _dev(d["v"][:, :, t:t + 1]), 0.8)
+        out_ref, lse_ref = oc.decode(d["q"], w.sm_scale)
+        out, lse = akvq.decode_attention(gc, _dev(d["q"]), w.sm_scale, n_split=2)
+        assert_attention_close(out, lse, out_ref, lse_ref, f"step {t}")
+    assert_cache_equal(oc, gc, "after decode steps")
+
+
+# ------------------------------------------------------------------------------------------- error paths (no launch)
+def test_argument_errors():
+    L = akvq.lib()
+    gc = akvq.Cache(1, 2, 128, 64, 64)
+    q = torch.zeros(1, 2, D, dtype=torch.float16, device="cuda")
+    with pytest.raises(akvq.AkvqError, match="invalid argument"):
+        akvq.decode_attention(gc, q, 0.1)                    # T_len == 0
+    k = torch.zeros(1, 2, 65, D, dtype=torch.float16, device="cuda")
+    with pytest.raises(akvq.AkvqError, match="capacity"):
+        akvq.quantize_append(gc, k, k, 0.8)                  # 65 rows into T_cap 64
+    with pytest.raises(akvq.AkvqError, match="invalid argument"):
+        akvq.quantize_append(gc, k[:, :, :4].contiguous(), k[:, :, :4].contiguous(), 1.5)   # clip out of (0,1]
+    bad = akvq.akvq_cache(1, 2, 96, 64, 64, 0)
+    import ctypes as C
+    sizes = (C.c_size_t * 8)()
+    assert L.akvq_cache_bytes(C.byref(bad), sizes) == -2     # unsupported group size
+    qt = torch.zeros(1, 4, 24, D, dtype=torch.float16, device="cuda")
+    kk = torch.zeros(1, 2, 64, D, dtype=torch.float16, device="cuda")
+    with pytest.raises(akvq.AkvqError, match="unsupported"):
+        akvq.select_salient(gc, akvq.MODE_PSA, q_tail=qt, k=kk, top_k=4, sm_scale=0.1)      # W not a multiple of 16
+    qt = torch.zeros(1, 4, 16, D, dtype=torch.float16, device="cuda")
+    with pytest.raises(akvq.AkvqError, match="capacity"):
+        akvq.select_salient(gc, akvq.MODE_PSA, q_tail=qt, k=kk, top_k=65, sm_scale=0.1)     # top_k > S_cap
