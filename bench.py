@@ -60,6 +60,69 @@ def cpu_baseline(w, layer, data):
             "decode_kv_tokens_per_s": w.B * w.T / (t3 - t2)}, oc
 
 
+def phase_bench(args, w, akvq, synth, torch, np):
+    """Time one call of the path on its own, rotating through distinct buffer sets larger than the last-level cache."""
+    layer = 0 if not w.tsa_layers else 2          # a PSA layer when the workload has both kinds
+    if w.mode(layer) == "tsa":
+        layer = 0
+    per_set = algorithmic_bytes(w, layer)
+    n_sets = args.sets or max(2, int(np.ceil(1.2e9 / max(per_set["decode"], 1))) if args.phase == "decode" else 2)
+    t_cap = (w.T + 63) // 64 * 64
+    sets = []
+    for i in range(n_sets):
+        d = synth.generate(w, layer=layer + 100 * i, device="cuda")
+        cache = akvq.Cache(w.B, w.Hkv, w.G, t_cap, w.s_cap(layer))
+        sets.append((d, cache))
+
+    def prepare(d, cache, upto):
+        cache.T_len = 0
+        if w.mode(layer) == "tsa":
+            akvq.select_salient(cache, akvq.MODE_TSA, is_text=d["is_text"])
+        else:
+            akvq.select_salient(cache, akvq.MODE_PSA, q_tail=d["q_tail"], k=d["k"], top_k=w.top_k, sm_scale=w.sm_scale)
+        if upto == "select":
+            return
+        akvq.quantize_append(cache, d["k"], d["v"], w.clip)
+
+    def call(d, cache):
+        if args.phase == "decode":
+            akvq.decode_attention(cache, d["q"], w.sm_scale, n_split=args.n_split)
+        elif args.phase == "quantize":
+            cache.T_len = 0
+            akvq.quantize_append(cache, d["k"], d["v"], w.clip)
+        else:
+            prepare(d, cache, "select")
+
+    for d, cache in sets:
+        prepare(d, cache, "quantize" if args.phase == "decode" else "select")
+    if args.phase == "decode":      # the inputs are no longer needed: keep HBM for the caches
+        for d, _ in sets:
+            d.pop("k"); d.pop("v")
+    torch.cuda.synchronize()
+    for i in range(args.warmup * n_sets):
+        call(*sets[i % n_sets])
+    torch.cuda.synchronize()
+    n_calls = args.steps * n_sets
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(n_calls):
+        call(*sets[i % n_sets])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / n_calls
+    nbytes = per_set[args.phase]
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    out = {"metric": f"{args.phase} call alone", "workload": w.name, "layer_mode": w.mode(layer), "ms_per_call": round(ms, 5),
+           "kv_tokens_per_s": w.B * w.T / (ms * 1e-3), "n_sets": n_sets, "calls": n_calls,
+           "n_split": args.n_split or akvq.lib().akvq_decode_default_splits(w.B, w.Hkv, w.T),
+           "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                        "algorithmic_bytes_per_launch": nbytes}}
+    if args.phase == "quantize":
+        out["input_GBps"] = round(per_set["quantize_in"] / (ms * 1e-3) / 1e9, 1)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +132,9 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
+    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select"],
+                    help="time one call only (per-kernel studies; the default 'all' is the benchmark line)")
+    ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through in --phase runs")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -82,6 +148,8 @@ def main():
     akvq.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.phase != "all":
+        return phase_bench(args, w, akvq, synth, torch, np)
     L = args.layers or w.n_layers
     t_cap = (w.T + 63) // 64 * 64
 

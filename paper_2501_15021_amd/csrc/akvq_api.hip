@@ -87,10 +87,11 @@ size_t akvq_decode_workspace_bytes(int B, int Hq, int n_split) {
 
 int akvq_decode_default_splits(int B, int Hkv, int T_len) {
   if (B <= 0 || Hkv <= 0 || T_len <= 0) return 1;
-  const long units = (long)B * Hkv;
+  const long units = (long)B * Hkv;            // one workgroup of four wavefronts per (unit, split)
+  if (units >= 512) return 1;                  // already two workgroups per CU: finish in one kernel, no merge pass
   const int tiles = (T_len + 63) / 64;
-  long want = (8192 + units - 1) / units;      // enough wavefronts to fill 256 CUs several times over
-  long cap = tiles / 4 > 1 ? tiles / 4 : 1;    // but keep at least four 64-token tiles per split
+  long want = (1024 + units - 1) / units;
+  long cap = tiles / 16 > 1 ? tiles / 16 : 1;  // keep at least four 64-token tiles per wavefront
   if (want > cap) want = cap;
   if (want > 64) want = 64;
   if (want < 1) want = 1;

@@ -1,13 +1,16 @@
 // Read path of the AKVQ-VL cache: decode attention straight from the packed 2-bit + bfloat16 cache
 // (decode step of Section II-A over the cache of Section III-C, arXiv 2501.15021).
 //
-// One wavefront owns one (batch, kv-head, KV-split).  Both contractions run on the matrix cores with the
-// 2-bit codes expanded to bfloat16 integers in registers (one and-or per two codes, see akvq_device.h):
+// A workgroup of four wavefronts owns one (batch, kv-head, KV-split); the wavefronts take its 64-token (MHA) or
+// 32-token (GQA) tiles round-robin and merge their partial softmaxes through LDS.  Both contractions run on the
+// matrix cores with the 2-bit codes expanded to bfloat16 integers in registers (one and-or per two codes, see
+// akvq_device.h):
 //   scores  S = Q~ * C_K^T   : rows = the query vector split into bfloat16 terms, K-dim = 128 channels,
 //   output  O = W  * C_V     : rows = (softmax weight x scale) split into bfloat16 terms, K-dim = 32 tokens.
 // Scale, zero-point and the constants of the expansion are applied to the small side of each product
 // (per token for S, per channel-class for O), so the streamed bytes are touched once, by one and-or each.
-// The cache block layout makes each lane's 128-bit load its own matrix-core operand: no shuffles.
+// The cache block layout makes each lane's 128-bit load its own matrix-core operand: no shuffles.  The next
+// tile's loads are issued before the current tile is consumed.
 #include "akvq_device.h"
 #include "akvq_kernels.h"
 
@@ -15,8 +18,10 @@ namespace akvq {
 
 namespace {
 
+constexpr int kWaves = 4;  // wavefronts per workgroup
+
 // ------------------------------------------------------------------------------------------------
-// Rotate the query (orthonormal 128-point Walsh-Hadamard, Section III-C.2) inside one wavefront, through LDS.
+// Rotate a query (orthonormal 128-point Walsh-Hadamard, Section III-C.2) inside one wavefront, through LDS.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *qf, int lane) {
   uint32_t two = reinterpret_cast<const uint32_t *>(q_row)[lane];
@@ -43,6 +48,7 @@ __device__ __forceinline__ int k_channel_exp(int e) { return pair_exp((e & 7) >>
 __device__ __forceinline__ float pow4_neg(int k) { return k == 0 ? 1.0f : (k == 1 ? 0.25f : 0.0625f); }
 
 __device__ __forceinline__ uint32_t pack16(uint32_t lo, uint32_t hi) { return (lo & 0xFFFFu) | (hi << 16); }
+__device__ __forceinline__ uint32_t hi16(float f) { return __float_as_uint(f) >> 16; }
 
 struct Meta {
   float scale, zero;
@@ -56,54 +62,125 @@ __device__ __forceinline__ Meta unpack_meta(uint32_t w) {
   return m;
 }
 
+// two-term bfloat16 split of a non-negative weight: w ~= hi + lo (16 significant bits)
+__device__ __forceinline__ void split2(float w, float &hif, float &lof) {
+  hif = bf16_bits_to_f32(f32_to_bf16_rne(w));
+  lof = bf16_bits_to_f32(f32_to_bf16_rne(w - hif));
+}
+
+// ---- DPP reductions over the wavefront (result in every lane) ----
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float lane_bcast(float v, int l) {
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
+}
+__device__ __forceinline__ float row_max_dpp(float v) {  // max over each row of 16 lanes
+  v = fmaxf(v, dpp_f<0xB1>(v));   // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp_f<0x4E>(v));   // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp_f<0x141>(v));  // row_half_mirror
+  v = fmaxf(v, dpp_f<0x140>(v));  // row_mirror
+  return v;
+}
+__device__ __forceinline__ float row_sum_dpp(float v) {
+  v += dpp_f<0xB1>(v);
+  v += dpp_f<0x4E>(v);
+  v += dpp_f<0x141>(v);
+  v += dpp_f<0x140>(v);
+  return v;
+}
+__device__ __forceinline__ float wave_max_dpp(float v) {
+  v = row_max_dpp(v);
+  return fmaxf(fmaxf(lane_bcast(v, 0), lane_bcast(v, 16)), fmaxf(lane_bcast(v, 32), lane_bcast(v, 48)));
+}
+__device__ __forceinline__ float wave_sum_dpp(float v) {
+  v = row_sum_dpp(v);
+  return (lane_bcast(v, 0) + lane_bcast(v, 16)) + (lane_bcast(v, 32) + lane_bcast(v, 48));
+}
+
+// Final step shared by both kernels: thread d < 128 holds the merged, normalised o~[d]; rotate back through
+// LDS (every thread of the workgroup takes part in the barriers) and store.
+__device__ __forceinline__ void unrotate_store(float o, float *buf, float *out_row, bool out_rotated, int tid) {
+  if (!out_rotated) {
+    if (tid < kD) buf[tid] = o;
+    __syncthreads();
+#pragma unroll
+    for (int h = 1; h < kD; h *= 2) {
+      float mine = 0.f, other = 0.f;
+      if (tid < kD) { mine = buf[tid]; other = buf[tid ^ h]; }
+      __syncthreads();
+      if (tid < kD) buf[tid] = (tid & h) ? (other - mine) : (mine + other);
+      __syncthreads();
+    }
+    if (tid < kD) o = buf[tid] * inv_sqrt128();
+  }
+  if (tid < kD) out_row[tid] = o;
+}
+
 // ------------------------------------------------------------------------------------------------
 // MHA (one query head per KV head).  A tile is 64 tokens = two cache blocks; the query's three bfloat16 terms
 // sit in rows 4g..4g+2 of the A operand used for token group g, so after the 16 products lane l holds the
 // three partial dot products of token l: one token per lane for the softmax.
 // ------------------------------------------------------------------------------------------------
+template <int NG>
+struct MhaTile {
+  u32x4 kc[2], vc[2];
+  uint32_t km[NG], vm[NG];
+};
+
 template <int G>
-__global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   constexpr int NG = kD / G;
   __shared__ float qf[kD];
   __shared__ uint16_t q_scaled[3][kD];   // terms of q~[e] * 4^-k(e): A operand for the code stream
   __shared__ uint16_t q_plain[3][kD];    // terms of q~[e]: A operand for bfloat16 rows
-  __shared__ __attribute__((aligned(16))) uint16_t w_lds[2][NG][2][2][kTokBlock];  // [blk][group][xy][term][slot]
+  __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][2][NG][2][2][kTokBlock];
   __shared__ __attribute__((aligned(16))) uint16_t zero16[8];
+  __shared__ float mrg_m[kWaves], mrg_l[kWaves];
+  __shared__ float mrg_o[kWaves][kD];
 
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
   const int split = blockIdx.x;
   const int bh = blockIdx.y;  // Hq == Hkv here
   const int mrow = lane & 15, qd = lane >> 4;
+  auto &w_lds = w_lds_all[wave];  // [blk][group][xy][term][slot]
 
-  if (lane < 8) zero16[lane] = 0;
-  rotate_query_lds(a.q + (size_t)bh * kD, qf, lane);
-
-  // ---- query terms, bias of the expansion constant, per-group sums ----
-  float bias_part[NG], qsum_part[NG];
-#pragma unroll
-  for (int g = 0; g < NG; ++g) bias_part[g] = qsum_part[g] = 0.0f;
-#pragma unroll
-  for (int rep = 0; rep < 2; ++rep) {
-    const int e = lane + 64 * rep;
+  if (tid < 8) zero16[tid] = 0;
+  if (wave == 0) rotate_query_lds(a.q + (size_t)bh * kD, qf, lane);
+  __syncthreads();
+  if (tid < kD) {
+    const int e = tid;
     const float v = qf[e];
     uint32_t hi, mid, lo;
     split3_bf16(v, hi, mid, lo);
     q_plain[0][e] = (uint16_t)hi; q_plain[1][e] = (uint16_t)mid; q_plain[2][e] = (uint16_t)lo;
-    const float vs = v * pow4_neg(k_channel_exp(e));
-    split3_bf16(vs, hi, mid, lo);
+    split3_bf16(v * pow4_neg(k_channel_exp(e)), hi, mid, lo);
     q_scaled[0][e] = (uint16_t)hi; q_scaled[1][e] = (uint16_t)mid; q_scaled[2][e] = (uint16_t)lo;
-    const float rs = bf16_bits_to_f32(hi) + bf16_bits_to_f32(mid) + bf16_bits_to_f32(lo);
-    const int g = (NG == 2) ? rep : 0;  // e < 64 -> group 0
-    bias_part[g] += rs;
-    qsum_part[g] += v;
   }
+  __syncthreads();
+
+  // ---- bias of the expansion constant and per-group sums of the query (each wave, redundantly) ----
   float qbias[NG], qsum[NG];
+  {
+    float bias_part[NG], qsum_part[NG];
 #pragma unroll
-  for (int g = 0; g < NG; ++g) {
-    qbias[g] = kCodeBias * wave_sum(bias_part[g]);
-    qsum[g] = wave_sum(qsum_part[g]);
+    for (int g = 0; g < NG; ++g) bias_part[g] = qsum_part[g] = 0.0f;
+#pragma unroll
+    for (int rep = 0; rep < 2; ++rep) {
+      const int e = lane + 64 * rep;
+      const int g = (NG == 2) ? rep : 0;  // e < 64 -> group 0
+      bias_part[g] += bf16_bits_to_f32(q_scaled[0][e]) + bf16_bits_to_f32(q_scaled[1][e]) +
+                      bf16_bits_to_f32(q_scaled[2][e]);
+      qsum_part[g] += qf[e];
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      qbias[g] = kCodeBias * wave_sum_dpp(bias_part[g]);
+      qsum[g] = wave_sum_dpp(qsum_part[g]);
+    }
   }
-  wave_lds_sync();
 
   // ---- A operands for the code stream: [token group g][kc], row 4g+term, K-slot pair i ----
   bf16x8 a_k[4][4];
@@ -111,16 +188,14 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
   for (int g = 0; g < 4; ++g) {
     const int term = mrow - 4 * g;
     const bool live = term >= 0 && term < 3;
+    const int tc = term < 0 ? 0 : (term > 2 ? 2 : term);
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc) {
       u32x4 r;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         const int e_lo = 32 * (2 * (kc >> 1)) + 8 * qd + 4 * (kc & 1) + i;
-        const int e_hi = e_lo + 32;
-        r[i] = live ? pack16(q_scaled[term < 0 ? 0 : (term > 2 ? 2 : term)][e_lo],
-                             q_scaled[term < 0 ? 0 : (term > 2 ? 2 : term)][e_hi])
-                    : 0u;
+        r[i] = live ? pack16(q_scaled[tc][e_lo], q_scaled[tc][e_lo + 32]) : 0u;
       }
       a_k[g][kc] = __builtin_bit_cast(bf16x8, r);
     }
@@ -140,7 +215,7 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
 
   // online-softmax bookkeeping shared by the code stream and the bfloat16 rows
   auto softmax_step = [&](float score, bool ok, float &p) -> bool {
-    const float tile_max = wave_max(ok ? score : -INFINITY);
+    const float tile_max = wave_max_dpp(ok ? score : -INFINITY);
     const float m_new = fmaxf(m_run, tile_max);
     if (m_new == -INFINITY) { p = 0.0f; return false; }
     if (m_new > m_run) {
@@ -163,25 +238,30 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
   const int tile_begin = split * tiles_per_split;
   const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
   const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
-  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords;
-  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords;
-  const uint32_t *km_base = a.k_meta + (size_t)bh * a.T_cap * NG;
-  const uint32_t *vm_base = a.v_meta + (size_t)bh * a.T_cap * NG;
+  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
+  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
+  const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + lane) * NG;
+  const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + lane) * NG;
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const int t = tile * 64 + lane;
-    u32x4 kcv[2], vcv[2];
+  auto load_tile = [&](int tile, MhaTile<NG> &t) {
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
-      kcv[b2] = *reinterpret_cast<const u32x4 *>(kc_base + ((size_t)(2 * tile + b2) * kBlockWords) + lane * 4);
-      vcv[b2] = *reinterpret_cast<const u32x4 *>(vc_base + ((size_t)(2 * tile + b2) * kBlockWords) + lane * 4);
+      t.kc[b2] = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)(2 * tile + b2) * kBlockWords);
+      t.vc[b2] = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)(2 * tile + b2) * kBlockWords);
     }
-    uint32_t kmw[NG], vmw[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      kmw[g] = km_base[(size_t)t * NG + g];
-      vmw[g] = vm_base[(size_t)t * NG + g];
+      t.km[g] = km_base[(size_t)tile * 64 * NG + g];
+      t.vm[g] = vm_base[(size_t)tile * 64 * NG + g];
     }
+  };
+
+  MhaTile<NG> cur, nxt;
+  int tile = tile_begin + wave;
+  if (tile < tile_end) load_tile(tile, cur);
+  for (; tile < tile_end; tile += kWaves) {
+    if (tile + kWaves < tile_end) load_tile(tile + kWaves, nxt);
+    const int t = tile * 64 + lane;
 
     // scores: lane l ends up with the terms of token l in acc[0..2]
     f32x4 acc[NG];
@@ -192,7 +272,7 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
         const int tg = 2 * b2 + hf;
-        const uint32_t w0 = kcv[b2][2 * hf], w1 = kcv[b2][2 * hf + 1];
+        const uint32_t w0 = cur.kc[b2][2 * hf], w1 = cur.kc[b2][2 * hf + 1];
         acc[0] = mfma_bf16(a_k[tg][0], expand_x(w0), acc[0]);
         acc[0] = mfma_bf16(a_k[tg][1], expand_y(w0), acc[0]);
         acc[NG - 1] = mfma_bf16(a_k[tg][2], expand_x(w1), acc[NG - 1]);
@@ -202,7 +282,7 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
     bool salient = false;
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const Meta mk = unpack_meta(kmw[g]);
+      const Meta mk = unpack_meta(cur.km[g]);
       salient = salient || mk.salient;
       const float raw = (acc[g][0] + acc[g][1] + acc[g][2]) - qbias[g];
       score += mk.scale * (raw - mk.zero * qsum[g]);
@@ -210,53 +290,52 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
     score *= a.sm_scale;
     const bool ok = (t < a.T_len) && !salient;
     float p;
-    if (!softmax_step(score, ok, p)) continue;
-
-    // weights for the value contraction: w = p * scale_V, as two bfloat16 terms, pre-divided by the 4^k of their slot
+    if (softmax_step(score, ok, p)) {
+      // weights for the value contraction: w = p * scale_V as two bfloat16 terms, pre-divided by the 4^k of its slot
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const Meta mv = unpack_meta(vmw[g]);
-      const float wv = ok ? p * mv.scale : 0.0f;
-      const uint32_t hi = f32_to_bf16_rne(wv);
-      const float hif = bf16_bits_to_f32(hi);
-      const uint32_t lo = f32_to_bf16_rne(wv - hif);
-      const float lof = bf16_bits_to_f32(lo);
-      const float wr = hif + lof;
-      w_lds[blk_of_lane][g][0][0][slot] = (uint16_t)(__float_as_uint(hif * cx) >> 16);
-      w_lds[blk_of_lane][g][0][1][slot] = (uint16_t)(__float_as_uint(lof * cx) >> 16);
-      w_lds[blk_of_lane][g][1][0][slot] = (uint16_t)(__float_as_uint(hif * cy) >> 16);
-      w_lds[blk_of_lane][g][1][1][slot] = (uint16_t)(__float_as_uint(lof * cy) >> 16);
-      sx[g] += wr * cx;
-      sy[g] += wr * cy;
-      sz[g] += wr * mv.zero;
-    }
-    wave_lds_sync();
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-      bf16x8 a_v[NG][2];
-#pragma unroll
-      for (int g = 0; g < NG; ++g)
-#pragma unroll
-        for (int xy = 0; xy < 2; ++xy) {
-          const uint16_t *src = mrow < 2 ? &w_lds[b2][g][xy][mrow][8 * qd] : zero16;
-          a_v[g][xy] = *reinterpret_cast<const bf16x8 *>(src);
-        }
-#pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const int g = (NG == 2) ? (w & 1) : 0;
-        const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
-        acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(vcv[b2][w]), acc_o[nbx]);
-        acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(vcv[b2][w]), acc_o[nby]);
+      for (int g = 0; g < NG; ++g) {
+        const Meta mv = unpack_meta(cur.vm[g]);
+        float hif, lof;
+        split2(ok ? p * mv.scale : 0.0f, hif, lof);
+        const float wr = hif + lof;
+        w_lds[blk_of_lane][g][0][0][slot] = (uint16_t)hi16(hif * cx);
+        w_lds[blk_of_lane][g][0][1][slot] = (uint16_t)hi16(lof * cx);
+        w_lds[blk_of_lane][g][1][0][slot] = (uint16_t)hi16(hif * cy);
+        w_lds[blk_of_lane][g][1][1][slot] = (uint16_t)hi16(lof * cy);
+        sx[g] += wr * cx;
+        sy[g] += wr * cy;
+        sz[g] += wr * mv.zero;
       }
+      wave_lds_sync();
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) {
+        bf16x8 a_v[NG][2];
+#pragma unroll
+        for (int g = 0; g < NG; ++g)
+#pragma unroll
+          for (int xy = 0; xy < 2; ++xy) {
+            const uint16_t *src = mrow < 2 ? &w_lds[b2][g][xy][mrow][8 * qd] : zero16;
+            a_v[g][xy] = *reinterpret_cast<const bf16x8 *>(src);
+          }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const int g = (NG == 2) ? (w & 1) : 0;
+          const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
+          acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(cur.vc[b2][w]), acc_o[nbx]);
+          acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(cur.vc[b2][w]), acc_o[nby]);
+        }
+      }
+      wave_lds_sync();
     }
-    wave_lds_sync();
+    cur = nxt;
   }
 
-  // ================= bfloat16 (salient) rows: units of 64 overlay slots, dealt round-robin to the splits =========
+  // ================= bfloat16 (salient) rows: units of 64 overlay slots dealt to splits, then to wavefronts =========
   int cnt = a.sal_cnt[bh];
   cnt = min(max(cnt, 0), a.S_cap);
   const int n_units = (cnt + 63) / 64;
-  if (split < n_units) {
+  const int first_unit = split + wave * a.n_split;
+  if (first_unit < n_units) {
     bf16x8 a_s[4][4];
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
@@ -277,7 +356,7 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
     const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
     const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
-    for (int unit = split; unit < n_units; unit += a.n_split) {
+    for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
       const int s_lane = unit * 64 + lane;
       f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -293,11 +372,10 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
       float p;
       if (!softmax_step(score, ok, p)) continue;
       {
-        const float wv = ok ? p : 0.0f;
-        const uint32_t hi = f32_to_bf16_rne(wv);
-        const uint32_t lo = f32_to_bf16_rne(wv - bf16_bits_to_f32(hi));
-        w_lds[blk_of_lane][0][0][0][slot] = (uint16_t)hi;
-        w_lds[blk_of_lane][0][0][1][slot] = (uint16_t)lo;
+        float hif, lof;
+        split2(ok ? p : 0.0f, hif, lof);
+        w_lds[blk_of_lane][0][0][0][slot] = (uint16_t)hi16(hif);
+        w_lds[blk_of_lane][0][0][1][slot] = (uint16_t)hi16(lof);
       }
       wave_lds_sync();
 #pragma unroll
@@ -324,24 +402,47 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
     }
   }
 
-  // ================= partial result of this split =================
-  const float l_tot = wave_sum(l_run);
-  float corr_x[NG], corr_y[NG];
+  // ================= merge the four wavefronts, then either finish (one split) or store the partial =================
+  {
+    const float l_tot = wave_sum_dpp(l_run);
+    float corr_x[NG], corr_y[NG];
 #pragma unroll
-  for (int g = 0; g < NG; ++g) {
-    const float z = wave_sum(sz[g]);
-    corr_x[g] = kCodeBias * wave_sum(sx[g]) + z;
-    corr_y[g] = kCodeBias * wave_sum(sy[g]) + z;
-  }
-  float *dst = a.partial + ((size_t)bh * a.n_split + split) * kPartialStride;
-  if (lane == 0) { dst[0] = m_run; dst[1] = l_tot; }
-  if (lane < 16) {
-#pragma unroll
-    for (int nb = 0; nb < 8; ++nb) {
-      const int g = (NG == 2) ? (nb >> 2) : 0;
-      const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
-      dst[4 + 16 * nb + lane] = (acc_o[nb][0] + acc_o[nb][1]) - corr;
+    for (int g = 0; g < NG; ++g) {
+      const float z = wave_sum_dpp(sz[g]);
+      corr_x[g] = kCodeBias * wave_sum_dpp(sx[g]) + z;
+      corr_y[g] = kCodeBias * wave_sum_dpp(sy[g]) + z;
     }
+    if (lane == 0) { mrg_m[wave] = m_run; mrg_l[wave] = l_tot; }
+    if (lane < 16) {
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb) {
+        const int g = (NG == 2) ? (nb >> 2) : 0;
+        const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
+        mrg_o[wave][16 * nb + lane] = (acc_o[nb][0] + acc_o[nb][1]) - corr;
+      }
+    }
+  }
+  __syncthreads();
+  float m_all = -INFINITY, l_all = 0.0f, o = 0.0f;
+  if (tid < kD) {
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, mrg_m[w]);
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      if (mrg_m[w] == -INFINITY) continue;
+      const float wgt = __expf(mrg_m[w] - m_all);
+      l_all += wgt * mrg_l[w];
+      o += wgt * mrg_o[w][tid];
+    }
+  }
+  if (a.n_split == 1) {
+    if (tid < kD) o = o / l_all;
+    unrotate_store(o, qf, a.out + (size_t)bh * kD, a.out_rotated != 0, tid);
+    if (a.lse && tid == 0) a.lse[bh] = m_all + __logf(l_all);
+  } else if (tid < kD) {
+    float *dst = a.partial + ((size_t)bh * a.n_split + split) * kPartialStride;
+    if (tid == 0) { dst[0] = m_all; dst[1] = l_all; }
+    dst[4 + tid] = o;
   }
 }
 
@@ -350,52 +451,68 @@ __global__ __launch_bounds__(64) void decode_mha_kernel(DecodeArgs a) {
 // (32 tokens, two token groups of 16).  Rows 2h+term of the A operand carry the two bfloat16 terms of head h,
 // so lane (n, q) receives heads 2q, 2q+1 of token n, and the same lanes own those heads' output rows.
 // ------------------------------------------------------------------------------------------------
+template <int NG>
+struct GqaTile {
+  u32x4 kc, vc;
+  uint32_t km[2][NG], vm[2][NG];
+};
+
 template <int G>
-__global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   constexpr int NG = kD / G;
-  __shared__ float qf[kD];
+  __shared__ float qf[8][kD];
   __shared__ uint16_t q_scaled[16][kD];  // row 2h+term
   __shared__ uint16_t q_plain[16][kD];
-  __shared__ float qbias_lds[8][NG], qsum_lds[8][NG];
-  __shared__ __attribute__((aligned(16))) uint16_t w_lds[NG][2][16][kTokBlock];  // [group][xy][row][slot]
+  __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][NG][2][16][kTokBlock];  // [group][xy][row][slot]
+  __shared__ float mrg_m[kWaves][8], mrg_l[kWaves][8];
+  __shared__ float mrg_o[kWaves][8][kD];
 
-  const int lane = threadIdx.x;
+  const int tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
   const int split = blockIdx.x;
   const int bh = blockIdx.y;  // b * Hkv + hkv
   const int R = a.Hq / a.Hkv;
   const int b = bh / a.Hkv, hkv = bh % a.Hkv;
   const int mrow = lane & 15, qd = lane >> 4;
+  auto &w_lds = w_lds_all[wave];
 
-  for (int x = lane; x < 16 * kD; x += 64) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
+  for (int x = tid; x < 16 * kD; x += 64 * kWaves) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
   for (int x = lane; x < NG * 2 * 16 * kTokBlock; x += 64) (&w_lds[0][0][0][0])[x] = 0;
-  wave_lds_sync();
-  for (int h = 0; h < R; ++h) {
-    rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf, lane);
+  for (int h = wave; h < R; h += kWaves) rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf[h], lane);
+  __syncthreads();
+  for (int x = tid; x < R * kD; x += 64 * kWaves) {
+    const int h = x >> 7, e = x & 127;
+    const float v = qf[h][e];
+    float hif, lof;
+    split2(v, hif, lof);
+    q_plain[2 * h][e] = (uint16_t)hi16(hif); q_plain[2 * h + 1][e] = (uint16_t)hi16(lof);
+    split2(v * pow4_neg(k_channel_exp(e)), hif, lof);
+    q_scaled[2 * h][e] = (uint16_t)hi16(hif); q_scaled[2 * h + 1][e] = (uint16_t)hi16(lof);
+  }
+  __syncthreads();
+
+  // this lane scores heads h0 = 2*qd and h0+1: their bias / group sums
+  const int h0 = 2 * qd;
+  float qbias[2][NG], qsum[2][NG];
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    const int h = min(h0 + hh, 7);
     float bias_part[NG], qsum_part[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) bias_part[g] = qsum_part[g] = 0.0f;
+    // 16 lanes of the row share the work: lane mrow sums channels mrow, mrow+16, ...
 #pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
-      const int e = lane + 64 * rep;
-      const float v = qf[e];
-      uint32_t hi = f32_to_bf16_rne(v);
-      uint32_t lo = f32_to_bf16_rne(v - bf16_bits_to_f32(hi));
-      q_plain[2 * h][e] = (uint16_t)hi; q_plain[2 * h + 1][e] = (uint16_t)lo;
-      const float vs = v * pow4_neg(k_channel_exp(e));
-      hi = f32_to_bf16_rne(vs);
-      lo = f32_to_bf16_rne(vs - bf16_bits_to_f32(hi));
-      q_scaled[2 * h][e] = (uint16_t)hi; q_scaled[2 * h + 1][e] = (uint16_t)lo;
-      const int g = (NG == 2) ? rep : 0;
-      bias_part[g] += bf16_bits_to_f32(hi) + bf16_bits_to_f32(lo);
-      qsum_part[g] += v;
+    for (int c = 0; c < 8; ++c) {
+      const int e = mrow + 16 * c;
+      const int g = (NG == 2) ? (c >> 2) : 0;
+      bias_part[g] += bf16_bits_to_f32(q_scaled[2 * h][e]) + bf16_bits_to_f32(q_scaled[2 * h + 1][e]);
+      qsum_part[g] += (h < R) ? qf[h][e] : 0.0f;
     }
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const float bsum = kCodeBias * wave_sum(bias_part[g]);
-      const float qs = wave_sum(qsum_part[g]);
-      if (lane == 0) { qbias_lds[h][g] = bsum; qsum_lds[h][g] = qs; }
+      qbias[hh][g] = kCodeBias * row_sum_dpp(bias_part[g]);
+      qsum[hh][g] = row_sum_dpp(qsum_part[g]);
     }
-    wave_lds_sync();
   }
 
   bf16x8 a_k[4];
@@ -409,16 +526,6 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
     }
     a_k[kc] = __builtin_bit_cast(bf16x8, r);
   }
-  // this lane scores heads h0 = 2*qd and h0+1
-  const int h0 = 2 * qd;
-  float qbias[2][NG], qsum[2][NG];
-#pragma unroll
-  for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      qbias[hh][g] = (h0 + hh < R) ? qbias_lds[h0 + hh][g] : 0.0f;
-      qsum[hh][g] = (h0 + hh < R) ? qsum_lds[h0 + hh][g] : 0.0f;
-    }
 
   f32x4 acc_o[8];
 #pragma unroll
@@ -433,23 +540,12 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
   const int ii = mrow & 3;  // token n = mrow of its group: pair position
   const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
 
-  auto row_max16 = [](float v) {
-#pragma unroll
-    for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-    return v;
-  };
-  auto row_sum16 = [](float v) {
-#pragma unroll
-    for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-    return v;
-  };
-
   // scores sc[hh][tg] of heads h0+hh for tokens (16*tg + mrow) of the tile; ok[tg]; returns weights p[hh][tg]
   auto softmax_step = [&](const float (&sc)[2][2], const bool (&ok)[2], float (&p)[2][2]) {
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
       float mx = fmaxf(ok[0] ? sc[hh][0] : -INFINITY, ok[1] ? sc[hh][1] : -INFINITY);
-      mx = row_max16(mx);
+      mx = row_max_dpp(mx);
       const float m_new = fmaxf(m_run[hh], mx);
       if (m_new > m_run[hh]) {
         const float alpha = (m_run[hh] == -INFINITY) ? 0.0f : __expf(m_run[hh] - m_new);
@@ -474,23 +570,28 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
   const int tile_begin = split * tiles_per_split;
   const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
   const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
-  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords;
-  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords;
-  const uint32_t *km_base = a.k_meta + (size_t)bh * a.T_cap * NG;
-  const uint32_t *vm_base = a.v_meta + (size_t)bh * a.T_cap * NG;
+  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
+  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
+  const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + mrow) * NG;
+  const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + mrow) * NG;
 
-  for (int tile = tile_begin; tile < tile_end; ++tile) {
-    const u32x4 kcv = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)tile * kBlockWords + lane * 4);
-    const u32x4 vcv = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)tile * kBlockWords + lane * 4);
-    uint32_t kmw[2][NG], vmw[2][NG];
+  auto load_tile = [&](int tile, GqaTile<NG> &t) {
+    t.kc = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)tile * kBlockWords);
+    t.vc = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)tile * kBlockWords);
 #pragma unroll
     for (int tg = 0; tg < 2; ++tg)
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
-        const size_t t = (size_t)tile * 32 + 16 * tg + mrow;
-        kmw[tg][g] = km_base[t * NG + g];
-        vmw[tg][g] = vm_base[t * NG + g];
+        t.km[tg][g] = km_base[((size_t)tile * 32 + 16 * tg) * NG + g];
+        t.vm[tg][g] = vm_base[((size_t)tile * 32 + 16 * tg) * NG + g];
       }
+  };
+
+  GqaTile<NG> cur, nxt;
+  int tile = tile_begin + wave;
+  if (tile < tile_end) load_tile(tile, cur);
+  for (; tile < tile_end; tile += kWaves) {
+    if (tile + kWaves < tile_end) load_tile(tile + kWaves, nxt);
     float sc[2][2];
     bool ok[2];
 #pragma unroll
@@ -498,7 +599,7 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
       f32x4 acc[NG];
 #pragma unroll
       for (int g = 0; g < NG; ++g) acc[g] = (f32x4){0.f, 0.f, 0.f, 0.f};
-      const uint32_t w0 = kcv[2 * tg], w1 = kcv[2 * tg + 1];
+      const uint32_t w0 = cur.kc[2 * tg], w1 = cur.kc[2 * tg + 1];
       acc[0] = mfma_bf16(a_k[0], expand_x(w0), acc[0]);
       acc[0] = mfma_bf16(a_k[1], expand_y(w0), acc[0]);
       acc[NG - 1] = mfma_bf16(a_k[2], expand_x(w1), acc[NG - 1]);
@@ -507,7 +608,7 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
       float s0 = 0.f, s1 = 0.f;
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
-        const Meta mk = unpack_meta(kmw[tg][g]);
+        const Meta mk = unpack_meta(cur.km[tg][g]);
         salient = salient || mk.salient;
         s0 += mk.scale * (((acc[g][0] + acc[g][1]) - qbias[0][g]) - mk.zero * qsum[0][g]);
         s1 += mk.scale * (((acc[g][2] + acc[g][3]) - qbias[1][g]) - mk.zero * qsum[1][g]);
@@ -523,27 +624,21 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
     for (int g = 0; g < NG; ++g)
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
-        uint32_t hi[2], lo[2];
         float hif[2], lof[2];
 #pragma unroll
         for (int tg = 0; tg < 2; ++tg) {
-          const Meta mv = unpack_meta(vmw[tg][g]);
-          const float wv = ok[tg] ? p[hh][tg] * mv.scale : 0.0f;  // rows past T_len hold arbitrary meta
-          hi[tg] = f32_to_bf16_rne(wv);
-          hif[tg] = bf16_bits_to_f32(hi[tg]);
-          lo[tg] = f32_to_bf16_rne(wv - hif[tg]);
-          lof[tg] = bf16_bits_to_f32(lo[tg]);
+          const Meta mv = unpack_meta(cur.vm[tg][g]);
+          split2(ok[tg] ? p[hh][tg] * mv.scale : 0.0f, hif[tg], lof[tg]);  // rows past T_len hold arbitrary meta
           const float wr = hif[tg] + lof[tg];
           sx[hh][g] += wr * cx;
           sy[hh][g] += wr * cy;
           sz[hh][g] += wr * mv.zero;
         }
         const int row = 4 * qd + 2 * hh;
-        auto bits = [](float f) { return __float_as_uint(f) >> 16; };
-        reinterpret_cast<uint32_t *>(&w_lds[g][0][row][0])[mrow] = pack16(bits(hif[0] * cx), bits(hif[1] * cx));
-        reinterpret_cast<uint32_t *>(&w_lds[g][0][row + 1][0])[mrow] = pack16(bits(lof[0] * cx), bits(lof[1] * cx));
-        reinterpret_cast<uint32_t *>(&w_lds[g][1][row][0])[mrow] = pack16(bits(hif[0] * cy), bits(hif[1] * cy));
-        reinterpret_cast<uint32_t *>(&w_lds[g][1][row + 1][0])[mrow] = pack16(bits(lof[0] * cy), bits(lof[1] * cy));
+        reinterpret_cast<uint32_t *>(&w_lds[g][0][row][0])[mrow] = pack16(hi16(hif[0] * cx), hi16(hif[1] * cx));
+        reinterpret_cast<uint32_t *>(&w_lds[g][0][row + 1][0])[mrow] = pack16(hi16(lof[0] * cx), hi16(lof[1] * cx));
+        reinterpret_cast<uint32_t *>(&w_lds[g][1][row][0])[mrow] = pack16(hi16(hif[0] * cy), hi16(hif[1] * cy));
+        reinterpret_cast<uint32_t *>(&w_lds[g][1][row + 1][0])[mrow] = pack16(hi16(lof[0] * cy), hi16(lof[1] * cy));
       }
     wave_lds_sync();
     bf16x8 a_v[NG][2];
@@ -556,17 +651,19 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
     for (int w = 0; w < 4; ++w) {
       const int g = (NG == 2) ? (w & 1) : 0;
       const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
-      acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(vcv[w]), acc_o[nbx]);
-      acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(vcv[w]), acc_o[nby]);
+      acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(cur.vc[w]), acc_o[nbx]);
+      acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(cur.vc[w]), acc_o[nby]);
     }
     wave_lds_sync();
+    cur = nxt;
   }
 
   // ================= bfloat16 (salient) rows: units of 32 overlay slots =================
   int cnt = a.sal_cnt[bh];
   cnt = min(max(cnt, 0), a.S_cap);
   const int n_units = (cnt + 31) / 32;
-  if (split < n_units) {
+  const int first_unit = split + wave * a.n_split;
+  if (first_unit < n_units) {
     bf16x8 a_s[4];
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc) {
@@ -581,7 +678,7 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
     const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
     const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
-    for (int unit = split; unit < n_units; unit += a.n_split) {
+    for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
       float sc[2][2];
       bool ok[2];
 #pragma unroll
@@ -602,15 +699,12 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
       softmax_step(sc, ok, p);
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
-        uint32_t hi[2], lo[2];
+        float hif[2], lof[2];
 #pragma unroll
-        for (int tg = 0; tg < 2; ++tg) {
-          hi[tg] = f32_to_bf16_rne(p[hh][tg]);
-          lo[tg] = f32_to_bf16_rne(p[hh][tg] - bf16_bits_to_f32(hi[tg]));
-        }
+        for (int tg = 0; tg < 2; ++tg) split2(p[hh][tg], hif[tg], lof[tg]);
         const int row = 4 * qd + 2 * hh;
-        reinterpret_cast<uint32_t *>(&w_lds[0][0][row][0])[mrow] = pack16(hi[0], hi[1]);
-        reinterpret_cast<uint32_t *>(&w_lds[0][0][row + 1][0])[mrow] = pack16(lo[0], lo[1]);
+        reinterpret_cast<uint32_t *>(&w_lds[0][0][row][0])[mrow] = pack16(hi16(hif[0]), hi16(hif[1]));
+        reinterpret_cast<uint32_t *>(&w_lds[0][0][row + 1][0])[mrow] = pack16(hi16(lof[0]), hi16(lof[1]));
       }
       wave_lds_sync();
       const bf16x8 a_v = *reinterpret_cast<const bf16x8 *>(&w_lds[0][0][mrow][8 * qd]);
@@ -631,27 +725,50 @@ __global__ __launch_bounds__(64) void decode_gqa_kernel(DecodeArgs a) {
     }
   }
 
-  // ================= partial results =================
+  // ================= merge the four wavefronts =================
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     const int h = h0 + hh;
-    const float l_tot = row_sum16(l_run[hh]);
+    const float l_tot = row_sum_dpp(l_run[hh]);
     float corr_x[NG], corr_y[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const float z = row_sum16(sz[hh][g]);
-      corr_x[g] = kCodeBias * row_sum16(sx[hh][g]) + z;
-      corr_y[g] = kCodeBias * row_sum16(sy[hh][g]) + z;
+      const float z = row_sum_dpp(sz[hh][g]);
+      corr_x[g] = kCodeBias * row_sum_dpp(sx[hh][g]) + z;
+      corr_y[g] = kCodeBias * row_sum_dpp(sy[hh][g]) + z;
     }
-    if (h < R) {
-      float *dst = a.partial + (((size_t)b * a.Hq + hkv * R + h) * a.n_split + split) * kPartialStride;
-      if (mrow == 0) { dst[0] = m_run[hh]; dst[1] = l_tot; }
+    if (mrow == 0) { mrg_m[wave][h] = m_run[hh]; mrg_l[wave][h] = l_tot; }
 #pragma unroll
-      for (int nb = 0; nb < 8; ++nb) {
-        const int g = (NG == 2) ? (nb >> 2) : 0;
-        const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
-        dst[4 + 16 * nb + mrow] = (acc_o[nb][2 * hh] + acc_o[nb][2 * hh + 1]) - corr;
+    for (int nb = 0; nb < 8; ++nb) {
+      const int g = (NG == 2) ? (nb >> 2) : 0;
+      const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
+      mrg_o[wave][h][16 * nb + mrow] = (acc_o[nb][2 * hh] + acc_o[nb][2 * hh + 1]) - corr;
+    }
+  }
+  __syncthreads();
+  for (int h = 0; h < R; ++h) {  // uniform trip count: the barriers inside unrotate_store are reached by all threads
+    float m_all = -INFINITY, l_all = 0.0f, o = 0.0f;
+    if (tid < kD) {
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, mrg_m[w][h]);
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        if (mrg_m[w][h] == -INFINITY) continue;
+        const float wgt = __expf(mrg_m[w][h] - m_all);
+        l_all += wgt * mrg_l[w][h];
+        o += wgt * mrg_o[w][h][tid];
       }
+    }
+    const size_t bhq = (size_t)b * a.Hq + hkv * R + h;
+    if (a.n_split == 1) {
+      if (tid < kD) o = o / l_all;
+      __syncthreads();  // qf[0] is reused as the rotation buffer
+      unrotate_store(o, qf[0], a.out + bhq * kD, a.out_rotated != 0, tid);
+      if (a.lse && tid == 0) a.lse[bhq] = m_all + __logf(l_all);
+    } else if (tid < kD) {
+      float *dst = a.partial + (bhq * a.n_split + split) * kPartialStride;
+      if (tid == 0) { dst[0] = m_all; dst[1] = l_all; }
+      dst[4 + tid] = o;
     }
   }
 }
@@ -675,26 +792,14 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
     o += wgt * part[(size_t)s * kPartialStride + 4 + d];
   }
   o = o / l_all;
-  if (!a.out_rotated) {
-    of[d] = o;
-    __syncthreads();
-#pragma unroll
-    for (int h = 1; h < kD; h *= 2) {
-      const float mine = of[d], other = of[d ^ h];
-      __syncthreads();
-      of[d] = (d & h) ? (other - mine) : (mine + other);
-      __syncthreads();
-    }
-    o = of[d] * inv_sqrt128();
-  }
-  a.out[(size_t)bhq * kD + d] = o;
+  unrotate_store(o, of, a.out + (size_t)bhq * kD, a.out_rotated != 0, d);
   if (a.lse && d == 0) a.lse[bhq] = m_all + __logf(l_all);
 }
 
 }  // namespace
 
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream) {
-  dim3 grid(a.n_split, a.B * a.Hkv), block(64);
+  dim3 grid(a.n_split, a.B * a.Hkv), block(64 * kWaves);
   if (a.Hq == a.Hkv) {
     if (G == 128) hipLaunchKernelGGL(decode_mha_kernel<128>, grid, block, 0, stream, a);
     else hipLaunchKernelGGL(decode_mha_kernel<64>, grid, block, 0, stream, a);
@@ -703,7 +808,7 @@ hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t strea
     else hipLaunchKernelGGL(decode_gqa_kernel<64>, grid, block, 0, stream, a);
   }
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
+  if (e != hipSuccess || a.n_split == 1) return e;
   hipLaunchKernelGGL(decode_combine_kernel, dim3(a.B * a.Hq), dim3(128), 0, stream, a);
   return hipGetLastError();
 }
