@@ -12,6 +12,7 @@ SOURCES = ["akvq_api.hip", "akvq_quantize.hip", "akvq_decode.hip", "akvq_select.
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-mfma-vgpr-form",   # keep MFMA accumulators in VGPRs: no AGPR<->VGPR copies around VALU use
          "-Wall", "-Wno-unused-function"]
 
 

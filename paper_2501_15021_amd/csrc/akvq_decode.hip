@@ -45,6 +45,13 @@ __device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *q
 // exponent k of the 4^k factor that the expansion attaches to channel e of a K row (see the K block layout:
 // channel e sits in code pair e%8 of its word; pairs 0..3 are the X operand, 4..7 the Y operand)
 __device__ __forceinline__ int k_channel_exp(int e) { return pair_exp((e & 7) >> 2, e & 3); }
+// position of channel e inside the 128-entry A-operand image of a K row: MFMA kc = 2*(e/64) + (e%8)/4, lane group
+// qd = (e%32)/8, pair i = e%4, element 2i + (e/32)%2
+__device__ __forceinline__ int k_operand_pos(int e) {
+  const int m = e >> 5, j = (e >> 3) & 3, ie = e & 7;
+  const int kc = 2 * (m >> 1) + (ie >> 2);
+  return (4 * kc + j) * 8 + 2 * (ie & 3) + (m & 1);
+}
 __device__ __forceinline__ float pow4_neg(int k) { return k == 0 ? 1.0f : (k == 1 ? 0.25f : 0.0625f); }
 
 __device__ __forceinline__ uint32_t pack16(uint32_t lo, uint32_t hi) { return (lo & 0xFFFFu) | (hi << 16); }
@@ -133,8 +140,9 @@ template <int G>
 __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   constexpr int NG = kD / G;
   __shared__ float qf[kD];
-  __shared__ uint16_t q_scaled[3][kD];   // terms of q~[e] * 4^-k(e): A operand for the code stream
-  __shared__ uint16_t q_plain[3][kD];    // terms of q~[e]: A operand for bfloat16 rows
+  // terms of q~[e] * 4^-k(e) in A-operand order (see k_operand_pos): the code stream's A operand, 16 bytes per lane
+  __shared__ __attribute__((aligned(16))) uint16_t q_scaled[3][kD];
+  __shared__ __attribute__((aligned(16))) uint16_t q_plain[3][kD];  // terms of q~[e], natural order: bfloat16 rows
   __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][2][NG][2][2][kTokBlock];
   __shared__ __attribute__((aligned(16))) uint16_t zero16[8];
   __shared__ float mrg_m[kWaves], mrg_l[kWaves];
@@ -145,6 +153,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   const int split = blockIdx.x;
   const int bh = blockIdx.y;  // Hq == Hkv here
   const int mrow = lane & 15, qd = lane >> 4;
+  const ExpandK ex;
   auto &w_lds = w_lds_all[wave];  // [blk][group][xy][term][slot]
 
   if (tid < 8) zero16[tid] = 0;
@@ -157,7 +166,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     split3_bf16(v, hi, mid, lo);
     q_plain[0][e] = (uint16_t)hi; q_plain[1][e] = (uint16_t)mid; q_plain[2][e] = (uint16_t)lo;
     split3_bf16(v * pow4_neg(k_channel_exp(e)), hi, mid, lo);
-    q_scaled[0][e] = (uint16_t)hi; q_scaled[1][e] = (uint16_t)mid; q_scaled[2][e] = (uint16_t)lo;
+    const int p = k_operand_pos(e);
+    q_scaled[0][p] = (uint16_t)hi; q_scaled[1][p] = (uint16_t)mid; q_scaled[2][p] = (uint16_t)lo;
   }
   __syncthreads();
 
@@ -169,8 +179,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     for (int g = 0; g < NG; ++g) bias_part[g] = qsum_part[g] = 0.0f;
 #pragma unroll
     for (int rep = 0; rep < 2; ++rep) {
-      const int e = lane + 64 * rep;
-      const int g = (NG == 2) ? rep : 0;  // e < 64 -> group 0
+      const int e = lane + 64 * rep;      // operand position and channel alike: both halves split at 64
+      const int g = (NG == 2) ? rep : 0;
       bias_part[g] += bf16_bits_to_f32(q_scaled[0][e]) + bf16_bits_to_f32(q_scaled[1][e]) +
                       bf16_bits_to_f32(q_scaled[2][e]);
       qsum_part[g] += qf[e];
@@ -182,7 +192,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     }
   }
 
-  // ---- A operands for the code stream: [token group g][kc], row 4g+term, K-slot pair i ----
+  // ---- A operands for the code stream: [token group g][kc], row 4g+term ----
   bf16x8 a_k[4][4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
@@ -191,13 +201,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     const int tc = term < 0 ? 0 : (term > 2 ? 2 : term);
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc) {
-      u32x4 r;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int e_lo = 32 * (2 * (kc >> 1)) + 8 * qd + 4 * (kc & 1) + i;
-        r[i] = live ? pack16(q_scaled[tc][e_lo], q_scaled[tc][e_lo + 32]) : 0u;
-      }
-      a_k[g][kc] = __builtin_bit_cast(bf16x8, r);
+      const u32x4 r = *reinterpret_cast<const u32x4 *>(&q_scaled[tc][(4 * kc + qd) * 8]);
+      a_k[g][kc] = __builtin_bit_cast(bf16x8, live ? r : (u32x4){0u, 0u, 0u, 0u});
     }
   }
 
@@ -273,10 +278,10 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
       for (int hf = 0; hf < 2; ++hf) {
         const int tg = 2 * b2 + hf;
         const uint32_t w0 = cur.kc[b2][2 * hf], w1 = cur.kc[b2][2 * hf + 1];
-        acc[0] = mfma_bf16(a_k[tg][0], expand_x(w0), acc[0]);
-        acc[0] = mfma_bf16(a_k[tg][1], expand_y(w0), acc[0]);
-        acc[NG - 1] = mfma_bf16(a_k[tg][2], expand_x(w1), acc[NG - 1]);
-        acc[NG - 1] = mfma_bf16(a_k[tg][3], expand_y(w1), acc[NG - 1]);
+        acc[0] = mfma_bf16(a_k[tg][0], ex.x(w0), acc[0]);
+        acc[0] = mfma_bf16(a_k[tg][1], ex.y(w0), acc[0]);
+        acc[NG - 1] = mfma_bf16(a_k[tg][2], ex.x(w1), acc[NG - 1]);
+        acc[NG - 1] = mfma_bf16(a_k[tg][3], ex.y(w1), acc[NG - 1]);
       }
     float score = 0.0f;
     bool salient = false;
@@ -321,8 +326,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
         for (int w = 0; w < 4; ++w) {
           const int g = (NG == 2) ? (w & 1) : 0;
           const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
-          acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(cur.vc[b2][w]), acc_o[nbx]);
-          acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(cur.vc[b2][w]), acc_o[nby]);
+          acc_o[nbx] = mfma_bf16(a_v[g][0], ex.x(cur.vc[b2][w]), acc_o[nbx]);
+          acc_o[nby] = mfma_bf16(a_v[g][1], ex.y(cur.vc[b2][w]), acc_o[nby]);
         }
       }
       wave_lds_sync();
@@ -344,13 +349,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
       const int tc = term < 0 ? 0 : (term > 2 ? 2 : term);
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) {
-        u32x4 r;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int e = 32 * kc + 8 * qd + 2 * i;
-          r[i] = live ? pack16(q_plain[tc][e], q_plain[tc][e + 1]) : 0u;
-        }
-        a_s[g][kc] = __builtin_bit_cast(bf16x8, r);
+        const u32x4 r = *reinterpret_cast<const u32x4 *>(&q_plain[tc][32 * kc + 8 * qd]);
+        a_s[g][kc] = __builtin_bit_cast(bf16x8, live ? r : (u32x4){0u, 0u, 0u, 0u});
       }
     }
     const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
@@ -461,8 +461,8 @@ template <int G>
 __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   constexpr int NG = kD / G;
   __shared__ float qf[8][kD];
-  __shared__ uint16_t q_scaled[16][kD];  // row 2h+term
-  __shared__ uint16_t q_plain[16][kD];
+  __shared__ __attribute__((aligned(16))) uint16_t q_scaled[16][kD];  // row 2h+term, A-operand order
+  __shared__ __attribute__((aligned(16))) uint16_t q_plain[16][kD];   // row 2h+term, natural order
   __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][NG][2][16][kTokBlock];  // [group][xy][row][slot]
   __shared__ float mrg_m[kWaves][8], mrg_l[kWaves][8];
   __shared__ float mrg_o[kWaves][8][kD];
@@ -474,6 +474,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   const int R = a.Hq / a.Hkv;
   const int b = bh / a.Hkv, hkv = bh % a.Hkv;
   const int mrow = lane & 15, qd = lane >> 4;
+  const ExpandK ex;
   auto &w_lds = w_lds_all[wave];
 
   for (int x = tid; x < 16 * kD; x += 64 * kWaves) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
@@ -487,7 +488,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     split2(v, hif, lof);
     q_plain[2 * h][e] = (uint16_t)hi16(hif); q_plain[2 * h + 1][e] = (uint16_t)hi16(lof);
     split2(v * pow4_neg(k_channel_exp(e)), hif, lof);
-    q_scaled[2 * h][e] = (uint16_t)hi16(hif); q_scaled[2 * h + 1][e] = (uint16_t)hi16(lof);
+    const int p = k_operand_pos(e);
+    q_scaled[2 * h][p] = (uint16_t)hi16(hif); q_scaled[2 * h + 1][p] = (uint16_t)hi16(lof);
   }
   __syncthreads();
 
@@ -517,15 +519,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 
   bf16x8 a_k[4];
 #pragma unroll
-  for (int kc = 0; kc < 4; ++kc) {
-    u32x4 r;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int e_lo = 32 * (2 * (kc >> 1)) + 8 * qd + 4 * (kc & 1) + i;
-      r[i] = pack16(q_scaled[mrow][e_lo], q_scaled[mrow][e_lo + 32]);
-    }
-    a_k[kc] = __builtin_bit_cast(bf16x8, r);
-  }
+  for (int kc = 0; kc < 4; ++kc)
+    a_k[kc] = *reinterpret_cast<const bf16x8 *>(&q_scaled[mrow][(4 * kc + qd) * 8]);
 
   f32x4 acc_o[8];
 #pragma unroll
@@ -600,10 +595,10 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
       for (int g = 0; g < NG; ++g) acc[g] = (f32x4){0.f, 0.f, 0.f, 0.f};
       const uint32_t w0 = cur.kc[2 * tg], w1 = cur.kc[2 * tg + 1];
-      acc[0] = mfma_bf16(a_k[0], expand_x(w0), acc[0]);
-      acc[0] = mfma_bf16(a_k[1], expand_y(w0), acc[0]);
-      acc[NG - 1] = mfma_bf16(a_k[2], expand_x(w1), acc[NG - 1]);
-      acc[NG - 1] = mfma_bf16(a_k[3], expand_y(w1), acc[NG - 1]);
+      acc[0] = mfma_bf16(a_k[0], ex.x(w0), acc[0]);
+      acc[0] = mfma_bf16(a_k[1], ex.y(w0), acc[0]);
+      acc[NG - 1] = mfma_bf16(a_k[2], ex.x(w1), acc[NG - 1]);
+      acc[NG - 1] = mfma_bf16(a_k[3], ex.y(w1), acc[NG - 1]);
       bool salient = false;
       float s0 = 0.f, s1 = 0.f;
 #pragma unroll
@@ -651,8 +646,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     for (int w = 0; w < 4; ++w) {
       const int g = (NG == 2) ? (w & 1) : 0;
       const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
-      acc_o[nbx] = mfma_bf16(a_v[g][0], expand_x(cur.vc[w]), acc_o[nbx]);
-      acc_o[nby] = mfma_bf16(a_v[g][1], expand_y(cur.vc[w]), acc_o[nby]);
+      acc_o[nbx] = mfma_bf16(a_v[g][0], ex.x(cur.vc[w]), acc_o[nbx]);
+      acc_o[nby] = mfma_bf16(a_v[g][1], ex.y(cur.vc[w]), acc_o[nby]);
     }
     wave_lds_sync();
     cur = nxt;
@@ -666,15 +661,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   if (first_unit < n_units) {
     bf16x8 a_s[4];
 #pragma unroll
-    for (int kc = 0; kc < 4; ++kc) {
-      u32x4 r;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int e = 32 * kc + 8 * qd + 2 * i;
-        r[i] = pack16(q_plain[mrow][e], q_plain[mrow][e + 1]);
-      }
-      a_s[kc] = __builtin_bit_cast(bf16x8, r);
-    }
+    for (int kc = 0; kc < 4; ++kc)
+      a_s[kc] = *reinterpret_cast<const bf16x8 *>(&q_plain[mrow][32 * kc + 8 * qd]);
     const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
     const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;

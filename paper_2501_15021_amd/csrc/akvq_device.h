@@ -70,19 +70,28 @@ __device__ __forceinline__ void wave_lds_sync() {
 // position inside the 7-bit mantissa: 0, 1 or 2).  The constant 128 and the factor 4^k are undone on the
 // other operand of the contraction, so expansion costs one and-or per two codes (plus two shifts per word).
 // Pairs 0..3 form the "X" operand (factors 4^{0,1,2,0}), pairs 4..7 the "Y" operand (4^{1,2,0,1}).
-__device__ __forceinline__ uint32_t expand_pair(uint32_t w, int k) {
-  return (w & (0x00030003u << (2 * k))) | 0x43004300u;
-}
-__device__ __forceinline__ bf16x8 expand_x(uint32_t w) {
-  uint32_t w6 = w >> 6;
-  u32x4 r = {expand_pair(w, 0), expand_pair(w, 1), expand_pair(w, 2), expand_pair(w6, 0)};
-  return __builtin_bit_cast(bf16x8, r);
-}
-__device__ __forceinline__ bf16x8 expand_y(uint32_t w) {
-  uint32_t w6 = w >> 6, w12 = w >> 12;
-  u32x4 r = {expand_pair(w6, 1), expand_pair(w6, 2), expand_pair(w12, 0), expand_pair(w12, 1)};
-  return __builtin_bit_cast(bf16x8, r);
-}
+// The masks and the constant are kept as opaque register values (not literals) so that the compiler selects the
+// three-operand and-or instruction, whose encoding takes no literal operands: D = (w & mask) | magic in one op.
+struct ExpandK {
+  uint32_t magic;    // 0x4300'4300, vector register
+  uint32_t mask[3];  // 0x0003'0003 << {0,2,4}, scalar registers
+  __device__ __forceinline__ ExpandK() {
+    uint32_t m = 0x43004300u, m0 = 0x00030003u, m1 = 0x000C000Cu, m2 = 0x00300030u;
+    asm volatile("" : "+v"(m), "+s"(m0), "+s"(m1), "+s"(m2));
+    magic = m; mask[0] = m0; mask[1] = m1; mask[2] = m2;
+  }
+  __device__ __forceinline__ uint32_t pair(uint32_t w, int k) const { return (w & mask[k]) | magic; }
+  __device__ __forceinline__ bf16x8 x(uint32_t w) const {
+    const uint32_t w6 = w >> 6;
+    u32x4 r = {pair(w, 0), pair(w, 1), pair(w, 2), pair(w6, 0)};
+    return __builtin_bit_cast(bf16x8, r);
+  }
+  __device__ __forceinline__ bf16x8 y(uint32_t w) const {
+    const uint32_t w6 = w >> 6, w12 = w >> 12;
+    u32x4 r = {pair(w6, 1), pair(w6, 2), pair(w12, 0), pair(w12, 1)};
+    return __builtin_bit_cast(bf16x8, r);
+  }
+};
 // exponent k (factor 4^k) carried by pair i of the X / Y operand
 __device__ __forceinline__ int pair_exp(int xy, int i) {
   // X: {0,1,2,0}   Y: {1,2,0,1}
