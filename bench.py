@@ -132,7 +132,7 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
-    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select"],
+    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "copy"],
                     help="time one call only (per-kernel studies; the default 'all' is the benchmark line)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through in --phase runs")
     args = ap.parse_args()
@@ -148,6 +148,23 @@ def main():
     akvq.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.phase == "copy":
+        # a plain device-to-device copy of known size: calibrates the HBM byte counters of rocprofv3 --pmc
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        dst.copy_(src)
+        e0.record()
+        for _ in range(args.steps):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / args.steps
+        print(json.dumps({"metric": "plain copy", "bytes_read": n, "bytes_written": n, "ms_per_call": round(ms, 4),
+                          "GBps_read_plus_write": round(2 * n / (ms * 1e-3) / 1e9, 1)}))
+        return
     if args.phase != "all":
         return phase_bench(args, w, akvq, synth, torch, np)
     L = args.layers or w.n_layers
