@@ -49,12 +49,17 @@ __global__ __launch_bounds__(256) void select_tsa_kernel(SelectArgs a) {
 }
 
 // ---- pivot scoring ---------------------------------------------------------------------------------------
+// Each workgroup (4 wavefronts) owns kScoreChunk consecutive keys of one (batch, head); a wavefront walks its quarter
+// in groups of 16 keys, with the next group's loads in flight while the current one goes through the matrix cores.
+// Logits are kept in the base-2 domain (sm_scale * log2(e) folded into one multiply) so that exponentials are bare
+// v_exp_f32; both passes use the same domain, so the statistics carry over unchanged.
+constexpr int kGroupsPerWave = kScoreChunk / (4 * 16);
+
 // binary16 pair (packed) -> bfloat16 pair (packed), each rounded to nearest even
 __device__ __forceinline__ uint32_t half2_to_bf16x2(uint32_t hh) {
-  return f32_to_bf16_rne(half_bits_to_float(hh & 0xFFFFu)) | (f32_to_bf16_rne(half_bits_to_float(hh >> 16)) << 16);
+  return pack_bf16x2(half_bits_to_float(hh & 0xFFFFu), half_bits_to_float(hh >> 16));
 }
-__device__ __forceinline__ bf16x8 load_row8_as_bf16(const uint16_t *p) {
-  u32x4 raw = *reinterpret_cast<const u32x4 *>(p);
+__device__ __forceinline__ bf16x8 rows8_as_bf16(u32x4 raw) {
   u32x4 r = {half2_to_bf16x2(raw[0]), half2_to_bf16x2(raw[1]), half2_to_bf16x2(raw[2]), half2_to_bf16x2(raw[3])};
   return __builtin_bit_cast(bf16x8, r);
 }
@@ -69,18 +74,27 @@ __device__ __forceinline__ float row_sum16(float v) {
   return v;
 }
 
-// logits of the W tail rows of one query head against 16 keys: s[rb][i] = row 16*rb + 4*qd + i, key column = mrow.
+struct KeyGroup {
+  u32x4 raw[4];  // 16 keys x 128 channels as this lane's four 8-channel pieces (binary16)
+};
+__device__ __forceinline__ void load_key_group(const uint16_t *k_rows, int t_first, int T, int mrow, int qd, KeyGroup &g) {
+  const int t = t_first + mrow;
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) {
+    if (t < T) g.raw[kc] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
+    else g.raw[kc] = (u32x4){0u, 0u, 0u, 0u};
+  }
+}
+
+// base-2 logits of the W tail rows of one query head against 16 keys: s[rb][i] = row 16*rb + 4*qd + i, key = mrow.
 // Entries the causal mask removes (or keys beyond T) come back as -inf.
 template <int NRB>
-__device__ __forceinline__ void score_16keys(const bf16x8 (&a_q)[4][4], const uint16_t *k_rows, int t_first, int T, int W,
-                                             float sm_scale, int mrow, int qd, float (&s)[4][4]) {
+__device__ __forceinline__ void score_16keys(const bf16x8 (&a_q)[4][4], const KeyGroup &g, int t_first, int T, int W,
+                                             float scale2, int mrow, int qd, float (&s)[4][4]) {
   const int t = t_first + mrow;
   bf16x8 kb[4];
 #pragma unroll
-  for (int kc = 0; kc < 4; ++kc) {
-    if (t < T) kb[kc] = load_row8_as_bf16(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
-    else kb[kc] = __builtin_bit_cast(bf16x8, (u32x4){0u, 0u, 0u, 0u});
-  }
+  for (int kc = 0; kc < 4; ++kc) kb[kc] = rows8_as_bf16(g.raw[kc]);
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
     f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -90,7 +104,7 @@ __device__ __forceinline__ void score_16keys(const bf16x8 (&a_q)[4][4], const ui
     for (int i = 0; i < 4; ++i) {
       const int row = 16 * rb + 4 * qd + i;
       const bool seen = t < T && t <= T - W + row;  // causal: row sits at position T-W+row
-      s[rb][i] = seen ? sm_scale * acc[i] : -INFINITY;
+      s[rb][i] = seen ? scale2 * acc[i] : -INFINITY;
     }
   }
 }
@@ -101,10 +115,14 @@ __device__ __forceinline__ void load_query_rows(const uint16_t *q_head, int mrow
   for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
-      a_q[rb][kc] = load_row8_as_bf16(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd);
+      a_q[rb][kc] = rows8_as_bf16(
+          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd));
 }
 
-// pass 1: per (b, hq, chunk of 256 keys): running max and sum of exponentials of every tail row
+constexpr float kLog2e = 1.4426950408889634f;
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // bare v_exp_f32
+
+// pass 1: per (b, hq, chunk): running max and sum of exponentials (base 2) of every tail row
 template <int NRB>
 __global__ __launch_bounds__(256) void psa_row_stats_kernel(SelectArgs a) {
   __shared__ float st_m[4][64], st_l[4][64];
@@ -112,44 +130,60 @@ __global__ __launch_bounds__(256) void psa_row_stats_kernel(SelectArgs a) {
   const int b = bhq / a.Hq, hq = bhq % a.Hq, hkv = hq / (a.Hq / a.Hkv);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
   const uint16_t *k_rows = a.k + ((size_t)b * a.Hkv + hkv) * a.T * kD;
+  const float scale2 = a.sm_scale * kLog2e;
   bf16x8 a_q[4][4];
   load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, a_q);
-  float s[4][4][4];
-  const int t_wave = chunk * kScoreChunk + wave * 64;
+  float m[4][4], l[4][4];
 #pragma unroll
-  for (int tg = 0; tg < 4; ++tg)
-    score_16keys<NRB>(a_q, k_rows, t_wave + 16 * tg, a.T, a.W, a.sm_scale, mrow, qd, s[tg]);
+  for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { m[rb][i] = -INFINITY; l[rb][i] = 0.0f; }
+  const int t_wave = chunk * kScoreChunk + wave * (kScoreChunk / 4);
+  KeyGroup cur, nxt;
+  load_key_group(k_rows, t_wave, a.T, mrow, qd, cur);
+  for (int g = 0; g < kGroupsPerWave; ++g) {
+    const int t_first = t_wave + 16 * g;
+    if (t_first >= a.T) break;
+    if (g + 1 < kGroupsPerWave) load_key_group(k_rows, t_first + 16, a.T, mrow, qd, nxt);
+    float s[4][4];
+    score_16keys<NRB>(a_q, cur, t_first, a.T, a.W, scale2, mrow, qd, s);
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float m_new = fmaxf(m[rb][i], s[rb][i]);
+        const float m_ref = (m_new == -INFINITY) ? 0.0f : m_new;
+        l[rb][i] = l[rb][i] * fast_exp2(m[rb][i] - m_ref) + fast_exp2(s[rb][i] - m_ref);
+        m[rb][i] = m_new;
+      }
+    cur = nxt;
+  }
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      float m = fmaxf(fmaxf(s[0][rb][i], s[1][rb][i]), fmaxf(s[2][rb][i], s[3][rb][i]));
-      m = row_max16(m);
-      float l = 0.0f;
-      if (m != -INFINITY) {
-#pragma unroll
-        for (int tg = 0; tg < 4; ++tg) l += __expf(s[tg][rb][i] - m);
-      }
-      l = row_sum16(l);
-      if (mrow == 0) { st_m[wave][16 * rb + 4 * qd + i] = m; st_l[wave][16 * rb + 4 * qd + i] = l; }
+      const float mr = row_max16(m[rb][i]);
+      const float m_ref = (mr == -INFINITY) ? 0.0f : mr;
+      const float lr = row_sum16(l[rb][i] * fast_exp2(m[rb][i] - m_ref));
+      if (mrow == 0) { st_m[wave][16 * rb + 4 * qd + i] = mr; st_l[wave][16 * rb + 4 * qd + i] = lr; }
     }
   __syncthreads();
   if (threadIdx.x < a.W) {
     const int row = threadIdx.x;
-    float m = -INFINITY;
+    float mm = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) m = fmaxf(m, st_m[w][row]);
-    float l = 0.0f;
+    for (int w = 0; w < 4; ++w) mm = fmaxf(mm, st_m[w][row]);
+    float ll = 0.0f;
 #pragma unroll
     for (int w = 0; w < 4; ++w)
-      if (st_m[w][row] != -INFINITY) l += st_l[w][row] * __expf(st_m[w][row] - m);
+      if (st_m[w][row] != -INFINITY) ll += st_l[w][row] * fast_exp2(st_m[w][row] - mm);
     float *dst = a.row_stats + (((size_t)bhq * a.n_chunk + chunk) * a.W + row) * 2;
-    dst[0] = m;
-    dst[1] = l;
+    dst[0] = mm;
+    dst[1] = ll;
   }
 }
 
-// pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads and the tail rows of exp(s - m_row) / l_row
+// pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads and the tail rows of 2^(s - m_row) / l_row
 template <int NRB>
 __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
   __shared__ float row_m[64], row_il[64];
@@ -157,46 +191,58 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
   const int b = bh / a.Hkv, hkv = bh % a.Hkv, R = a.Hq / a.Hkv;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
   const uint16_t *k_rows = a.k + (size_t)bh * a.T * kD;
-  const int t_wave = chunk * kScoreChunk + wave * 64;
-  float col[4] = {0.f, 0.f, 0.f, 0.f};
+  const float scale2 = a.sm_scale * kLog2e;
+  const int t_wave = chunk * kScoreChunk + wave * (kScoreChunk / 4);
+  float col[kGroupsPerWave];
+#pragma unroll
+  for (int g = 0; g < kGroupsPerWave; ++g) col[g] = 0.0f;
   for (int h = 0; h < R; ++h) {
     const int bhq = b * a.Hq + hkv * R + h;
     __syncthreads();
     if (threadIdx.x < a.W) {  // merge the chunk statistics of this row
       const int row = threadIdx.x;
       const float *src = a.row_stats + ((size_t)bhq * a.n_chunk * a.W + row) * 2;
-      float m = -INFINITY;
-      for (int c = 0; c < a.n_chunk; ++c) m = fmaxf(m, src[(size_t)c * a.W * 2]);
-      float l = 0.0f;
+      float mm = -INFINITY;
+      for (int c = 0; c < a.n_chunk; ++c) mm = fmaxf(mm, src[(size_t)c * a.W * 2]);
+      float ll = 0.0f;
       for (int c = 0; c < a.n_chunk; ++c) {
         const float mc = src[(size_t)c * a.W * 2];
-        if (mc != -INFINITY) l += src[(size_t)c * a.W * 2 + 1] * __expf(mc - m);
+        if (mc != -INFINITY) ll += src[(size_t)c * a.W * 2 + 1] * fast_exp2(mc - mm);
       }
-      row_m[row] = m;
-      row_il[row] = 1.0f / l;
+      row_m[row] = mm;
+      row_il[row] = 1.0f / ll;
     }
     __syncthreads();
     bf16x8 a_q[4][4];
     load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, a_q);
+    float rm[4][4], ril[4][4];
 #pragma unroll
-    for (int tg = 0; tg < 4; ++tg) {
-      float s[4][4];
-      score_16keys<NRB>(a_q, k_rows, t_wave + 16 * tg, a.T, a.W, a.sm_scale, mrow, qd, s);
+    for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
+      for (int i = 0; i < 4; ++i) { rm[rb][i] = row_m[16 * rb + 4 * qd + i]; ril[rb][i] = row_il[16 * rb + 4 * qd + i]; }
+    KeyGroup cur, nxt;
+    load_key_group(k_rows, t_wave, a.T, mrow, qd, cur);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = 16 * rb + 4 * qd + i;
-          if (s[rb][i] != -INFINITY) col[tg] += __expf(s[rb][i] - row_m[row]) * row_il[row];
-        }
+    for (int g = 0; g < kGroupsPerWave; ++g) {
+      const int t_first = t_wave + 16 * g;
+      if (t_first < a.T) {  // uniform over the wavefront
+        if (g + 1 < kGroupsPerWave) load_key_group(k_rows, t_first + 16, a.T, mrow, qd, nxt);
+        float s[4][4];
+        score_16keys<NRB>(a_q, cur, t_first, a.T, a.W, scale2, mrow, qd, s);
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) col[g] += fast_exp2(s[rb][i] - rm[rb][i]) * ril[rb][i];  // 2^-inf = 0 for masked
+        cur = nxt;
+      }
     }
   }
 #pragma unroll
-  for (int tg = 0; tg < 4; ++tg) {
-    float c = col[tg];
+  for (int g = 0; g < kGroupsPerWave; ++g) {
+    float c = col[g];
     c += __shfl_xor(c, 16, kWave);
     c += __shfl_xor(c, 32, kWave);
-    const int t = t_wave + 16 * tg + mrow;
+    const int t = t_wave + 16 * g + mrow;
     if (qd == 0 && t < a.T) a.mass[(size_t)bh * a.T + t] = c;
   }
 }
