@@ -69,16 +69,21 @@ __device__ __forceinline__ Meta unpack_meta(uint32_t w) {
   return m;
 }
 
-// two-term bfloat16 split of a non-negative weight: w ~= hi + lo (16 significant bits)
+// two-term bfloat16 split, w ~= hi + lo (16 significant bits): hi is w truncated to its upper 16 bits (so storing
+// the upper half of the register stores hi), lo is the exactly representable remainder rounded to bfloat16
 __device__ __forceinline__ void split2(float w, float &hif, float &lof) {
-  hif = bf16_bits_to_f32(f32_to_bf16_rne(w));
-  lof = bf16_bits_to_f32(f32_to_bf16_rne(w - hif));
+  hif = __uint_as_float(__float_as_uint(w) & 0xFFFF0000u);
+  lof = __uint_as_float(pack_bf16x2(w - hif, 0.0f) << 16);
 }
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kLazyMax = 12.0f;  // the softmax reference is raised only when a score exceeds it by 2^12
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // bare v_exp_f32
 
 // ---- DPP reductions over the wavefront (result in every lane) ----
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
 }
 __device__ __forceinline__ float lane_bcast(float v, int l) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), l));
@@ -209,30 +214,34 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   f32x4 acc_o[8];
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) acc_o[nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m_run = -INFINITY, l_run = 0.0f;
-  float sx[NG], sy[NG], sz[NG];
+  float m_run = -INFINITY, l_run = 0.0f;  // softmax reference (base-2 domain) and this lane's share of the sum
+  float swx[NG], szx[NG];                // running sums of w*cx and w*cx*zero over this lane's tokens
 #pragma unroll
-  for (int g = 0; g < NG; ++g) sx[g] = sy[g] = sz[g] = 0.0f;
+  for (int g = 0; g < NG; ++g) swx[g] = szx[g] = 0.0f;
+  const float sm2 = a.sm_scale * kLog2e;
 
   const int r16 = lane & 15, half = (lane >> 4) & 1, blk_of_lane = lane >> 5;
   const int slot = 2 * r16 + half, ii = r16 & 3;
   const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
+  const float ryx = cy / cx, rcx = 1.0f / cx;  // exact powers of two
 
-  // online-softmax bookkeeping shared by the code stream and the bfloat16 rows
+  // online-softmax bookkeeping shared by the code stream and the bfloat16 rows.  The reference m_run is only
+  // raised when some score exceeds it by more than kLazyMax, so the common tile costs one compare and one branch;
+  // weights are then at most 2^kLazyMax, which fp32 sums and the bfloat16 term split absorb.
   auto softmax_step = [&](float score, bool ok, float &p) -> bool {
-    const float tile_max = wave_max_dpp(ok ? score : -INFINITY);
-    const float m_new = fmaxf(m_run, tile_max);
-    if (m_new == -INFINITY) { p = 0.0f; return false; }
-    if (m_new > m_run) {
-      const float alpha = (m_run == -INFINITY) ? 0.0f : __expf(m_run - m_new);
+    const float sc = ok ? score : -INFINITY;
+    if (__ballot(sc > m_run + kLazyMax) != 0ull) {
+      const float m_new = wave_max_dpp(sc);
+      const float alpha = (m_run == -INFINITY) ? 0.0f : fast_exp2(m_run - m_new);
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb) acc_o[nb] *= alpha;
       l_run *= alpha;
 #pragma unroll
-      for (int g = 0; g < NG; ++g) { sx[g] *= alpha; sy[g] *= alpha; sz[g] *= alpha; }
+      for (int g = 0; g < NG; ++g) { swx[g] *= alpha; szx[g] *= alpha; }
       m_run = m_new;
     }
-    p = ok ? __expf(score - m_new) : 0.0f;
+    if (m_run == -INFINITY) { p = 0.0f; return false; }
+    p = fast_exp2(sc - m_run);
     l_run += p;
     return true;
   };
@@ -292,7 +301,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
       const float raw = (acc[g][0] + acc[g][1] + acc[g][2]) - qbias[g];
       score += mk.scale * (raw - mk.zero * qsum[g]);
     }
-    score *= a.sm_scale;
+    score *= sm2;
     const bool ok = (t < a.T_len) && !salient;
     float p;
     if (softmax_step(score, ok, p)) {
@@ -300,16 +309,16 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
         const Meta mv = unpack_meta(cur.vm[g]);
-        float hif, lof;
-        split2(ok ? p * mv.scale : 0.0f, hif, lof);
-        const float wr = hif + lof;
-        w_lds[blk_of_lane][g][0][0][slot] = (uint16_t)hi16(hif * cx);
-        w_lds[blk_of_lane][g][0][1][slot] = (uint16_t)hi16(lof * cx);
-        w_lds[blk_of_lane][g][1][0][slot] = (uint16_t)hi16(hif * cy);
-        w_lds[blk_of_lane][g][1][1][slot] = (uint16_t)hi16(lof * cy);
-        sx[g] += wr * cx;
-        sy[g] += wr * cy;
-        sz[g] += wr * mv.zero;
+        float hix, lox;
+        split2(ok ? p * (mv.scale * cx) : 0.0f, hix, lox);  // rows past T_len hold arbitrary meta
+        const float hiy = hix * ryx, loy = lox * ryx;           // exact
+        w_lds[blk_of_lane][g][0][0][slot] = (uint16_t)hi16(hix);
+        w_lds[blk_of_lane][g][0][1][slot] = (uint16_t)hi16(lox);
+        w_lds[blk_of_lane][g][1][0][slot] = (uint16_t)hi16(hiy);
+        w_lds[blk_of_lane][g][1][1][slot] = (uint16_t)hi16(loy);
+        const float wxr = hix + lox;
+        swx[g] += wxr;
+        szx[g] += wxr * mv.zero;
       }
       wave_lds_sync();
 #pragma unroll
@@ -367,7 +376,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
               ks_base + (size_t)(unit * 64 + 16 * g + mrow) * kD + 32 * kc + 8 * qd);
           acc = mfma_bf16(a_s[g][kc], kb, acc);
         }
-      const float score = a.sm_scale * (acc[0] + acc[1] + acc[2]);
+      const float score = sm2 * (acc[0] + acc[1] + acc[2]);
       const bool ok = (s_lane < cnt) && (sidx[min(s_lane, a.S_cap - 1)] < a.T_len);
       float p;
       if (!softmax_step(score, ok, p)) continue;
@@ -408,9 +417,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     float corr_x[NG], corr_y[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const float z = wave_sum_dpp(sz[g]);
-      corr_x[g] = kCodeBias * wave_sum_dpp(sx[g]) + z;
-      corr_y[g] = kCodeBias * wave_sum_dpp(sy[g]) + z;
+      const float z = wave_sum_dpp(szx[g] * rcx);
+      corr_x[g] = kCodeBias * wave_sum_dpp(swx[g]) + z;
+      corr_y[g] = kCodeBias * wave_sum_dpp(swx[g] * ryx) + z;
     }
     if (lane == 0) { mrg_m[wave] = m_run; mrg_l[wave] = l_tot; }
     if (lane < 16) {
@@ -430,7 +439,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
 #pragma unroll
     for (int w = 0; w < kWaves; ++w) {
       if (mrg_m[w] == -INFINITY) continue;
-      const float wgt = __expf(mrg_m[w] - m_all);
+      const float wgt = fast_exp2(mrg_m[w] - m_all);
       l_all += wgt * mrg_l[w];
       o += wgt * mrg_o[w][tid];
     }
@@ -438,7 +447,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   if (a.n_split == 1) {
     if (tid < kD) o = o / l_all;
     unrotate_store(o, qf, a.out + (size_t)bh * kD, a.out_rotated != 0, tid);
-    if (a.lse && tid == 0) a.lse[bh] = m_all + __logf(l_all);
+    if (a.lse && tid == 0) a.lse[bh] = (m_all + __log2f(l_all)) * kLn2;
   } else if (tid < kD) {
     float *dst = a.partial + ((size_t)bh * a.n_split + split) * kPartialStride;
     if (tid == 0) { dst[0] = m_all; dst[1] = l_all; }
@@ -532,6 +541,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
     for (int g = 0; g < NG; ++g) sx[hh][g] = sy[hh][g] = sz[hh][g] = 0.0f;
 
+  const float sm2 = a.sm_scale * kLog2e;  // scores live in the base-2 domain
   const int ii = mrow & 3;  // token n = mrow of its group: pair position
   const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
 
@@ -543,7 +553,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       mx = row_max_dpp(mx);
       const float m_new = fmaxf(m_run[hh], mx);
       if (m_new > m_run[hh]) {
-        const float alpha = (m_run[hh] == -INFINITY) ? 0.0f : __expf(m_run[hh] - m_new);
+        const float alpha = (m_run[hh] == -INFINITY) ? 0.0f : fast_exp2(m_run[hh] - m_new);
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) { acc_o[nb][2 * hh] *= alpha; acc_o[nb][2 * hh + 1] *= alpha; }
         l_run[hh] *= alpha;
@@ -553,7 +563,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       }
 #pragma unroll
       for (int tg = 0; tg < 2; ++tg) {
-        p[hh][tg] = (ok[tg] && m_new != -INFINITY) ? __expf(sc[hh][tg] - m_new) : 0.0f;
+        p[hh][tg] = (ok[tg] && m_new != -INFINITY) ? fast_exp2(sc[hh][tg] - m_new) : 0.0f;
         l_run[hh] += p[hh][tg];
       }
     }
@@ -608,8 +618,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
         s0 += mk.scale * (((acc[g][0] + acc[g][1]) - qbias[0][g]) - mk.zero * qsum[0][g]);
         s1 += mk.scale * (((acc[g][2] + acc[g][3]) - qbias[1][g]) - mk.zero * qsum[1][g]);
       }
-      sc[0][tg] = s0 * a.sm_scale;
-      sc[1][tg] = s1 * a.sm_scale;
+      sc[0][tg] = s0 * sm2;
+      sc[1][tg] = s1 * sm2;
       ok[tg] = (tile * 32 + 16 * tg + mrow < a.T_len) && !salient;
     }
     float p[2][2];
@@ -679,8 +689,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
               *reinterpret_cast<const bf16x8 *>(ks_base + (size_t)s_lane * kD + 32 * kc + 8 * qd);
           acc = mfma_bf16(a_s[kc], kb, acc);
         }
-        sc[0][tg] = a.sm_scale * (acc[0] + acc[1]);
-        sc[1][tg] = a.sm_scale * (acc[2] + acc[3]);
+        sc[0][tg] = sm2 * (acc[0] + acc[1]);
+        sc[1][tg] = sm2 * (acc[2] + acc[3]);
         ok[tg] = (s_lane < cnt) && (sidx[min(s_lane, a.S_cap - 1)] < a.T_len);
       }
       float p[2][2];
@@ -742,7 +752,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
         if (mrg_m[w][h] == -INFINITY) continue;
-        const float wgt = __expf(mrg_m[w][h] - m_all);
+        const float wgt = fast_exp2(mrg_m[w][h] - m_all);
         l_all += wgt * mrg_l[w][h];
         o += wgt * mrg_o[w][h][tid];
       }
@@ -752,7 +762,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       if (tid < kD) o = o / l_all;
       __syncthreads();  // qf[0] is reused as the rotation buffer
       unrotate_store(o, qf[0], a.out + bhq * kD, a.out_rotated != 0, tid);
-      if (a.lse && tid == 0) a.lse[bhq] = m_all + __logf(l_all);
+      if (a.lse && tid == 0) a.lse[bhq] = (m_all + __log2f(l_all)) * kLn2;
     } else if (tid < kD) {
       float *dst = a.partial + (bhq * a.n_split + split) * kPartialStride;
       if (tid == 0) { dst[0] = m_all; dst[1] = l_all; }
@@ -775,13 +785,13 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
   for (int s = 0; s < a.n_split; ++s) {
     const float ms = part[(size_t)s * kPartialStride];
     if (ms == -INFINITY) continue;
-    const float wgt = __expf(ms - m_all);
+    const float wgt = fast_exp2(ms - m_all);
     l_all += wgt * part[(size_t)s * kPartialStride + 1];
     o += wgt * part[(size_t)s * kPartialStride + 4 + d];
   }
   o = o / l_all;
   unrotate_store(o, of, a.out + (size_t)bhq * kD, a.out_rotated != 0, d);
-  if (a.lse && d == 0) a.lse[bhq] = m_all + __logf(l_all);
+  if (a.lse && d == 0) a.lse[bhq] = (m_all + __log2f(l_all)) * kLn2;
 }
 
 }  // namespace
