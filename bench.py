@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "copy"],
                     help="time one call only (per-kernel studies; the default 'all' is the benchmark line)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through in --phase runs")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (sweeps)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -148,6 +149,9 @@ def main():
     akvq.lib()  # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
+    if args.batch:
+        import dataclasses
+        w = dataclasses.replace(w, B=args.batch, name=f"{w.name}(B={args.batch})")
     if args.phase == "copy":
         # a plain device-to-device copy of known size: calibrates the HBM byte counters of rocprofv3 --pmc
         n = 1 << 30

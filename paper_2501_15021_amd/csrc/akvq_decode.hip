@@ -52,6 +52,12 @@ __device__ __forceinline__ int k_operand_pos(int e) {
   const int kc = 2 * (m >> 1) + (ie >> 2);
   return (4 * kc + j) * 8 + 2 * (ie & 3) + (m & 1);
 }
+// position of channel e inside the 128-byte A-operand image of the int8 score product: word kc = e/64, lane group
+// qd = (e%32)/8, code slot s = 8*((e/32)%2) + e%8 -> register j = s%4, byte b = s/4 -> byte 4j + b of the lane's 16
+__device__ __forceinline__ int k_digit_pos(int e) {
+  const int kc = e >> 6, j_lane = (e >> 3) & 3, slot = 8 * ((e >> 5) & 1) + (e & 7);
+  return (4 * kc + j_lane) * 16 + 4 * (slot & 3) + (slot >> 2);
+}
 __device__ __forceinline__ float pow4_neg(int k) { return k == 0 ? 1.0f : (k == 1 ? 0.25f : 0.0625f); }
 
 __device__ __forceinline__ uint32_t pack16(uint32_t lo, uint32_t hi) { return (lo & 0xFFFFu) | (hi << 16); }
@@ -145,8 +151,10 @@ template <int G>
 __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   constexpr int NG = kD / G;
   __shared__ float qf[kD];
-  // terms of q~[e] * 4^-k(e) in A-operand order (see k_operand_pos): the code stream's A operand, 16 bytes per lane
-  __shared__ __attribute__((aligned(16))) uint16_t q_scaled[3][kD];
+  // three signed 7-bit digits of q~[e] / U (U a power of two, |q~|/U < 2^20), as int8, in A-operand order of the
+  // 16x16x64 int8 product (see k_digit_pos): the code stream's A operand, 16 bytes per lane
+  __shared__ __attribute__((aligned(16))) int8_t q_digit[3][kD];
+  __shared__ float q_red[kWaves];
   __shared__ __attribute__((aligned(16))) uint16_t q_plain[3][kD];  // terms of q~[e], natural order: bfloat16 rows
   __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][2][NG][2][2][kTokBlock];
   __shared__ __attribute__((aligned(16))) uint16_t zero16[8];
@@ -164,52 +172,59 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   if (tid < 8) zero16[tid] = 0;
   if (wave == 0) rotate_query_lds(a.q + (size_t)bh * kD, qf, lane);
   __syncthreads();
+  // fixed-point unit of the query: U = 2^ceil(log2 max|q~|) / 2^20 (the digits then cover it exactly, 21 bits)
+  float q_unit_inv;
+  {
+    float mx = tid < kD ? fabsf(qf[tid]) : 0.0f;
+    mx = wave_max_dpp(mx);
+    if (lane == 0) q_red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(q_red[0], q_red[1]), fmaxf(q_red[2], q_red[3]));
+    const uint32_t e_biased = min(max(__float_as_uint(mx) >> 23, 20u), 250u);  // mx < 2^(e_biased - 126)
+    q_unit_inv = __uint_as_float((273u - e_biased) << 23);                     // 2^20 / 2^(e_biased - 126)
+  }
+  const float q_unit = 1.0f / q_unit_inv;
   if (tid < kD) {
     const int e = tid;
     const float v = qf[e];
     uint32_t hi, mid, lo;
     split3_bf16(v, hi, mid, lo);
     q_plain[0][e] = (uint16_t)hi; q_plain[1][e] = (uint16_t)mid; q_plain[2][e] = (uint16_t)lo;
-    split3_bf16(v * pow4_neg(k_channel_exp(e)), hi, mid, lo);
-    const int p = k_operand_pos(e);
-    q_scaled[0][p] = (uint16_t)hi; q_scaled[1][p] = (uint16_t)mid; q_scaled[2][p] = (uint16_t)lo;
+    const int n = (int)rintf(v * q_unit_inv);                     // |n| <= 2^20
+    const int d2 = (n << 25) >> 25, n1 = (n - d2) >> 7;           // balanced base-128 digits, each in [-64, 64]
+    const int d1 = (n1 << 25) >> 25, d0 = (n1 - d1) >> 7;
+    const int p = k_digit_pos(e);
+    q_digit[0][p] = (int8_t)d0; q_digit[1][p] = (int8_t)d1; q_digit[2][p] = (int8_t)d2;
+    qf[e] = (float)n;                                             // the value the digits represent, in units of U
   }
   __syncthreads();
 
-  // ---- bias of the expansion constant and per-group sums of the query (each wave, redundantly) ----
-  float qbias[NG], qsum[NG];
+  // ---- per-group sums of the (digitised) query, in units of U ----
+  float qsum[NG];
   {
-    float bias_part[NG], qsum_part[NG];
+    float qsum_part[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) bias_part[g] = qsum_part[g] = 0.0f;
+    for (int g = 0; g < NG; ++g) qsum_part[g] = 0.0f;
 #pragma unroll
-    for (int rep = 0; rep < 2; ++rep) {
-      const int e = lane + 64 * rep;      // operand position and channel alike: both halves split at 64
-      const int g = (NG == 2) ? rep : 0;
-      bias_part[g] += bf16_bits_to_f32(q_scaled[0][e]) + bf16_bits_to_f32(q_scaled[1][e]) +
-                      bf16_bits_to_f32(q_scaled[2][e]);
-      qsum_part[g] += qf[e];
-    }
+    for (int rep = 0; rep < 2; ++rep) qsum_part[(NG == 2) ? rep : 0] += qf[lane + 64 * rep];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      qbias[g] = kCodeBias * wave_sum_dpp(bias_part[g]);
-      qsum[g] = wave_sum_dpp(qsum_part[g]);
-    }
+    for (int g = 0; g < NG; ++g) qsum[g] = wave_sum_dpp(qsum_part[g]);
   }
 
-  // ---- A operands for the code stream: [token group g][kc], row 4g+term ----
-  bf16x8 a_k[4][4];
+  // ---- A operands for the code stream: [token group g][word kc], row 4g+digit ----
+  i32x4 a_k[4][2];
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
-    const int term = mrow - 4 * g;
-    const bool live = term >= 0 && term < 3;
-    const int tc = term < 0 ? 0 : (term > 2 ? 2 : term);
+    const int dig = mrow - 4 * g;
+    const bool live = dig >= 0 && dig < 3;
+    const int dc = dig < 0 ? 0 : (dig > 2 ? 2 : dig);
 #pragma unroll
-    for (int kc = 0; kc < 4; ++kc) {
-      const u32x4 r = *reinterpret_cast<const u32x4 *>(&q_scaled[tc][(4 * kc + qd) * 8]);
-      a_k[g][kc] = __builtin_bit_cast(bf16x8, live ? r : (u32x4){0u, 0u, 0u, 0u});
+    for (int kc = 0; kc < 2; ++kc) {
+      const u32x4 r = *reinterpret_cast<const u32x4 *>(&q_digit[dc][(4 * kc + qd) * 16]);
+      a_k[g][kc] = __builtin_bit_cast(i32x4, live ? r : (u32x4){0u, 0u, 0u, 0u});
     }
   }
+  const ExpandI8 ex8;
 
   f32x4 acc_o[8];
 #pragma unroll
@@ -277,20 +292,17 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     if (tile + kWaves < tile_end) load_tile(tile + kWaves, nxt);
     const int t = tile * 64 + lane;
 
-    // scores: lane l ends up with the terms of token l in acc[0..2]
-    f32x4 acc[NG];
+    // scores: lane l ends up with the three digit products of token l in acc[0..2] (exact integers)
+    i32x4 acc[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) acc[g] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < NG; ++g) acc[g] = (i32x4){0, 0, 0, 0};
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
         const int tg = 2 * b2 + hf;
-        const uint32_t w0 = cur.kc[b2][2 * hf], w1 = cur.kc[b2][2 * hf + 1];
-        acc[0] = mfma_bf16(a_k[tg][0], ex.x(w0), acc[0]);
-        acc[0] = mfma_bf16(a_k[tg][1], ex.y(w0), acc[0]);
-        acc[NG - 1] = mfma_bf16(a_k[tg][2], ex.x(w1), acc[NG - 1]);
-        acc[NG - 1] = mfma_bf16(a_k[tg][3], ex.y(w1), acc[NG - 1]);
+        acc[0] = mfma_i8(a_k[tg][0], ex8(cur.kc[b2][2 * hf]), acc[0]);
+        acc[NG - 1] = mfma_i8(a_k[tg][1], ex8(cur.kc[b2][2 * hf + 1]), acc[NG - 1]);
       }
     float score = 0.0f;
     bool salient = false;
@@ -298,9 +310,10 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     for (int g = 0; g < NG; ++g) {
       const Meta mk = unpack_meta(cur.km[g]);
       salient = salient || mk.salient;
-      const float raw = (acc[g][0] + acc[g][1] + acc[g][2]) - qbias[g];
+      const float raw = (float)acc[g][0] * 16384.0f + ((float)acc[g][1] * 128.0f + (float)acc[g][2]);
       score += mk.scale * (raw - mk.zero * qsum[g]);
     }
+    score *= q_unit;
     score *= sm2;
     const bool ok = (t < a.T_len) && !salient;
     float p;

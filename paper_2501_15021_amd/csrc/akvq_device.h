@@ -106,6 +106,25 @@ __device__ __forceinline__ int pair_exp(int xy, int i) {
 }
 constexpr float kCodeBias = 128.0f; // the 2^7 every expanded code carries
 
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+// 16x16x64 int8 product: per lane 16 K-slots (4 registers x 4 bytes); exact int32 accumulation
+__device__ __forceinline__ i32x4 mfma_i8(i32x4 a, i32x4 b, i32x4 c) {
+  return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+}
+// 16 two-bit codes of one word -> 16 int8 values (register j, byte b = code slot 4b + j): three shifts, four ands
+struct ExpandI8 {
+  uint32_t mask;  // 0x03030303 in a scalar register
+  __device__ __forceinline__ ExpandI8() {
+    uint32_t m = 0x03030303u;
+    asm volatile("" : "+s"(m));
+    mask = m;
+  }
+  __device__ __forceinline__ i32x4 operator()(uint32_t w) const {
+    u32x4 r = {w & mask, (w >> 2) & mask, (w >> 4) & mask, (w >> 6) & mask};
+    return __builtin_bit_cast(i32x4, r);
+  }
+};
+
 __device__ __forceinline__ f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
