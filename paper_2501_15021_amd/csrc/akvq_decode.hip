@@ -288,6 +288,10 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   MhaTile<NG> cur, nxt;
   int tile = tile_begin + wave;
   if (tile < tile_end) load_tile(tile, cur);
+#pragma unroll
+  for (int b2 = 0; b2 < 2; ++b2) { settle(cur.kc[b2]); settle(cur.vc[b2]); }
+#pragma unroll
+  for (int g = 0; g < NG; ++g) { settle(cur.km[g]); settle(cur.vm[g]); }
   for (; tile < tile_end; tile += kWaves) {
     if (tile + kWaves < tile_end) load_tile(tile + kWaves, nxt);
     const int t = tile * 64 + lane;
@@ -608,6 +612,11 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   GqaTile<NG> cur, nxt;
   int tile = tile_begin + wave;
   if (tile < tile_end) load_tile(tile, cur);
+  settle(cur.kc); settle(cur.vc);
+#pragma unroll
+  for (int tg = 0; tg < 2; ++tg)
+#pragma unroll
+    for (int g = 0; g < NG; ++g) { settle(cur.km[tg][g]); settle(cur.vm[tg][g]); }
   for (; tile < tile_end; tile += kWaves) {
     if (tile + kWaves < tile_end) load_tile(tile + kWaves, nxt);
     float sc[2][2];

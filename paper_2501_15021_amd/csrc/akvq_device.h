@@ -52,6 +52,13 @@ __device__ __forceinline__ void split3_bf16(float v, uint32_t &hi, uint32_t &mid
   lo = f32_to_bf16_rne(r2);
 }
 
+// Make the compiler treat these registers as consumed here, so that any load filling them is waited for at this
+// point.  Used once before a software-pipelined loop: the loop header then starts with no load outstanding, and the
+// waits inside the loop count only the loads of the tile being prefetched (otherwise the first-iteration state makes
+// every iteration wait for its own prefetch right after issuing it).
+__device__ __forceinline__ void settle(u32x4 &v) { asm volatile("" : "+v"(v)); }
+__device__ __forceinline__ void settle(uint32_t &v) { asm volatile("" : "+v"(v)); }
+
 // ---- wave-level reductions (64 lanes) ----
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll

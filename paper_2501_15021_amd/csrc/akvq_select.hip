@@ -141,6 +141,8 @@ __global__ __launch_bounds__(256) void psa_row_stats_kernel(SelectArgs a) {
   const int t_wave = chunk * kScoreChunk + wave * (kScoreChunk / 4);
   KeyGroup cur, nxt;
   load_key_group(k_rows, t_wave, a.T, mrow, qd, cur);
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) settle(cur.raw[kc]);
   for (int g = 0; g < kGroupsPerWave; ++g) {
     const int t_first = t_wave + 16 * g;
     if (t_first >= a.T) break;
@@ -222,6 +224,8 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
       for (int i = 0; i < 4; ++i) { rm[rb][i] = row_m[16 * rb + 4 * qd + i]; ril[rb][i] = row_il[16 * rb + 4 * qd + i]; }
     KeyGroup cur, nxt;
     load_key_group(k_rows, t_wave, a.T, mrow, qd, cur);
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) settle(cur.raw[kc]);
 #pragma unroll
     for (int g = 0; g < kGroupsPerWave; ++g) {
       const int t_first = t_wave + 16 * g;
