@@ -148,7 +148,7 @@ struct MhaTile {
 };
 
 template <int G>
-__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
+__device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   constexpr int NG = kD / G;
   __shared__ float qf[kD];
   // three signed 7-bit digits of q~[e] / U (U a power of two, |q~|/U < 2^20), as int8, in A-operand order of the
@@ -157,7 +157,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   __shared__ float q_red[kWaves];
   __shared__ __attribute__((aligned(16))) uint16_t q_plain[3][kD];  // terms of q~[e], natural order: bfloat16 rows
   __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][2][NG][2][2][kTokBlock];
-  __shared__ __attribute__((aligned(16))) uint16_t zero16[8];
+  __shared__ __attribute__((aligned(16))) uint16_t zero16[64];  // 128 zero bytes: operand rows that carry nothing
   __shared__ float mrg_m[kWaves], mrg_l[kWaves];
   __shared__ float mrg_o[kWaves][kD];
 
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   const ExpandK ex;
   auto &w_lds = w_lds_all[wave];  // [blk][group][xy][term][slot]
 
-  if (tid < 8) zero16[tid] = 0;
+  if (tid < 64) zero16[tid] = 0;
   if (wave == 0) rotate_query_lds(a.q + (size_t)bh * kD, qf, lane);
   __syncthreads();
   // fixed-point unit of the query: U = 2^ceil(log2 max|q~|) / 2^20 (the digits then cover it exactly, 21 bits)
@@ -211,18 +211,14 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     for (int g = 0; g < NG; ++g) qsum[g] = wave_sum_dpp(qsum_part[g]);
   }
 
-  // ---- A operands for the code stream: [token group g][word kc], row 4g+digit ----
-  i32x4 a_k[4][2];
+  // ---- A operands for the code stream, per token group g: row 4g+digit carries that digit, other rows are zero.
+  // They stay in LDS (two 128-bit reads per product) instead of 32 registers: the kernel then fits four
+  // wavefronts per SIMD, which is what keeps enough loads in flight.
+  const int8_t *a_src[4];
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     const int dig = mrow - 4 * g;
-    const bool live = dig >= 0 && dig < 3;
-    const int dc = dig < 0 ? 0 : (dig > 2 ? 2 : dig);
-#pragma unroll
-    for (int kc = 0; kc < 2; ++kc) {
-      const u32x4 r = *reinterpret_cast<const u32x4 *>(&q_digit[dc][(4 * kc + qd) * 16]);
-      a_k[g][kc] = __builtin_bit_cast(i32x4, live ? r : (u32x4){0u, 0u, 0u, 0u});
-    }
+    a_src[g] = (dig >= 0 && dig < 3) ? &q_digit[dig][qd * 16] : reinterpret_cast<const int8_t *>(zero16);
   }
   const ExpandI8 ex8;
 
@@ -305,8 +301,11 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
         const int tg = 2 * b2 + hf;
-        acc[0] = mfma_i8(a_k[tg][0], ex8(cur.kc[b2][2 * hf]), acc[0]);
-        acc[NG - 1] = mfma_i8(a_k[tg][1], ex8(cur.kc[b2][2 * hf + 1]), acc[NG - 1]);
+        const int8_t *ap = a_src[tg];
+        asm volatile("" : "+v"(ap));  // keep the operand reads inside the loop (see above)
+        const i32x4 a0 = *reinterpret_cast<const i32x4 *>(ap), a1 = *reinterpret_cast<const i32x4 *>(ap + 64);
+        acc[0] = mfma_i8(a0, ex8(cur.kc[b2][2 * hf]), acc[0]);
+        acc[NG - 1] = mfma_i8(a1, ex8(cur.kc[b2][2 * hf + 1]), acc[NG - 1]);
       }
     float score = 0.0f;
     bool salient = false;
@@ -367,32 +366,24 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
   const int n_units = (cnt + 63) / 64;
   const int first_unit = split + wave * a.n_split;
   if (first_unit < n_units) {
-    bf16x8 a_s[4][4];
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int term = mrow - 4 * g;
-      const bool live = term >= 0 && term < 3;
-      const int tc = term < 0 ? 0 : (term > 2 ? 2 : term);
-#pragma unroll
-      for (int kc = 0; kc < 4; ++kc) {
-        const u32x4 r = *reinterpret_cast<const u32x4 *>(&q_plain[tc][32 * kc + 8 * qd]);
-        a_s[g][kc] = __builtin_bit_cast(bf16x8, live ? r : (u32x4){0u, 0u, 0u, 0u});
-      }
-    }
     const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
     const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
     for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
       const int s_lane = unit * 64 + lane;
       f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int g = 0; g < 4; ++g)
+#pragma unroll 1
+      for (int g = 0; g < 4; ++g) {  // one token group at a time keeps the register footprint of this phase small
+        const int term = mrow - 4 * g;
+        const uint16_t *ap = (term >= 0 && term < 3) ? &q_plain[term][8 * qd] : zero16;
+        const int kstep = (term >= 0 && term < 3) ? 32 : 0;  // the zero row is re-read for every kc
 #pragma unroll
         for (int kc = 0; kc < 4; ++kc) {
           const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(
               ks_base + (size_t)(unit * 64 + 16 * g + mrow) * kD + 32 * kc + 8 * qd);
-          acc = mfma_bf16(a_s[g][kc], kb, acc);
+          acc = mfma_bf16(*reinterpret_cast<const bf16x8 *>(ap + kstep * kc), kb, acc);
         }
+      }
       const float score = sm2 * (acc[0] + acc[1] + acc[2]);
       const bool ok = (s_lane < cnt) && (sidx[min(s_lane, a.S_cap - 1)] < a.T_len);
       float p;
@@ -471,6 +462,14 @@ __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel(DecodeArgs a) {
     dst[4 + tid] = o;
   }
 }
+
+// G = 128 fits four wavefronts per SIMD (128 registers); G = 64 carries a second set of group accumulators and would
+// spill at that size, so it runs at three.
+__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(4, 4))) void decode_mha_kernel_g128(
+    DecodeArgs a) {
+  decode_mha_body<128>(a);
+}
+__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel_g64(DecodeArgs a) { decode_mha_body<64>(a); }
 
 // ------------------------------------------------------------------------------------------------
 // GQA (R = Hq/Hkv query heads share a KV head, 2 <= R <= 8; also valid for R = 1).  A tile is one cache block
@@ -821,8 +820,8 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream) {
   dim3 grid(a.n_split, a.B * a.Hkv), block(64 * kWaves);
   if (a.Hq == a.Hkv) {
-    if (G == 128) hipLaunchKernelGGL(decode_mha_kernel<128>, grid, block, 0, stream, a);
-    else hipLaunchKernelGGL(decode_mha_kernel<64>, grid, block, 0, stream, a);
+    if (G == 128) hipLaunchKernelGGL(decode_mha_kernel_g128, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(decode_mha_kernel_g64, grid, block, 0, stream, a);
   } else {
     if (G == 128) hipLaunchKernelGGL(decode_gqa_kernel<128>, grid, block, 0, stream, a);
     else hipLaunchKernelGGL(decode_gqa_kernel<64>, grid, block, 0, stream, a);
