@@ -153,9 +153,9 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   __shared__ float qf[kD];
   // three signed 7-bit digits of q~[e] / U (U a power of two, |q~|/U < 2^20), as int8, in A-operand order of the
   // 16x16x64 int8 product (see k_digit_pos): the code stream's A operand, 16 bytes per lane
-  __shared__ __attribute__((aligned(16))) int8_t q_digit[3][kD];
+  __shared__ __attribute__((aligned(16))) int8_t q_digit[4][kD];  // row 3 stays zero: operand rows that carry nothing
   __shared__ float q_red[kWaves];
-  __shared__ __attribute__((aligned(16))) uint16_t q_plain[3][kD];  // terms of q~[e], natural order: bfloat16 rows
+  __shared__ __attribute__((aligned(16))) uint16_t q_plain[4][kD];  // terms of q~[e], natural order; row 3 stays zero
   __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][2][NG][2][2][kTokBlock];
   __shared__ __attribute__((aligned(16))) uint16_t zero16[64];  // 128 zero bytes: operand rows that carry nothing
   __shared__ float mrg_m[kWaves], mrg_l[kWaves];
@@ -170,6 +170,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   auto &w_lds = w_lds_all[wave];  // [blk][group][xy][term][slot]
 
   if (tid < 64) zero16[tid] = 0;
+  if (tid < kD) { q_digit[3][tid] = 0; q_plain[3][tid] = 0; }
   if (wave == 0) rotate_query_lds(a.q + (size_t)bh * kD, qf, lane);
   __syncthreads();
   // fixed-point unit of the query: U = 2^ceil(log2 max|q~|) / 2^20 (the digits then cover it exactly, 21 bits)
@@ -214,11 +215,11 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   // ---- A operands for the code stream, per token group g: row 4g+digit carries that digit, other rows are zero.
   // They stay in LDS (two 128-bit reads per product) instead of 32 registers: the kernel then fits four
   // wavefronts per SIMD, which is what keeps enough loads in flight.
-  const int8_t *a_src[4];
+  uint32_t a_off[4];  // byte offset of this lane's operand row inside q_digit, per token group
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
     const int dig = mrow - 4 * g;
-    a_src[g] = (dig >= 0 && dig < 3) ? &q_digit[dig][qd * 16] : reinterpret_cast<const int8_t *>(zero16);
+    a_off[g] = (uint32_t)(((dig >= 0 && dig < 3) ? dig : 3) * kD + qd * 16);
   }
   const ExpandI8 ex8;
 
@@ -281,15 +282,14 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     }
   };
 
-  MhaTile<NG> cur, nxt;
-  int tile = tile_begin + wave;
-  if (tile < tile_end) load_tile(tile, cur);
-#pragma unroll
-  for (int b2 = 0; b2 < 2; ++b2) { settle(cur.kc[b2]); settle(cur.vc[b2]); }
-#pragma unroll
-  for (int g = 0; g < NG; ++g) { settle(cur.km[g]); settle(cur.vm[g]); }
-  for (; tile < tile_end; tile += kWaves) {
-    if (tile + kWaves < tile_end) load_tile(tile + kWaves, nxt);
+  // Three tile buffers: while tile k is consumed, the loads of tiles k+1 and k+2 are in flight.  Loads are issued
+  // unconditionally (the index is clamped to the wavefront's last tile) so that the number of outstanding loads is
+  // the same on every path and the waits inside the loop count exactly two tiles of loads.
+  const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
+  const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
+  auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
+  MhaTile<NG> tb[3];
+  auto process = [&](const MhaTile<NG> &cur, int tile) {
     const int t = tile * 64 + lane;
 
     // scores: lane l ends up with the three digit products of token l in acc[0..2] (exact integers)
@@ -301,9 +301,10 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf) {
         const int tg = 2 * b2 + hf;
-        const int8_t *ap = a_src[tg];
-        asm volatile("" : "+v"(ap));  // keep the operand reads inside the loop (see above)
-        const i32x4 a0 = *reinterpret_cast<const i32x4 *>(ap), a1 = *reinterpret_cast<const i32x4 *>(ap + 64);
+        uint32_t off = a_off[tg];
+        asm volatile("" : "+v"(off));  // keep the operand reads inside the loop (see above)
+        const i32x4 a0 = *reinterpret_cast<const i32x4 *>(&q_digit[0][0] + off);
+        const i32x4 a1 = *reinterpret_cast<const i32x4 *>(&q_digit[0][0] + off + 64);
         acc[0] = mfma_i8(a0, ex8(cur.kc[b2][2 * hf]), acc[0]);
         acc[NG - 1] = mfma_i8(a1, ex8(cur.kc[b2][2 * hf + 1]), acc[NG - 1]);
       }
@@ -357,7 +358,27 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
       }
       wave_lds_sync();
     }
-    cur = nxt;
+  };
+  if (n_mine > 0) {
+    load_tile(tile_at(0), tb[0]);
+    load_tile(tile_at(1), tb[1]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+#pragma unroll
+      for (int b2 = 0; b2 < 2; ++b2) { settle(tb[i].kc[b2]); settle(tb[i].vc[b2]); }
+#pragma unroll
+      for (int g = 0; g < NG; ++g) { settle(tb[i].km[g]); settle(tb[i].vm[g]); }
+    }
+    for (int k = 0; k < n_mine; k += 3) {
+      load_tile(tile_at(k + 2), tb[2]);
+      process(tb[0], tile_at(k));
+      if (k + 1 >= n_mine) break;
+      load_tile(tile_at(k + 3), tb[0]);
+      process(tb[1], tile_at(k + 1));
+      if (k + 2 >= n_mine) break;
+      load_tile(tile_at(k + 4), tb[1]);
+      process(tb[2], tile_at(k + 2));
+    }
   }
 
   // ================= bfloat16 (salient) rows: units of 64 overlay slots dealt to splits, then to wavefronts =========
@@ -375,13 +396,12 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
 #pragma unroll 1
       for (int g = 0; g < 4; ++g) {  // one token group at a time keeps the register footprint of this phase small
         const int term = mrow - 4 * g;
-        const uint16_t *ap = (term >= 0 && term < 3) ? &q_plain[term][8 * qd] : zero16;
-        const int kstep = (term >= 0 && term < 3) ? 32 : 0;  // the zero row is re-read for every kc
+        const uint16_t *ap = &q_plain[(term >= 0 && term < 3) ? term : 3][8 * qd];
 #pragma unroll
         for (int kc = 0; kc < 4; ++kc) {
           const bf16x8 kb = *reinterpret_cast<const bf16x8 *>(
               ks_base + (size_t)(unit * 64 + 16 * g + mrow) * kD + 32 * kc + 8 * qd);
-          acc = mfma_bf16(*reinterpret_cast<const bf16x8 *>(ap + kstep * kc), kb, acc);
+          acc = mfma_bf16(*reinterpret_cast<const bf16x8 *>(ap + 32 * kc), kb, acc);
         }
       }
       const float score = sm2 * (acc[0] + acc[1] + acc[2]);
@@ -463,12 +483,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   }
 }
 
-// G = 128 fits four wavefronts per SIMD (128 registers); G = 64 carries a second set of group accumulators and would
-// spill at that size, so it runs at three.
-__global__ __launch_bounds__(64 * kWaves) __attribute__((amdgpu_waves_per_eu(4, 4))) void decode_mha_kernel_g128(
-    DecodeArgs a) {
-  decode_mha_body<128>(a);
-}
+__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel_g128(DecodeArgs a) { decode_mha_body<128>(a); }
 __global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel_g64(DecodeArgs a) { decode_mha_body<64>(a); }
 
 // ------------------------------------------------------------------------------------------------

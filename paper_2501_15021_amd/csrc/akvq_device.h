@@ -71,11 +71,14 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// LDS traffic between lanes of one wavefront only needs the wave's own memory ops to have landed.
+// LDS traffic between lanes of one wavefront needs no hardware wait: a wavefront's LDS instructions execute in
+// issue order, so a read issued after a write sees it.  What is needed is that the compiler keeps that order (the
+// memory clobber) and does not move code across (the wave barrier).  A release/acquire fence is deliberately NOT
+// used here: it would also drain every outstanding global load, i.e. the prefetch of the next tiles.
 __device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  asm volatile("" ::: "memory");
   __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  asm volatile("" ::: "memory");
 }
 
 // ---- 2-bit codes -> bfloat16 matrix-core operands --------------------------------------------------
