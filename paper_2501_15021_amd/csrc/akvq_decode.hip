@@ -565,39 +565,59 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   f32x4 acc_o[8];
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) acc_o[nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-  float sx[2][NG], sy[2][NG], sz[2][NG];
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};  // softmax reference (base 2) and partial sums
+  float swx[2][NG], szx[2][NG];  // running sums of w*cx and w*cx*zero over this lane's tokens, per head
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-    for (int g = 0; g < NG; ++g) sx[hh][g] = sy[hh][g] = sz[hh][g] = 0.0f;
+    for (int g = 0; g < NG; ++g) swx[hh][g] = szx[hh][g] = 0.0f;
 
   const float sm2 = a.sm_scale * kLog2e;  // scores live in the base-2 domain
   const int ii = mrow & 3;  // token n = mrow of its group: pair position
   const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
+  const float ryx = cy / cx, rcx = 1.0f / cx;  // exact powers of two
 
-  // scores sc[hh][tg] of heads h0+hh for tokens (16*tg + mrow) of the tile; ok[tg]; returns weights p[hh][tg]
+  // scores sc[hh][tg] of heads h0+hh for tokens (16*tg + mrow) of the tile; ok[tg]; returns weights p[hh][tg].
+  // The reference of a head is raised (and its accumulators rescaled) only when one of its scores exceeds it by more
+  // than kLazyMax; the common tile pays one compare and one uniform branch.
   auto softmax_step = [&](const float (&sc)[2][2], const bool (&ok)[2], float (&p)[2][2]) {
+    float scm[2][2], top[2];
+    bool need = false;
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-      float mx = fmaxf(ok[0] ? sc[hh][0] : -INFINITY, ok[1] ? sc[hh][1] : -INFINITY);
-      mx = row_max_dpp(mx);
-      const float m_new = fmaxf(m_run[hh], mx);
-      if (m_new > m_run[hh]) {
-        const float alpha = (m_run[hh] == -INFINITY) ? 0.0f : fast_exp2(m_run[hh] - m_new);
 #pragma unroll
-        for (int nb = 0; nb < 8; ++nb) { acc_o[nb][2 * hh] *= alpha; acc_o[nb][2 * hh + 1] *= alpha; }
-        l_run[hh] *= alpha;
+      for (int tg = 0; tg < 2; ++tg) scm[hh][tg] = ok[tg] ? sc[hh][tg] : -INFINITY;
+      top[hh] = fmaxf(scm[hh][0], scm[hh][1]);
+      need = need || (top[hh] > m_run[hh] + kLazyMax);
+    }
+    if (__ballot(need) != 0ull) {
 #pragma unroll
-        for (int g = 0; g < NG; ++g) { sx[hh][g] *= alpha; sy[hh][g] *= alpha; sz[hh][g] *= alpha; }
-        m_run[hh] = m_new;
+      for (int hh = 0; hh < 2; ++hh) {
+        const float mx = row_max_dpp(top[hh]);  // the 16 lanes of a row share a head
+        if (mx > m_run[hh] + kLazyMax) {
+          const float alpha = (m_run[hh] == -INFINITY) ? 0.0f : fast_exp2(m_run[hh] - mx);
+#pragma unroll
+          for (int nb = 0; nb < 8; ++nb) { acc_o[nb][2 * hh] *= alpha; acc_o[nb][2 * hh + 1] *= alpha; }
+          l_run[hh] *= alpha;
+#pragma unroll
+          for (int g = 0; g < NG; ++g) { swx[hh][g] *= alpha; szx[hh][g] *= alpha; }
+          m_run[hh] = mx;
+        }
       }
+    }
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      const float m_ref = (m_run[hh] == -INFINITY) ? 0.0f : m_run[hh];
 #pragma unroll
       for (int tg = 0; tg < 2; ++tg) {
-        p[hh][tg] = (ok[tg] && m_new != -INFINITY) ? fast_exp2(sc[hh][tg] - m_new) : 0.0f;
+        p[hh][tg] = fast_exp2(scm[hh][tg] - m_ref);
         l_run[hh] += p[hh][tg];
       }
     }
+  };
+  // upper halves of two floats packed into one word (two bfloat16 values that are already exact in 16 bits)
+  auto pack_hi = [](float lo, float hi) {
+    return __builtin_amdgcn_perm(__float_as_uint(hi), __float_as_uint(lo), 0x07060302u);
   };
 
   // ================= code stream =================
@@ -615,24 +635,21 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     t.kc = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)tile * kBlockWords);
     t.vc = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)tile * kBlockWords);
 #pragma unroll
-    for (int tg = 0; tg < 2; ++tg)
-#pragma unroll
-      for (int g = 0; g < NG; ++g) {
-        t.km[tg][g] = km_base[((size_t)tile * 32 + 16 * tg) * NG + g];
-        t.vm[tg][g] = vm_base[((size_t)tile * 32 + 16 * tg) * NG + g];
+    for (int tg = 0; tg < 2; ++tg) {
+      const size_t off = ((size_t)tile * 32 + 16 * tg) * NG;
+      if constexpr (NG == 2) {
+        const u32x2 k2 = *reinterpret_cast<const u32x2 *>(km_base + off);
+        const u32x2 v2 = *reinterpret_cast<const u32x2 *>(vm_base + off);
+        t.km[tg][0] = k2[0]; t.km[tg][1] = k2[1];
+        t.vm[tg][0] = v2[0]; t.vm[tg][1] = v2[1];
+      } else {
+        t.km[tg][0] = km_base[off];
+        t.vm[tg][0] = vm_base[off];
       }
+    }
   };
 
-  GqaTile<NG> cur, nxt;
-  int tile = tile_begin + wave;
-  if (tile < tile_end) load_tile(tile, cur);
-  settle(cur.kc); settle(cur.vc);
-#pragma unroll
-  for (int tg = 0; tg < 2; ++tg)
-#pragma unroll
-    for (int g = 0; g < NG; ++g) { settle(cur.km[tg][g]); settle(cur.vm[tg][g]); }
-  for (; tile < tile_end; tile += kWaves) {
-    if (tile + kWaves < tile_end) load_tile(tile + kWaves, nxt);
+  auto process = [&](const GqaTile<NG> &cur, int tile) {
     float sc[2][2];
     bool ok[2];
 #pragma unroll
@@ -662,25 +679,31 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     softmax_step(sc, ok, p);
     // weights: rows 4*qd + {0,1,2,3} = (head h0: hi, lo; head h0+1: hi, lo); slots 2*mrow (+1 for the second group)
 #pragma unroll
-    for (int g = 0; g < NG; ++g)
+    for (int g = 0; g < NG; ++g) {
+      float sxc[2], zv[2];
+#pragma unroll
+      for (int tg = 0; tg < 2; ++tg) {
+        const Meta mv = unpack_meta(cur.vm[tg][g]);
+        sxc[tg] = ok[tg] ? mv.scale * cx : 0.0f;  // rows past T_len hold arbitrary meta
+        zv[tg] = mv.zero;
+      }
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
-        float hif[2], lof[2];
+        float hix[2], lox[2];
 #pragma unroll
         for (int tg = 0; tg < 2; ++tg) {
-          const Meta mv = unpack_meta(cur.vm[tg][g]);
-          split2(ok[tg] ? p[hh][tg] * mv.scale : 0.0f, hif[tg], lof[tg]);  // rows past T_len hold arbitrary meta
-          const float wr = hif[tg] + lof[tg];
-          sx[hh][g] += wr * cx;
-          sy[hh][g] += wr * cy;
-          sz[hh][g] += wr * mv.zero;
+          split2(p[hh][tg] * sxc[tg], hix[tg], lox[tg]);
+          const float wxr = hix[tg] + lox[tg];
+          swx[hh][g] += wxr;
+          szx[hh][g] += wxr * zv[tg];
         }
         const int row = 4 * qd + 2 * hh;
-        reinterpret_cast<uint32_t *>(&w_lds[g][0][row][0])[mrow] = pack16(hi16(hif[0] * cx), hi16(hif[1] * cx));
-        reinterpret_cast<uint32_t *>(&w_lds[g][0][row + 1][0])[mrow] = pack16(hi16(lof[0] * cx), hi16(lof[1] * cx));
-        reinterpret_cast<uint32_t *>(&w_lds[g][1][row][0])[mrow] = pack16(hi16(hif[0] * cy), hi16(hif[1] * cy));
-        reinterpret_cast<uint32_t *>(&w_lds[g][1][row + 1][0])[mrow] = pack16(hi16(lof[0] * cy), hi16(lof[1] * cy));
+        reinterpret_cast<uint32_t *>(&w_lds[g][0][row][0])[mrow] = pack_hi(hix[0], hix[1]);
+        reinterpret_cast<uint32_t *>(&w_lds[g][0][row + 1][0])[mrow] = pack_hi(lox[0], lox[1]);
+        reinterpret_cast<uint32_t *>(&w_lds[g][1][row][0])[mrow] = pack_hi(hix[0] * ryx, hix[1] * ryx);
+        reinterpret_cast<uint32_t *>(&w_lds[g][1][row + 1][0])[mrow] = pack_hi(lox[0] * ryx, lox[1] * ryx);
       }
+    }
     wave_lds_sync();
     bf16x8 a_v[NG][2];
 #pragma unroll
@@ -696,7 +719,34 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       acc_o[nby] = mfma_bf16(a_v[g][1], ex.y(cur.vc[w]), acc_o[nby]);
     }
     wave_lds_sync();
-    cur = nxt;
+  };
+
+  // three tile buffers, two tiles of loads in flight (see the MHA kernel)
+  const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
+  const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
+  auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
+  GqaTile<NG> tb[3];
+  if (n_mine > 0) {
+    load_tile(tile_at(0), tb[0]);
+    load_tile(tile_at(1), tb[1]);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      settle(tb[i].kc); settle(tb[i].vc);
+#pragma unroll
+      for (int tg = 0; tg < 2; ++tg)
+#pragma unroll
+        for (int g = 0; g < NG; ++g) { settle(tb[i].km[tg][g]); settle(tb[i].vm[tg][g]); }
+    }
+    for (int k = 0; k < n_mine; k += 3) {
+      load_tile(tile_at(k + 2), tb[2]);
+      process(tb[0], tile_at(k));
+      if (k + 1 >= n_mine) break;
+      load_tile(tile_at(k + 3), tb[0]);
+      process(tb[1], tile_at(k + 1));
+      if (k + 2 >= n_mine) break;
+      load_tile(tile_at(k + 4), tb[1]);
+      process(tb[2], tile_at(k + 2));
+    }
   }
 
   // ================= bfloat16 (salient) rows: units of 32 overlay slots =================
@@ -767,9 +817,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     float corr_x[NG], corr_y[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      const float z = row_sum_dpp(sz[hh][g]);
-      corr_x[g] = kCodeBias * row_sum_dpp(sx[hh][g]) + z;
-      corr_y[g] = kCodeBias * row_sum_dpp(sy[hh][g]) + z;
+      const float z = row_sum_dpp(szx[hh][g] * rcx);
+      corr_x[g] = kCodeBias * row_sum_dpp(swx[hh][g]) + z;
+      corr_y[g] = kCodeBias * row_sum_dpp(swx[hh][g] * ryx) + z;
     }
     if (mrow == 0) { mrg_m[wave][h] = m_run[hh]; mrg_l[wave][h] = l_tot; }
 #pragma unroll
