@@ -90,7 +90,7 @@ int akvq_decode_default_splits(int B, int Hkv, int T_len) {
   const long units = (long)B * Hkv;            // one workgroup of four wavefronts per (unit, split)
   if (units >= 512) return 1;                  // already two workgroups per CU: finish in one kernel, no merge pass
   const int tiles = (T_len + 63) / 64;
-  long want = (1024 + units - 1) / units;
+  long want = (512 + units - 1) / units;       // two workgroups per CU; more splits only add merge work
   long cap = tiles / 16 > 1 ? tiles / 16 : 1;  // keep at least four 64-token tiles per wavefront
   if (want > cap) want = cap;
   if (want > 64) want = 64;

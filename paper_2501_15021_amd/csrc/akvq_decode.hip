@@ -44,7 +44,7 @@ __device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *q
 
 // exponent k of the 4^k factor that the expansion attaches to channel e of a K row (see the K block layout:
 // channel e sits in code pair e%8 of its word; pairs 0..3 are the X operand, 4..7 the Y operand)
-__device__ __forceinline__ int k_channel_exp(int e) { return pair_exp((e & 7) >> 2, e & 3); }
+__device__ __forceinline__ int k_channel_exp(int e) { return pair_exp(e & 3); }
 // position of channel e inside the 128-entry A-operand image of a K row: MFMA kc = 2*(e/64) + (e%8)/4, lane group
 // qd = (e%32)/8, pair i = e%4, element 2i + (e/32)%2
 __device__ __forceinline__ int k_operand_pos(int e) {
@@ -156,7 +156,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   __shared__ __attribute__((aligned(16))) int8_t q_digit[4][kD];  // row 3 stays zero: operand rows that carry nothing
   __shared__ float q_red[kWaves];
   __shared__ __attribute__((aligned(16))) uint16_t q_plain[4][kD];  // terms of q~[e], natural order; row 3 stays zero
-  __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][2][NG][2][2][kTokBlock];
+  __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][2][NG][2][kTokBlock];
   __shared__ __attribute__((aligned(16))) uint16_t zero16[64];  // 128 zero bytes: operand rows that carry nothing
   __shared__ float mrg_m[kWaves], mrg_l[kWaves];
   __shared__ float mrg_o[kWaves][kD];
@@ -167,7 +167,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   const int bh = blockIdx.y;  // Hq == Hkv here
   const int mrow = lane & 15, qd = lane >> 4;
   const ExpandK ex;
-  auto &w_lds = w_lds_all[wave];  // [blk][group][xy][term][slot]
+  auto &w_lds = w_lds_all[wave];  // [blk][group][term][slot]
 
   if (tid < 64) zero16[tid] = 0;
   if (tid < kD) { q_digit[3][tid] = 0; q_plain[3][tid] = 0; }
@@ -234,8 +234,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
 
   const int r16 = lane & 15, half = (lane >> 4) & 1, blk_of_lane = lane >> 5;
   const int slot = 2 * r16 + half, ii = r16 & 3;
-  const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
-  const float ryx = cy / cx, rcx = 1.0f / cx;  // exact powers of two
+  const float cx = pow4_neg(pair_exp(ii)), rcx = 1.0f / cx;  // exact powers of two
 
   // online-softmax bookkeeping shared by the code stream and the bfloat16 rows.  The reference m_run is only
   // raised when some score exceeds it by more than kLazyMax, so the common tile costs one compare and one branch;
@@ -328,32 +327,27 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
         const Meta mv = unpack_meta(cur.vm[g]);
         float hix, lox;
         split2(ok ? p * (mv.scale * cx) : 0.0f, hix, lox);  // rows past T_len hold arbitrary meta
-        const float hiy = hix * ryx, loy = lox * ryx;           // exact
-        w_lds[blk_of_lane][g][0][0][slot] = (uint16_t)hi16(hix);
-        w_lds[blk_of_lane][g][0][1][slot] = (uint16_t)hi16(lox);
-        w_lds[blk_of_lane][g][1][0][slot] = (uint16_t)hi16(hiy);
-        w_lds[blk_of_lane][g][1][1][slot] = (uint16_t)hi16(loy);
+        w_lds[blk_of_lane][g][0][slot] = (uint16_t)hi16(hix);
+        w_lds[blk_of_lane][g][1][slot] = (uint16_t)hi16(lox);
         const float wxr = hix + lox;
         swx[g] += wxr;
-        szx[g] += wxr * mv.zero;
+        szx[g] = __builtin_fmaf(wxr, mv.zero, szx[g]);
       }
       wave_lds_sync();
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
-        bf16x8 a_v[NG][2];
+        bf16x8 a_v[NG];
 #pragma unroll
-        for (int g = 0; g < NG; ++g)
-#pragma unroll
-          for (int xy = 0; xy < 2; ++xy) {
-            const uint16_t *src = mrow < 2 ? &w_lds[b2][g][xy][mrow][8 * qd] : zero16;
-            a_v[g][xy] = *reinterpret_cast<const bf16x8 *>(src);
-          }
+        for (int g = 0; g < NG; ++g) {
+          const uint16_t *src = mrow < 2 ? &w_lds[b2][g][mrow][8 * qd] : zero16;
+          a_v[g] = *reinterpret_cast<const bf16x8 *>(src);
+        }
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
           const int g = (NG == 2) ? (w & 1) : 0;
           const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
-          acc_o[nbx] = mfma_bf16(a_v[g][0], ex.x(cur.vc[b2][w]), acc_o[nbx]);
-          acc_o[nby] = mfma_bf16(a_v[g][1], ex.y(cur.vc[b2][w]), acc_o[nby]);
+          acc_o[nbx] = mfma_bf16(a_v[g], ex.x(cur.vc[b2][w]), acc_o[nbx]);
+          acc_o[nby] = mfma_bf16(a_v[g], ex.y(cur.vc[b2][w]), acc_o[nby]);
         }
       }
       wave_lds_sync();
@@ -411,13 +405,13 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
       {
         float hif, lof;
         split2(ok ? p : 0.0f, hif, lof);
-        w_lds[blk_of_lane][0][0][0][slot] = (uint16_t)hi16(hif);
-        w_lds[blk_of_lane][0][0][1][slot] = (uint16_t)hi16(lof);
+        w_lds[blk_of_lane][0][0][slot] = (uint16_t)hi16(hif);
+        w_lds[blk_of_lane][0][1][slot] = (uint16_t)hi16(lof);
       }
       wave_lds_sync();
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
-        const uint16_t *src = mrow < 2 ? &w_lds[b2][0][0][mrow][8 * qd] : zero16;
+        const uint16_t *src = mrow < 2 ? &w_lds[b2][0][mrow][8 * qd] : zero16;
         const bf16x8 a_v = *reinterpret_cast<const bf16x8 *>(src);
         // which of this lane's 8 K-slots (pair i, half) are real rows: mask the others (unwritten memory)
         uint32_t keep[4];
@@ -442,20 +436,14 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   // ================= merge the four wavefronts, then either finish (one split) or store the partial =================
   {
     const float l_tot = wave_sum_dpp(l_run);
-    float corr_x[NG], corr_y[NG];
+    float corr[NG];  // what the expansion constant and the zero-points added to every channel of the group
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const float z = wave_sum_dpp(szx[g] * rcx);
-      corr_x[g] = kCodeBias * wave_sum_dpp(swx[g]) + z;
-      corr_y[g] = kCodeBias * wave_sum_dpp(swx[g] * ryx) + z;
-    }
+    for (int g = 0; g < NG; ++g) corr[g] = kCodeBias * wave_sum_dpp(swx[g]) + wave_sum_dpp(szx[g] * rcx);
     if (lane == 0) { mrg_m[wave] = m_run; mrg_l[wave] = l_tot; }
     if (lane < 16) {
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb) {
-        const int g = (NG == 2) ? (nb >> 2) : 0;
-        const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
-        mrg_o[wave][16 * nb + lane] = (acc_o[nb][0] + acc_o[nb][1]) - corr;
+        mrg_o[wave][16 * nb + lane] = (acc_o[nb][0] + acc_o[nb][1]) - corr[(NG == 2) ? (nb >> 2) : 0];
       }
     }
   }
@@ -503,7 +491,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   __shared__ float qf[8][kD];
   __shared__ __attribute__((aligned(16))) uint16_t q_scaled[16][kD];  // row 2h+term, A-operand order
   __shared__ __attribute__((aligned(16))) uint16_t q_plain[16][kD];   // row 2h+term, natural order
-  __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][NG][2][16][kTokBlock];  // [group][xy][row][slot]
+  __shared__ __attribute__((aligned(16))) uint16_t w_lds_all[kWaves][NG][16][kTokBlock];  // [group][row][slot]
   __shared__ float mrg_m[kWaves][8], mrg_l[kWaves][8];
   __shared__ float mrg_o[kWaves][8][kD];
 
@@ -518,7 +506,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   auto &w_lds = w_lds_all[wave];
 
   for (int x = tid; x < 16 * kD; x += 64 * kWaves) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
-  for (int x = lane; x < NG * 2 * 16 * kTokBlock; x += 64) (&w_lds[0][0][0][0])[x] = 0;
+  for (int x = lane; x < NG * 16 * kTokBlock; x += 64) (&w_lds[0][0][0])[x] = 0;
   for (int h = wave; h < R; h += kWaves) rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf[h], lane);
   __syncthreads();
   for (int x = tid; x < R * kD; x += 64 * kWaves) {
@@ -574,8 +562,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 
   const float sm2 = a.sm_scale * kLog2e;  // scores live in the base-2 domain
   const int ii = mrow & 3;  // token n = mrow of its group: pair position
-  const float cx = pow4_neg(pair_exp(0, ii)), cy = pow4_neg(pair_exp(1, ii));
-  const float ryx = cy / cx, rcx = 1.0f / cx;  // exact powers of two
+  const float cx = pow4_neg(pair_exp(ii)), rcx = 1.0f / cx;  // exact powers of two
 
   // scores sc[hh][tg] of heads h0+hh for tokens (16*tg + mrow) of the tile; ok[tg]; returns weights p[hh][tg].
   // The reference of a head is raised (and its accumulators rescaled) only when one of its scores exceeds it by more
@@ -668,8 +655,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       for (int g = 0; g < NG; ++g) {
         const Meta mk = unpack_meta(cur.km[tg][g]);
         salient = salient || mk.salient;
-        s0 += mk.scale * (((acc[g][0] + acc[g][1]) - qbias[0][g]) - mk.zero * qsum[0][g]);
-        s1 += mk.scale * (((acc[g][2] + acc[g][3]) - qbias[1][g]) - mk.zero * qsum[1][g]);
+        // scale * (dot - 128*sum(q') - zero*sum(q)); qbias already holds 128*sum(q')
+        s0 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[0][g], (acc[g][0] + acc[g][1]) - qbias[0][g]), s0);
+        s1 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[1][g], (acc[g][2] + acc[g][3]) - qbias[1][g]), s1);
       }
       sc[0][tg] = s0 * sm2;
       sc[1][tg] = s1 * sm2;
@@ -695,28 +683,23 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
           split2(p[hh][tg] * sxc[tg], hix[tg], lox[tg]);
           const float wxr = hix[tg] + lox[tg];
           swx[hh][g] += wxr;
-          szx[hh][g] += wxr * zv[tg];
+          szx[hh][g] = __builtin_fmaf(wxr, zv[tg], szx[hh][g]);
         }
         const int row = 4 * qd + 2 * hh;
-        reinterpret_cast<uint32_t *>(&w_lds[g][0][row][0])[mrow] = pack_hi(hix[0], hix[1]);
-        reinterpret_cast<uint32_t *>(&w_lds[g][0][row + 1][0])[mrow] = pack_hi(lox[0], lox[1]);
-        reinterpret_cast<uint32_t *>(&w_lds[g][1][row][0])[mrow] = pack_hi(hix[0] * ryx, hix[1] * ryx);
-        reinterpret_cast<uint32_t *>(&w_lds[g][1][row + 1][0])[mrow] = pack_hi(lox[0] * ryx, lox[1] * ryx);
+        reinterpret_cast<uint32_t *>(&w_lds[g][row][0])[mrow] = pack_hi(hix[0], hix[1]);
+        reinterpret_cast<uint32_t *>(&w_lds[g][row + 1][0])[mrow] = pack_hi(lox[0], lox[1]);
       }
     }
     wave_lds_sync();
-    bf16x8 a_v[NG][2];
+    bf16x8 a_v[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g)
-#pragma unroll
-      for (int xy = 0; xy < 2; ++xy)
-        a_v[g][xy] = *reinterpret_cast<const bf16x8 *>(&w_lds[g][xy][mrow][8 * qd]);
+    for (int g = 0; g < NG; ++g) a_v[g] = *reinterpret_cast<const bf16x8 *>(&w_lds[g][mrow][8 * qd]);
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const int g = (NG == 2) ? (w & 1) : 0;
       const int nbx = 4 * (w & 1) + (w >> 1), nby = nbx + 2;
-      acc_o[nbx] = mfma_bf16(a_v[g][0], ex.x(cur.vc[w]), acc_o[nbx]);
-      acc_o[nby] = mfma_bf16(a_v[g][1], ex.y(cur.vc[w]), acc_o[nby]);
+      acc_o[nbx] = mfma_bf16(a_v[g], ex.x(cur.vc[w]), acc_o[nbx]);
+      acc_o[nby] = mfma_bf16(a_v[g], ex.y(cur.vc[w]), acc_o[nby]);
     }
     wave_lds_sync();
   };
@@ -787,11 +770,11 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
         for (int tg = 0; tg < 2; ++tg) split2(p[hh][tg], hif[tg], lof[tg]);
         const int row = 4 * qd + 2 * hh;
-        reinterpret_cast<uint32_t *>(&w_lds[0][0][row][0])[mrow] = pack16(hi16(hif[0]), hi16(hif[1]));
-        reinterpret_cast<uint32_t *>(&w_lds[0][0][row + 1][0])[mrow] = pack16(hi16(lof[0]), hi16(lof[1]));
+        reinterpret_cast<uint32_t *>(&w_lds[0][row][0])[mrow] = pack_hi(hif[0], hif[1]);
+        reinterpret_cast<uint32_t *>(&w_lds[0][row + 1][0])[mrow] = pack_hi(lof[0], lof[1]);
       }
       wave_lds_sync();
-      const bf16x8 a_v = *reinterpret_cast<const bf16x8 *>(&w_lds[0][0][mrow][8 * qd]);
+      const bf16x8 a_v = *reinterpret_cast<const bf16x8 *>(&w_lds[0][mrow][8 * qd]);
       uint32_t keep[4];
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -814,19 +797,13 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   for (int hh = 0; hh < 2; ++hh) {
     const int h = h0 + hh;
     const float l_tot = row_sum_dpp(l_run[hh]);
-    float corr_x[NG], corr_y[NG];
+    float corr[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      const float z = row_sum_dpp(szx[hh][g] * rcx);
-      corr_x[g] = kCodeBias * row_sum_dpp(swx[hh][g]) + z;
-      corr_y[g] = kCodeBias * row_sum_dpp(swx[hh][g] * ryx) + z;
-    }
+    for (int g = 0; g < NG; ++g) corr[g] = kCodeBias * row_sum_dpp(swx[hh][g]) + row_sum_dpp(szx[hh][g] * rcx);
     if (mrow == 0) { mrg_m[wave][h] = m_run[hh]; mrg_l[wave][h] = l_tot; }
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) {
-      const int g = (NG == 2) ? (nb >> 2) : 0;
-      const float corr = ((nb >> 1) & 1) ? corr_y[g] : corr_x[g];
-      mrg_o[wave][h][16 * nb + mrow] = (acc_o[nb][2 * hh] + acc_o[nb][2 * hh + 1]) - corr;
+      mrg_o[wave][h][16 * nb + mrow] = (acc_o[nb][2 * hh] + acc_o[nb][2 * hh + 1]) - corr[(NG == 2) ? (nb >> 2) : 0];
     }
   }
   __syncthreads();

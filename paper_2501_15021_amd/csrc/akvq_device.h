@@ -86,7 +86,7 @@ __device__ __forceinline__ void wave_lds_sync() {
 // OR-ing a masked pair into 0x4300'4300 yields two bfloat16 numbers 128 + 4^k * code (k = the field's
 // position inside the 7-bit mantissa: 0, 1 or 2).  The constant 128 and the factor 4^k are undone on the
 // other operand of the contraction, so expansion costs one and-or per two codes (plus two shifts per word).
-// Pairs 0..3 form the "X" operand (factors 4^{0,1,2,0}), pairs 4..7 the "Y" operand (4^{1,2,0,1}).
+// Pairs 0..3 form the "X" operand, pairs 4..7 the "Y" operand; both carry the factors 4^{0,1,2,0}.
 // The masks and the constant are kept as opaque register values (not literals) so that the compiler selects the
 // three-operand and-or instruction, whose encoding takes no literal operands: D = (w & mask) | magic in one op.
 struct ExpandK {
@@ -104,16 +104,14 @@ struct ExpandK {
     return __builtin_bit_cast(bf16x8, r);
   }
   __device__ __forceinline__ bf16x8 y(uint32_t w) const {
-    const uint32_t w6 = w >> 6, w12 = w >> 12;
-    u32x4 r = {pair(w6, 1), pair(w6, 2), pair(w12, 0), pair(w12, 1)};
+    const uint32_t w8 = w >> 8, w14 = w >> 14;
+    u32x4 r = {pair(w8, 0), pair(w8, 1), pair(w8, 2), pair(w14, 0)};
     return __builtin_bit_cast(bf16x8, r);
   }
 };
-// exponent k (factor 4^k) carried by pair i of the X / Y operand
-__device__ __forceinline__ int pair_exp(int xy, int i) {
-  // X: {0,1,2,0}   Y: {1,2,0,1}
-  return xy == 0 ? (i == 3 ? 0 : i) : (i == 0 ? 1 : (i == 1 ? 2 : (i == 2 ? 0 : 1)));
-}
+// exponent k (factor 4^k) carried by pair i of either operand: {0,1,2,0} (the Y operand shifts by 8 and 14 so that
+// it repeats the X pattern; one set of pre-divided weights then serves both)
+__device__ __forceinline__ int pair_exp(int i) { return i == 3 ? 0 : i; }
 constexpr float kCodeBias = 128.0f; // the 2^7 every expanded code carries
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
