@@ -26,16 +26,9 @@ constexpr int kQuadXor2 = 0x4E;  // quad_perm [2,3,0,1]
 constexpr int kRowRor4 = 0x124;  // rotate right by 4 inside a row of 16 lanes
 constexpr int kRowRor8 = 0x128;
 
-// One cross-lane butterfly level: the lane whose index bit is clear keeps a+b, its partner keeps a-b.
-// sign_mask is 0 for the lower lane and 0x80000000 for the upper one; (own ^ sign) is exact, so the single
-// rounding is that of the add, as the specification of the transform requires.
-template <int CTRL>
-__device__ __forceinline__ float cross_butterfly(float own, uint32_t sign_mask) {
-  float partner = dpp_move<CTRL>(own);
-  float signed_own = __uint_as_float(__float_as_uint(own) ^ sign_mask);
-  return partner + signed_own;
-}
-
+// A cross-lane butterfly level: the lane whose index bit is clear keeps a+b, its partner keeps a-b.  Each lane adds
+// its partner's value to its own value with the sign bit flipped where the bit is set; the flip is exact, so the
+// single rounding is that of the add, as the specification of the transform requires.
 // un-normalised 128-point butterfly over u[4][8] (m, i) with the j index spread over the quad
 __device__ __forceinline__ void wht128_quad(float (&u)[4][8], int j) {
   // strides 1, 2, 4: inside i
@@ -50,17 +43,27 @@ __device__ __forceinline__ void wht128_quad(float (&u)[4][8], int j) {
           u[m][i] = a + b;
           u[m][i + h] = a - b;
         }
-  // strides 8, 16: across the quad (j bit 0, j bit 1)
+  // strides 8, 16: across the quad (j bit 0, j bit 1).  All sign flips of a level are issued before its
+  // DPP adds so that no add reads a register written by the instruction just before it (no hazard stalls).
   const uint32_t s1 = (j & 1) ? 0x80000000u : 0u;
   const uint32_t s2 = (j & 2) ? 0x80000000u : 0u;
+  float sg[4][8];
 #pragma unroll
   for (int m = 0; m < 4; ++m)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) u[m][i] = cross_butterfly<kQuadXor1>(u[m][i], s1);
+    for (int i = 0; i < 8; ++i) sg[m][i] = __uint_as_float(__float_as_uint(u[m][i]) ^ s1);
 #pragma unroll
   for (int m = 0; m < 4; ++m)
 #pragma unroll
-    for (int i = 0; i < 8; ++i) u[m][i] = cross_butterfly<kQuadXor2>(u[m][i], s2);
+    for (int i = 0; i < 8; ++i) u[m][i] = dpp_move<kQuadXor1>(u[m][i]) + sg[m][i];
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) sg[m][i] = __uint_as_float(__float_as_uint(u[m][i]) ^ s2);
+#pragma unroll
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) u[m][i] = dpp_move<kQuadXor2>(u[m][i]) + sg[m][i];
   // strides 32, 64: inside m
 #pragma unroll
   for (int h = 1; h < 4; h *= 2)
@@ -112,11 +115,16 @@ __device__ __forceinline__ GroupQ group_params(float umin, float umax, float kap
 }
 
 // Eq. 3: clamp(round(x/scale + zero), 0, 3); the fused multiply-add rounds the exact sum once, to an integer.
-__device__ __forceinline__ uint32_t code_of(float u, const GroupQ &g) {
+// Returns the bit pattern of 1.5*2^23 + code: the code sits in the two low bits, the rest is the constant kMagicBits.
+__device__ __forceinline__ uint32_t code_bits(float u, const GroupQ &g) {
   float t = __fmaf_rn(u, g.rcpu, g.magic_zero);
   t = fminf(fmaxf(t, kMagic), kMagic + 3.0f);
-  return __float_as_uint(t) - kMagicBits;
+  return __float_as_uint(t);
 }
+// Packing adds the raw patterns with shifts (one shift-add per code); what the constant part of every pattern
+// contributes is a compile-time constant (mod 2^32) that is subtracted once per word.
+constexpr uint32_t kPack16Bias = (uint32_t)(0x4B400000ull * 0x55555555ull);   // sum over s<16 of kMagicBits << 2s
+constexpr uint32_t kPack4Bias = (uint32_t)(0x4B400000ull * 0x01010101ull);    // sum over b<4 of kMagicBits << 8b
 
 template <int G>
 __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
@@ -160,7 +168,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   wave_lds_sync();
 
   uint32_t kw[2][2];         // K words of token half h: [h][group-of-64 word]
-  uint32_t vcode[2][2][8];   // V: [mpair][xy... packed per (i)] built below
+  uint32_t vcode[2][8];      // V: [mpair][i]: raw patterns of (X, Y) x (half 0, half 1) in the four byte lanes
   uint32_t vmask_part = 0;
   bool valid[2];
   uint32_t meta_out[2][NG];
@@ -201,8 +209,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           u32x4 o;
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            o[w] = f32_to_bf16_rne(__fmul_rn(u[m][2 * w], kappa)) |
-                   (f32_to_bf16_rne(__fmul_rn(u[m][2 * w + 1], kappa)) << 16);
+            o[w] = pack_bf16x2(__fmul_rn(u[m][2 * w], kappa), __fmul_rn(u[m][2 * w + 1], kappa));
           *reinterpret_cast<u32x4 *>(dst + 32 * m + 8 * j) = o;
         }
       } else {
@@ -214,7 +221,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           for (int i = 0; i < 8; ++i) {
             const int e = 32 * m + 8 * j + i, nb = e >> 4, n = e & 15;
             plane[(size_t)sb * 4096 + nb * 512 + (16 * sq + n) * 8 + 2 * sii + sh] =
-                (uint16_t)f32_to_bf16_rne(__fmul_rn(u[m][i], kappa));
+                (uint16_t)pack_bf16x2(__fmul_rn(u[m][i], kappa), 0.0f);
           }
       }
     }
@@ -242,29 +249,27 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 
     // ---- codes ----
     if (tensor == 0) {
-      // K word (m/2): slot 8*(m%2)+i at bits 2*slot
+      // K word (m/2): slot 8*(m%2)+i at bits 2*slot; built from the top slot down by shift-adds
 #pragma unroll
       for (int wq = 0; wq < 2; ++wq) {
         uint32_t word = 0;
 #pragma unroll
-        for (int mm = 0; mm < 2; ++mm)
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int m = 2 * wq + mm;
-            word |= code_of(u[m][i], gq[m / (4 / NG)]) << (2 * (8 * mm + i));
-          }
-        kw[h][wq] = word;
+        for (int slot = 15; slot >= 0; --slot) {
+          const int m = 2 * wq + (slot >> 3), i = slot & 7;
+          word = (word << 2) + code_bits(u[m][i], gq[m / (4 / NG)]);
+        }
+        kw[h][wq] = word - kPack16Bias;
       }
     } else {
-      // V: byte lanes of a partial word: token half h, X (m even) / Y (m odd)
+      // V: byte lanes of a partial word: token half h, X (m even) / Y (m odd); biases removed after both halves
 #pragma unroll
       for (int mp = 0; mp < 2; ++mp)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          uint32_t cx = code_of(u[2 * mp][i], gq[(2 * mp) / (4 / NG)]);
-          uint32_t cy = code_of(u[2 * mp + 1][i], gq[(2 * mp + 1) / (4 / NG)]);
-          uint32_t part = (cx | (cy << 8)) << (16 * h);
-          if (h == 0) vcode[0][mp][i] = part; else vcode[0][mp][i] |= part;
+          const uint32_t bx = code_bits(u[2 * mp][i], gq[(2 * mp) / (4 / NG)]);
+          const uint32_t by = code_bits(u[2 * mp + 1][i], gq[(2 * mp + 1) / (4 / NG)]);
+          const uint32_t part = (by << 8) + bx;
+          if (h == 0) vcode[mp][i] = part; else vcode[mp][i] = (part << 16) + vcode[mp][i];
         }
       if (valid[h]) vmask_part |= 0x0303u << (16 * h);
     }
@@ -305,7 +310,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
     if (mask != 0u) {
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        uint32_t w0 = vcode[0][0][i] << (2 * ii), w1 = vcode[0][1][i] << (2 * ii);
+        uint32_t w0 = (vcode[0][i] - kPack4Bias) << (2 * ii), w1 = (vcode[1][i] - kPack4Bias) << (2 * ii);
         w0 |= dpp_move_u<kRowRor4>(w0);
         w1 |= dpp_move_u<kRowRor4>(w1);
         w0 |= dpp_move_u<kRowRor8>(w0);
