@@ -145,58 +145,51 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   const int t0 = blk * kTokBlock;
   const int t_end = a.T_len + a.n_new;
 
-  // ---- which tokens of this block are salient, and at which overlay slot (rank in the ascending list) ----
+  // ---- issue this wavefront's row loads first: nothing below depends on anything but the block index ----
+  bool valid[2];
+  u32x4 raw[2][4];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int t = t0 + 16 * h + r;
+    valid[h] = (t >= a.T_len) && (t < t_end);
+    const uint16_t *row = src + ((size_t)bh * a.n_new + (valid[h] ? t - a.T_len : 0)) * kD;
+#pragma unroll
+    for (int m = 0; m < 4; ++m)
+      raw[h][m] = valid[h] ? *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j) : (u32x4){0u, 0u, 0u, 0u};
+  }
+
+  // ---- which tokens of this block are salient, and at which overlay slot (rank in the ascending list).
+  // The whole list is scanned with independent, coalesced loads (64 entries per instruction) whose latency overlaps
+  // with the row loads above; a search with dependent loads would serialise several memory round trips per block.
   int *slot_of = slot_of_lds[wave];
+  if (lane < kTokBlock) slot_of[lane] = -1;
+  const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
   int cnt = a.sal_cnt[bh];
   cnt = min(max(cnt, 0), a.S_cap);
-  const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
-  if (lane < kTokBlock) slot_of[lane] = -1;
-  int lb = 0;
-  {
-    int lo = 0, hi = cnt;  // first entry >= t0 (same value in every lane)
-    while (lo < hi) {
-      int mid = (lo + hi) >> 1;
-      if (sidx[mid] < t0) lo = mid + 1; else hi = mid;
-    }
-    lb = lo;
-  }
   wave_lds_sync();
-  if (lane < kTokBlock && lb + lane < cnt) {
-    int e = sidx[lb + lane];
-    if (e >= t0 && e < t0 + kTokBlock) slot_of[e - t0] = lb + lane;
+  for (int base = 0; base < a.S_cap; base += 64) {  // S_cap is a multiple of 64
+    const int e = sidx[base + lane];
+    if (base + lane < cnt && e >= t0 && e < t0 + kTokBlock) slot_of[e - t0] = base + lane;
   }
   wave_lds_sync();
 
   uint32_t kw[2][2];         // K words of token half h: [h][group-of-64 word]
   uint32_t vcode[2][8];      // V: [mpair][i]: raw patterns of (X, Y) x (half 0, half 1) in the four byte lanes
   uint32_t vmask_part = 0;
-  bool valid[2];
   uint32_t meta_out[2][NG];
   int slots[2];
 
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
-    const int t = t0 + 16 * h + r;
-    valid[h] = (t >= a.T_len) && (t < t_end);
     slots[h] = slot_of[16 * h + r];
     float u[4][8];
-    if (valid[h]) {
-      const uint16_t *row = src + ((size_t)bh * a.n_new + (t - a.T_len)) * kD;
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        u32x4 raw = *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j);
+    for (int m = 0; m < 4; ++m)
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          u[m][2 * w] = half_bits_to_float(raw[w] & 0xFFFFu);
-          u[m][2 * w + 1] = half_bits_to_float(raw[w] >> 16);
-        }
+      for (int w = 0; w < 4; ++w) {
+        u[m][2 * w] = half_bits_to_float(raw[h][m][w] & 0xFFFFu);
+        u[m][2 * w + 1] = half_bits_to_float(raw[h][m][w] >> 16);
       }
-    } else {
-#pragma unroll
-      for (int m = 0; m < 4; ++m)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) u[m][i] = 0.0f;
-    }
     if (rotate) wht128_quad(u, j);
 
     // ---- bfloat16 overlay for salient rows (Section III-C.1: salient tokens keep 16-bit precision) ----
