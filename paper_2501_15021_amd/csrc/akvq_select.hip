@@ -54,6 +54,8 @@ __global__ __launch_bounds__(256) void select_tsa_kernel(SelectArgs a) {
 // Logits are kept in the base-2 domain (sm_scale * log2(e) folded into one multiply) so that exponentials are bare
 // v_exp_f32; both passes use the same domain, so the statistics carry over unchanged.
 constexpr int kGroupsPerWave = kScoreChunk / (4 * 16);
+constexpr int kKeyDepth = 1;  // key groups in flight ahead of the one being scored
+static_assert(kGroupsPerWave % (kKeyDepth + 1) == 0, "the scoring loop is unrolled over the key ring");
 
 // binary16 pair (packed) -> bfloat16 pair (packed), each rounded to nearest even
 __device__ __forceinline__ uint32_t half2_to_bf16x2(uint32_t hh) {
@@ -78,48 +80,48 @@ struct KeyGroup {
   u32x4 raw[4];  // 16 keys x 128 channels as this lane's four 8-channel pieces (binary16)
 };
 __device__ __forceinline__ void load_key_group(const uint16_t *k_rows, int t_first, int T, int mrow, int qd, KeyGroup &g) {
-  const int t = t_first + mrow;
+  const int t = min(t_first + mrow, T - 1);  // rows past the end repeat the last key; the causal mask removes them
 #pragma unroll
-  for (int kc = 0; kc < 4; ++kc) {
-    if (t < T) g.raw[kc] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
-    else g.raw[kc] = (u32x4){0u, 0u, 0u, 0u};
-  }
+  for (int kc = 0; kc < 4; ++kc)
+    g.raw[kc] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
 }
 
-// base-2 logits of the W tail rows of one query head against 16 keys: s[rb][i] = row 16*rb + 4*qd + i, key = mrow.
-// Entries the causal mask removes (or keys beyond T) come back as -inf.
+// dot products of the W tail rows of one query head with 16 keys: acc[rb][i] = row 16*rb + 4*qd + i, key = mrow
 template <int NRB>
-__device__ __forceinline__ void score_16keys(const bf16x8 (&a_q)[4][4], const KeyGroup &g, int t_first, int T, int W,
-                                             float scale2, int mrow, int qd, float (&s)[4][4]) {
-  const int t = t_first + mrow;
+__device__ __forceinline__ void score_16keys(const u32x4 *q_lds, const KeyGroup &g, int mrow, int qd, f32x4 (&acc)[4]) {
+  // The query operands live in LDS and are re-read for every key group: the offset is made opaque so the reads are
+  // not hoisted out of the caller's loop into 64 registers (which would cost a wavefront of occupancy).
+  uint32_t lane_off = (uint32_t)(qd * 16 + mrow);
+  asm volatile("" : "+v"(lane_off));
   bf16x8 kb[4];
 #pragma unroll
   for (int kc = 0; kc < 4; ++kc) kb[kc] = rows8_as_bf16(g.raw[kc]);
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
-    f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) acc = mfma_bf16(a_q[rb][kc], kb[kc], acc);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = 16 * rb + 4 * qd + i;
-      const bool seen = t < T && t <= T - W + row;  // causal: row sits at position T-W+row
-      s[rb][i] = seen ? scale2 * acc[i] : -INFINITY;
-    }
-  }
-}
-
-template <int NRB>
-__device__ __forceinline__ void load_query_rows(const uint16_t *q_head, int mrow, int qd, bf16x8 (&a_q)[4][4]) {
-#pragma unroll
-  for (int rb = 0; rb < NRB; ++rb)
+    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
-      a_q[rb][kc] = rows8_as_bf16(
-          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd));
+      acc[rb] = mfma_bf16(__builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), kb[kc], acc[rb]);
+  }
+}
+// causal visibility of key t for tail row `row` (the row sits at position T-W+row); keys past the end are never seen
+__device__ __forceinline__ bool key_seen(int t, int row, int T, int W) { return t < T && t <= T - W + row; }
+// a group of 16 keys starting at t_first needs per-element masking only if it reaches past position T-W
+__device__ __forceinline__ bool group_has_masked(int t_first, int T, int W) { return t_first + 15 > T - W; }
+
+// the W tail rows of one query head as matrix-core A operands in LDS: slot (rb, kc, lane) is what lane (mrow, qd)
+// feeds for row block rb and channel step kc; wavefront w converts row blocks w, w+4, ...
+template <int NRB>
+__device__ __forceinline__ void stage_query_rows(const uint16_t *q_head, int wave, int mrow, int qd, u32x4 *q_lds) {
+  for (int rb = wave; rb < NRB; rb += 4)
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc)
+      q_lds[(rb * 4 + kc) * 64 + qd * 16 + mrow] = __builtin_bit_cast(u32x4, rows8_as_bf16(
+          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd)));
 }
 
 constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLazyRaise = 12.0f;  // a row reference is raised only for logits this far (base 2) above it
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // bare v_exp_f32
 
 // pass 1: per (b, hq, chunk): running max and sum of exponentials (base 2) of every tail row
@@ -131,43 +133,82 @@ __global__ __launch_bounds__(256) void psa_row_stats_kernel(SelectArgs a) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
   const uint16_t *k_rows = a.k + ((size_t)b * a.Hkv + hkv) * a.T * kD;
   const float scale2 = a.sm_scale * kLog2e;
-  bf16x8 a_q[4][4];
-  load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, a_q);
+  __shared__ u32x4 q_lds[NRB * 4 * 64];
+  const int t_wave = chunk * kScoreChunk + wave * (kScoreChunk / 4);
+  // kKeyDepth groups of keys are in flight ahead of the one being scored (a ring of register buffers; loads are
+  // unconditional with clamped addresses, so the wait counts the compiler derives stay exact).  The first keys are
+  // requested before the query rows are staged, so the two latencies overlap.
+  KeyGroup ring[kKeyDepth + 1];
+#pragma unroll
+  for (int p = 0; p < kKeyDepth; ++p) load_key_group(k_rows, t_wave + 16 * p, a.T, mrow, qd, ring[p]);
+  stage_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, wave, mrow, qd, q_lds);
+  __syncthreads();
   float m[4][4], l[4][4];
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb)
 #pragma unroll
     for (int i = 0; i < 4; ++i) { m[rb][i] = -INFINITY; l[rb][i] = 0.0f; }
-  const int t_wave = chunk * kScoreChunk + wave * (kScoreChunk / 4);
-  KeyGroup cur, nxt;
-  load_key_group(k_rows, t_wave, a.T, mrow, qd, cur);
 #pragma unroll
-  for (int kc = 0; kc < 4; ++kc) settle(cur.raw[kc]);
-  for (int g = 0; g < kGroupsPerWave; ++g) {
+  for (int p = 0; p < kKeyDepth; ++p)
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) settle(ring[p].raw[kc]);
+  for (int g0 = 0; g0 < kGroupsPerWave; g0 += kKeyDepth + 1)
+#pragma unroll
+  for (int u = 0; u <= kKeyDepth; ++u) {
+    const int g = g0 + u;
     const int t_first = t_wave + 16 * g;
-    if (t_first >= a.T) break;
-    if (g + 1 < kGroupsPerWave) load_key_group(k_rows, t_first + 16, a.T, mrow, qd, nxt);
-    float s[4][4];
-    score_16keys<NRB>(a_q, cur, t_first, a.T, a.W, scale2, mrow, qd, s);
+    load_key_group(k_rows, t_wave + 16 * min(g + kKeyDepth, kGroupsPerWave - 1), a.T, mrow, qd,
+                   ring[(u + kKeyDepth) % (kKeyDepth + 1)]);
+    if (t_first >= a.T) continue;  // uniform over the wavefront
+    const KeyGroup &cur = ring[u];
+    f32x4 acc[4];
+    score_16keys<NRB>(q_lds, cur, mrow, qd, acc);
+    // m[rb][i] is a reference shared by the 16 lanes (keys) of a row, not the running maximum: it is raised only
+    // when a logit exceeds it by more than kLazyRaise, so in the common case (nothing masked, no such logit) the
+    // sums just grow.  Otherwise (first group, a new large logit, the causal edge) the references are raised to the
+    // row maxima of this group and the sums rescaled.
+    bool slow = group_has_masked(t_first, a.T, a.W);
+    float x[4][4];
+    if (!slow) {
+      float top = -INFINITY;
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+      for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float m_new = fmaxf(m[rb][i], s[rb][i]);
-        const float m_ref = (m_new == -INFINITY) ? 0.0f : m_new;
-        l[rb][i] = l[rb][i] * fast_exp2(m[rb][i] - m_ref) + fast_exp2(s[rb][i] - m_ref);
-        m[rb][i] = m_new;
-      }
-    cur = nxt;
+        for (int i = 0; i < 4; ++i) {
+          x[rb][i] = __builtin_fmaf(acc[rb][i], scale2, -m[rb][i]);
+          top = fmaxf(top, x[rb][i]);
+        }
+      slow = __ballot(!(top <= kLazyRaise)) != 0ull;
+    }
+    if (!slow) {
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) l[rb][i] += fast_exp2(x[rb][i]);
+    } else {
+      int t = t_first + mrow;
+      asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool seen = key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W);
+          const float sv = seen ? scale2 * acc[rb][i] : -INFINITY;
+          const float top = row_max16(sv);
+          if (top > m[rb][i]) {  // uniform over the row's lanes; a reference of -inf goes with a zero sum
+            l[rb][i] *= fast_exp2(m[rb][i] - top);
+            m[rb][i] = top;
+          }
+          if (seen) l[rb][i] += fast_exp2(sv - m[rb][i]);
+        }
+    }
   }
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const float mr = row_max16(m[rb][i]);
-      const float m_ref = (mr == -INFINITY) ? 0.0f : mr;
-      const float lr = row_sum16(l[rb][i] * fast_exp2(m[rb][i] - m_ref));
-      if (mrow == 0) { st_m[wave][16 * rb + 4 * qd + i] = mr; st_l[wave][16 * rb + 4 * qd + i] = lr; }
+      const float lr = row_sum16(l[rb][i]);  // the row's lanes share the reference
+      if (mrow == 0) { st_m[wave][16 * rb + 4 * qd + i] = m[rb][i]; st_l[wave][16 * rb + 4 * qd + i] = lr; }
     }
   __syncthreads();
   if (threadIdx.x < a.W) {
@@ -188,7 +229,8 @@ __global__ __launch_bounds__(256) void psa_row_stats_kernel(SelectArgs a) {
 // pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads and the tail rows of 2^(s - m_row) / l_row
 template <int NRB>
 __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
-  __shared__ float row_m[64], row_il[64];
+  __shared__ __attribute__((aligned(16))) float row_m[64], row_il[64];
+  __shared__ u32x4 q_lds[NRB * 4 * 64];
   const int chunk = blockIdx.x, bh = blockIdx.y;
   const int b = bh / a.Hkv, hkv = bh % a.Hkv, R = a.Hq / a.Hkv;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
@@ -200,6 +242,9 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
   for (int g = 0; g < kGroupsPerWave; ++g) col[g] = 0.0f;
   for (int h = 0; h < R; ++h) {
     const int bhq = b * a.Hq + hkv * R + h;
+    KeyGroup ring[kKeyDepth + 1];  // first keys requested before the row statistics and query rows are staged
+#pragma unroll
+    for (int p = 0; p < kKeyDepth; ++p) load_key_group(k_rows, t_wave + 16 * p, a.T, mrow, qd, ring[p]);
     __syncthreads();
     if (threadIdx.x < a.W) {  // merge the chunk statistics of this row
       const int row = threadIdx.x;
@@ -214,30 +259,41 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
       row_m[row] = mm;
       row_il[row] = 1.0f / ll;
     }
+    stage_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, wave, mrow, qd, q_lds);
     __syncthreads();
-    bf16x8 a_q[4][4];
-    load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, a_q);
-    float rm[4][4], ril[4][4];
 #pragma unroll
-    for (int rb = 0; rb < NRB; ++rb)
+    for (int p = 0; p < kKeyDepth; ++p)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { rm[rb][i] = row_m[16 * rb + 4 * qd + i]; ril[rb][i] = row_il[16 * rb + 4 * qd + i]; }
-    KeyGroup cur, nxt;
-    load_key_group(k_rows, t_wave, a.T, mrow, qd, cur);
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) settle(cur.raw[kc]);
+      for (int kc = 0; kc < 4; ++kc) settle(ring[p].raw[kc]);
 #pragma unroll
     for (int g = 0; g < kGroupsPerWave; ++g) {
       const int t_first = t_wave + 16 * g;
+      load_key_group(k_rows, t_wave + 16 * min(g + kKeyDepth, kGroupsPerWave - 1), a.T, mrow, qd,
+                     ring[(g + kKeyDepth) % (kKeyDepth + 1)]);
       if (t_first < a.T) {  // uniform over the wavefront
-        if (g + 1 < kGroupsPerWave) load_key_group(k_rows, t_first + 16, a.T, mrow, qd, nxt);
-        float s[4][4];
-        score_16keys<NRB>(a_q, cur, t_first, a.T, a.W, scale2, mrow, qd, s);
+        const KeyGroup &cur = ring[g % (kKeyDepth + 1)];
+        f32x4 acc[4];
+        score_16keys<NRB>(q_lds, cur, mrow, qd, acc);
+        uint32_t row_off = (uint32_t)(4 * qd);  // opaque for the same reason as the query operands
+        asm volatile("" : "+v"(row_off));
+        const bool masked = group_has_masked(t_first, a.T, a.W);  // uniform over the wavefront
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
+        for (int rb = 0; rb < NRB; ++rb) {
+          const f32x4 rm = *reinterpret_cast<const f32x4 *>(row_m + 16 * rb + row_off);
+          const f32x4 ril = *reinterpret_cast<const f32x4 *>(row_il + 16 * rb + row_off);
+          if (!masked) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) col[g] += fast_exp2(s[rb][i] - rm[rb][i]) * ril[rb][i];  // 2^-inf = 0 for masked
-        cur = nxt;
+            for (int i = 0; i < 4; ++i)
+              col[g] = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[i])), ril[i], col[g]);
+          } else {
+            int t = t_first + mrow;
+            asm volatile("" : "+v"(t));  // keeps the masks of all groups from being precomputed ahead of the loop
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W))
+                col[g] = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[i])), ril[i], col[g]);
+          }
+        }
       }
     }
   }
@@ -249,6 +305,28 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
     const int t = t_wave + 16 * g + mrow;
     if (qd == 0 && t < a.T) a.mass[(size_t)bh * a.T + t] = c;
   }
+}
+
+// inclusive prefix sum of one int per thread over the 256-thread workgroup, plus the workgroup total
+__device__ __forceinline__ int block_inclusive_scan(int v, int *wave_tot, int &total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int up = __shfl_up(v, off, kWave);
+    if (lane >= off) v += up;
+  }
+  __syncthreads();  // previous use of wave_tot finished
+  if (lane == kWave - 1) wave_tot[wave] = v;
+  __syncthreads();
+  int before = 0, tot = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const int c = wave_tot[w];
+    if (w < wave) before += c;
+    tot += c;
+  }
+  total = tot;
+  return before + v;
 }
 
 // exact top-k of non-negative fp32 keys by radix select; equal keys go to the lower position; output ascending
@@ -272,37 +350,48 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
       if ((bits & hi_mask) == (prefix & hi_mask)) atomicAdd(&hist[(bits >> (8 * pass)) & 0xFF], 1);
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-      int remaining = need, bin = 255;
-      for (; bin > 0; --bin) {
-        if (hist[bin] >= remaining) break;
-        remaining -= hist[bin];
-      }
+    // thread i looks at bin 255-i: the prefix sum over threads is the count of candidates in bins >= that bin; the
+    // digit of the k-th largest key is the first bin (from the top) where that count reaches `need`
+    const int bin = 255 - (int)threadIdx.x;
+    const int mine = hist[bin];
+    int total;
+    const int upto = block_inclusive_scan(mine, wave_tot, total);
+    if (upto >= need && upto - mine < need) {
       sh_prefix = prefix | ((uint32_t)bin << (8 * pass));
-      sh_need = remaining;
+      sh_need = need - (upto - mine);
     }
     __syncthreads();
     prefix = sh_prefix;
     need = sh_need;
-    __syncthreads();
   }
-  // prefix = bit pattern of the k-th largest key; `need` of the keys equal to it are taken, lowest positions first
-  int n_out = 0, n_equal = 0;
-  for (int base = 0; base < a.T; base += 256) {
-    const int t = base + threadIdx.x;
-    const uint32_t bits = t < a.T ? __float_as_uint(mass[t]) : 0u;
-    const bool greater = t < a.T && bits > prefix;
-    const bool equal = t < a.T && bits == prefix;
-    int tot_eq;
-    const int eq_rank = n_equal + block_flag_scan(equal, wave_tot, tot_eq);
-    const bool take = greater || (equal && eq_rank < need);
-    int tot_take;
-    const int pos = n_out + block_flag_scan(take, wave_tot, tot_take);
-    if (take && pos < a.S_cap) out[pos] = t;
-    n_out += tot_take;
-    n_equal += tot_eq;
+  // prefix = bit pattern of the k-th largest key; `need` of the keys equal to it are taken, lowest positions first.
+  // Each thread owns a contiguous run of positions, so two workgroup scans (equal keys, taken keys) order the output.
+  const int per = (a.T + 255) / 256;
+  const int t0 = min((int)threadIdx.x * per, a.T), t1 = min(t0 + per, a.T);
+  int n_eq = 0;
+  for (int t = t0; t < t1; ++t) n_eq += __float_as_uint(mass[t]) == prefix;
+  int tot_eq;
+  int eq_rank = block_inclusive_scan(n_eq, wave_tot, tot_eq) - n_eq;
+  int n_take = 0;
+  {
+    int r = eq_rank;
+    for (int t = t0; t < t1; ++t) {
+      const uint32_t bits = __float_as_uint(mass[t]);
+      n_take += bits > prefix || (bits == prefix && r++ < need);
+    }
   }
-  if (threadIdx.x == 0) a.sal_cnt[bh] = n_out;
+  int tot_take;
+  int pos = block_inclusive_scan(n_take, wave_tot, tot_take) - n_take;
+  if (n_take > 0) {
+    for (int t = t0; t < t1; ++t) {
+      const uint32_t bits = __float_as_uint(mass[t]);
+      if (bits > prefix || (bits == prefix && eq_rank++ < need)) {
+        if (pos < a.S_cap) out[pos] = t;
+        ++pos;
+      }
+    }
+  }
+  if (threadIdx.x == 0) a.sal_cnt[bh] = tot_take;
 }
 
 }  // namespace
@@ -312,26 +401,19 @@ hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream) {
+template <int NRB>
+static void launch_psa_passes(const SelectArgs &a, hipStream_t stream) {
   const dim3 block(256);
-  const dim3 g1(a.n_chunk, a.B * a.Hq), g2(a.n_chunk, a.B * a.Hkv);
+  hipLaunchKernelGGL(psa_row_stats_kernel<NRB>, dim3(a.n_chunk, a.B * a.Hq), block, 0, stream, a);
+  hipLaunchKernelGGL(psa_mass_kernel<NRB>, dim3(a.n_chunk, a.B * a.Hkv), block, 0, stream, a);
+}
+
+hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream) {
   switch (a.W / 16) {
-    case 1:
-      hipLaunchKernelGGL(psa_row_stats_kernel<1>, g1, block, 0, stream, a);
-      hipLaunchKernelGGL(psa_mass_kernel<1>, g2, block, 0, stream, a);
-      break;
-    case 2:
-      hipLaunchKernelGGL(psa_row_stats_kernel<2>, g1, block, 0, stream, a);
-      hipLaunchKernelGGL(psa_mass_kernel<2>, g2, block, 0, stream, a);
-      break;
-    case 3:
-      hipLaunchKernelGGL(psa_row_stats_kernel<3>, g1, block, 0, stream, a);
-      hipLaunchKernelGGL(psa_mass_kernel<3>, g2, block, 0, stream, a);
-      break;
-    default:
-      hipLaunchKernelGGL(psa_row_stats_kernel<4>, g1, block, 0, stream, a);
-      hipLaunchKernelGGL(psa_mass_kernel<4>, g2, block, 0, stream, a);
-      break;
+    case 1: launch_psa_passes<1>(a, stream); break;
+    case 2: launch_psa_passes<2>(a, stream); break;
+    case 3: launch_psa_passes<3>(a, stream); break;
+    default: launch_psa_passes<4>(a, stream); break;
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
