@@ -44,7 +44,7 @@ struct SelectArgs {
   int B, Hq, Hkv, T, W, top_k, S_cap, n_chunk;
   float sm_scale;
 };
-constexpr int kScoreChunk = 1024;  // keys per scoring workgroup
+constexpr int kScoreChunk = 2048;  // keys per scoring workgroup
 hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream);
 

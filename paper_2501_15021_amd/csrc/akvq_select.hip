@@ -237,9 +237,10 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
   const uint16_t *k_rows = a.k + (size_t)bh * a.T * kD;
   const float scale2 = a.sm_scale * kLog2e;
   const int t_wave = chunk * kScoreChunk + wave * (kScoreChunk / 4);
-  float col[kGroupsPerWave];
-#pragma unroll
-  for (int g = 0; g < kGroupsPerWave; ++g) col[g] = 0.0f;
+  // column sums of the chunk, one slot per (row quarter qd, key): every slot has a single owning lane, so the sums
+  // over key groups and over the heads of the group are plain read-add-write in a fixed order
+  __shared__ float col_lds[4 * kScoreChunk];
+  for (int i = threadIdx.x; i < 4 * kScoreChunk; i += 256) col_lds[i] = 0.0f;
   for (int h = 0; h < R; ++h) {
     const int bhq = b * a.Hq + hkv * R + h;
     KeyGroup ring[kKeyDepth + 1];  // first keys requested before the row statistics and query rows are staged
@@ -265,45 +266,49 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
     for (int p = 0; p < kKeyDepth; ++p)
 #pragma unroll
       for (int kc = 0; kc < 4; ++kc) settle(ring[p].raw[kc]);
+    for (int g0 = 0; g0 < kGroupsPerWave; g0 += kKeyDepth + 1)
 #pragma unroll
-    for (int g = 0; g < kGroupsPerWave; ++g) {
+    for (int u = 0; u <= kKeyDepth; ++u) {
+      const int g = g0 + u;
       const int t_first = t_wave + 16 * g;
       load_key_group(k_rows, t_wave + 16 * min(g + kKeyDepth, kGroupsPerWave - 1), a.T, mrow, qd,
-                     ring[(g + kKeyDepth) % (kKeyDepth + 1)]);
-      if (t_first < a.T) {  // uniform over the wavefront
-        const KeyGroup &cur = ring[g % (kKeyDepth + 1)];
-        f32x4 acc[4];
-        score_16keys<NRB>(q_lds, cur, mrow, qd, acc);
-        uint32_t row_off = (uint32_t)(4 * qd);  // opaque for the same reason as the query operands
-        asm volatile("" : "+v"(row_off));
-        const bool masked = group_has_masked(t_first, a.T, a.W);  // uniform over the wavefront
+                     ring[(u + kKeyDepth) % (kKeyDepth + 1)]);
+      if (t_first >= a.T) continue;  // uniform over the wavefront
+      const KeyGroup &cur = ring[u];
+      f32x4 acc[4];
+      score_16keys<NRB>(q_lds, cur, mrow, qd, acc);
+      uint32_t row_off = (uint32_t)(4 * qd);  // opaque for the same reason as the query operands
+      asm volatile("" : "+v"(row_off));
+      const bool masked = group_has_masked(t_first, a.T, a.W);  // uniform over the wavefront
+      float c0 = 0.0f, c1 = 0.0f;  // two chains: even and odd row blocks
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb) {
-          const f32x4 rm = *reinterpret_cast<const f32x4 *>(row_m + 16 * rb + row_off);
-          const f32x4 ril = *reinterpret_cast<const f32x4 *>(row_il + 16 * rb + row_off);
-          if (!masked) {
+      for (int rb = 0; rb < NRB; ++rb) {
+        const f32x4 rm = *reinterpret_cast<const f32x4 *>(row_m + 16 * rb + row_off);
+        const f32x4 ril = *reinterpret_cast<const f32x4 *>(row_il + 16 * rb + row_off);
+        float &c = (rb & 1) ? c1 : c0;
+        if (!masked) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-              col[g] = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[i])), ril[i], col[g]);
-          } else {
-            int t = t_first + mrow;
-            asm volatile("" : "+v"(t));  // keeps the masks of all groups from being precomputed ahead of the loop
+          for (int i = 0; i < 4; ++i)
+            c = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[i])), ril[i], c);
+        } else {
+          int t = t_first + mrow;
+          asm volatile("" : "+v"(t));  // keeps the masks of all groups from being precomputed ahead of the loop
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-              if (key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W))
-                col[g] = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[i])), ril[i], col[g]);
-          }
+          for (int i = 0; i < 4; ++i)
+            if (key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W))
+              c = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[i])), ril[i], c);
         }
       }
+      float *slot = col_lds + qd * kScoreChunk + (t_first - chunk * kScoreChunk) + mrow;
+      *slot += c0 + c1;
     }
   }
-#pragma unroll
-  for (int g = 0; g < kGroupsPerWave; ++g) {
-    float c = col[g];
-    c += __shfl_xor(c, 16, kWave);
-    c += __shfl_xor(c, 32, kWave);
-    const int t = t_wave + 16 * g + mrow;
-    if (qd == 0 && t < a.T) a.mass[(size_t)bh * a.T + t] = c;
+  __syncthreads();
+  for (int i = threadIdx.x; i < kScoreChunk; i += 256) {
+    const int t = chunk * kScoreChunk + i;
+    if (t < a.T)
+      a.mass[(size_t)bh * a.T + t] =
+          (col_lds[i] + col_lds[kScoreChunk + i]) + (col_lds[2 * kScoreChunk + i] + col_lds[3 * kScoreChunk + i]);
   }
 }
 
@@ -329,16 +334,29 @@ __device__ __forceinline__ int block_inclusive_scan(int v, int *wave_tot, int &t
   return before + v;
 }
 
-// exact top-k of non-negative fp32 keys by radix select; equal keys go to the lower position; output ascending
+// exact top-k of non-negative fp32 keys by radix select; equal keys go to the lower position; output ascending.
+// STAGED: the row of keys is copied to LDS once and every pass reads it from there.
+constexpr int kTopkStageMax = 32768;  // keys (128 KB of LDS)
+constexpr int kTopkListMax = 256;     // selected positions ordered through LDS when k is at most this
+template <bool STAGED>
 __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
+  extern __shared__ float keys_lds[];
   __shared__ int hist[256];
   __shared__ int wave_tot[4];
   __shared__ uint32_t sh_prefix;
   __shared__ int sh_need;
-  const int bh = blockIdx.x;
+  __shared__ int list_n;
+  __shared__ int list[kTopkListMax];
+  const int bh = blockIdx.x, lane = threadIdx.x & 63;
   const float *mass = a.mass + (size_t)bh * a.T;
   int32_t *out = a.sal_idx + (size_t)bh * a.S_cap;
   const int k = min(a.top_k, a.T);
+  if (STAGED) {
+    for (int t = threadIdx.x; t < a.T; t += 256) keys_lds[t] = mass[t];
+    if (threadIdx.x == 0) list_n = 0;
+    __syncthreads();
+  }
+  const float *keys = STAGED ? keys_lds : mass;
   uint32_t prefix = 0;
   int need = k;
   for (int pass = 3; pass >= 0; --pass) {
@@ -346,8 +364,18 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
     __syncthreads();
     const uint32_t hi_mask = pass == 3 ? 0u : (0xFFFFFFFFu << (8 * (pass + 1)));
     for (int t = threadIdx.x; t < a.T; t += 256) {
-      const uint32_t bits = __float_as_uint(mass[t]);
-      if ((bits & hi_mask) == (prefix & hi_mask)) atomicAdd(&hist[(bits >> (8 * pass)) & 0xFF], 1);
+      const uint32_t bits = __float_as_uint(keys[t]);
+      if ((bits & hi_mask) == (prefix & hi_mask)) {
+        // the leading digits of the keys of a wavefront mostly coincide: one add for all of them then
+        const int bin = (bits >> (8 * pass)) & 0xFF;
+        const int first = __builtin_amdgcn_readfirstlane(bin);
+        const unsigned long long active = __ballot(true), same = __ballot(bin == first);
+        if (same == active) {
+          if (lane == __ffsll((long long)active) - 1) atomicAdd(&hist[first], __popcll(active));
+        } else {
+          atomicAdd(&hist[bin], 1);
+        }
+      }
     }
     __syncthreads();
     // thread i looks at bin 255-i: the prefix sum over threads is the count of candidates in bins >= that bin; the
@@ -359,24 +387,41 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
     if (upto >= need && upto - mine < need) {
       sh_prefix = prefix | ((uint32_t)bin << (8 * pass));
       sh_need = need - (upto - mine);
+      if (pass == 0) hist[0] = mine;  // number of keys equal to the k-th largest (bin 0's own count is not needed again)
     }
     __syncthreads();
     prefix = sh_prefix;
     need = sh_need;
   }
   // prefix = bit pattern of the k-th largest key; `need` of the keys equal to it are taken, lowest positions first.
-  // Each thread owns a contiguous run of positions, so two workgroup scans (equal keys, taken keys) order the output.
+  const int n_equal = hist[0];
+  if (STAGED && k <= kTopkListMax && n_equal == need) {
+    // every key >= prefix is taken: gather their positions in any order, then order the short list by rank
+    for (int t = threadIdx.x; t < a.T; t += 256)
+      if (__float_as_uint(keys[t]) >= prefix) list[atomicAdd(&list_n, 1)] = t;
+    __syncthreads();
+    if ((int)threadIdx.x < k) {
+      const int mine = list[threadIdx.x];
+      int rank = 0;
+      for (int j = 0; j < k; ++j) rank += list[j] < mine;
+      if (rank < a.S_cap) out[rank] = mine;
+    }
+    if (threadIdx.x == 0) a.sal_cnt[bh] = k;
+    return;
+  }
+  // general case: each thread owns a contiguous run of positions, so two workgroup scans (equal keys, taken keys)
+  // order the output
   const int per = (a.T + 255) / 256;
   const int t0 = min((int)threadIdx.x * per, a.T), t1 = min(t0 + per, a.T);
   int n_eq = 0;
-  for (int t = t0; t < t1; ++t) n_eq += __float_as_uint(mass[t]) == prefix;
+  for (int t = t0; t < t1; ++t) n_eq += __float_as_uint(keys[t]) == prefix;
   int tot_eq;
   int eq_rank = block_inclusive_scan(n_eq, wave_tot, tot_eq) - n_eq;
   int n_take = 0;
   {
     int r = eq_rank;
     for (int t = t0; t < t1; ++t) {
-      const uint32_t bits = __float_as_uint(mass[t]);
+      const uint32_t bits = __float_as_uint(keys[t]);
       n_take += bits > prefix || (bits == prefix && r++ < need);
     }
   }
@@ -384,7 +429,7 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   int pos = block_inclusive_scan(n_take, wave_tot, tot_take) - n_take;
   if (n_take > 0) {
     for (int t = t0; t < t1; ++t) {
-      const uint32_t bits = __float_as_uint(mass[t]);
+      const uint32_t bits = __float_as_uint(keys[t]);
       if (bits > prefix || (bits == prefix && eq_rank++ < need)) {
         if (pos < a.S_cap) out[pos] = t;
         ++pos;
@@ -417,7 +462,16 @@ hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(topk_kernel, dim3(a.B * a.Hkv), dim3(256), 0, stream, a);
+  if (a.T <= kTopkStageMax) {
+    const size_t lds = (size_t)a.T * sizeof(float);
+    if (lds > 48 * 1024) {  // large dynamic LDS has to be opted into
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, a);
+  } else
+    hipLaunchKernelGGL(topk_kernel<false>, dim3(a.B * a.Hkv), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
