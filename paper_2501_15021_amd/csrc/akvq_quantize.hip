@@ -26,14 +26,54 @@ constexpr int kQuadXor2 = 0x4E;  // quad_perm [2,3,0,1]
 constexpr int kRowRor4 = 0x124;  // rotate right by 4 inside a row of 16 lanes
 constexpr int kRowRor8 = 0x128;
 
-// A cross-lane butterfly level: the lane whose index bit is clear keeps a+b, its partner keeps a-b.  Each lane adds
-// its partner's value to its own value with the sign bit flipped where the bit is set; the flip is exact, so the
-// single rounding is that of the add, as the specification of the transform requires.
-// un-normalised 128-point butterfly over u[4][8] (m, i) with the j index spread over the quad
-__device__ __forceinline__ void wht128_quad(float (&u)[4][8], int j) {
-  // strides 1, 2, 4: inside i
+// A cross-lane butterfly level: the lane whose index bit is clear keeps a+b, its partner should keep a-b (a = the
+// lower lane's value).  One DPP multiply-add per element does it: own += c * partner with c = +1 in the lower lane and
+// -1 in the upper one.  The product is exact and the sum is rounded once, exactly like the add of the specification;
+// the upper lane ends up with b-a, i.e. the negated result, and since every later level is linear that lane simply
+// carries all its values negated from then on (rounding to nearest is symmetric in sign).  After both cross-lane
+// levels lanes j = 1, 2 hold negated values; quad_sign(j) is folded into the per-lane constants that consume them.
+__device__ __forceinline__ float quad_sign(int j) { return (j == 1 || j == 2) ? -1.0f : 1.0f; }
+
+// Eight elements of one level.  The leading s_nop covers the wait states a DPP read needs after the VALU write of
+// its source register (and after an EXEC write): the compiler does not track hazards of inline assembly.
+#define AKVQ_DPP_FMAC8(CTRL, NOP)                                                                              \
+  asm volatile("s_nop " NOP "\n\t"                                                                            \
+               "v_fmac_f32_dpp %0, %0, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+               "v_fmac_f32_dpp %1, %1, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+               "v_fmac_f32_dpp %2, %2, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+               "v_fmac_f32_dpp %3, %3, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+               "v_fmac_f32_dpp %4, %4, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+               "v_fmac_f32_dpp %5, %5, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+               "v_fmac_f32_dpp %6, %6, %8 " CTRL " row_mask:0xf bank_mask:0xf\n\t"                            \
+               "v_fmac_f32_dpp %7, %7, %8 " CTRL " row_mask:0xf bank_mask:0xf"                                \
+               : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7]) \
+               : "v"(c))
+__device__ __forceinline__ void quad_level_xor1(float (&x)[8], float c, bool first) {
+  if (first) AKVQ_DPP_FMAC8("quad_perm:[1,0,3,2]", "4"); else AKVQ_DPP_FMAC8("quad_perm:[1,0,3,2]", "1");
+}
+__device__ __forceinline__ void quad_level_xor2(float (&x)[8], float c, bool first) {
+  if (first) AKVQ_DPP_FMAC8("quad_perm:[2,3,0,1]", "4"); else AKVQ_DPP_FMAC8("quad_perm:[2,3,0,1]", "1");
+}
+#undef AKVQ_DPP_FMAC8
+
+// First level (stride 1) straight from the packed binary16 pair: lo + hi and lo - hi, each one mixed-precision
+// multiply-add (the widening is exact, the sum is rounded once, as widening followed by an fp32 add would be).
+__device__ __forceinline__ void level1_from_half2(uint32_t w, float &sum, float &diff) {
+  asm("v_fma_mix_f32 %0, %1, 1.0, %1 op_sel:[0,0,1] op_sel_hi:[1,0,1]" : "=v"(sum) : "v"(w));
+  asm("v_fma_mix_f32 %0, %1, 1.0, -%1 op_sel:[0,0,1] op_sel_hi:[1,0,1]" : "=v"(diff) : "v"(w));
+}
+
+// un-normalised 128-point butterfly of one row held as raw[m] (eight binary16 channels 32m+8j..+7 per m) with the j
+// index spread over the quad; the result in lane j is quad_sign(j) times the transform
+__device__ __forceinline__ void wht128_quad(const u32x4 (&raw)[4], float (&u)[4][8], int j) {
+  // stride 1
 #pragma unroll
-  for (int h = 1; h < 8; h *= 2)
+  for (int m = 0; m < 4; ++m)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) level1_from_half2(raw[m][w], u[m][2 * w], u[m][2 * w + 1]);
+  // strides 2, 4: inside i
+#pragma unroll
+  for (int h = 2; h < 8; h *= 2)
 #pragma unroll
     for (int m = 0; m < 4; ++m)
 #pragma unroll
@@ -43,27 +83,12 @@ __device__ __forceinline__ void wht128_quad(float (&u)[4][8], int j) {
           u[m][i] = a + b;
           u[m][i + h] = a - b;
         }
-  // strides 8, 16: across the quad (j bit 0, j bit 1).  All sign flips of a level are issued before its
-  // DPP adds so that no add reads a register written by the instruction just before it (no hazard stalls).
-  const uint32_t s1 = (j & 1) ? 0x80000000u : 0u;
-  const uint32_t s2 = (j & 2) ? 0x80000000u : 0u;
-  float sg[4][8];
+  // strides 8, 16: across the quad (j bit 0, j bit 1)
+  const float c1 = (j & 1) ? -1.0f : 1.0f, c2 = (j & 2) ? -1.0f : 1.0f;
 #pragma unroll
-  for (int m = 0; m < 4; ++m)
+  for (int m = 0; m < 4; ++m) quad_level_xor1(u[m], c1, m == 0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) sg[m][i] = __uint_as_float(__float_as_uint(u[m][i]) ^ s1);
-#pragma unroll
-  for (int m = 0; m < 4; ++m)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) u[m][i] = dpp_move<kQuadXor1>(u[m][i]) + sg[m][i];
-#pragma unroll
-  for (int m = 0; m < 4; ++m)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) sg[m][i] = __uint_as_float(__float_as_uint(u[m][i]) ^ s2);
-#pragma unroll
-  for (int m = 0; m < 4; ++m)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) u[m][i] = dpp_move<kQuadXor2>(u[m][i]) + sg[m][i];
+  for (int m = 0; m < 4; ++m) quad_level_xor2(u[m], c2, m == 0);
   // strides 32, 64: inside m
 #pragma unroll
   for (int h = 1; h < 4; h *= 2)
@@ -142,6 +167,8 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   const uint16_t *src = tensor == 0 ? a.k_new : a.v_new;
   const bool rotate = tensor == 0 ? true : (a.rotate_v != 0);
   const float kappa = rotate ? inv_sqrt128() : 1.0f;
+  const float lane_sign = rotate ? quad_sign(j) : 1.0f;  // this lane holds lane_sign * (transformed values)
+  const float kappa_s = lane_sign * kappa;
   const int t0 = blk * kTokBlock;
   const int t_end = a.T_len + a.n_new;
 
@@ -182,15 +209,18 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     slots[h] = slot_of[16 * h + r];
-    float u[4][8];
+    float u[4][8];  // lane_sign times the (rotated) row
+    if (rotate) {
+      wht128_quad(raw[h], u, j);
+    } else {
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
+      for (int m = 0; m < 4; ++m)
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        u[m][2 * w] = half_bits_to_float(raw[h][m][w] & 0xFFFFu);
-        u[m][2 * w + 1] = half_bits_to_float(raw[h][m][w] >> 16);
-      }
-    if (rotate) wht128_quad(u, j);
+        for (int w = 0; w < 4; ++w) {
+          u[m][2 * w] = half_bits_to_float(raw[h][m][w] & 0xFFFFu);
+          u[m][2 * w + 1] = half_bits_to_float(raw[h][m][w] >> 16);
+        }
+    }
 
     // ---- bfloat16 overlay for salient rows (Section III-C.1: salient tokens keep 16-bit precision) ----
     if (valid[h] && slots[h] >= 0) {
@@ -202,7 +232,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           u32x4 o;
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            o[w] = pack_bf16x2(__fmul_rn(u[m][2 * w], kappa), __fmul_rn(u[m][2 * w + 1], kappa));
+            o[w] = pack_bf16x2(__fmul_rn(u[m][2 * w], kappa_s), __fmul_rn(u[m][2 * w + 1], kappa_s));
           *reinterpret_cast<u32x4 *>(dst + 32 * m + 8 * j) = o;
         }
       } else {
@@ -214,7 +244,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           for (int i = 0; i < 8; ++i) {
             const int e = 32 * m + 8 * j + i, nb = e >> 4, n = e & 15;
             plane[(size_t)sb * 4096 + nb * 512 + (16 * sq + n) * 8 + 2 * sii + sh] =
-                (uint16_t)pack_bf16x2(__fmul_rn(u[m][i], kappa), 0.0f);
+                (uint16_t)pack_bf16x2(__fmul_rn(u[m][i], kappa_s), 0.0f);
           }
       }
     }
@@ -232,11 +262,17 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           mn = fminf(mn, u[m][i]);
           mx = fmaxf(mx, u[m][i]);
         }
+      if (lane_sign < 0.0f) {  // extrema of the true values
+        const float t = mn;
+        mn = -mx;
+        mx = -t;
+      }
       mn = fminf(mn, dpp_move<kQuadXor1>(mn));
       mx = fmaxf(mx, dpp_move<kQuadXor1>(mx));
       mn = fminf(mn, dpp_move<kQuadXor2>(mn));
       mx = fmaxf(mx, dpp_move<kQuadXor2>(mx));
       gq[g] = group_params(mn, mx, kappa, a.clip);
+      gq[g].rcpu *= lane_sign;  // codes are taken from the signed values this lane holds
       meta_out[h][g] = gq[g].meta | (slots[h] >= 0 ? 0x8000u : 0u);
     }
 
