@@ -172,31 +172,45 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   const int t0 = blk * kTokBlock;
   const int t_end = a.T_len + a.n_new;
 
-  // ---- issue this wavefront's row loads first: nothing below depends on anything but the block index ----
+  // ---- which tokens of this block are salient, and at which overlay slot (rank in the ascending list).
+  // The list is ascending, so the block's entries are one contiguous run of at most 32.  Lane l samples entry
+  // l*stride; the number of samples below the block start locates the run within one stride, and a second load of
+  // 64 consecutive entries covers it.  Lists of up to 64 entries need the first load only.  Both loads are
+  // independent of the row loads, which are issued in between so that all latencies overlap.
+  int *slot_of = slot_of_lds[wave];
+  const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+  int cnt = a.sal_cnt[bh];
+  cnt = min(max(cnt, 0), a.S_cap);
+  const int stride = (cnt + 63) >> 6;
+  int e1 = 0x7FFFFFFF;
+  if (lane * stride < cnt) e1 = sidx[lane * stride];
+
   bool valid[2];
   u32x4 raw[2][4];
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int t = t0 + 16 * h + r;
     valid[h] = (t >= a.T_len) && (t < t_end);
-    const uint16_t *row = src + ((size_t)bh * a.n_new + (valid[h] ? t - a.T_len : 0)) * kD;
+    // rows outside the appended range read a clamped (valid) address; nothing derived from them is stored
+    const uint16_t *row = src + ((size_t)bh * a.n_new + min(max(t - a.T_len, 0), a.n_new - 1)) * kD;
 #pragma unroll
-    for (int m = 0; m < 4; ++m)
-      raw[h][m] = valid[h] ? *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j) : (u32x4){0u, 0u, 0u, 0u};
+    for (int m = 0; m < 4; ++m) raw[h][m] = *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j);
   }
 
-  // ---- which tokens of this block are salient, and at which overlay slot (rank in the ascending list).
-  // The whole list is scanned with independent, coalesced loads (64 entries per instruction) whose latency overlaps
-  // with the row loads above; a search with dependent loads would serialise several memory round trips per block.
-  int *slot_of = slot_of_lds[wave];
   if (lane < kTokBlock) slot_of[lane] = -1;
-  const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
-  int cnt = a.sal_cnt[bh];
-  cnt = min(max(cnt, 0), a.S_cap);
   wave_lds_sync();
-  for (int base = 0; base < a.S_cap; base += 64) {  // S_cap is a multiple of 64
-    const int e = sidx[base + lane];
-    if (base + lane < cnt && e >= t0 && e < t0 + kTokBlock) slot_of[e - t0] = base + lane;
+  if (stride <= 1) {
+    if (e1 >= t0 && e1 < t0 + kTokBlock) slot_of[e1 - t0] = lane;
+  } else if (stride <= 32) {
+    const int below = __popcll(__ballot(e1 < t0));  // samples before the block: the run starts after the last of them
+    const int idx = max(below - 1, 0) * stride + lane;
+    const int e2 = idx < cnt ? sidx[idx] : 0x7FFFFFFF;
+    if (e2 >= t0 && e2 < t0 + kTokBlock) slot_of[e2 - t0] = idx;
+  } else {
+    for (int base = 0; base < cnt; base += 64) {
+      const int e = base + lane < cnt ? sidx[base + lane] : 0x7FFFFFFF;
+      if (e >= t0 && e < t0 + kTokBlock) slot_of[e - t0] = base + lane;
+    }
   }
   wave_lds_sync();
 

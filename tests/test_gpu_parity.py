@@ -92,6 +92,24 @@ def test_quantize_append_bit_exact(orc, G, T, clip, fill):
     assert_cache_equal(oc, gc, f"G={G} T={T}")
 
 
+@pytest.mark.parametrize("T,every", [(700, 3), (2304, 1), (1500, 7)])
+def test_quantize_long_salient_lists(orc, T, every):
+    """Salient lists longer than one wavefront: the kernel locates a block's run of entries by sampling the list
+    (and by a plain scan beyond 2048 entries); slots and overlay rows must still match the oracle exactly."""
+    w = synth.small(f"qlist{T}", B=1, Hq=2, Hkv=2, T=T, G=128)
+    d = _np(synth.generate(w, seed=77 + T))
+    mask = np.zeros((w.B, T), dtype=np.uint8)
+    mask[:, ::every] = 1
+    mask[:, 5:40] = 1  # a dense run inside the first blocks
+    n_sal = int(mask[0].sum())
+    oc, gc = make_pair(orc, w, t_cap=(T + 63) // 64 * 64, s_cap=(n_sal + 63) // 64 * 64)
+    oc.select_tsa(mask)
+    copy_salient_to_gpu(oc, gc)
+    oc.quantize_append(d["k"], d["v"], 0.8)
+    akvq.quantize_append(gc, _dev(d["k"]), _dev(d["v"]), 0.8)
+    assert_cache_equal(oc, gc, f"T={T} every={every} salient={n_sal}")
+
+
 def test_quantize_append_in_pieces_and_single_rows(orc):
     w = synth.small("pieces", B=1, Hq=2, Hkv=2, T=100, G=64)
     d = _np(synth.generate(w, seed=103))
