@@ -169,6 +169,43 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   const ExpandK ex;
   auto &w_lds = w_lds_all[wave];  // [blk][group][term][slot]
 
+  // ---- tile bookkeeping and the first two tiles' loads come first: they do not depend on the query, so their
+  // latency overlaps with the query rotation below ----
+  const int n_tiles = (a.T_len + 63) / 64;
+  const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
+  const int tile_begin = split * tiles_per_split;
+  const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
+  const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
+  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
+  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
+  const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + lane) * NG;
+  const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + lane) * NG;
+
+  auto load_tile = [&](int tile, MhaTile<NG> &t) {
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2) {
+      t.kc[b2] = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)(2 * tile + b2) * kBlockWords);
+      t.vc[b2] = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)(2 * tile + b2) * kBlockWords);
+    }
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+      t.km[g] = km_base[(size_t)tile * 64 * NG + g];
+      t.vm[g] = vm_base[(size_t)tile * 64 * NG + g];
+    }
+  };
+
+  // Three tile buffers: while tile k is consumed, the loads of tiles k+1 and k+2 are in flight.  Loads are issued
+  // unconditionally (the index is clamped to the wavefront's last tile) so that the number of outstanding loads is
+  // the same on every path and the waits inside the loop count exactly two tiles of loads.
+  const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
+  const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
+  auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
+  MhaTile<NG> tb[3];
+  if (n_mine > 0) {
+    load_tile(tile_at(0), tb[0]);
+    load_tile(tile_at(1), tb[1]);
+  }
+
   if (tid < 64) zero16[tid] = 0;
   if (tid < kD) { q_digit[3][tid] = 0; q_plain[3][tid] = 0; }
   if (wave == 0) rotate_query_lds(a.q + (size_t)bh * kD, qf, lane);
@@ -258,36 +295,6 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   };
 
   // ================= code stream =================
-  const int n_tiles = (a.T_len + 63) / 64;
-  const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
-  const int tile_begin = split * tiles_per_split;
-  const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
-  const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
-  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
-  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
-  const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + lane) * NG;
-  const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + lane) * NG;
-
-  auto load_tile = [&](int tile, MhaTile<NG> &t) {
-#pragma unroll
-    for (int b2 = 0; b2 < 2; ++b2) {
-      t.kc[b2] = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)(2 * tile + b2) * kBlockWords);
-      t.vc[b2] = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)(2 * tile + b2) * kBlockWords);
-    }
-#pragma unroll
-    for (int g = 0; g < NG; ++g) {
-      t.km[g] = km_base[(size_t)tile * 64 * NG + g];
-      t.vm[g] = vm_base[(size_t)tile * 64 * NG + g];
-    }
-  };
-
-  // Three tile buffers: while tile k is consumed, the loads of tiles k+1 and k+2 are in flight.  Loads are issued
-  // unconditionally (the index is clamped to the wavefront's last tile) so that the number of outstanding loads is
-  // the same on every path and the waits inside the loop count exactly two tiles of loads.
-  const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
-  const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
-  auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
-  MhaTile<NG> tb[3];
   auto process = [&](const MhaTile<NG> &cur, int tile) {
     const int t = tile * 64 + lane;
 
@@ -354,8 +361,6 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     }
   };
   if (n_mine > 0) {
-    load_tile(tile_at(0), tb[0]);
-    load_tile(tile_at(1), tb[1]);
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
 #pragma unroll
