@@ -21,25 +21,26 @@ namespace {
 constexpr int kWaves = 4;  // wavefronts per workgroup
 
 // ------------------------------------------------------------------------------------------------
-// Rotate a query (orthonormal 128-point Walsh-Hadamard, Section III-C.2) inside one wavefront, through LDS.
+// Orthonormal 128-point Walsh-Hadamard transform (Section III-C.2) of a vector held by one wavefront, two elements
+// per lane: x0 = element `lane`, x1 = element `lane + 64`.  Strides 1..32 exchange lanes, stride 64 stays in the lane.
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *qf, int lane) {
-  uint32_t two = reinterpret_cast<const uint32_t *>(q_row)[lane];
-  qf[2 * lane] = half_bits_to_float(two & 0xFFFFu);
-  qf[2 * lane + 1] = half_bits_to_float(two >> 16);
-  wave_lds_sync();
+__device__ __forceinline__ void wht128_wave(float &x0, float &x1, int lane) {
 #pragma unroll
-  for (int h = 1; h < kD; h *= 2) {
-    int i = ((lane / h) * 2 * h) + (lane % h);
-    float x = qf[i], y = qf[i + h];
-    wave_lds_sync();
-    qf[i] = x + y;
-    qf[i + h] = x - y;
-    wave_lds_sync();
+  for (int h = 1; h < kWave; h *= 2) {
+    const float p0 = __shfl_xor(x0, h, kWave), p1 = __shfl_xor(x1, h, kWave);
+    x0 = (lane & h) ? p0 - x0 : x0 + p0;
+    x1 = (lane & h) ? p1 - x1 : x1 + p1;
   }
-  qf[lane] *= inv_sqrt128();
-  qf[lane + 64] *= inv_sqrt128();
-  wave_lds_sync();
+  const float s = x0 + x1, d = x0 - x1;
+  x0 = s * inv_sqrt128();
+  x1 = d * inv_sqrt128();
+}
+// rotate a query row inside one wavefront and leave it in LDS (the caller synchronises before other waves read it)
+__device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *qf, int lane) {
+  float x0 = half_bits_to_float(q_row[lane]), x1 = half_bits_to_float(q_row[lane + 64]);
+  wht128_wave(x0, x1, lane);
+  qf[lane] = x0;
+  qf[lane + 64] = x1;
 }
 
 // exponent k of the 4^k factor that the expansion attaches to channel e of a K row (see the K block layout:
@@ -117,23 +118,13 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
   return (lane_bcast(v, 0) + lane_bcast(v, 16)) + (lane_bcast(v, 32) + lane_bcast(v, 48));
 }
 
-// Final step shared by both kernels: thread d < 128 holds the merged, normalised o~[d]; rotate back through
-// LDS (every thread of the workgroup takes part in the barriers) and store.
-__device__ __forceinline__ void unrotate_store(float o, float *buf, float *out_row, bool out_rotated, int tid) {
-  if (!out_rotated) {
-    if (tid < kD) buf[tid] = o;
-    __syncthreads();
-#pragma unroll
-    for (int h = 1; h < kD; h *= 2) {
-      float mine = 0.f, other = 0.f;
-      if (tid < kD) { mine = buf[tid]; other = buf[tid ^ h]; }
-      __syncthreads();
-      if (tid < kD) buf[tid] = (tid & h) ? (other - mine) : (mine + other);
-      __syncthreads();
-    }
-    if (tid < kD) o = buf[tid] * inv_sqrt128();
-  }
-  if (tid < kD) out_row[tid] = o;
+// Final step: `row` (LDS, 128 floats, complete and visible to this wavefront) is the merged, normalised o~; rotate
+// it back (H is its own inverse) unless the caller wants it rotated, and store.  One wavefront does the whole row.
+__device__ __forceinline__ void unrotate_store_wave(const float *row, float *out_row, bool out_rotated, int lane) {
+  float x0 = row[lane], x1 = row[lane + 64];
+  if (!out_rotated) wht128_wave(x0, x1, lane);
+  out_row[lane] = x0;
+  out_row[lane + 64] = x1;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -391,9 +382,17 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
     for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
       const int s_lane = unit * 64 + lane;
+      // only the token groups (16 slots) and blocks (32 slots) that hold rows are touched; the first block of value
+      // rows and the positions are requested together with the key rows so that the phase costs one round trip
+      const int n_grp = min(4, (cnt - unit * 64 + 15) >> 4), n_blk = min(2, (cnt - unit * 64 + 31) >> 5);
+      const int pos_lane = sidx[min(s_lane, a.S_cap - 1)];
+      u32x4 vb0[8];
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb)
+        vb0[nb] = *reinterpret_cast<const u32x4 *>(vs_base + (size_t)(unit * 2) * 4096 + nb * 512 + (16 * qd + mrow) * 8);
       f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
-      for (int g = 0; g < 4; ++g) {  // one token group at a time keeps the register footprint of this phase small
+      for (int g = 0; g < n_grp; ++g) {  // one token group at a time keeps the register footprint of this phase small
         const int term = mrow - 4 * g;
         const uint16_t *ap = &q_plain[(term >= 0 && term < 3) ? term : 3][8 * qd];
 #pragma unroll
@@ -404,7 +403,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
         }
       }
       const float score = sm2 * (acc[0] + acc[1] + acc[2]);
-      const bool ok = (s_lane < cnt) && (sidx[min(s_lane, a.S_cap - 1)] < a.T_len);
+      const bool ok = (s_lane < cnt) && (pos_lane < a.T_len);
       float p;
       if (!softmax_step(score, ok, p)) continue;
       {
@@ -416,6 +415,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
       wave_lds_sync();
 #pragma unroll
       for (int b2 = 0; b2 < 2; ++b2) {
+        if (b2 >= n_blk) break;
         const uint16_t *src = mrow < 2 ? &w_lds[b2][0][mrow][8 * qd] : zero16;
         const bf16x8 a_v = *reinterpret_cast<const bf16x8 *>(src);
         // which of this lane's 8 K-slots (pair i, half) are real rows: mask the others (unwritten memory)
@@ -427,8 +427,9 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
         }
 #pragma unroll
         for (int nb = 0; nb < 8; ++nb) {
-          u32x4 vb = *reinterpret_cast<const u32x4 *>(
-              vs_base + (size_t)(unit * 2 + b2) * 4096 + nb * 512 + (16 * qd + mrow) * 8);
+          u32x4 vb = vb0[nb];
+          if (b2 == 1)
+            vb = *reinterpret_cast<const u32x4 *>(vs_base + (size_t)(unit * 2 + 1) * 4096 + nb * 512 + (16 * qd + mrow) * 8);
 #pragma unroll
           for (int i = 0; i < 4; ++i) vb[i] &= keep[i];
           acc_o[nb] = mfma_bf16(a_v, __builtin_bit_cast(bf16x8, vb), acc_o[nb]);
@@ -466,9 +467,10 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     }
   }
   if (a.n_split == 1) {
-    if (tid < kD) o = o / l_all;
-    unrotate_store(o, qf, a.out + (size_t)bh * kD, a.out_rotated != 0, tid);
+    if (tid < kD) qf[tid] = o / l_all;  // the query is no longer needed: its buffer carries the row to wavefront 0
     if (a.lse && tid == 0) a.lse[bh] = (m_all + __log2f(l_all)) * kLn2;
+    __syncthreads();
+    if (wave == 0) unrotate_store_wave(qf, a.out + (size_t)bh * kD, a.out_rotated != 0, lane);
   } else if (tid < kD) {
     float *dst = a.partial + ((size_t)bh * a.n_split + split) * kPartialStride;
     if (tid == 0) { dst[0] = m_all; dst[1] = l_all; }
@@ -751,21 +753,33 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
     for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
+      // the value rows and the positions are requested together with the key rows (one round trip for the phase);
+      // a token group (16 slots) without rows is not read
+      const int n_grp = min(2, (cnt - unit * 32 + 15) >> 4);
+      int pos_lane[2];
+#pragma unroll
+      for (int tg = 0; tg < 2; ++tg) pos_lane[tg] = sidx[min(unit * 32 + 16 * tg + mrow, a.S_cap - 1)];
+      u32x4 vb_all[8];
+#pragma unroll
+      for (int nb = 0; nb < 8; ++nb)
+        vb_all[nb] = *reinterpret_cast<const u32x4 *>(vs_base + (size_t)unit * 4096 + nb * 512 + (16 * qd + mrow) * 8);
       float sc[2][2];
       bool ok[2];
 #pragma unroll
       for (int tg = 0; tg < 2; ++tg) {
         f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
         const int s_lane = unit * 32 + 16 * tg + mrow;
+        if (tg < n_grp) {
 #pragma unroll
-        for (int kc = 0; kc < 4; ++kc) {
-          const bf16x8 kb =
-              *reinterpret_cast<const bf16x8 *>(ks_base + (size_t)s_lane * kD + 32 * kc + 8 * qd);
-          acc = mfma_bf16(a_s[kc], kb, acc);
+          for (int kc = 0; kc < 4; ++kc) {
+            const bf16x8 kb =
+                *reinterpret_cast<const bf16x8 *>(ks_base + (size_t)s_lane * kD + 32 * kc + 8 * qd);
+            acc = mfma_bf16(a_s[kc], kb, acc);
+          }
         }
         sc[0][tg] = sm2 * (acc[0] + acc[1]);
         sc[1][tg] = sm2 * (acc[2] + acc[3]);
-        ok[tg] = (s_lane < cnt) && (sidx[min(s_lane, a.S_cap - 1)] < a.T_len);
+        ok[tg] = (s_lane < cnt) && (pos_lane[tg] < a.T_len);
       }
       float p[2][2];
       softmax_step(sc, ok, p);
@@ -788,7 +802,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       }
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb) {
-        u32x4 vb = *reinterpret_cast<const u32x4 *>(vs_base + (size_t)unit * 4096 + nb * 512 + (16 * qd + mrow) * 8);
+        u32x4 vb = vb_all[nb];
 #pragma unroll
         for (int i = 0; i < 4; ++i) vb[i] &= keep[i];
         acc_o[nb] = mfma_bf16(a_v, __builtin_bit_cast(bf16x8, vb), acc_o[nb]);
@@ -812,7 +826,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     }
   }
   __syncthreads();
-  for (int h = 0; h < R; ++h) {  // uniform trip count: the barriers inside unrotate_store are reached by all threads
+  for (int h = 0; h < R; ++h) {
     float m_all = -INFINITY, l_all = 0.0f, o = 0.0f;
     if (tid < kD) {
 #pragma unroll
@@ -827,15 +841,18 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     }
     const size_t bhq = (size_t)b * a.Hq + hkv * R + h;
     if (a.n_split == 1) {
-      if (tid < kD) o = o / l_all;
-      __syncthreads();  // qf[0] is reused as the rotation buffer
-      unrotate_store(o, qf[0], a.out + bhq * kD, a.out_rotated != 0, tid);
+      if (tid < kD) qf[h][tid] = o / l_all;  // the queries are no longer needed: their buffers carry the rows
       if (a.lse && tid == 0) a.lse[bhq] = (m_all + __log2f(l_all)) * kLn2;
     } else if (tid < kD) {
       float *dst = a.partial + (bhq * a.n_split + split) * kPartialStride;
       if (tid == 0) { dst[0] = m_all; dst[1] = l_all; }
       dst[4 + tid] = o;
     }
+  }
+  if (a.n_split == 1) {
+    __syncthreads();
+    for (int h = wave; h < R; h += kWaves)
+      unrotate_store_wave(qf[h], a.out + ((size_t)b * a.Hq + hkv * R + h) * kD, a.out_rotated != 0, lane);
   }
 }
 
@@ -857,9 +874,10 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
     l_all += wgt * part[(size_t)s * kPartialStride + 1];
     o += wgt * part[(size_t)s * kPartialStride + 4 + d];
   }
-  o = o / l_all;
-  unrotate_store(o, of, a.out + (size_t)bhq * kD, a.out_rotated != 0, d);
+  of[d] = o / l_all;
   if (a.lse && d == 0) a.lse[bhq] = (m_all + __log2f(l_all)) * kLn2;
+  __syncthreads();
+  if (d < kWave) unrotate_store_wave(of, a.out + (size_t)bhq * kD, a.out_rotated != 0, d);
 }
 
 }  // namespace
