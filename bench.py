@@ -22,6 +22,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+# HBM bytes per launch counted by rocprofv3 (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, factors from a 1 GiB copy),
+# mean over the 32 layers of cfg2; the runs and the raw figures are in profiles/bench_cfg2_kernel_trace.md.
+# Reported as roofline.traffic for that workload only; other workloads report null.
+MEASURED_TRAFFIC_CFG2 = {"quantize": 1253893530, "select": 1127269786, "decode": 168239104}
 METRIC = "decode-attn KV tokens/s/GPU + achieved HBM GB/s (% peak); quantize GB/s"
 
 
@@ -232,7 +236,8 @@ def main():
     def roof(name, nbytes, ms, kernel):
         gbps = nbytes / (ms * 1e-3) / 1e9
         return {"kernel": kernel, "bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(gbps / HBM_PEAK_GBPS, 4),
+                "traffic": MEASURED_TRAFFIC_CFG2.get(name) if w.name == "cfg2" else None,
                 "avg_launch_ms": round(ms / L, 4), "algorithmic_bytes_per_launch": nbytes // L}
 
     rooflines = {
@@ -247,7 +252,7 @@ def main():
         "value": kv_tokens / (tot["decode"] * 1e-3),
         "unit": "KV tokens/s (decode attention; whole-path and quantize rates in 'extra')",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u2 codes / bf16 MFMA / f32 accumulate",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u2 codes; int8 and bf16 MFMA; f32 accumulate",
         "data": "synthetic (seeded; LLaVA-1.5-shaped prompt layout, outlier channels and pivot tokens planted)",
         "config": {"workload": f"{w.name}: {L} layers x B={w.B} x Hq={w.Hq}/Hkv={w.Hkv} x T={w.T}, G={w.G}, "
                                f"TSA layers {list(w.tsa_layers)}, PSA top-{w.top_k}, clip {w.clip}",
