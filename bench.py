@@ -267,6 +267,9 @@ def main():
             "decode_ms_per_layer": {m: round(float(np.mean(v)), 4) for m, v in phase_ms["decode"].items()},
             "quantize_ms_per_layer": {m: round(float(np.mean(v)), 4) for m, v in phase_ms["quantize"].items()},
             "select_ms_per_layer": {m: round(float(np.mean(v)), 4) for m, v in phase_ms["select"].items()},
+            "call_ms_p10_median_p90": {
+                name: {m: [round(float(x), 4) for x in np.percentile(v, (10, 50, 90))] for m, v in phase_ms[name].items()}
+                for name in phase_ms},
             "n_split": args.n_split or akvq.lib().akvq_decode_default_splits(w.B, w.Hkv, w.T),
         },
     }
