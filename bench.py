@@ -69,6 +69,8 @@ def phase_bench(args, w, akvq, synth, torch, np):
     layer = 0 if not w.tsa_layers else 2          # a PSA layer when the workload has both kinds
     if w.mode(layer) == "tsa":
         layer = 0
+    if args.layer >= 0:
+        layer = args.layer                        # e.g. --layer 0 times a text-salient layer of cfg2
     per_set = algorithmic_bytes(w, layer)
     n_sets = args.sets or max(2, int(np.ceil(1.2e9 / max(per_set["decode"], 1))) if args.phase == "decode" else 2)
     t_cap = (w.T + 63) // 64 * 64
@@ -134,6 +136,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
+    ap.add_argument("--layer", type=int, default=-1, help="layer whose mode (TSA/PSA) a --phase run uses")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
     ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "copy"],

@@ -128,7 +128,11 @@ __device__ __forceinline__ GroupQ group_params(float umin, float umax, float kap
     if (s16 >= 0x7C00u) s16 = 0x7BFFu;
   }
   float s = half_bits_to_float(s16);
-  float rcp = __fdiv_rn(1.0f, s);
+  // 1/s correctly rounded: s has an 11-bit significand (binary16), so 1/s is either exact or at least 2^-35 (relative)
+  // away from any rounding boundary of fp32, far more than the 2^-45 error left by one Newton step on the hardware
+  // reciprocal (accurate to 1 ulp); the fused step rounds once.
+  const float r0 = __builtin_amdgcn_rcpf(s);
+  float rcp = __builtin_fmaf(r0, __builtin_fmaf(-s, r0, 1.0f), r0);
   float zr = rintf(__fmul_rn(cmin, rcp));
   int z = (zr != zr) ? 0 : -(int)fminf(fmaxf(zr, -40000.0f), 40000.0f);
   z = min(32767, max(-32768, z));
@@ -300,6 +304,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
         for (int slot = 15; slot >= 0; --slot) {
           const int m = 2 * wq + (slot >> 3), i = slot & 7;
           word = (word << 2) + code_bits(u[m][i], gq[m / (4 / NG)]);
+          asm("" : "+v"(word));  // keep the chain one shift-add per code (re-association costs more instructions)
         }
         kw[h][wq] = word - kPack16Bias;
       }
@@ -350,23 +355,40 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
     uint32_t mask = vmask_part << (2 * ii);
     mask |= dpp_move_u<kRowRor4>(mask);
     mask |= dpp_move_u<kRowRor8>(mask);
-    if (mask != 0u) {
+    if (mask != 0u) {  // uniform over the four rows of a chunk; in practice over the wavefront
+      // all cross-lane work first, outside any divergent control flow: complete words of the lane's eight chunks
+      uint32_t w[2][8];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        uint32_t w0 = (vcode[0][i] - kPack4Bias) << (2 * ii), w1 = (vcode[1][i] - kPack4Bias) << (2 * ii);
-        w0 |= dpp_move_u<kRowRor4>(w0);
-        w1 |= dpp_move_u<kRowRor4>(w1);
-        w0 |= dpp_move_u<kRowRor8>(w0);
-        w1 |= dpp_move_u<kRowRor8>(w1);
-        if ((i >> 1) == ii) {  // each of the four rows stores two of the eight chunks
-          uint32_t *dst = a.v_codes + blk_word + (size_t)(16 * q + 8 * (j & 1) + i) * 4 + 2 * (j >> 1);
-          if (mask != 0xFFFFFFFFu) {  // block only partly new: keep the other tokens' bits
-            w0 = (dst[0] & ~mask) | (w0 & mask);
-            w1 = (dst[1] & ~mask) | (w1 & mask);
-          }
-          u32x2 o = {w0, w1};
-          *reinterpret_cast<u32x2 *>(dst) = o;
+      for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int mp = 0; mp < 2; ++mp) {
+          uint32_t x = (vcode[mp][i] - kPack4Bias) << (2 * ii);
+          x |= dpp_move_u<kRowRor4>(x);
+          x |= dpp_move_u<kRowRor8>(x);
+          w[mp][i] = x;
         }
+      // each of the four rows stores two of the eight chunks: i = 2*ii and 2*ii + 1
+      uint32_t sel[2][2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int mp = 0; mp < 2; ++mp) {
+          uint32_t x = w[mp][c];
+          x = ii == 1 ? w[mp][2 + c] : x;
+          x = ii == 2 ? w[mp][4 + c] : x;
+          x = ii == 3 ? w[mp][6 + c] : x;
+          sel[c][mp] = x;
+        }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        uint32_t *dst = a.v_codes + blk_word + (size_t)(16 * q + 8 * (j & 1) + 2 * ii + c) * 4 + 2 * (j >> 1);
+        uint32_t w0 = sel[c][0], w1 = sel[c][1];
+        if (mask != 0xFFFFFFFFu) {  // block only partly new: keep the other tokens' bits
+          w0 = (dst[0] & ~mask) | (w0 & mask);
+          w1 = (dst[1] & ~mask) | (w1 & mask);
+        }
+        u32x2 o = {w0, w1};
+        *reinterpret_cast<u32x2 *>(dst) = o;
       }
     }
   }

@@ -110,6 +110,34 @@ def test_quantize_long_salient_lists(orc, T, every):
     assert_cache_equal(oc, gc, f"T={T} every={every} salient={n_sal}")
 
 
+def test_quantize_reciprocal_ties_over_scale_values(orc):
+    """Rows built so that the stored scale is a chosen binary16 value s (extrema -s and 2s, clip 1) and the other
+    elements sit on multiples of s/4: x/s + zero then lands exactly on .5 ties up to the rounding of 1/s, so the
+    code of such an element is decided by the last bit of the reciprocal.  Sweeps 3328 scale values (every eighth
+    significand over 26 binades) through the un-rotated value path and compares codes and meta bit for bit."""
+    sig = 1024 + 8 * np.arange(128)
+    exps = np.arange(-12, 14)
+    scales = (sig[None, :].astype(np.float64) * 2.0 ** (exps[:, None] - 10)).reshape(-1)
+    T = scales.size
+    assert T % 64 == 0
+    rng = np.random.default_rng(5)
+    mult = rng.integers(-4, 9, size=(T, 128)).astype(np.float64) / 4.0      # multiples of 1/4 in [-1, 2]
+    mult[:, 0], mult[:, 1] = -1.0, 2.0
+    mult[:, 2:8] = np.array([-0.5, 0.5, 1.5, -0.25, 0.75, 1.25])
+    rows = (mult * scales[:, None]).astype(np.float16)
+    assert np.array_equal(rows.astype(np.float64), mult * scales[:, None])   # all exactly representable
+    v = rows[None, None]
+    k = np.ascontiguousarray(v[:, :, ::-1])
+    w = synth.small("ties", B=1, Hq=1, Hkv=1, T=T, G=128, clip=1.0)
+    oc, gc = make_pair(orc, w, t_cap=T, s_cap=64)
+    oc.quantize_append(k, v, 1.0, rotate_v=False)
+    akvq.quantize_append(gc, _dev(k), _dev(v), 1.0, flags=akvq.V_PREROTATED)
+    assert_cache_equal(oc, gc, "reciprocal ties")
+    meta = oc.v_meta[0, 0, :T, 0]
+    got_scale = (meta & 0x7FFF).astype(np.uint16).view(np.float16).astype(np.float64)
+    assert np.array_equal(got_scale, scales)                                  # the sweep really hit every scale
+
+
 def test_quantize_append_in_pieces_and_single_rows(orc):
     w = synth.small("pieces", B=1, Hq=2, Hkv=2, T=100, G=64)
     d = _np(synth.generate(w, seed=103))
