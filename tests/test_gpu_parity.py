@@ -298,6 +298,14 @@ def test_decode_mha_small(orc, mode, G):
     run_decode_case(orc, w, d, mode, 7, n_splits=(1, 2, 3))
 
 
+@pytest.mark.parametrize("mode", ["tsa", "psa"])
+def test_decode_mha_many_workgroups(orc, mode):
+    """More (batch, head) units than the chip holds workgroups at once, with and without a KV split."""
+    w = synth.small("dmha_wide", B=17, Hq=32, Hkv=32, T=150, G=128, n_text_head=11, n_text_tail=6, top_k=5, W=16)
+    d = _np(synth.generate(w, seed=131))
+    run_decode_case(orc, w, d, mode, 5, n_splits=(1, 2))
+
+
 @pytest.mark.parametrize("T", [1, 2, 31, 33, 64, 65, 127, 129])
 def test_decode_ragged_lengths(orc, T):
     w = synth.small("ragged", B=1, Hq=2, Hkv=2, T=140, G=128, n_text_head=3, n_text_tail=3, W=16)
