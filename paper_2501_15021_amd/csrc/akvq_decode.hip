@@ -70,7 +70,7 @@ struct Meta {
 };
 __device__ __forceinline__ Meta unpack_meta(uint32_t w) {
   Meta m;
-  m.scale = half_bits_to_float(w & 0x7FFFu);
+  m.scale = __builtin_fabsf(half_bits_to_float(w & 0xFFFFu));  // bit 15 is the salient flag: dropped by the abs modifier
   m.zero = (float)((int)w >> 16);
   m.salient = (w & 0x8000u) != 0;
   return m;
@@ -561,11 +561,18 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) acc_o[nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
   float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};  // softmax reference (base 2) and partial sums
-  float swx[2][NG], szx[2][NG];  // running sums of w*cx and w*cx*zero over this lane's tokens, per head
+  // Per head and group: szx = running sum of w*cx*zero over this lane's tokens; the sum of the weights themselves
+  // (what the expansion constant 128 multiplies) comes out of the matrix cores: one extra product per group and tile
+  // against an all-ones operand sums exactly the bfloat16 terms the value product uses, over all 32 slots.
+  f32x4 acc_one[NG];
+#pragma unroll
+  for (int g = 0; g < NG; ++g) acc_one[g] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, (u32x4){0x3F803F80u, 0x3F803F80u, 0x3F803F80u, 0x3F803F80u});
+  float szx[2][NG];
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-    for (int g = 0; g < NG; ++g) swx[hh][g] = szx[hh][g] = 0.0f;
+    for (int g = 0; g < NG; ++g) szx[hh][g] = 0.0f;
 
   const float sm2 = a.sm_scale * kLog2e;  // scores live in the base-2 domain
   const int ii = mrow & 3;  // token n = mrow of its group: pair position
@@ -594,7 +601,11 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
           for (int nb = 0; nb < 8; ++nb) { acc_o[nb][2 * hh] *= alpha; acc_o[nb][2 * hh + 1] *= alpha; }
           l_run[hh] *= alpha;
 #pragma unroll
-          for (int g = 0; g < NG; ++g) { swx[hh][g] *= alpha; szx[hh][g] *= alpha; }
+          for (int g = 0; g < NG; ++g) {
+            acc_one[g][2 * hh] *= alpha;
+            acc_one[g][2 * hh + 1] *= alpha;
+            szx[hh][g] *= alpha;
+          }
           m_run[hh] = mx;
         }
       }
@@ -684,23 +695,26 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       }
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
-        float hix[2], lox[2];
-#pragma unroll
-        for (int tg = 0; tg < 2; ++tg) {
-          split2(p[hh][tg] * sxc[tg], hix[tg], lox[tg]);
-          const float wxr = hix[tg] + lox[tg];
-          swx[hh][g] += wxr;
-          szx[hh][g] = __builtin_fmaf(wxr, zv[tg], szx[hh][g]);
-        }
+        // hi term = the weight truncated to bfloat16 (the upper half of the register), lo term = the remainder
+        // rounded to bfloat16; the zero-point sum takes the fp32 weight (it differs from hi+lo by 2^-17 relative,
+        // on a term of the size of the result itself)
+        const float w0 = p[hh][0] * sxc[0], w1 = p[hh][1] * sxc[1];
+        const float r0 = w0 - __uint_as_float(__float_as_uint(w0) & 0xFFFF0000u);
+        const float r1 = w1 - __uint_as_float(__float_as_uint(w1) & 0xFFFF0000u);
+        szx[hh][g] = __builtin_fmaf(w0, zv[0], szx[hh][g]);
+        szx[hh][g] = __builtin_fmaf(w1, zv[1], szx[hh][g]);
         const int row = 4 * qd + 2 * hh;
-        reinterpret_cast<uint32_t *>(&w_lds[g][row][0])[mrow] = pack_hi(hix[0], hix[1]);
-        reinterpret_cast<uint32_t *>(&w_lds[g][row + 1][0])[mrow] = pack_hi(lox[0], lox[1]);
+        reinterpret_cast<uint32_t *>(&w_lds[g][row][0])[mrow] = pack_hi(w0, w1);
+        reinterpret_cast<uint32_t *>(&w_lds[g][row + 1][0])[mrow] = pack_bf16x2(r0, r1);
       }
     }
     wave_lds_sync();
     bf16x8 a_v[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) a_v[g] = *reinterpret_cast<const bf16x8 *>(&w_lds[g][mrow][8 * qd]);
+    for (int g = 0; g < NG; ++g) {
+      a_v[g] = *reinterpret_cast<const bf16x8 *>(&w_lds[g][mrow][8 * qd]);
+      acc_one[g] = mfma_bf16(a_v[g], ones, acc_one[g]);
+    }
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const int g = (NG == 2) ? (w & 1) : 0;
@@ -818,7 +832,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     const float l_tot = row_sum_dpp(l_run[hh]);
     float corr[NG];
 #pragma unroll
-    for (int g = 0; g < NG; ++g) corr[g] = kCodeBias * row_sum_dpp(swx[hh][g]) + row_sum_dpp(szx[hh][g] * rcx);
+    for (int g = 0; g < NG; ++g)  // acc_one already holds the sum over all slots (every column the same)
+      corr[g] = kCodeBias * (acc_one[g][2 * hh] + acc_one[g][2 * hh + 1]) + row_sum_dpp(szx[hh][g] * rcx);
     if (mrow == 0) { mrg_m[wave][h] = m_run[hh]; mrg_l[wave][h] = l_tot; }
 #pragma unroll
     for (int nb = 0; nb < 8; ++nb) {
