@@ -516,9 +516,12 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   for (int x = lane; x < NG * 16 * kTokBlock; x += 64) (&w_lds[0][0][0])[x] = 0;
   for (int h = wave; h < R; h += kWaves) rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf[h], lane);
   __syncthreads();
+  // sm_scale * log2(e) is folded into the staged queries (and through them into the bias and group sums), so the
+  // products already are base-2 logits
+  const float sm2 = a.sm_scale * kLog2e;
   for (int x = tid; x < R * kD; x += 64 * kWaves) {
     const int h = x >> 7, e = x & 127;
-    const float v = qf[h][e];
+    const float v = qf[h][e] * sm2;
     float hif, lof;
     split2(v, hif, lof);
     q_plain[2 * h][e] = (uint16_t)hi16(hif); q_plain[2 * h + 1][e] = (uint16_t)hi16(lof);
@@ -543,7 +546,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       const int e = mrow + 16 * c;
       const int g = (NG == 2) ? (c >> 2) : 0;
       bias_part[g] += bf16_bits_to_f32(q_scaled[2 * h][e]) + bf16_bits_to_f32(q_scaled[2 * h + 1][e]);
-      qsum_part[g] += (h < R) ? qf[h][e] : 0.0f;
+      qsum_part[g] += (h < R) ? qf[h][e] * sm2 : 0.0f;
     }
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
@@ -556,6 +559,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
   for (int kc = 0; kc < 4; ++kc)
     a_k[kc] = *reinterpret_cast<const bf16x8 *>(&q_scaled[mrow][(4 * kc + qd) * 8]);
+  f32x4 acc_init[NG];  // rows (head h0: hi, lo; head h0+1: hi, lo): the bias enters through the hi rows
+#pragma unroll
+  for (int g = 0; g < NG; ++g) acc_init[g] = (f32x4){-qbias[0][g], 0.f, -qbias[1][g], 0.f};
 
   f32x4 acc_o[8];
 #pragma unroll
@@ -574,7 +580,6 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
     for (int g = 0; g < NG; ++g) szx[hh][g] = 0.0f;
 
-  const float sm2 = a.sm_scale * kLog2e;  // scores live in the base-2 domain
   const int ii = mrow & 3;  // token n = mrow of its group: pair position
   const float cx = pow4_neg(pair_exp(ii)), rcx = 1.0f / cx;  // exact powers of two
 
@@ -661,7 +666,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     for (int tg = 0; tg < 2; ++tg) {
       f32x4 acc[NG];
 #pragma unroll
-      for (int g = 0; g < NG; ++g) acc[g] = (f32x4){0.f, 0.f, 0.f, 0.f};
+      for (int g = 0; g < NG; ++g) acc[g] = acc_init[g];  // starts at -128*sum(q'): the expansion constant's share
       const uint32_t w0 = cur.kc[2 * tg], w1 = cur.kc[2 * tg + 1];
       acc[0] = mfma_bf16(a_k[0], ex.x(w0), acc[0]);
       acc[0] = mfma_bf16(a_k[1], ex.y(w0), acc[0]);
@@ -673,12 +678,12 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       for (int g = 0; g < NG; ++g) {
         const Meta mk = unpack_meta(cur.km[tg][g]);
         salient = salient || mk.salient;
-        // scale * (dot - 128*sum(q') - zero*sum(q)); qbias already holds 128*sum(q')
-        s0 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[0][g], (acc[g][0] + acc[g][1]) - qbias[0][g]), s0);
-        s1 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[1][g], (acc[g][2] + acc[g][3]) - qbias[1][g]), s1);
+        // scale * (dot - 128*sum(q') - zero*sum(q)); the accumulators started at -128*sum(q')
+        s0 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[0][g], acc[g][0] + acc[g][1]), s0);
+        s1 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[1][g], acc[g][2] + acc[g][3]), s1);
       }
-      sc[0][tg] = s0 * sm2;
-      sc[1][tg] = s1 * sm2;
+      sc[0][tg] = s0;
+      sc[1][tg] = s1;
       ok[tg] = (tile * 32 + 16 * tg + mrow < a.T_len) && !salient;
     }
     float p[2][2];
@@ -791,8 +796,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
             acc = mfma_bf16(a_s[kc], kb, acc);
           }
         }
-        sc[0][tg] = sm2 * (acc[0] + acc[1]);
-        sc[1][tg] = sm2 * (acc[2] + acc[3]);
+        sc[0][tg] = acc[0] + acc[1];
+        sc[1][tg] = acc[2] + acc[3];
         ok[tg] = (s_lane < cnt) && (pos_lane[tg] < a.T_len);
       }
       float p[2][2];
