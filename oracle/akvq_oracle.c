@@ -122,11 +122,12 @@ void orc_fwht128_f32(const float *x, float *u) {
  * ---------------------------------------------------------------------------------------- */
 #define ORC_INV_SQRT128_BITS 0x3DB504F3u /* 2^-3.5 rounded to binary32 */
 #define ORC_ONE_THIRD_BITS 0x3EAAAAABu   /* 1/3 rounded to binary32 */
+#define ORC_ONE_FIFTEENTH_BITS 0x3D888889u /* 1/15 rounded to binary32 */
 
-static uint8_t round_clamp_code(double p, int zero) {
-  /* clamp( round_half_even(p + zero), 0, 3 ) evaluated exactly; p is an exact product of two binary32 numbers */
+static uint8_t round_clamp_code(double p, int zero, int top) {
+  /* clamp( round_half_even(p + zero), 0, top ) evaluated exactly; p is an exact product of two binary32 numbers */
   if (!(p == p)) return 0;               /* nan: unspecified, keep it in range */
-  if (p > 1.0e6) return (zero > -1000000) ? 3 : 0;
+  if (p > 1.0e6) return (zero > -1000000) ? (uint8_t)top : 0;
   if (p < -1.0e6) return 0;
   double fl = floor(p);
   double frac = p - fl;                  /* exact */
@@ -134,12 +135,22 @@ static uint8_t round_clamp_code(double p, int zero) {
   if (frac > 0.5) k += 1;
   else if (frac == 0.5 && (k & 1L)) k += 1; /* tie -> even result */
   if (k < 0) k = 0;
-  if (k > 3) k = 3;
+  if (k > top) k = top;
   return (uint8_t)k;
 }
 
 void orc_quantize_row(const uint16_t *x_f16, int G, float clip, int rotate,
                       uint8_t *codes, uint16_t *scale_bits, int16_t *zero, uint16_t *y_bf16) {
+  orc_quantize_row_bits(x_f16, G, clip, rotate, 2, codes, scale_bits, zero, y_bf16);
+}
+
+/* Eq. 3-6 with n = n_bits (2 or 4).  For 4 bits (the text tier of Section III-C.1) the same readings apply with
+ * 2^n - 1 = 15; the stored scale saturates at 16376 so that four times it is still a binary16 number (the cache
+ * stores a 4-bit row as two 2-bit rows, see orc_quantize_append_tiered). */
+void orc_quantize_row_bits(const uint16_t *x_f16, int G, float clip, int rotate, int n_bits,
+                           uint8_t *codes, uint16_t *scale_bits, int16_t *zero, uint16_t *y_bf16) {
+  const int top = (1 << n_bits) - 1;
+  const uint16_t s16_max = n_bits == 2 ? 0x7BFF : 0x73FF;
   float xf[ORC_D], u[ORC_D];
   for (int e = 0; e < ORC_D; ++e) xf[e] = orc_half_to_float(x_f16[e]);
   float kappa;
@@ -155,7 +166,7 @@ void orc_quantize_row(const uint16_t *x_f16, int G, float clip, int rotate,
     volatile float y = u[e] * kappa;
     y_bf16[e] = orc_float_to_bf16_rne(y);
   }
-  const float third = bits_to_float(ORC_ONE_THIRD_BITS);
+  const float third = bits_to_float(n_bits == 2 ? ORC_ONE_THIRD_BITS : ORC_ONE_FIFTEENTH_BITS);
   for (int g = 0; g < ORC_D / G; ++g) {
     float umin = u[g * G], umax = u[g * G];
     for (int e = g * G; e < (g + 1) * G; ++e) {
@@ -167,15 +178,15 @@ void orc_quantize_row(const uint16_t *x_f16, int G, float clip, int rotate,
     /* reading: clipped_min = clip * min, clipped_max = clip * max */
     volatile float cmin = clip * gmin, cmax = clip * gmax;
     volatile float range = cmax - cmin;
-    volatile float s32 = range * third;         /* Eq. 5 with 2^n - 1 = 3 */
+    volatile float s32 = range * third;         /* Eq. 5: range / (2^n - 1) as a multiply by the rounded reciprocal */
     /* reading: the scale is stored as binary16, rounded UP so that the top level never falls below cmax */
     uint16_t s16;
     if (!(s32 > 0.0f)) s16 = 0x3C00;            /* constant group (or nan): scale 1 */
     else {
       s16 = orc_float_to_half_rne(s32);
-      if (s16 >= 0x7C00) s16 = 0x7BFF;          /* saturate at 65504 */
+      if (s16 > s16_max) s16 = s16_max;         /* saturate (65504 for 2 bits) */
       else if (orc_half_to_float(s16) < s32) s16 = (uint16_t)(s16 + 1);
-      if (s16 >= 0x7C00) s16 = 0x7BFF;
+      if (s16 > s16_max) s16 = s16_max;
     }
     float s = orc_half_to_float(s16);
     volatile float rcp = 1.0f / s;              /* all further arithmetic uses the stored scale */
@@ -190,7 +201,7 @@ void orc_quantize_row(const uint16_t *x_f16, int G, float clip, int rotate,
      * round-to-integer, and the integer zero is added before rounding (changes ties only) */
     volatile float rcpu = rcp * kappa;
     for (int e = g * G; e < (g + 1) * G; ++e)
-      codes[e] = round_clamp_code((double)u[e] * (double)rcpu, (int)z);
+      codes[e] = round_clamp_code((double)u[e] * (double)rcpu, (int)z, top);
     scale_bits[g] = s16;
     zero[g] = (int16_t)z;
   }
@@ -389,6 +400,81 @@ void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Tiered write path (Section III-C.1: text tokens 4-bit, the rest 2-bit).  Cache row T_len + r of batch element b
+ * takes source token row_src[b][r] and tier row_tier[b][r]:
+ *   0  plain 2-bit row (as orc_quantize_append, overlay included when the row is listed in sal_idx);
+ *   1  coarse half of a 4-bit token, 2  its fine half (always the next row; the pair starts on an even row):
+ *      the token is quantized to 4 bits (scale s, zero z4, code c4), then stored as two 2-bit rows
+ *        coarse: codes c4 >> 2, scale 4*s, zero z4 >> 2 (floor);   fine: codes c4 & 3, scale s, zero z4 & 3
+ *      so that  4*s*(hi - zc) + s*(lo - zf) = s*(c4 - z4)  exactly;
+ *   3  padding row: flagged like a salient row without an overlay slot, so decode ignores it.
+ * fine_mask [B][T_cap/32]: bit (t % 32) of word t/32 is set for fine halves, cleared for every other written row.
+ * reading (the paper gives no storage format): this pairing is this build's own; parity unpinned by the paper,
+ * pinned by the identity above and by attention over directly dequantized 4-bit values.
+ * ---------------------------------------------------------------------------------------- */
+void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint16_t *v_src, int n_src,
+                                const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
+                                float clip4, int rotate_v, uint32_t *fine_mask) {
+  const int ng = ORC_D / c->G;
+  const int nbh = c->B * c->Hkv;
+  for (int b = 0; b < c->B; ++b)
+    for (int i = 0; i < n_rows; ++i) {
+      int t = c->T_len + i;
+      uint32_t *w = fine_mask + (size_t)b * (c->T_cap / 32) + t / 32;
+      if (row_tier[(size_t)b * n_rows + i] == 2) *w |= 1u << (t % 32); else *w &= ~(1u << (t % 32));
+    }
+#pragma omp parallel for schedule(dynamic)
+  for (int bh = 0; bh < nbh; ++bh) {
+    int b = bh / c->Hkv, h = bh % c->Hkv;
+    for (int i = 0; i < n_rows; ++i) {
+      int t = c->T_len + i;
+      int tier = row_tier[(size_t)b * n_rows + i];
+      int src = row_src[(size_t)b * n_rows + i];
+      int slot = tier == 0 ? salient_slot(c, b, h, t) : -1;
+      for (int tensor = 0; tensor < 2; ++tensor) {
+        uint32_t *meta = (tensor == 0 ? c->k_meta : c->v_meta) + ((size_t)bh * c->T_cap + t) * ng;
+        if (tier == 3) {
+          for (int e = 0; e < ORC_D; ++e) put_code(c, tensor, b, h, t, e, 0);
+          for (int g = 0; g < ng; ++g) meta[g] = 0x3C00u | 0x8000u;
+          continue;
+        }
+        const uint16_t *row = (tensor == 0 ? k_src : v_src) + ((size_t)bh * n_src + src) * ORC_D;
+        uint8_t codes[ORC_D]; uint16_t sb[2]; int16_t z[2]; uint16_t ybf[ORC_D];
+        const int rot = tensor == 0 ? 1 : rotate_v;
+        if (tier == 0) {
+          orc_quantize_row_bits(row, c->G, clip2, rot, 2, codes, sb, z, ybf);
+          for (int e = 0; e < ORC_D; ++e) put_code(c, tensor, b, h, t, e, codes[e]);
+          for (int g = 0; g < ng; ++g)
+            meta[g] = (uint32_t)sb[g] | (slot >= 0 ? 0x8000u : 0u) | ((uint32_t)(uint16_t)z[g] << 16);
+          if (slot >= 0) {
+            if (tensor == 0) memcpy(c->k_sal + ((size_t)bh * c->S_cap + slot) * ORC_D, ybf, sizeof(ybf));
+            else {
+              uint16_t *plane = c->v_sal + (size_t)bh * c->S_cap * ORC_D;
+              for (int e = 0; e < ORC_D; ++e) plane[orc_vsal_pos(slot, e)] = ybf[e];
+            }
+          }
+        } else {
+          orc_quantize_row_bits(row, c->G, clip4, rot, 4, codes, sb, z, ybf);
+          for (int e = 0; e < ORC_D; ++e)
+            put_code(c, tensor, b, h, t, e, tier == 1 ? (uint8_t)(codes[e] >> 2) : (uint8_t)(codes[e] & 3));
+          for (int g = 0; g < ng; ++g) {
+            uint16_t s_row = sb[g];
+            int z_row;
+            if (tier == 1) {
+              s_row = orc_float_to_half_rne(4.0f * orc_half_to_float(sb[g])); /* exact: sb <= 16376 */
+              z_row = (z[g] >= 0) ? (z[g] >> 2) : -((-(int)z[g] + 3) >> 2);  /* floor(z4 / 4) */
+            } else {
+              z_row = (int)z[g] - 4 * ((z[g] >= 0) ? (z[g] >> 2) : -((-(int)z[g] + 3) >> 2)); /* z4 mod 4 in 0..3 */
+            }
+            meta[g] = (uint32_t)s_row | ((uint32_t)(uint16_t)(int16_t)z_row << 16);
+          }
+        }
+      }
+    }
+  }
+}
+
+/* ------------------------------------------------------------------------------------------
  * Read path: softmax attention of one decode query over the cached rows (Section II-A, Eq. 2 context),
  * using the dequantized (Eq. 4) or bfloat16 rows, all in fp64, dense, two-pass softmax.
  * The query is rotated with the dense H_128 (Section III-C: rotate Q and K after RoPE); the output is
@@ -419,6 +505,14 @@ static void cached_row(const orc_cache *c, int tensor, int b, int h, int t, int 
 
 void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const uint16_t *q_row, double sm_scale,
                               int unrotate, double *out, double *lse) {
+  orc_decode_attention_one_tiered(c, NULL, Hq, b, hq, q_row, sm_scale, unrotate, out, lse);
+}
+
+/* fine_mask (may be NULL): rows flagged there are the fine halves of 4-bit tokens; such a row and the row before
+ * it are one token whose value is the sum of the two dequantized rows (Eq. 4 applied to each half). */
+void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, int b, int hq,
+                                     const uint16_t *q_row, double sm_scale, int unrotate, double *out,
+                                     double *lse) {
   const int r = Hq / c->Hkv;
   const int h = hq / r;
   const int T = c->T_len;
@@ -433,24 +527,41 @@ void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const u
     for (int s = 0; s < n; ++s) if (idx[s] >= 0 && idx[s] < T) slot_of[idx[s]] = s;
   }
   double *score = (double *)malloc(sizeof(double) * (size_t)T);
-  double row[ORC_D];
+  double row[ORC_D], row2[ORC_D];
   double mx = -INFINITY;
+  const uint32_t *fm = fine_mask ? fine_mask + (size_t)b * (c->T_cap / 32) : NULL;
+#define ORC_IS_FINE(t) (fm && ((fm[(t) / 32] >> ((t) % 32)) & 1u))
+  /* a token = one row, or a (coarse, fine) pair of rows; skipped rows: fine halves (counted with their coarse row)
+   * and rows flagged salient that have no overlay slot (padding) */
   for (int t = 0; t < T; ++t) {
+    score[t] = -INFINITY;
+    if (ORC_IS_FINE(t)) continue;
+    if (slot_of[t] < 0 && (c->k_meta[(bh_index(c, b, h) * c->T_cap + t) * (ORC_D / c->G)] & 0x8000u)) continue;
     cached_row(c, 0, b, h, t, slot_of[t], row);
+    if (t + 1 < T && ORC_IS_FINE(t + 1)) {
+      cached_row(c, 0, b, h, t + 1, -1, row2);
+      for (int e = 0; e < ORC_D; ++e) row[e] += row2[e];
+    }
     double acc = 0.0;
     for (int e = 0; e < ORC_D; ++e) acc += qrot[e] * row[e];
     score[t] = sm_scale * acc;
     if (score[t] > mx) mx = score[t];
   }
   double den = 0.0;
-  for (int t = 0; t < T; ++t) den += exp(score[t] - mx);
+  for (int t = 0; t < T; ++t) if (score[t] != -INFINITY) den += exp(score[t] - mx);
   double orot[ORC_D];
   for (int e = 0; e < ORC_D; ++e) orot[e] = 0.0;
   for (int t = 0; t < T; ++t) {
+    if (score[t] == -INFINITY) continue;
     double p = exp(score[t] - mx) / den;
     cached_row(c, 1, b, h, t, slot_of[t], row);
+    if (t + 1 < T && ORC_IS_FINE(t + 1)) {
+      cached_row(c, 1, b, h, t + 1, -1, row2);
+      for (int e = 0; e < ORC_D; ++e) row[e] += row2[e];
+    }
     for (int e = 0; e < ORC_D; ++e) orot[e] += p * row[e];
   }
+#undef ORC_IS_FINE
   if (unrotate) orc_wht_dense_f64(ORC_D, orot, out);
   else memcpy(out, orot, sizeof(orot));
   if (lse) *lse = mx + log(den);
@@ -459,11 +570,16 @@ void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const u
 
 void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int unrotate,
                           double *out, double *lse) {
+  orc_decode_attention_tiered(c, NULL, Hq, q, sm_scale, unrotate, out, lse);
+}
+
+void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, const uint16_t *q,
+                                 double sm_scale, int unrotate, double *out, double *lse) {
   const int n = c->B * Hq;
 #pragma omp parallel for schedule(dynamic)
   for (int x = 0; x < n; ++x) {
     int b = x / Hq, hq = x % Hq;
-    orc_decode_attention_one(c, Hq, b, hq, q + (size_t)x * ORC_D, sm_scale, unrotate,
-                             out + (size_t)x * ORC_D, lse ? lse + x : NULL);
+    orc_decode_attention_one_tiered(c, fine_mask, Hq, b, hq, q + (size_t)x * ORC_D, sm_scale, unrotate,
+                                    out + (size_t)x * ORC_D, lse ? lse + x : NULL);
   }
 }

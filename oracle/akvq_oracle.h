@@ -57,9 +57,12 @@ void orc_fwht128_f32(const float *x, float *u);
 
 /* ---- quantizer (Section III-C, Eq. 3-6) for one head vector ---- */
 /* x_f16: 128 binary16 bit patterns.  rotate!=0: rotate by H_128 first.  Outputs: codes[128] in 0..3 (natural rotated
- * channel order), scale_bits[D/G], zero[D/G], y_bf16[128] (rotated row as bfloat16).  n_bits is fixed to 2. */
+ * channel order), scale_bits[D/G], zero[D/G], y_bf16[128] (rotated row as bfloat16).  Two bits. */
 void orc_quantize_row(const uint16_t *x_f16, int G, float clip, int rotate,
                       uint8_t *codes, uint16_t *scale_bits, int16_t *zero, uint16_t *y_bf16);
+/* The same with n_bits = 2 or 4 (codes in 0..2^n-1); 4 bits is the text tier of Section III-C.1. */
+void orc_quantize_row_bits(const uint16_t *x_f16, int G, float clip, int rotate, int n_bits,
+                           uint8_t *codes, uint16_t *scale_bits, int16_t *zero, uint16_t *y_bf16);
 /* Dequantized value of Eq. 4 in fp64 from stored fields. */
 double orc_dequant(uint8_t code, uint16_t scale_bits, int16_t zero);
 
@@ -79,6 +82,12 @@ void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t
 /* Write path: rows [T_len, T_len+n_new) of K and V ([B][Hkv][n_new][128] binary16).  Does not change T_len. */
 void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_new, int n_new, float clip,
                          int rotate_v);
+/* Tiered write path: cache row T_len + r of batch b takes source token row_src[b][r] (index into k_src / v_src,
+ * [B][Hkv][n_src][128]) with tier row_tier[b][r]: 0 = 2-bit, 1 / 2 = coarse / fine half of a 4-bit token (two 2-bit
+ * rows), 3 = padding.  fine_mask [B][T_cap/32] marks the fine halves.  Does not change T_len. */
+void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint16_t *v_src, int n_src,
+                                const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
+                                float clip4, int rotate_v, uint32_t *fine_mask);
 /* Read path: decode attention (Eq. 2 with the dequantized cache), fp64.  q [B][Hq][128] binary16.
  * out [B][Hq][128]; lse (optional) [B][Hq].  unrotate!=0: out = o~ * H_128. */
 void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int unrotate,
@@ -86,6 +95,13 @@ void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double 
 /* One (b,hq) output only -- used to spot-check full-size runs. */
 void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const uint16_t *q_row, double sm_scale,
                               int unrotate, double *out, double *lse);
+
+/* The same over a cache with 4-bit tokens stored as row pairs (fine_mask may be NULL: no such tokens). */
+void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, const uint16_t *q,
+                                 double sm_scale, int unrotate, double *out, double *lse);
+void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, int b, int hq,
+                                     const uint16_t *q_row, double sm_scale, int unrotate, double *out,
+                                     double *lse);
 
 #ifdef __cplusplus
 }
