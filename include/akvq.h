@@ -64,6 +64,12 @@ enum {
   AKVQ_OUT_ROTATED = 2u   /* decode_attention: leave the output in the rotated domain (H folded into W_O) */
 };
 
+/* Tier of a cache row written by akvq_quantize_append_tiered (Section III-C.1: text tokens 4-bit, the rest 2-bit).
+ * A 4-bit token occupies two consecutive cache rows, the first on an even row: its 4-bit code c4, scale s and
+ * zero-point z4 are stored as a coarse 2-bit row (codes c4 >> 2, scale 4*s, zero floor(z4/4)) and a fine 2-bit row
+ * (codes c4 & 3, scale s, zero z4 mod 4), so that the two dequantized rows add up to s*(c4 - z4) exactly. */
+enum { AKVQ_TIER_2BIT = 0, AKVQ_TIER_4BIT_COARSE = 1, AKVQ_TIER_4BIT_FINE = 2, AKVQ_TIER_PAD = 3 };
+
 /* One layer's cache.  Plain data; every pointer is device memory owned by the caller (layout above).
  * T_len is the number of valid rows; the caller advances it after akvq_quantize_append. */
 typedef struct akvq_cache {
@@ -126,6 +132,33 @@ int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_n
  */
 int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
                           int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
+
+/*
+ * akvq_quantize_append_tiered -- the write path with the 4-bit text tier of Section III-C.1.
+ *   Cache row T_len + r of batch element b takes source token row_src[b][r] (an index into k_src / v_src, device,
+ *   [B][Hkv][n_src][128] binary16) and tier row_tier[b][r] (device, [B][n_rows] uint8, AKVQ_TIER_*):
+ *     2BIT         as akvq_quantize_append with clip2 (overlay and salient bit if the row is listed in c->sal_idx);
+ *     4BIT_COARSE  / 4BIT_FINE: the two halves of one token quantized to 4 bits (Eq. 3-6 with 15 levels, clip4, scale
+ *                  stored as binary16 rounded up and at most 16376); the pair must start on an even cache row, both
+ *                  rows name the same source token, and neither may be listed in c->sal_idx;
+ *     PAD          a row decode ignores (used to align a pair); its meta carries the salient bit, no overlay row.
+ *   fine_mask: device, [B][T_cap/32] uint32, zero-initialised by the caller before the first append; bit t%32 of word
+ *   t/32 is set for fine halves and cleared for every other row written here.
+ *   row_src entries are clamped to [0, n_src); other violations of the rules above give unspecified values, no fault.
+ *   Does not modify c->T_len (advance it by n_rows).
+ */
+int akvq_quantize_append_tiered(const akvq_cache *c, const void *k_src, const void *v_src, int n_src,
+                                const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
+                                float clip4, uint32_t *fine_mask, uint32_t flags, void *stream);
+
+/*
+ * akvq_decode_attention_tiered -- akvq_decode_attention over a cache that holds 4-bit tokens as row pairs:
+ *   a row flagged in fine_mask and the row before it are one token (their scores add up before the softmax, the
+ *   token is counted once, both rows take its weight).  fine_mask NULL = akvq_decode_attention.
+ */
+int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const void *q, int Hq,
+                                 float sm_scale, float *out, float *lse_out, int n_split, void *workspace,
+                                 size_t workspace_bytes, uint32_t flags, void *stream);
 
 #ifdef __cplusplus
 }

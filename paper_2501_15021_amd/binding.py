@@ -21,7 +21,9 @@ V_PREROTATED, OUT_ROTATED = 1, 2
 
 EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
-           "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention"]
+           "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention",
+           "akvq_quantize_append_tiered", "akvq_decode_attention_tiered"]
+TIER_2BIT, TIER_4BIT_COARSE, TIER_4BIT_FINE, TIER_PAD = 0, 1, 2, 3
 
 
 class AkvqError(RuntimeError):
@@ -68,6 +70,14 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention.restype = C.c_int
         L.akvq_decode_attention.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+        L.akvq_quantize_append_tiered.restype = C.c_int
+        L.akvq_quantize_append_tiered.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                                  C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_void_p, C.c_uint32,
+                                                  C.c_void_p]
+        L.akvq_decode_attention_tiered.restype = C.c_int
+        L.akvq_decode_attention_tiered.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_void_p, C.c_int, C.c_float,
+                                                   C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t,
+                                                   C.c_uint32, C.c_void_p]
         _lib = L
     return _lib
 
@@ -91,6 +101,7 @@ class Cache:
 
     def __init__(self, B: int, Hkv: int, G: int, T_cap: int, S_cap: int, device="cuda", fill: Optional[int] = None):
         self.B, self.Hkv, self.G, self.T_cap, self.S_cap, self.T_len = B, Hkv, G, T_cap, S_cap, 0
+        self.fine_mask: Optional[torch.Tensor] = None  # [B, T_cap/32] int32, created by the first tiered append
         shape = akvq_cache(B, Hkv, G, T_cap, S_cap, 0)
         sizes = (C.c_size_t * 8)()
         _check(lib().akvq_cache_bytes(C.byref(shape), sizes), "akvq_cache_bytes")
@@ -163,6 +174,24 @@ def quantize_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, clip
     cache.T_len += n_new
 
 
+def quantize_append_tiered(cache: Cache, k_src: torch.Tensor, v_src: torch.Tensor, row_src: torch.Tensor,
+                           row_tier: torch.Tensor, clip2: float, clip4: float, flags: int = 0) -> None:
+    """akvq_quantize_append_tiered: cache rows [T_len, T_len + n_rows) from source tokens row_src [B, n_rows] int32
+    with tiers row_tier [B, n_rows] uint8; keeps the fine-half mask in cache.fine_mask; advances cache.T_len."""
+    assert k_src.dtype == torch.float16 and v_src.dtype == torch.float16
+    assert k_src.is_contiguous() and v_src.is_contiguous() and k_src.shape == v_src.shape
+    assert row_src.dtype == torch.int32 and row_tier.dtype == torch.uint8
+    assert row_src.is_contiguous() and row_tier.is_contiguous() and row_src.shape == row_tier.shape
+    n_src, n_rows = k_src.shape[2], row_src.shape[1]
+    if cache.fine_mask is None:
+        cache.fine_mask = torch.zeros(cache.B, cache.T_cap // 32, dtype=torch.int32, device=k_src.device)
+    c = cache.struct()
+    _check(lib().akvq_quantize_append_tiered(C.byref(c), _ptr(k_src), _ptr(v_src), n_src, _ptr(row_src),
+                                             _ptr(row_tier), n_rows, clip2, clip4, _ptr(cache.fine_mask), flags,
+                                             _stream()), "akvq_quantize_append_tiered")
+    cache.T_len += n_rows
+
+
 def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: int = 0, flags: int = 0,
                      out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None):
     """akvq_decode_attention: returns (out [B,Hq,128] fp32, lse [B,Hq] fp32)."""
@@ -176,6 +205,11 @@ def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: in
     if lse is None:
         lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
     c = cache.struct()
+    if cache.fine_mask is not None:
+        _check(lib().akvq_decode_attention_tiered(C.byref(c), _ptr(cache.fine_mask), _ptr(q), Hq, sm_scale, _ptr(out),
+                                                  _ptr(lse), n_split, _ptr(ws), ws.numel(), flags, _stream()),
+               "akvq_decode_attention_tiered")
+        return out, lse
     _check(lib().akvq_decode_attention(C.byref(c), _ptr(q), Hq, sm_scale, _ptr(out), _ptr(lse), n_split, _ptr(ws),
                                        ws.numel(), flags, _stream()), "akvq_decode_attention")
     return out, lse

@@ -133,16 +133,18 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
   return hip_status(akvq::launch_select_psa(a, s));
 }
 
-int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_new, int n_new, float clip,
-                         uint32_t flags, void *stream) {
+static int quantize_common(const akvq_cache *c, const void *k_new, const void *v_new, int n_src, int n_new,
+                           float clip, float clip4, const int32_t *row_src, const uint8_t *row_tier,
+                           uint32_t *fine_mask, uint32_t flags, void *stream) {
   int st = check_cache_shape(c);
   if (st != AKVQ_OK) return st;
   st = check_cache_pointers(c);
   if (st != AKVQ_OK) return st;
-  if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new <= 0) return AKVQ_ERR_INVALID_ARG;
-  if (!(clip > 0.0f) || clip > 1.0f) return AKVQ_ERR_INVALID_ARG;
+  if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new <= 0 || n_src <= 0) return AKVQ_ERR_INVALID_ARG;
+  if (!(clip > 0.0f) || clip > 1.0f || !(clip4 > 0.0f) || clip4 > 1.0f) return AKVQ_ERR_INVALID_ARG;
   if ((long)c->T_len + n_new > c->T_cap) return AKVQ_ERR_CAPACITY;
   akvq::QuantArgs a{};
+  a.row_src = row_src; a.row_tier = row_tier; a.fine_mask = fine_mask; a.n_src = n_src; a.clip4 = clip4;
   a.k_new = static_cast<const uint16_t *>(k_new);
   a.v_new = static_cast<const uint16_t *>(v_new);
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
@@ -155,8 +157,29 @@ int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_n
   return hip_status(akvq::launch_quantize_append(a, c->B, c->G, static_cast<hipStream_t>(stream)));
 }
 
+int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_new, int n_new, float clip,
+                         uint32_t flags, void *stream) {
+  return quantize_common(c, k_new, v_new, n_new, n_new, clip, 1.0f, nullptr, nullptr, nullptr, flags, stream);
+}
+
+int akvq_quantize_append_tiered(const akvq_cache *c, const void *k_src, const void *v_src, int n_src,
+                                const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
+                                float clip4, uint32_t *fine_mask, uint32_t flags, void *stream) {
+  if (!row_src || !row_tier || !fine_mask || !aligned16(row_src) || !aligned16(row_tier) || !aligned16(fine_mask))
+    return AKVQ_ERR_INVALID_ARG;
+  return quantize_common(c, k_src, v_src, n_src, n_rows, clip2, clip4, row_src, row_tier, fine_mask, flags, stream);
+}
+
 int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
                           int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
+  return akvq_decode_attention_tiered(c, nullptr, q, Hq, sm_scale, out, lse_out, n_split, workspace, workspace_bytes,
+                                      flags, stream);
+}
+
+int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const void *q, int Hq,
+                                 float sm_scale, float *out, float *lse_out, int n_split, void *workspace,
+                                 size_t workspace_bytes, uint32_t flags, void *stream) {
+  if (fine_mask && !aligned16(fine_mask)) return AKVQ_ERR_INVALID_ARG;
   int st = check_cache_shape(c);
   if (st != AKVQ_OK) return st;
   st = check_cache_pointers(c);
@@ -173,6 +196,7 @@ int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_s
   akvq::DecodeArgs a{};
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
   a.k_sal = c->k_sal; a.v_sal = c->v_sal; a.sal_idx = c->sal_idx; a.sal_cnt = c->sal_cnt;
+  a.fine_mask = fine_mask;
   a.q = static_cast<const uint16_t *>(q);
   a.partial = static_cast<float *>(workspace);
   a.out = out; a.lse = lse_out;

@@ -136,9 +136,13 @@ template <int NG>
 struct MhaTile {
   u32x4 kc[2], vc[2];
   uint32_t km[NG], vm[NG];
+  uint32_t fm;  // fine-half mask word of this lane's 32-row block (only loaded by the PAIRS instantiations)
 };
 
-template <int G>
+// PAIRS: the cache holds 4-bit tokens as (coarse, fine) pairs of 2-bit rows on (even, odd) rows, flagged in
+// a.fine_mask: the two rows' scores add up to the token's score, the token enters the softmax sum once, and each row
+// takes the token's weight times its own scale in the value product.
+template <int G, bool PAIRS>
 __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   constexpr int NG = kD / G;
   __shared__ float qf[kD];
@@ -171,8 +175,10 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
   const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + lane) * NG;
   const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + lane) * NG;
+  const uint32_t *fm_base = PAIRS ? a.fine_mask + (size_t)(bh / a.Hkv) * plane_blocks + (lane >> 5) : nullptr;
 
   auto load_tile = [&](int tile, MhaTile<NG> &t) {
+    if constexpr (PAIRS) t.fm = fm_base[2 * tile];
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
       t.kc[b2] = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)(2 * tile + b2) * kBlockWords);
@@ -267,7 +273,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   // online-softmax bookkeeping shared by the code stream and the bfloat16 rows.  The reference m_run is only
   // raised when some score exceeds it by more than kLazyMax, so the common tile costs one compare and one branch;
   // weights are then at most 2^kLazyMax, which fp32 sums and the bfloat16 term split absorb.
-  auto softmax_step = [&](float score, bool ok, float &p) -> bool {
+  auto softmax_step = [&](float score, bool ok, bool count, float &p) -> bool {
     const float sc = ok ? score : -INFINITY;
     if (__ballot(sc > m_run + kLazyMax) != 0ull) {
       const float m_new = wave_max_dpp(sc);
@@ -281,7 +287,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     }
     if (m_run == -INFINITY) { p = 0.0f; return false; }
     p = fast_exp2(sc - m_run);
-    l_run += p;
+    l_run += count ? p : 0.0f;  // the fine half of a 4-bit token carries the token's weight but is not a token
     return true;
   };
 
@@ -317,8 +323,16 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     score *= q_unit;
     score *= sm2;
     const bool ok = (t < a.T_len) && !salient;
+    bool count = true;
+    if constexpr (PAIRS) {
+      const uint32_t from_me = cur.fm >> (lane & 31);      // bit 0: this row is a fine half; bit 1: the next row is
+      const bool fine = (from_me & 1u) != 0u, coarse = (from_me & 2u) != 0u;  // pairs start on even rows
+      const float partner = dpp_f<0xB1>(score);            // lane ^ 1
+      score = (fine || coarse) ? score + partner : score;
+      count = !fine;
+    }
     float p;
-    if (softmax_step(score, ok, p)) {
+    if (softmax_step(score, ok, count, p)) {
       // weights for the value contraction: w = p * scale_V as two bfloat16 terms, pre-divided by the 4^k of its slot
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
@@ -405,7 +419,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
       const float score = sm2 * (acc[0] + acc[1] + acc[2]);
       const bool ok = (s_lane < cnt) && (pos_lane < a.T_len);
       float p;
-      if (!softmax_step(score, ok, p)) continue;
+      if (!softmax_step(score, ok, true, p)) continue;
       {
         float hif, lof;
         split2(ok ? p : 0.0f, hif, lof);
@@ -478,8 +492,14 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   }
 }
 
-__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel_g128(DecodeArgs a) { decode_mha_body<128>(a); }
-__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel_g64(DecodeArgs a) { decode_mha_body<64>(a); }
+__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel_g128(DecodeArgs a) { decode_mha_body<128, false>(a); }
+__global__ __launch_bounds__(64 * kWaves) void decode_mha_kernel_g64(DecodeArgs a) { decode_mha_body<64, false>(a); }
+__global__ __launch_bounds__(64 * kWaves) void decode_mha_pairs_kernel_g128(DecodeArgs a) {
+  decode_mha_body<128, true>(a);
+}
+__global__ __launch_bounds__(64 * kWaves) void decode_mha_pairs_kernel_g64(DecodeArgs a) {
+  decode_mha_body<64, true>(a);
+}
 
 // ------------------------------------------------------------------------------------------------
 // GQA (R = Hq/Hkv query heads share a KV head, 2 <= R <= 8; also valid for R = 1).  A tile is one cache block
@@ -490,9 +510,10 @@ template <int NG>
 struct GqaTile {
   u32x4 kc, vc;
   uint32_t km[2][NG], vm[2][NG];
+  uint32_t fm;  // fine-half mask word of the block (only loaded by the PAIRS instantiations)
 };
 
-template <int G>
+template <int G, bool PAIRS>
 __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   constexpr int NG = kD / G;
   __shared__ float qf[8][kD];
@@ -586,7 +607,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   // scores sc[hh][tg] of heads h0+hh for tokens (16*tg + mrow) of the tile; ok[tg]; returns weights p[hh][tg].
   // The reference of a head is raised (and its accumulators rescaled) only when one of its scores exceeds it by more
   // than kLazyMax; the common tile pays one compare and one uniform branch.
-  auto softmax_step = [&](const float (&sc)[2][2], const bool (&ok)[2], float (&p)[2][2]) {
+  auto softmax_step = [&](const float (&sc)[2][2], const bool (&ok)[2], const bool (&count)[2], float (&p)[2][2]) {
     float scm[2][2], top[2];
     bool need = false;
 #pragma unroll
@@ -621,7 +642,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
       for (int tg = 0; tg < 2; ++tg) {
         p[hh][tg] = fast_exp2(scm[hh][tg] - m_ref);
-        l_run[hh] += p[hh][tg];
+        l_run[hh] += count[tg] ? p[hh][tg] : 0.0f;  // a fine half carries its token's weight but is not a token
       }
     }
   };
@@ -641,7 +662,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + mrow) * NG;
   const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + mrow) * NG;
 
+  const uint32_t *fm_base = PAIRS ? a.fine_mask + (size_t)b * plane_blocks : nullptr;
   auto load_tile = [&](int tile, GqaTile<NG> &t) {
+    if constexpr (PAIRS) t.fm = fm_base[tile];
     t.kc = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)tile * kBlockWords);
     t.vc = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)tile * kBlockWords);
 #pragma unroll
@@ -686,8 +709,22 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       sc[1][tg] = s1;
       ok[tg] = (tile * 32 + 16 * tg + mrow < a.T_len) && !salient;
     }
+    bool count[2] = {true, true};
+    if constexpr (PAIRS) {
+#pragma unroll
+      for (int tg = 0; tg < 2; ++tg) {
+        const uint32_t from_me = cur.fm >> (16 * tg + mrow);  // bit 0: this row is a fine half; bit 1: the next one is
+        const bool pair = (from_me & 3u) != 0u;               // pairs start on even rows: the partner is lane ^ 1
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+          const float partner = dpp_f<0xB1>(sc[hh][tg]);
+          sc[hh][tg] = pair ? sc[hh][tg] + partner : sc[hh][tg];
+        }
+        count[tg] = (from_me & 1u) == 0u;
+      }
+    }
     float p[2][2];
-    softmax_step(sc, ok, p);
+    softmax_step(sc, ok, count, p);
     // weights: rows 4*qd + {0,1,2,3} = (head h0: hi, lo; head h0+1: hi, lo); slots 2*mrow (+1 for the second group)
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
@@ -801,7 +838,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
         ok[tg] = (s_lane < cnt) && (pos_lane[tg] < a.T_len);
       }
       float p[2][2];
-      softmax_step(sc, ok, p);
+      const bool count[2] = {true, true};
+      softmax_step(sc, ok, count, p);
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         float hif[2], lof[2];
@@ -905,11 +943,19 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream) {
   dim3 grid(a.n_split, a.B * a.Hkv), block(64 * kWaves);
   if (a.Hq == a.Hkv) {
-    if (G == 128) hipLaunchKernelGGL(decode_mha_kernel_g128, grid, block, 0, stream, a);
-    else hipLaunchKernelGGL(decode_mha_kernel_g64, grid, block, 0, stream, a);
+    if (a.fine_mask) {
+      if (G == 128) hipLaunchKernelGGL(decode_mha_pairs_kernel_g128, grid, block, 0, stream, a);
+      else hipLaunchKernelGGL(decode_mha_pairs_kernel_g64, grid, block, 0, stream, a);
+    } else {
+      if (G == 128) hipLaunchKernelGGL(decode_mha_kernel_g128, grid, block, 0, stream, a);
+      else hipLaunchKernelGGL(decode_mha_kernel_g64, grid, block, 0, stream, a);
+    }
+  } else if (a.fine_mask) {
+    if (G == 128) hipLaunchKernelGGL((decode_gqa_kernel<128, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((decode_gqa_kernel<64, true>), grid, block, 0, stream, a);
   } else {
-    if (G == 128) hipLaunchKernelGGL(decode_gqa_kernel<128>, grid, block, 0, stream, a);
-    else hipLaunchKernelGGL(decode_gqa_kernel<64>, grid, block, 0, stream, a);
+    if (G == 128) hipLaunchKernelGGL((decode_gqa_kernel<128, false>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((decode_gqa_kernel<64, false>), grid, block, 0, stream, a);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || a.n_split == 1) return e;

@@ -16,6 +16,12 @@ struct QuantArgs {
   int first_blk, n_blk;  // 32-token blocks touched by rows [T_len, T_len + n_new)
   float clip;
   int rotate_v;
+  // tiered append (all null / zero for the plain call): source row and tier of every new cache row, per batch element
+  const int32_t *row_src;   // [B][n_new]
+  const uint8_t *row_tier;  // [B][n_new]
+  uint32_t *fine_mask;      // [B][T_cap/32]
+  int n_src;                // rows per (b, kv-head) in k_new / v_new (= n_new for the plain call)
+  float clip4;
 };
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream);
 
@@ -23,6 +29,7 @@ struct DecodeArgs {
   const uint32_t *k_codes, *v_codes, *k_meta, *v_meta;
   const uint16_t *k_sal, *v_sal;
   const int32_t *sal_idx, *sal_cnt;
+  const uint32_t *fine_mask;  // [B][T_cap/32] or null: fine halves of 4-bit tokens stored as row pairs
   const uint16_t *q;  // [B][Hq][128] binary16
   float *partial;     // [B*Hq][n_split][kPartialStride] fp32
   float *out;         // [B][Hq][128]

@@ -6,6 +6,7 @@
 // token pair (t, t+16): lane (r, j) holds channels e = 32*m + 8*j + i (m<4, i<8) of tokens r and r+16 of the
 // block, so every global load is a 128-bit load and a quad covers 64 contiguous bytes of a row.  Butterfly
 // strides 1,2,4 and 32,64 stay in registers; strides 8,16 cross the quad with DPP quad_perm.
+#include "../../include/akvq.h"
 #include "akvq_device.h"
 #include "akvq_kernels.h"
 
@@ -107,25 +108,35 @@ struct GroupQ {
   uint32_t meta;      // scale bits | zero << 16 (salient flag added by the caller)
   float rcpu;         // kappa / scale
   float magic_zero;   // 1.5 * 2^23 + zero
+  uint32_t s16;       // scale bits and zero-point on their own (the 4-bit tier splits them over two rows)
+  int z;
 };
+// number of levels of the two tiers: 1/(2^n - 1) rounded to binary32, and the largest stored scale (the 4-bit tier
+// keeps 4*scale representable in binary16)
+struct TierQ {
+  float inv_levels;
+  uint32_t s16_max;
+};
+__device__ __forceinline__ TierQ tier_two_bit() { return {__uint_as_float(0x3EAAAAABu), 0x7BFFu}; }
+__device__ __forceinline__ TierQ tier_four_bit() { return {__uint_as_float(0x3D888889u), 0x73FFu}; }
 
 constexpr float kMagic = 12582912.0f;      // 1.5 * 2^23: adding it rounds to an integer in the low mantissa bits
 constexpr uint32_t kMagicBits = 0x4B400000u;
 
 // Eq. 5-6 for one group from the extrema of the un-normalised transform.
-__device__ __forceinline__ GroupQ group_params(float umin, float umax, float kappa, float clip) {
+__device__ __forceinline__ GroupQ group_params(float umin, float umax, float kappa, float clip, TierQ tq) {
   float gmin = __fmul_rn(umin, kappa), gmax = __fmul_rn(umax, kappa);
   float cmin = __fmul_rn(clip, gmin), cmax = __fmul_rn(clip, gmax);
   float range = __fsub_rn(cmax, cmin);
-  float s32 = __fmul_rn(range, __uint_as_float(0x3EAAAAABu));
+  float s32 = __fmul_rn(range, tq.inv_levels);
   uint32_t s16;
   if (!(s32 > 0.0f)) {
     s16 = 0x3C00u;
   } else {
     s16 = float_to_half_bits_rne(s32);
-    if (s16 >= 0x7C00u) s16 = 0x7BFFu;
+    if (s16 > tq.s16_max) s16 = tq.s16_max;
     else if (half_bits_to_float(s16) < s32) s16 += 1u;
-    if (s16 >= 0x7C00u) s16 = 0x7BFFu;
+    if (s16 > tq.s16_max) s16 = tq.s16_max;
   }
   float s = half_bits_to_float(s16);
   // 1/s correctly rounded: s has an 11-bit significand (binary16), so 1/s is either exact or at least 2^-35 (relative)
@@ -140,6 +151,8 @@ __device__ __forceinline__ GroupQ group_params(float umin, float umax, float kap
   g.meta = s16 | ((uint32_t)(z & 0xFFFF) << 16);
   g.rcpu = __fmul_rn(rcp, kappa);
   g.magic_zero = kMagic + (float)z;
+  g.s16 = s16;
+  g.z = z;
   return g;
 }
 
@@ -150,12 +163,21 @@ __device__ __forceinline__ uint32_t code_bits(float u, const GroupQ &g) {
   t = fminf(fmaxf(t, kMagic), kMagic + 3.0f);
   return __float_as_uint(t);
 }
+// The same for a row of any tier: clamp to the tier's top level, then keep the two bits this row stores (bits 2-3 of
+// a 4-bit code for the coarse half, bits 0-1 otherwise), again as the pattern of 1.5*2^23 + field.
+__device__ __forceinline__ uint32_t code_bits_tiered(float u, const GroupQ &g, float top, uint32_t shift, uint32_t keep) {
+  float t = __fmaf_rn(u, g.rcpu, g.magic_zero);
+  t = fminf(fmaxf(t, kMagic), top);
+  return kMagicBits | ((__float_as_uint(t) >> shift) & keep);
+}
 // Packing adds the raw patterns with shifts (one shift-add per code); what the constant part of every pattern
 // contributes is a compile-time constant (mod 2^32) that is subtracted once per word.
 constexpr uint32_t kPack16Bias = (uint32_t)(0x4B400000ull * 0x55555555ull);   // sum over s<16 of kMagicBits << 2s
 constexpr uint32_t kPack4Bias = (uint32_t)(0x4B400000ull * 0x01010101ull);    // sum over b<4 of kMagicBits << 8b
 
-template <int G>
+// TIERED: rows carry a tier and a source-row index (akvq_quantize_append_tiered); the plain instantiation is the
+// two-bit path with identity row mapping and none of the per-row tier arithmetic.
+template <int G, bool TIERED>
 __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   __shared__ int slot_of_lds[4][kTokBlock];
   const int wave = threadIdx.x >> 6;
@@ -190,15 +212,36 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   if (lane * stride < cnt) e1 = sidx[lane * stride];
 
   bool valid[2];
+  int tier[2] = {AKVQ_TIER_2BIT, AKVQ_TIER_2BIT};
   u32x4 raw[2][4];
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int t = t0 + 16 * h + r;
     valid[h] = (t >= a.T_len) && (t < t_end);
     // rows outside the appended range read a clamped (valid) address; nothing derived from them is stored
-    const uint16_t *row = src + ((size_t)bh * a.n_new + min(max(t - a.T_len, 0), a.n_new - 1)) * kD;
+    const int rel = min(max(t - a.T_len, 0), a.n_new - 1);
+    int src_row = rel;
+    if constexpr (TIERED) {
+      const size_t at = (size_t)(bh / a.Hkv) * a.n_new + rel;
+      src_row = min(max(a.row_src[at], 0), a.n_src - 1);
+      if (valid[h]) tier[h] = a.row_tier[at];
+    }
+    const uint16_t *row = src + ((size_t)bh * a.n_src + src_row) * kD;
 #pragma unroll
     for (int m = 0; m < 4; ++m) raw[h][m] = *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j);
+  }
+  if constexpr (TIERED) {
+    // fine-half mask of this block (one word per batch element): lane L < 32 looks at row t0 + L
+    if (tensor == 0 && bh % a.Hkv == 0) {
+      const int t = t0 + (lane & 31);
+      const bool in_range = lane < kTokBlock && t >= a.T_len && t < t_end;
+      const bool fine = in_range && a.row_tier[(size_t)(bh / a.Hkv) * a.n_new + (t - a.T_len)] == AKVQ_TIER_4BIT_FINE;
+      const uint32_t written = (uint32_t)__ballot(in_range), bits = (uint32_t)__ballot(fine);
+      if (lane == 0) {
+        uint32_t *w = a.fine_mask + (size_t)(bh / a.Hkv) * (a.T_cap / kTokBlock) + blk;
+        *w = (written == 0xFFFFFFFFu) ? bits : ((*w & ~written) | bits);
+      }
+    }
   }
 
   if (lane < kTokBlock) slot_of[lane] = -1;
@@ -227,6 +270,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     slots[h] = slot_of[16 * h + r];
+    if (TIERED && tier[h] != AKVQ_TIER_2BIT) slots[h] = -1;  // only plain rows can be salient
     float u[4][8];  // lane_sign times the (rotated) row
     if (rotate) {
       wht128_quad(raw[h], u, j);
@@ -289,10 +333,37 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
       mx = fmaxf(mx, dpp_move<kQuadXor1>(mx));
       mn = fminf(mn, dpp_move<kQuadXor2>(mn));
       mx = fmaxf(mx, dpp_move<kQuadXor2>(mx));
-      gq[g] = group_params(mn, mx, kappa, a.clip);
+      if constexpr (!TIERED) {
+        gq[g] = group_params(mn, mx, kappa, a.clip, tier_two_bit());
+        meta_out[h][g] = gq[g].meta | (slots[h] >= 0 ? 0x8000u : 0u);
+      } else {
+        const bool four = tier[h] == AKVQ_TIER_4BIT_COARSE || tier[h] == AKVQ_TIER_4BIT_FINE;
+        const TierQ t2 = tier_two_bit(), t4 = tier_four_bit();
+        const TierQ tq = {four ? t4.inv_levels : t2.inv_levels, four ? t4.s16_max : t2.s16_max};
+        gq[g] = group_params(mn, mx, kappa, four ? a.clip4 : a.clip, tq);
+        uint32_t mw = gq[g].meta | (slots[h] >= 0 ? 0x8000u : 0u);
+        if (tier[h] == AKVQ_TIER_4BIT_COARSE)  // scale 4*s (exact in binary16), zero floor(z4 / 4)
+          mw = float_to_half_bits_rne(4.0f * half_bits_to_float(gq[g].s16)) | ((uint32_t)((gq[g].z >> 2) & 0xFFFF) << 16);
+        else if (tier[h] == AKVQ_TIER_4BIT_FINE)  // scale s, zero z4 mod 4
+          mw = gq[g].s16 | ((uint32_t)(gq[g].z & 3) << 16);
+        else if (tier[h] == AKVQ_TIER_PAD)  // ignored by decode: salient bit without an overlay slot
+          mw = 0x3C00u | 0x8000u;
+        meta_out[h][g] = mw;
+      }
       gq[g].rcpu *= lane_sign;  // codes are taken from the signed values this lane holds
-      meta_out[h][g] = gq[g].meta | (slots[h] >= 0 ? 0x8000u : 0u);
     }
+    // per-row constants of the code extraction (tiered rows only)
+    float code_top = kMagic + 3.0f;
+    uint32_t code_shift = 0u, code_keep = 3u;
+    if constexpr (TIERED) {
+      if (tier[h] == AKVQ_TIER_4BIT_COARSE || tier[h] == AKVQ_TIER_4BIT_FINE) code_top = kMagic + 15.0f;
+      if (tier[h] == AKVQ_TIER_4BIT_COARSE) code_shift = 2u;
+      if (tier[h] == AKVQ_TIER_PAD) code_keep = 0u;
+    }
+    auto row_code = [&](float x, const GroupQ &q) {
+      if constexpr (TIERED) return code_bits_tiered(x, q, code_top, code_shift, code_keep);
+      else return code_bits(x, q);
+    };
 
     // ---- codes ----
     if (tensor == 0) {
@@ -303,7 +374,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 #pragma unroll
         for (int slot = 15; slot >= 0; --slot) {
           const int m = 2 * wq + (slot >> 3), i = slot & 7;
-          word = (word << 2) + code_bits(u[m][i], gq[m / (4 / NG)]);
+          word = (word << 2) + row_code(u[m][i], gq[m / (4 / NG)]);
           asm("" : "+v"(word));  // keep the chain one shift-add per code (re-association costs more instructions)
         }
         kw[h][wq] = word - kPack16Bias;
@@ -314,8 +385,8 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
       for (int mp = 0; mp < 2; ++mp)
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-          const uint32_t bx = code_bits(u[2 * mp][i], gq[(2 * mp) / (4 / NG)]);
-          const uint32_t by = code_bits(u[2 * mp + 1][i], gq[(2 * mp + 1) / (4 / NG)]);
+          const uint32_t bx = row_code(u[2 * mp][i], gq[(2 * mp) / (4 / NG)]);
+          const uint32_t by = row_code(u[2 * mp + 1][i], gq[(2 * mp + 1) / (4 / NG)]);
           const uint32_t part = (by << 8) + bx;
           if (h == 0) vcode[mp][i] = part; else vcode[mp][i] = (part << 16) + vcode[mp][i];
         }
@@ -398,8 +469,13 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream) {
   dim3 grid((a.n_blk + 3) / 4, B * a.Hkv, 2), block(256);
-  if (G == 128) hipLaunchKernelGGL(quantize_append_kernel<128>, grid, block, 0, stream, a);
-  else hipLaunchKernelGGL(quantize_append_kernel<64>, grid, block, 0, stream, a);
+  if (a.row_tier) {
+    if (G == 128) hipLaunchKernelGGL((quantize_append_kernel<128, true>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((quantize_append_kernel<64, true>), grid, block, 0, stream, a);
+  } else {
+    if (G == 128) hipLaunchKernelGGL((quantize_append_kernel<128, false>), grid, block, 0, stream, a);
+    else hipLaunchKernelGGL((quantize_append_kernel<64, false>), grid, block, 0, stream, a);
+  }
   return hipGetLastError();
 }
 

@@ -147,3 +147,37 @@ def generate(w: Workload, seed: int = BASE_SEED, layer: int = 0, device: str = "
     is_text = mask.to(dev)[None, :].expand(B, w.T).contiguous()
     return {"k": k, "v": v, "q_tail": q_tail, "q": q, "is_text": is_text, "pivots": pivots,
             "outlier_channels": outlier}
+
+
+def tiered_rows(is_text: np.ndarray, keep_plain=None):
+    """Row plan of a cache with the 4-bit text tier: text tokens become (coarse, fine) row pairs starting on even rows
+    (a padding row is inserted where needed), every other token (and every token listed in keep_plain[b]) one plain row.
+
+    is_text [B, T] uint8.  Returns (row_src [B, n_rows] int32, row_tier [B, n_rows] uint8, row_of_token [B, T] int32);
+    batch elements are padded with padding rows to a common, even n_rows.  Tiers: 0 plain 2-bit, 1 coarse, 2 fine, 3 pad.
+    """
+    B, T = is_text.shape
+    plans = []
+    for b in range(B):
+        keep = set(int(x) for x in (keep_plain[b] if keep_plain is not None else ()))
+        src, tier, row_of = [], [], np.zeros(T, dtype=np.int32)
+        for t in range(T):
+            if is_text[b, t] and t not in keep:
+                if len(src) % 2:
+                    src.append(t); tier.append(3)
+                row_of[t] = len(src)
+                src += [t, t]; tier += [1, 2]
+            else:
+                row_of[t] = len(src)
+                src.append(t); tier.append(0)
+        plans.append((src, tier, row_of))
+    n_rows = max(len(p[0]) for p in plans)
+    n_rows += n_rows % 2
+    row_src = np.zeros((B, n_rows), dtype=np.int32)
+    row_tier = np.full((B, n_rows), 3, dtype=np.uint8)
+    row_of_token = np.zeros((B, T), dtype=np.int32)
+    for b, (src, tier, row_of) in enumerate(plans):
+        row_src[b, :len(src)] = src
+        row_tier[b, :len(tier)] = tier
+        row_of_token[b] = row_of
+    return row_src, row_tier, row_of_token
