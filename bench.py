@@ -80,22 +80,59 @@ def phase_bench(args, w, akvq, synth, torch, np):
         cache = akvq.Cache(w.B, w.Hkv, w.G, t_cap, w.s_cap(layer))
         sets.append((d, cache))
 
+    tiered = None
+    if args.tiered:
+        # Section III-C.1 tiers: text tokens (all but position 0, a planted pivot) 4-bit as row pairs, pivot tokens
+        # 16-bit, the rest 2-bit.  The row plan depends on the prompt layout only, so it is built once on the host.
+        mask = sets[0][0]["is_text"].cpu().numpy()
+        row_src, row_tier, row_of = synth.tiered_rows(mask, [[0]] * w.B)
+        n_rows = row_src.shape[1]
+        t_cap = (n_rows + 63) // 64 * 64
+        tiered = {"row_src": torch.from_numpy(row_src).cuda(), "row_tier": torch.from_numpy(row_tier).cuda(),
+                  "row_of": torch.from_numpy(row_of).cuda().long(), "n_rows": n_rows,
+                  "plain": torch.from_numpy(((mask == 0) | (np.arange(w.T)[None, :] == 0))).cuda()}
+        sets = [(d, akvq.Cache(w.B, w.Hkv, w.G, t_cap, w.s_cap(layer))) for d, _ in sets]
+        n_pairs = int((row_tier == 2).sum(axis=1).max())
+        per_row = 2 * (32 + 4 * (128 // w.G))
+        per_set = dict(per_set)
+        per_set["decode"] = w.B * w.Hkv * ((n_rows - w.top_k) * per_row + w.top_k * 512)
+        per_set["quantize"] = per_set["quantize_in"] + w.B * w.Hkv * (n_rows * per_row + w.top_k * 512)
+
+    def to_rows(cache):
+        """salient token positions -> cache rows, keeping only tokens stored as plain rows (ascending order kept)"""
+        idx = cache.sal_idx.long().clamp_(min=0)
+        cnt = cache.counts().clamp(max=cache.S_cap)
+        b_ix = torch.arange(w.B, device=idx.device)[:, None, None].expand_as(idx)
+        ok = (torch.arange(cache.S_cap, device=idx.device)[None, None, :] < cnt[:, :, None]) & tiered["plain"][b_ix, idx]
+        rows = torch.where(ok, tiered["row_of"][b_ix, idx], torch.full_like(idx, 1 << 30))
+        rows, _ = torch.sort(rows, dim=-1)
+        cache.sal_idx.copy_(torch.where(rows < (1 << 30), rows, torch.full_like(rows, -1)).int())
+        cache.counts().copy_(ok.sum(-1).int())
+
+    def append(d, cache):
+        if tiered:
+            akvq.quantize_append_tiered(cache, d["k"], d["v"], tiered["row_src"], tiered["row_tier"], w.clip, 1.0)
+        else:
+            akvq.quantize_append(cache, d["k"], d["v"], w.clip)
+
     def prepare(d, cache, upto):
         cache.T_len = 0
         if w.mode(layer) == "tsa":
             akvq.select_salient(cache, akvq.MODE_TSA, is_text=d["is_text"])
         else:
             akvq.select_salient(cache, akvq.MODE_PSA, q_tail=d["q_tail"], k=d["k"], top_k=w.top_k, sm_scale=w.sm_scale)
+        if tiered:
+            to_rows(cache)
         if upto == "select":
             return
-        akvq.quantize_append(cache, d["k"], d["v"], w.clip)
+        append(d, cache)
 
     def call(d, cache):
         if args.phase == "decode":
             akvq.decode_attention(cache, d["q"], w.sm_scale, n_split=args.n_split)
         elif args.phase == "quantize":
             cache.T_len = 0
-            akvq.quantize_append(cache, d["k"], d["v"], w.clip)
+            append(d, cache)
         else:
             prepare(d, cache, "select")
 
@@ -118,7 +155,8 @@ def phase_bench(args, w, akvq, synth, torch, np):
     ms = e0.elapsed_time(e1) / n_calls
     nbytes = per_set[args.phase]
     gbps = nbytes / (ms * 1e-3) / 1e9
-    out = {"metric": f"{args.phase} call alone", "workload": w.name, "layer_mode": w.mode(layer), "ms_per_call": round(ms, 5),
+    out = {"metric": f"{args.phase} call alone" + (" (4-bit text tier as row pairs)" if tiered else ""),
+           "cache_rows": tiered["n_rows"] if tiered else w.T, "workload": w.name, "layer_mode": w.mode(layer), "ms_per_call": round(ms, 5),
            "kv_tokens_per_s": w.B * w.T / (ms * 1e-3), "n_sets": n_sets, "calls": n_calls,
            "n_split": args.n_split or akvq.lib().akvq_decode_default_splits(w.B, w.Hkv, w.T),
            "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -137,6 +175,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--layer", type=int, default=-1, help="layer whose mode (TSA/PSA) a --phase run uses")
+    ap.add_argument("--tiered", action="store_true",
+                    help="--phase decode|quantize with the 4-bit text tier (text tokens as row pairs, pivots 16-bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
     ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "copy"],

@@ -163,12 +163,13 @@ __device__ __forceinline__ uint32_t code_bits(float u, const GroupQ &g) {
   t = fminf(fmaxf(t, kMagic), kMagic + 3.0f);
   return __float_as_uint(t);
 }
-// The same for a row of any tier: clamp to the tier's top level, then keep the two bits this row stores (bits 2-3 of
-// a 4-bit code for the coarse half, bits 0-1 otherwise), again as the pattern of 1.5*2^23 + field.
-__device__ __forceinline__ uint32_t code_bits_tiered(float u, const GroupQ &g, float top, uint32_t shift, uint32_t keep) {
+// The same for a row of any tier: clamp to the tier's top level, then extract the field this row stores (bits 2-3 of
+// a 4-bit code for the coarse half, bits 0-1 otherwise, nothing for a padding row): one bit-field extract.  Returns the
+// bare field (no constant part), so the tiered kernel packs without the bias constants.
+__device__ __forceinline__ uint32_t code_bits_tiered(float u, const GroupQ &g, float top, uint32_t shift, uint32_t width) {
   float t = __fmaf_rn(u, g.rcpu, g.magic_zero);
   t = fminf(fmaxf(t, kMagic), top);
-  return kMagicBits | ((__float_as_uint(t) >> shift) & keep);
+  return __builtin_amdgcn_ubfe(__float_as_uint(t), shift, width);
 }
 // Packing adds the raw patterns with shifts (one shift-add per code); what the constant part of every pattern
 // contributes is a compile-time constant (mod 2^32) that is subtracted once per word.
@@ -354,12 +355,13 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
     }
     // per-row constants of the code extraction (tiered rows only)
     float code_top = kMagic + 3.0f;
-    uint32_t code_shift = 0u, code_keep = 3u;
+    uint32_t code_shift = 0u, code_keep = 2u;  // field offset and width in bits
     if constexpr (TIERED) {
       if (tier[h] == AKVQ_TIER_4BIT_COARSE || tier[h] == AKVQ_TIER_4BIT_FINE) code_top = kMagic + 15.0f;
       if (tier[h] == AKVQ_TIER_4BIT_COARSE) code_shift = 2u;
       if (tier[h] == AKVQ_TIER_PAD) code_keep = 0u;
     }
+    constexpr uint32_t kBias16 = TIERED ? 0u : kPack16Bias;
     auto row_code = [&](float x, const GroupQ &q) {
       if constexpr (TIERED) return code_bits_tiered(x, q, code_top, code_shift, code_keep);
       else return code_bits(x, q);
@@ -377,7 +379,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           word = (word << 2) + row_code(u[m][i], gq[m / (4 / NG)]);
           asm("" : "+v"(word));  // keep the chain one shift-add per code (re-association costs more instructions)
         }
-        kw[h][wq] = word - kPack16Bias;
+        kw[h][wq] = word - kBias16;
       }
     } else {
       // V: byte lanes of a partial word: token half h, X (m even) / Y (m odd); biases removed after both halves
@@ -433,7 +435,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
       for (int i = 0; i < 8; ++i)
 #pragma unroll
         for (int mp = 0; mp < 2; ++mp) {
-          uint32_t x = (vcode[mp][i] - kPack4Bias) << (2 * ii);
+          uint32_t x = (vcode[mp][i] - (TIERED ? 0u : kPack4Bias)) << (2 * ii);
           x |= dpp_move_u<kRowRor4>(x);
           x |= dpp_move_u<kRowRor8>(x);
           w[mp][i] = x;
