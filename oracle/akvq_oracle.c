@@ -407,16 +407,19 @@ void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_
  *      the token is quantized to 4 bits (scale s, zero z4, code c4), then stored as two 2-bit rows
  *        coarse: codes c4 >> 2, scale 4*s, zero z4 >> 2 (floor);   fine: codes c4 & 3, scale s, zero z4 & 3
  *      so that  4*s*(hi - zc) + s*(lo - zf) = s*(c4 - z4)  exactly;
- *   3  padding row: flagged like a salient row without an overlay slot, so decode ignores it.
+ *   3  padding row: meta = salient bit with scale bits 0 (a marker no real row has), so decode ignores it.
  * fine_mask [B][T_cap/32]: bit (t % 32) of word t/32 is set for fine halves, cleared for every other written row.
  * reading (the paper gives no storage format): this pairing is this build's own; parity unpinned by the paper,
  * pinned by the identity above and by attention over directly dequantized 4-bit values.
  * ---------------------------------------------------------------------------------------- */
 void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint16_t *v_src, int n_src,
                                 const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
-                                float clip4, int rotate_v, uint32_t *fine_mask) {
+                                float clip4, int rotate_v, uint32_t *fine_mask, uint16_t *k_win, uint16_t *v_win,
+                                int W) {
   const int ng = ORC_D / c->G;
   const int nbh = c->B * c->Hkv;
+  const int t_end = c->T_len + n_rows;
+  if (fine_mask)
   for (int b = 0; b < c->B; ++b)
     for (int i = 0; i < n_rows; ++i) {
       int t = c->T_len + i;
@@ -428,19 +431,34 @@ void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint1
     int b = bh / c->Hkv, h = bh % c->Hkv;
     for (int i = 0; i < n_rows; ++i) {
       int t = c->T_len + i;
-      int tier = row_tier[(size_t)b * n_rows + i];
-      int src = row_src[(size_t)b * n_rows + i];
+      int tier = row_tier ? row_tier[(size_t)b * n_rows + i] : 0;
+      int src = row_src ? row_src[(size_t)b * n_rows + i] : i;
       int slot = tier == 0 ? salient_slot(c, b, h, t) : -1;
+      /* recent window (Section III-B.1 keeps the most recent tokens 16-bit): the last W of the appended rows also go
+       * to ring slot t % W as bfloat16 (rotated), overwriting the row that leaves the window -- whose codes were
+       * written when it was appended, so leaving the window needs no work.  Fine halves and padding rows carry no
+       * token: their slots are zeroed. */
+      const int in_win = (W > 0) && (t >= t_end - W);
       for (int tensor = 0; tensor < 2; ++tensor) {
         uint32_t *meta = (tensor == 0 ? c->k_meta : c->v_meta) + ((size_t)bh * c->T_cap + t) * ng;
+        if (in_win && (tier == 2 || tier == 3)) {
+          if (tensor == 0) memset(k_win + ((size_t)bh * W + t % W) * ORC_D, 0, sizeof(uint16_t) * ORC_D);
+          else for (int e = 0; e < ORC_D; ++e) v_win[(size_t)bh * W * ORC_D + orc_vsal_pos(t % W, e)] = 0;
+        }
         if (tier == 3) {
           for (int e = 0; e < ORC_D; ++e) put_code(c, tensor, b, h, t, e, 0);
-          for (int g = 0; g < ng; ++g) meta[g] = 0x3C00u | 0x8000u;
+          for (int g = 0; g < ng; ++g) meta[g] = 0x8000u; /* scale bits 0 + salient bit: the padding marker */
           continue;
         }
         const uint16_t *row = (tensor == 0 ? k_src : v_src) + ((size_t)bh * n_src + src) * ORC_D;
         uint8_t codes[ORC_D]; uint16_t sb[2]; int16_t z[2]; uint16_t ybf[ORC_D];
         const int rot = tensor == 0 ? 1 : rotate_v;
+        if (in_win && tier != 2) { /* ybf does not depend on the bit width */
+          uint16_t yb[ORC_D]; uint8_t cc[ORC_D]; uint16_t s2[2]; int16_t z2[2];
+          orc_quantize_row_bits(row, c->G, clip2, rot, 2, cc, s2, z2, yb);
+          if (tensor == 0) memcpy(k_win + ((size_t)bh * W + t % W) * ORC_D, yb, sizeof(yb));
+          else for (int e = 0; e < ORC_D; ++e) v_win[(size_t)bh * W * ORC_D + orc_vsal_pos(t % W, e)] = yb[e];
+        }
         if (tier == 0) {
           orc_quantize_row_bits(row, c->G, clip2, rot, 2, codes, sb, z, ybf);
           for (int e = 0; e < ORC_D; ++e) put_code(c, tensor, b, h, t, e, codes[e]);
@@ -505,14 +523,33 @@ static void cached_row(const orc_cache *c, int tensor, int b, int h, int t, int 
 
 void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const uint16_t *q_row, double sm_scale,
                               int unrotate, double *out, double *lse) {
-  orc_decode_attention_one_tiered(c, NULL, Hq, b, hq, q_row, sm_scale, unrotate, out, lse);
+  orc_decode_attention_one_tiered(c, NULL, NULL, NULL, 0, Hq, b, hq, q_row, sm_scale, unrotate, out, lse);
+}
+
+/* first row of the recent window: the last W rows, the boundary moved up to an even row so that a (coarse, fine)
+ * pair is never split (the window then holds W or W-1 rows) */
+static int window_start(int T_len, int W) {
+  if (W <= 0) return T_len;
+  int t = T_len - W;
+  if (t < 0) t = 0;
+  return (t + 1) & ~1;
+}
+static void window_row(const uint16_t *k_win, const uint16_t *v_win, int W, size_t bh, int tensor, int t, double *row) {
+  int slot = t % W;
+  if (tensor == 0) {
+    const uint16_t *src = k_win + (bh * W + slot) * ORC_D;
+    for (int e = 0; e < ORC_D; ++e) row[e] = (double)orc_bf16_to_float(src[e]);
+  } else {
+    const uint16_t *plane = v_win + bh * W * ORC_D;
+    for (int e = 0; e < ORC_D; ++e) row[e] = (double)orc_bf16_to_float(plane[orc_vsal_pos(slot, e)]);
+  }
 }
 
 /* fine_mask (may be NULL): rows flagged there are the fine halves of 4-bit tokens; such a row and the row before
  * it are one token whose value is the sum of the two dequantized rows (Eq. 4 applied to each half). */
-void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, int b, int hq,
-                                     const uint16_t *q_row, double sm_scale, int unrotate, double *out,
-                                     double *lse) {
+void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
+                                     const uint16_t *v_win, int W, int Hq, int b, int hq, const uint16_t *q_row,
+                                     double sm_scale, int unrotate, double *out, double *lse) {
   const int r = Hq / c->Hkv;
   const int h = hq / r;
   const int T = c->T_len;
@@ -530,17 +567,24 @@ void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_ma
   double row[ORC_D], row2[ORC_D];
   double mx = -INFINITY;
   const uint32_t *fm = fine_mask ? fine_mask + (size_t)b * (c->T_cap / 32) : NULL;
+  const int t_win = window_start(T, (k_win && v_win) ? W : 0);
 #define ORC_IS_FINE(t) (fm && ((fm[(t) / 32] >> ((t) % 32)) & 1u))
   /* a token = one row, or a (coarse, fine) pair of rows; skipped rows: fine halves (counted with their coarse row)
    * and rows flagged salient that have no overlay slot (padding) */
   for (int t = 0; t < T; ++t) {
     score[t] = -INFINITY;
     if (ORC_IS_FINE(t)) continue;
-    if (slot_of[t] < 0 && (c->k_meta[(bh_index(c, b, h) * c->T_cap + t) * (ORC_D / c->G)] & 0x8000u)) continue;
-    cached_row(c, 0, b, h, t, slot_of[t], row);
-    if (t + 1 < T && ORC_IS_FINE(t + 1)) {
-      cached_row(c, 0, b, h, t + 1, -1, row2);
-      for (int e = 0; e < ORC_D; ++e) row[e] += row2[e];
+    const uint32_t mk = c->k_meta[(bh_index(c, b, h) * c->T_cap + t) * (ORC_D / c->G)];
+    if (t >= t_win) { /* recent window: the 16-bit ring row is the token, whatever its tier */
+      if ((mk & 0xFFFFu) == 0x8000u) continue; /* padding row */
+      window_row(k_win, v_win, W, bh_index(c, b, h), 0, t, row);
+    } else {
+      if (slot_of[t] < 0 && (mk & 0x8000u)) continue;
+      cached_row(c, 0, b, h, t, slot_of[t], row);
+      if (t + 1 < T && ORC_IS_FINE(t + 1)) {
+        cached_row(c, 0, b, h, t + 1, -1, row2);
+        for (int e = 0; e < ORC_D; ++e) row[e] += row2[e];
+      }
     }
     double acc = 0.0;
     for (int e = 0; e < ORC_D; ++e) acc += qrot[e] * row[e];
@@ -554,10 +598,14 @@ void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_ma
   for (int t = 0; t < T; ++t) {
     if (score[t] == -INFINITY) continue;
     double p = exp(score[t] - mx) / den;
-    cached_row(c, 1, b, h, t, slot_of[t], row);
-    if (t + 1 < T && ORC_IS_FINE(t + 1)) {
-      cached_row(c, 1, b, h, t + 1, -1, row2);
-      for (int e = 0; e < ORC_D; ++e) row[e] += row2[e];
+    if (t >= t_win) {
+      window_row(k_win, v_win, W, bh_index(c, b, h), 1, t, row);
+    } else {
+      cached_row(c, 1, b, h, t, slot_of[t], row);
+      if (t + 1 < T && ORC_IS_FINE(t + 1)) {
+        cached_row(c, 1, b, h, t + 1, -1, row2);
+        for (int e = 0; e < ORC_D; ++e) row[e] += row2[e];
+      }
     }
     for (int e = 0; e < ORC_D; ++e) orot[e] += p * row[e];
   }
@@ -570,16 +618,17 @@ void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_ma
 
 void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int unrotate,
                           double *out, double *lse) {
-  orc_decode_attention_tiered(c, NULL, Hq, q, sm_scale, unrotate, out, lse);
+  orc_decode_attention_tiered(c, NULL, NULL, NULL, 0, Hq, q, sm_scale, unrotate, out, lse);
 }
 
-void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, const uint16_t *q,
-                                 double sm_scale, int unrotate, double *out, double *lse) {
+void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
+                                 const uint16_t *v_win, int W, int Hq, const uint16_t *q, double sm_scale,
+                                 int unrotate, double *out, double *lse) {
   const int n = c->B * Hq;
 #pragma omp parallel for schedule(dynamic)
   for (int x = 0; x < n; ++x) {
     int b = x / Hq, hq = x % Hq;
-    orc_decode_attention_one_tiered(c, fine_mask, Hq, b, hq, q + (size_t)x * ORC_D, sm_scale, unrotate,
+    orc_decode_attention_one_tiered(c, fine_mask, k_win, v_win, W, Hq, b, hq, q + (size_t)x * ORC_D, sm_scale, unrotate,
                                     out + (size_t)x * ORC_D, lse ? lse + x : NULL);
   }
 }

@@ -87,7 +87,11 @@ void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_
  * rows), 3 = padding.  fine_mask [B][T_cap/32] marks the fine halves.  Does not change T_len. */
 void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint16_t *v_src, int n_src,
                                 const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
-                                float clip4, int rotate_v, uint32_t *fine_mask);
+                                float clip4, int rotate_v, uint32_t *fine_mask, uint16_t *k_win, uint16_t *v_win,
+                                int W);
+/* row_src / row_tier / fine_mask may be NULL (plain rows, identity mapping).  Recent window (W > 0): k_win
+ * [B][Hkv][W][128] and v_win [B][Hkv][W/32][4096] (tiled like v_sal) bfloat16 rings, zero-initialised by the caller;
+ * the last W appended rows are also written to slot t % W.  Decode then reads rows t >= window start from the ring. */
 /* Read path: decode attention (Eq. 2 with the dequantized cache), fp64.  q [B][Hq][128] binary16.
  * out [B][Hq][128]; lse (optional) [B][Hq].  unrotate!=0: out = o~ * H_128. */
 void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int unrotate,
@@ -97,11 +101,12 @@ void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const u
                               int unrotate, double *out, double *lse);
 
 /* The same over a cache with 4-bit tokens stored as row pairs (fine_mask may be NULL: no such tokens). */
-void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, const uint16_t *q,
-                                 double sm_scale, int unrotate, double *out, double *lse);
-void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, int Hq, int b, int hq,
-                                     const uint16_t *q_row, double sm_scale, int unrotate, double *out,
-                                     double *lse);
+void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
+                                 const uint16_t *v_win, int W, int Hq, const uint16_t *q, double sm_scale,
+                                 int unrotate, double *out, double *lse);
+void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
+                                     const uint16_t *v_win, int W, int Hq, int b, int hq, const uint16_t *q_row,
+                                     double sm_scale, int unrotate, double *out, double *lse);
 
 #ifdef __cplusplus
 }

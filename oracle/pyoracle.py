@@ -75,9 +75,10 @@ def lib():
         L.orc_quantize_row_bits.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_void_p]
         L.orc_quantize_append_tiered.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
-                                                 C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int, C.c_void_p]
-        L.orc_decode_attention_tiered.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int, C.c_void_p, C.c_double,
-                                                  C.c_int, C.c_void_p, C.c_void_p]
+                                                 C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_int, C.c_void_p,
+                                                 C.c_void_p, C.c_void_p, C.c_int]
+        L.orc_decode_attention_tiered.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                                  C.c_int, C.c_void_p, C.c_double, C.c_int, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -114,6 +115,9 @@ class OracleCache:
     sal_idx: np.ndarray = field(init=False)
     sal_cnt: np.ndarray = field(init=False)
     fine_mask: np.ndarray | None = field(init=False, default=None)  # [B, T_cap/32] uint32, set by the tiered append
+    W: int = field(init=False, default=0)                           # recent-window length (0 = none)
+    k_win: np.ndarray | None = field(init=False, default=None)      # [B, Hkv, W, 128] bf16 bits, ring by t % W
+    v_win: np.ndarray | None = field(init=False, default=None)      # [B, Hkv, W/32, 4096] bf16 bits, tiled
 
     def __post_init__(self):
         assert self.T_cap % 64 == 0 and self.S_cap % 64 == 0 and self.G in (64, 128)
@@ -159,23 +163,35 @@ class OracleCache:
         lib().orc_quantize_append(C.byref(c), _p(k_new), _p(v_new), n_new, clip, int(rotate_v))
         self.T_len += n_new
 
+    def enable_window(self, W: int):
+        """Keep the most recent W rows 16-bit (ring buffers, zero-initialised)."""
+        assert W % 64 == 0 and W > 0
+        self.W = W
+        self.k_win = np.zeros((self.B, self.Hkv, W, D), dtype=np.uint16)
+        self.v_win = np.zeros((self.B, self.Hkv, W // 32, 4096), dtype=np.uint16)
+
     def quantize_append_tiered(self, k_src, v_src, row_src, row_tier, clip2: float, clip4: float,
                                rotate_v: bool = True):
         """Rows [T_len, T_len + n_rows): row r of batch b takes source token row_src[b, r] with tier row_tier[b, r]
         (0 = 2-bit, 1 / 2 = coarse / fine half of a 4-bit token, 3 = padding); updates self.fine_mask."""
         k_src, v_src = _u16(k_src), _u16(v_src)
         n_src = k_src.shape[2]
-        row_src = np.ascontiguousarray(row_src, dtype=np.int32)
-        row_tier = np.ascontiguousarray(row_tier, dtype=np.uint8)
-        n_rows = row_src.shape[1]
-        assert row_src.shape == (self.B, n_rows) == row_tier.shape
+        if row_src is None:      # plain rows, identity mapping (only the window differs from quantize_append)
+            n_rows = n_src
+            assert row_tier is None
+        else:
+            row_src = np.ascontiguousarray(row_src, dtype=np.int32)
+            row_tier = np.ascontiguousarray(row_tier, dtype=np.uint8)
+            n_rows = row_src.shape[1]
+            assert row_src.shape == (self.B, n_rows) == row_tier.shape
+            if self.fine_mask is None:
+                self.fine_mask = np.zeros((self.B, self.T_cap // 32), dtype=np.uint32)
         assert k_src.shape == (self.B, self.Hkv, n_src, D) == v_src.shape
         assert self.T_len + n_rows <= self.T_cap
-        if self.fine_mask is None:
-            self.fine_mask = np.zeros((self.B, self.T_cap // 32), dtype=np.uint32)
         c = self._c()
         lib().orc_quantize_append_tiered(C.byref(c), _p(k_src), _p(v_src), n_src, _p(row_src), _p(row_tier), n_rows,
-                                         clip2, clip4, int(rotate_v), _p(self.fine_mask))
+                                         clip2, clip4, int(rotate_v), _p(self.fine_mask if row_src is not None else None),
+                                         _p(self.k_win), _p(self.v_win), self.W)
         self.T_len += n_rows
 
     def decode(self, q, sm_scale: float, unrotate: bool = True):
@@ -184,8 +200,8 @@ class OracleCache:
         out = np.zeros((B, Hq, D), dtype=np.float64)
         lse = np.zeros((B, Hq), dtype=np.float64)
         c = self._c()
-        lib().orc_decode_attention_tiered(C.byref(c), _p(self.fine_mask), Hq, _p(q), sm_scale, int(unrotate),
-                                          _p(out), _p(lse))
+        lib().orc_decode_attention_tiered(C.byref(c), _p(self.fine_mask), _p(self.k_win), _p(self.v_win), self.W, Hq,
+                                          _p(q), sm_scale, int(unrotate), _p(out), _p(lse))
         return out, lse
 
     def decode_one(self, b: int, hq: int, Hq: int, q_row, sm_scale: float, unrotate: bool = True):

@@ -135,3 +135,96 @@ def test_zero_point_split_handles_negative_and_large_zero_points(orc):
         mc, mf = int(oc.v_meta[0, 0, 0, 0]), int(oc.v_meta[0, 0, 1, 0])
         zc, zf = int(np.int16(np.uint16(mc >> 16))), int(np.int16(np.uint16(mf >> 16)))
         assert 0 <= zf <= 3 and 4 * zc + zf == int(z4[0])
+
+
+# ---------------------------------------------------------------------------------------- recent window
+def _brute_window(orc, k, v, q, b, h, G, T, t_win, sm):
+    kd, vd = [], []
+    for t in range(T):
+        for src, dst in ((k, kd), (v, vd)):
+            c, sb, z, ybf = orc.quantize_row_bits(src[b, h, t], G, 0.8, 2)
+            if t >= t_win:
+                dst.append(orc.bf16_bits_to_f64(ybf))
+            else:
+                s = sb.view(np.float16).astype(np.float64)
+                dst.append(np.repeat(s, G) * (c.astype(np.float64) - np.repeat(z.astype(np.float64), G)))
+    kd, vd = np.array(kd), np.array(vd)
+    sc = sm * kd @ orc.wht_dense(q[b, h].astype(np.float64))
+    p = np.exp(sc - sc.max()); p /= p.sum()
+    return orc.wht_dense(p @ vd)
+
+
+@pytest.mark.parametrize("T,W", [(200, 64), (70, 64), (40, 64), (129, 128)])
+def test_window_rows_are_read_sixteen_bit(orc, T, W):
+    B, H, G = 1, 2, 128
+    rng = np.random.default_rng(41 + T)
+    k = (rng.standard_normal((B, H, T, D)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, H, D)).astype(np.float16)
+    oc = orc.OracleCache(B, H, G, 256, 64)
+    oc.enable_window(W)
+    oc.quantize_append_tiered(k, v, None, None, 0.8, 1.0)
+    out, _ = oc.decode(q, 0.1)
+    t_win = (max(T - W, 0) + 1) & ~1          # the boundary sits on an even row
+    for h in range(H):
+        ref = _brute_window(orc, k, v, q, 0, h, G, T, t_win, 0.1)
+        assert np.abs(out[0, h] - ref).max() <= 1e-9 * max(1.0, np.abs(ref).max())
+
+
+def test_rows_leaving_the_window_fall_back_to_their_codes(orc):
+    """Appending row by row (each new row overwrites the ring slot of the row that leaves the window) must give the
+    same cache and the same attention as appending everything at once."""
+    B, H, G, T, W = 1, 2, 64, 150, 64
+    rng = np.random.default_rng(47)
+    k = (rng.standard_normal((B, H, T, D)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((B, H, T, D)).astype(np.float16)
+    q = rng.standard_normal((B, H, D)).astype(np.float16)
+    one = orc.OracleCache(B, H, G, 192, 64); one.enable_window(W)
+    one.quantize_append_tiered(k, v, None, None, 0.8, 1.0)
+    step = orc.OracleCache(B, H, G, 192, 64); step.enable_window(W)
+    step.quantize_append_tiered(k[:, :, :90], v[:, :, :90], None, None, 0.8, 1.0)
+    for t in range(90, T):
+        step.quantize_append_tiered(k[:, :, t:t + 1], v[:, :, t:t + 1], None, None, 0.8, 1.0)
+        if t in (100, 127, 149):
+            ref = orc.OracleCache(B, H, G, 192, 64); ref.enable_window(W)
+            ref.quantize_append_tiered(k[:, :, :t + 1], v[:, :, :t + 1], None, None, 0.8, 1.0)
+            a, _ = step.decode(q, 0.1); r, _ = ref.decode(q, 0.1)
+            assert np.abs(a - r).max() <= 1e-12
+    assert np.array_equal(step.k_codes, one.k_codes) and np.array_equal(step.v_meta, one.v_meta)
+    assert np.array_equal(step.k_win, one.k_win) and np.array_equal(step.v_win, one.v_win)
+
+
+def test_window_with_four_bit_pairs(orc):
+    """Pairs inside the window are read from the ring once (the fine half carries nothing there); pairs outside are
+    the sum of their halves; the padding row is no token anywhere."""
+    B, H, G, W = 1, 1, 128, 64
+    rng = np.random.default_rng(53)
+    n_tok = 60
+    k = (rng.standard_normal((B, H, n_tok, D)) * 1.5).astype(np.float16)
+    v = rng.standard_normal((B, H, n_tok, D)).astype(np.float16)
+    q = rng.standard_normal((B, H, D)).astype(np.float16)
+    mask = np.zeros((B, n_tok), dtype=np.uint8); mask[0, 3:9] = 1; mask[0, 41:52] = 1
+    row_src, row_tier, row_of = synth.tiered_rows(mask)
+    n_rows = row_src.shape[1]
+    oc = orc.OracleCache(B, H, G, 128, 64); oc.enable_window(W)
+    oc.quantize_append_tiered(k, v, row_src, row_tier, 0.8, 1.0)
+    out, _ = oc.decode(q, 0.1)
+    t_win = (max(n_rows - W, 0) + 1) & ~1
+    kd, vd = [], []
+    for r in range(n_rows):
+        tier, tok = int(row_tier[0, r]), int(row_src[0, r])
+        if tier in (2, 3):
+            continue
+        for src, dst in ((k, kd), (v, vd)):
+            bits, clip = (4, 1.0) if tier == 1 else (2, 0.8)
+            c, sb, z, ybf = orc.quantize_row_bits(src[0, 0, tok], G, clip, bits)
+            if r >= t_win:
+                dst.append(orc.bf16_bits_to_f64(ybf))
+            else:
+                s = float(sb.view(np.float16)[0])
+                dst.append(s * (c.astype(np.float64) - float(z[0])))
+    kd, vd = np.array(kd), np.array(vd)
+    sc = 0.1 * kd @ orc.wht_dense(q[0, 0].astype(np.float64))
+    p = np.exp(sc - sc.max()); p /= p.sum()
+    ref = orc.wht_dense(p @ vd)
+    assert np.abs(out[0, 0] - ref).max() <= 1e-9 * max(1.0, np.abs(ref).max())
