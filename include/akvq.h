@@ -70,6 +70,16 @@ enum {
  * (codes c4 & 3, scale s, zero z4 mod 4), so that the two dequantized rows add up to s*(c4 - z4) exactly. */
 enum { AKVQ_TIER_2BIT = 0, AKVQ_TIER_4BIT_COARSE = 1, AKVQ_TIER_4BIT_FINE = 2, AKVQ_TIER_PAD = 3 };
 
+/* Recent window (Section III-B.1: the most recent tokens stay 16-bit).  Two bfloat16 rings owned by the caller and
+ * zero-initialised before the first append: k_win [B][Hkv][W][128] (row-major), v_win [B][Hkv][W/32][4096] (tiled like
+ * v_sal).  Cache row t lives in slot t % W while it is among the last W rows; every row also gets its codes when it is
+ * appended, so a row that leaves the window needs no work ("quantize on evict" is free: the quantizer is per token).
+ * The window starts at the even row at or above T_len - W, so a 4-bit pair is never split.  W is a multiple of 64. */
+typedef struct akvq_window {
+  uint16_t *k_win, *v_win; /* device */
+  int32_t W;
+} akvq_window;
+
 /* One layer's cache.  Plain data; every pointer is device memory owned by the caller (layout above).
  * T_len is the number of valid rows; the caller advances it after akvq_quantize_append. */
 typedef struct akvq_cache {
@@ -141,7 +151,9 @@ int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_s
  *     4BIT_COARSE  / 4BIT_FINE: the two halves of one token quantized to 4 bits (Eq. 3-6 with 15 levels, clip4, scale
  *                  stored as binary16 rounded up and at most 16376); the pair must start on an even cache row, both
  *                  rows name the same source token, and neither may be listed in c->sal_idx;
- *     PAD          a row decode ignores (used to align a pair); its meta carries the salient bit, no overlay row.
+ *     PAD          a row decode ignores (used to align a pair); its meta is 0x8000 (salient bit, scale bits 0).
+ *   row_src, row_tier and fine_mask may all be NULL: plain rows with the identity mapping (n_rows = n_src).
+ *   win (may be NULL): the last W of the appended rows are also written to the recent-window rings.
  *   fine_mask: device, [B][T_cap/32] uint32, zero-initialised by the caller before the first append; bit t%32 of word
  *   t/32 is set for fine halves and cleared for every other row written here.
  *   row_src entries are clamped to [0, n_src); other violations of the rules above give unspecified values, no fault.
@@ -149,16 +161,18 @@ int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_s
  */
 int akvq_quantize_append_tiered(const akvq_cache *c, const void *k_src, const void *v_src, int n_src,
                                 const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
-                                float clip4, uint32_t *fine_mask, uint32_t flags, void *stream);
+                                float clip4, uint32_t *fine_mask, const akvq_window *win, uint32_t flags,
+                                void *stream);
 
 /*
  * akvq_decode_attention_tiered -- akvq_decode_attention over a cache that holds 4-bit tokens as row pairs:
  *   a row flagged in fine_mask and the row before it are one token (their scores add up before the softmax, the
- *   token is counted once, both rows take its weight).  fine_mask NULL = akvq_decode_attention.
+ *   token is counted once, both rows take its weight).  win (may be NULL): rows from the window start on are read
+ *   from the 16-bit rings instead of their codes.  fine_mask and win NULL = akvq_decode_attention.
  */
-int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const void *q, int Hq,
-                                 float sm_scale, float *out, float *lse_out, int n_split, void *workspace,
-                                 size_t workspace_bytes, uint32_t flags, void *stream);
+int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win,
+                                 const void *q, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                                 void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 
 #ifdef __cplusplus
 }

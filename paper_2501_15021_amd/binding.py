@@ -30,6 +30,10 @@ class AkvqError(RuntimeError):
     pass
 
 
+class akvq_window(C.Structure):
+    _fields_ = [("k_win", C.c_void_p), ("v_win", C.c_void_p), ("W", C.c_int32)]
+
+
 class akvq_cache(C.Structure):
     _fields_ = [("B", C.c_int32), ("Hkv", C.c_int32), ("G", C.c_int32), ("T_cap", C.c_int32),
                 ("S_cap", C.c_int32), ("T_len", C.c_int32),
@@ -72,12 +76,12 @@ def lib() -> C.CDLL:
                                             C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         L.akvq_quantize_append_tiered.restype = C.c_int
         L.akvq_quantize_append_tiered.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
-                                                  C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_void_p, C.c_uint32,
-                                                  C.c_void_p]
+                                                  C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_void_p,
+                                                  C.POINTER(akvq_window), C.c_uint32, C.c_void_p]
         L.akvq_decode_attention_tiered.restype = C.c_int
-        L.akvq_decode_attention_tiered.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_void_p, C.c_int, C.c_float,
-                                                   C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_size_t,
-                                                   C.c_uint32, C.c_void_p]
+        L.akvq_decode_attention_tiered.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.POINTER(akvq_window),
+                                                   C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_int,
+                                                   C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         _lib = L
     return _lib
 
@@ -102,6 +106,9 @@ class Cache:
     def __init__(self, B: int, Hkv: int, G: int, T_cap: int, S_cap: int, device="cuda", fill: Optional[int] = None):
         self.B, self.Hkv, self.G, self.T_cap, self.S_cap, self.T_len = B, Hkv, G, T_cap, S_cap, 0
         self.fine_mask: Optional[torch.Tensor] = None  # [B, T_cap/32] int32, created by the first tiered append
+        self.W = 0                                     # recent-window length (enable_window)
+        self.k_win: Optional[torch.Tensor] = None      # [B, Hkv, W, 128] bf16 bits, ring by row % W
+        self.v_win: Optional[torch.Tensor] = None      # [B, Hkv, W/32, 4096] bf16 bits, tiled
         shape = akvq_cache(B, Hkv, G, T_cap, S_cap, 0)
         sizes = (C.c_size_t * 8)()
         _check(lib().akvq_cache_bytes(C.byref(shape), sizes), "akvq_cache_bytes")
@@ -131,6 +138,19 @@ class Cache:
             ws = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.k_codes.device)
             self._ws[key] = ws
         return ws
+
+    def enable_window(self, W: int):
+        """Keep the most recent W rows 16-bit (zero-initialised rings)."""
+        assert W > 0 and W % 64 == 0
+        dev = self.k_codes.device
+        self.W = W
+        self.k_win = torch.zeros(self.B, self.Hkv, W, D, dtype=torch.int16, device=dev)
+        self.v_win = torch.zeros(self.B, self.Hkv, W // 32, 4096, dtype=torch.int16, device=dev)
+
+    def window_struct(self):
+        if self.W == 0:
+            return None
+        return akvq_window(self.k_win.data_ptr(), self.v_win.data_ptr(), self.W)
 
     def counts(self) -> torch.Tensor:
         return self.sal_cnt[: self.B * self.Hkv].view(self.B, self.Hkv)
@@ -180,15 +200,23 @@ def quantize_append_tiered(cache: Cache, k_src: torch.Tensor, v_src: torch.Tenso
     with tiers row_tier [B, n_rows] uint8; keeps the fine-half mask in cache.fine_mask; advances cache.T_len."""
     assert k_src.dtype == torch.float16 and v_src.dtype == torch.float16
     assert k_src.is_contiguous() and v_src.is_contiguous() and k_src.shape == v_src.shape
-    assert row_src.dtype == torch.int32 and row_tier.dtype == torch.uint8
-    assert row_src.is_contiguous() and row_tier.is_contiguous() and row_src.shape == row_tier.shape
-    n_src, n_rows = k_src.shape[2], row_src.shape[1]
-    if cache.fine_mask is None:
-        cache.fine_mask = torch.zeros(cache.B, cache.T_cap // 32, dtype=torch.int32, device=k_src.device)
+    n_src = k_src.shape[2]
+    if row_src is None:      # plain rows, identity mapping (what differs from quantize_append is the window)
+        assert row_tier is None
+        n_rows, mask = n_src, None
+    else:
+        assert row_src.dtype == torch.int32 and row_tier.dtype == torch.uint8
+        assert row_src.is_contiguous() and row_tier.is_contiguous() and row_src.shape == row_tier.shape
+        n_rows = row_src.shape[1]
+        if cache.fine_mask is None:
+            cache.fine_mask = torch.zeros(cache.B, cache.T_cap // 32, dtype=torch.int32, device=k_src.device)
+        mask = cache.fine_mask
     c = cache.struct()
+    win = cache.window_struct()
     _check(lib().akvq_quantize_append_tiered(C.byref(c), _ptr(k_src), _ptr(v_src), n_src, _ptr(row_src),
-                                             _ptr(row_tier), n_rows, clip2, clip4, _ptr(cache.fine_mask), flags,
-                                             _stream()), "akvq_quantize_append_tiered")
+                                             _ptr(row_tier), n_rows, clip2, clip4, _ptr(mask),
+                                             C.byref(win) if win else None, flags, _stream()),
+           "akvq_quantize_append_tiered")
     cache.T_len += n_rows
 
 
@@ -205,10 +233,11 @@ def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: in
     if lse is None:
         lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
     c = cache.struct()
-    if cache.fine_mask is not None:
-        _check(lib().akvq_decode_attention_tiered(C.byref(c), _ptr(cache.fine_mask), _ptr(q), Hq, sm_scale, _ptr(out),
-                                                  _ptr(lse), n_split, _ptr(ws), ws.numel(), flags, _stream()),
-               "akvq_decode_attention_tiered")
+    if cache.fine_mask is not None or cache.W:
+        win = cache.window_struct()
+        _check(lib().akvq_decode_attention_tiered(C.byref(c), _ptr(cache.fine_mask), C.byref(win) if win else None,
+                                                  _ptr(q), Hq, sm_scale, _ptr(out), _ptr(lse), n_split, _ptr(ws),
+                                                  ws.numel(), flags, _stream()), "akvq_decode_attention_tiered")
         return out, lse
     _check(lib().akvq_decode_attention(C.byref(c), _ptr(q), Hq, sm_scale, _ptr(out), _ptr(lse), n_split, _ptr(ws),
                                        ws.numel(), flags, _stream()), "akvq_decode_attention")

@@ -133,9 +133,16 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
   return hip_status(akvq::launch_select_psa(a, s));
 }
 
+static int check_window(const akvq_window *win) {
+  if (!win) return AKVQ_OK;
+  if (!win->k_win || !win->v_win || !aligned16(win->k_win) || !aligned16(win->v_win)) return AKVQ_ERR_INVALID_ARG;
+  if (win->W <= 0 || win->W % 64 != 0) return AKVQ_ERR_INVALID_ARG;
+  return AKVQ_OK;
+}
+
 static int quantize_common(const akvq_cache *c, const void *k_new, const void *v_new, int n_src, int n_new,
                            float clip, float clip4, const int32_t *row_src, const uint8_t *row_tier,
-                           uint32_t *fine_mask, uint32_t flags, void *stream) {
+                           uint32_t *fine_mask, const akvq_window *win, uint32_t flags, void *stream) {
   int st = check_cache_shape(c);
   if (st != AKVQ_OK) return st;
   st = check_cache_pointers(c);
@@ -145,6 +152,9 @@ static int quantize_common(const akvq_cache *c, const void *k_new, const void *v
   if ((long)c->T_len + n_new > c->T_cap) return AKVQ_ERR_CAPACITY;
   akvq::QuantArgs a{};
   a.row_src = row_src; a.row_tier = row_tier; a.fine_mask = fine_mask; a.n_src = n_src; a.clip4 = clip4;
+  st = check_window(win);
+  if (st != AKVQ_OK) return st;
+  if (win) { a.k_win = win->k_win; a.v_win = win->v_win; a.win_len = win->W; }
   a.k_new = static_cast<const uint16_t *>(k_new);
   a.v_new = static_cast<const uint16_t *>(v_new);
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
@@ -159,28 +169,35 @@ static int quantize_common(const akvq_cache *c, const void *k_new, const void *v
 
 int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_new, int n_new, float clip,
                          uint32_t flags, void *stream) {
-  return quantize_common(c, k_new, v_new, n_new, n_new, clip, 1.0f, nullptr, nullptr, nullptr, flags, stream);
+  return quantize_common(c, k_new, v_new, n_new, n_new, clip, 1.0f, nullptr, nullptr, nullptr, nullptr, flags, stream);
 }
 
 int akvq_quantize_append_tiered(const akvq_cache *c, const void *k_src, const void *v_src, int n_src,
                                 const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
-                                float clip4, uint32_t *fine_mask, uint32_t flags, void *stream) {
-  if (!row_src || !row_tier || !fine_mask || !aligned16(row_src) || !aligned16(row_tier) || !aligned16(fine_mask))
+                                float clip4, uint32_t *fine_mask, const akvq_window *win, uint32_t flags,
+                                void *stream) {
+  const bool mapped = row_src || row_tier || fine_mask;  // all three or none
+  if (mapped && (!row_src || !row_tier || !fine_mask || !aligned16(row_src) || !aligned16(row_tier) ||
+                 !aligned16(fine_mask)))
     return AKVQ_ERR_INVALID_ARG;
-  return quantize_common(c, k_src, v_src, n_src, n_rows, clip2, clip4, row_src, row_tier, fine_mask, flags, stream);
+  if (!mapped && n_rows != n_src) return AKVQ_ERR_INVALID_ARG;
+  return quantize_common(c, k_src, v_src, n_src, n_rows, clip2, clip4, row_src, row_tier, fine_mask, win, flags,
+                         stream);
 }
 
 int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
                           int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
-  return akvq_decode_attention_tiered(c, nullptr, q, Hq, sm_scale, out, lse_out, n_split, workspace, workspace_bytes,
-                                      flags, stream);
+  return akvq_decode_attention_tiered(c, nullptr, nullptr, q, Hq, sm_scale, out, lse_out, n_split, workspace,
+                                      workspace_bytes, flags, stream);
 }
 
-int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const void *q, int Hq,
-                                 float sm_scale, float *out, float *lse_out, int n_split, void *workspace,
-                                 size_t workspace_bytes, uint32_t flags, void *stream) {
+int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win,
+                                 const void *q, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                                 void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
   if (fine_mask && !aligned16(fine_mask)) return AKVQ_ERR_INVALID_ARG;
-  int st = check_cache_shape(c);
+  int st = check_window(win);
+  if (st != AKVQ_OK) return st;
+  st = check_cache_shape(c);
   if (st != AKVQ_OK) return st;
   st = check_cache_pointers(c);
   if (st != AKVQ_OK) return st;
@@ -197,6 +214,11 @@ int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask,
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
   a.k_sal = c->k_sal; a.v_sal = c->v_sal; a.sal_idx = c->sal_idx; a.sal_cnt = c->sal_cnt;
   a.fine_mask = fine_mask;
+  a.t_win = c->T_len;
+  if (win) {
+    a.k_win = win->k_win; a.v_win = win->v_win; a.win_len = win->W;
+    a.t_win = (((c->T_len > win->W) ? c->T_len - win->W : 0) + 1) & ~1;  // even row at or above T_len - W
+  }
   a.q = static_cast<const uint16_t *>(q);
   a.partial = static_cast<float *>(workspace);
   a.out = out; a.lse = lse_out;

@@ -166,7 +166,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
 
   // ---- tile bookkeeping and the first two tiles' loads come first: they do not depend on the query, so their
   // latency overlaps with the query rotation below ----
-  const int n_tiles = (a.T_len + 63) / 64;
+  const int n_tiles = (a.t_win + 63) / 64;  // rows from t_win on are read from the recent-window rings
   const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
   const int tile_begin = split * tiles_per_split;
   const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
@@ -322,7 +322,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     }
     score *= q_unit;
     score *= sm2;
-    const bool ok = (t < a.T_len) && !salient;
+    const bool ok = (t < a.t_win) && !salient;
     bool count = true;
     if constexpr (PAIRS) {
       const uint32_t from_me = cur.fm >> (lane & 31);      // bit 0: this row is a fine half; bit 1: the next row is
@@ -385,21 +385,16 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     }
   }
 
-  // ================= bfloat16 (salient) rows: units of 64 overlay slots dealt to splits, then to wavefronts =========
-  int cnt = a.sal_cnt[bh];
-  cnt = min(max(cnt, 0), a.S_cap);
-  const int n_units = (cnt + 63) / 64;
-  const int first_unit = split + wave * a.n_split;
-  if (first_unit < n_units) {
-    const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
-    const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
-    const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
-    for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
+  // ================= bfloat16 rows: units of 64 slots dealt to splits, then to wavefronts =========
+  // Used twice: the salient overlay (slot = rank in the salient list) and the recent-window rings (slot = row mod W).
+  auto bf16_units = [&](const uint16_t *ks_base, const uint16_t *vs_base, int cnt, auto &&row_ok) {
+    const int n_units = (cnt + 63) / 64;
+    for (int unit = split + wave * a.n_split; unit < n_units; unit += kWaves * a.n_split) {
       const int s_lane = unit * 64 + lane;
       // only the token groups (16 slots) and blocks (32 slots) that hold rows are touched; the first block of value
-      // rows and the positions are requested together with the key rows so that the phase costs one round trip
+      // rows and the row's validity are requested together with the key rows so that the phase costs one round trip
       const int n_grp = min(4, (cnt - unit * 64 + 15) >> 4), n_blk = min(2, (cnt - unit * 64 + 31) >> 5);
-      const int pos_lane = sidx[min(s_lane, a.S_cap - 1)];
+      const bool lane_ok = (s_lane < cnt) && row_ok(s_lane);
       u32x4 vb0[8];
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb)
@@ -417,7 +412,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
         }
       }
       const float score = sm2 * (acc[0] + acc[1] + acc[2]);
-      const bool ok = (s_lane < cnt) && (pos_lane < a.T_len);
+      const bool ok = lane_ok;
       float p;
       if (!softmax_step(score, ok, true, p)) continue;
       {
@@ -451,6 +446,30 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
       }
       wave_lds_sync();
     }
+  };
+  {
+    int cnt = a.sal_cnt[bh];
+    cnt = min(max(cnt, 0), a.S_cap);
+    const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+    bf16_units(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, cnt,
+               [&](int s) { return sidx[min(s, a.S_cap - 1)] < a.t_win; });  // rows in the window are read there
+  }
+  if (a.win_len > 0) {
+    // slot s holds the row of [t_win, T_len) congruent to s mod W; fine halves and padding rows carry no token
+    const int W = a.win_len;
+    bf16_units(a.k_win + (size_t)bh * W * kD, a.v_win + (size_t)bh * W * kD, W, [&](int s) {
+      int d = (a.T_len - 1 - s) % W;
+      d = d < 0 ? d + W : d;
+      const int t = a.T_len - 1 - d;
+      bool row = t >= a.t_win;
+      if constexpr (PAIRS) {
+        const int tc = max(t, 0);
+        const bool fine = ((a.fine_mask[(size_t)(bh / a.Hkv) * plane_blocks + tc / 32] >> (tc % 32)) & 1u) != 0u;
+        const bool pad = (a.k_meta[((size_t)bh * a.T_cap + tc) * NG] & 0xFFFFu) == 0x8000u;
+        row = row && !fine && !pad;
+      }
+      return row;
+    });
   }
 
   // ================= merge the four wavefronts, then either finish (one split) or store the partial =================
@@ -652,7 +671,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   };
 
   // ================= code stream =================
-  const int n_tiles = (a.T_len + 31) / 32;
+  const int n_tiles = (a.t_win + 31) / 32;  // rows from t_win on are read from the recent-window rings
   const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
   const int tile_begin = split * tiles_per_split;
   const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
@@ -707,7 +726,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       }
       sc[0][tg] = s0;
       sc[1][tg] = s1;
-      ok[tg] = (tile * 32 + 16 * tg + mrow < a.T_len) && !salient;
+      ok[tg] = (tile * 32 + 16 * tg + mrow < a.t_win) && !salient;
     }
     bool count[2] = {true, true};
     if constexpr (PAIRS) {
@@ -795,26 +814,26 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     }
   }
 
-  // ================= bfloat16 (salient) rows: units of 32 overlay slots =================
-  int cnt = a.sal_cnt[bh];
-  cnt = min(max(cnt, 0), a.S_cap);
-  const int n_units = (cnt + 31) / 32;
-  const int first_unit = split + wave * a.n_split;
-  if (first_unit < n_units) {
+  // ================= bfloat16 rows: units of 32 slots =================
+  // Used twice: the salient overlay (slot = rank in the salient list) and the recent-window rings (slot = row mod W).
+  auto bf16_units = [&](const uint16_t *ks_base, const uint16_t *vs_base, int cnt, auto &&row_ok) {
+    const int n_units = (cnt + 31) / 32;
+    const int first_unit = split + wave * a.n_split;
+    if (first_unit >= n_units) return;
     bf16x8 a_s[4];
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
       a_s[kc] = *reinterpret_cast<const bf16x8 *>(&q_plain[mrow][32 * kc + 8 * qd]);
-    const uint16_t *ks_base = a.k_sal + (size_t)bh * a.S_cap * kD;
-    const uint16_t *vs_base = a.v_sal + (size_t)bh * a.S_cap * kD;
-    const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
     for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
-      // the value rows and the positions are requested together with the key rows (one round trip for the phase);
-      // a token group (16 slots) without rows is not read
+      // the value rows and the rows' validity are requested together with the key rows (one round trip for the
+      // phase); a token group (16 slots) without rows is not read
       const int n_grp = min(2, (cnt - unit * 32 + 15) >> 4);
-      int pos_lane[2];
+      bool lane_ok[2];
 #pragma unroll
-      for (int tg = 0; tg < 2; ++tg) pos_lane[tg] = sidx[min(unit * 32 + 16 * tg + mrow, a.S_cap - 1)];
+      for (int tg = 0; tg < 2; ++tg) {
+        const int s_lane = unit * 32 + 16 * tg + mrow;
+        lane_ok[tg] = (s_lane < cnt) && row_ok(s_lane);
+      }
       u32x4 vb_all[8];
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb)
@@ -835,7 +854,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
         }
         sc[0][tg] = acc[0] + acc[1];
         sc[1][tg] = acc[2] + acc[3];
-        ok[tg] = (s_lane < cnt) && (pos_lane[tg] < a.T_len);
+        ok[tg] = lane_ok[tg];
       }
       float p[2][2];
       const bool count[2] = {true, true};
@@ -866,6 +885,30 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       }
       wave_lds_sync();
     }
+  };
+  {
+    int cnt = a.sal_cnt[bh];
+    cnt = min(max(cnt, 0), a.S_cap);
+    const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+    bf16_units(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, cnt,
+               [&](int s) { return sidx[min(s, a.S_cap - 1)] < a.t_win; });  // rows in the window are read there
+  }
+  if (a.win_len > 0) {
+    // slot s holds the row of [t_win, T_len) congruent to s mod W; fine halves and padding rows carry no token
+    const int W = a.win_len;
+    bf16_units(a.k_win + (size_t)bh * W * kD, a.v_win + (size_t)bh * W * kD, W, [&](int s) {
+      int d = (a.T_len - 1 - s) % W;
+      d = d < 0 ? d + W : d;
+      const int t = a.T_len - 1 - d;
+      bool row = t >= a.t_win;
+      if constexpr (PAIRS) {
+        const int tc = max(t, 0);
+        const bool fine = ((a.fine_mask[(size_t)b * plane_blocks + tc / 32] >> (tc % 32)) & 1u) != 0u;
+        const bool pad = (a.k_meta[((size_t)bh * a.T_cap + tc) * NG] & 0xFFFFu) == 0x8000u;
+        row = row && !fine && !pad;
+      }
+      return row;
+    });
   }
 
   // ================= merge the four wavefronts =================

@@ -22,6 +22,8 @@ struct QuantArgs {
   uint32_t *fine_mask;      // [B][T_cap/32]
   int n_src;                // rows per (b, kv-head) in k_new / v_new (= n_new for the plain call)
   float clip4;
+  uint16_t *k_win, *v_win;  // recent-window rings (null: none)
+  int win_len;
 };
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream);
 
@@ -30,6 +32,9 @@ struct DecodeArgs {
   const uint16_t *k_sal, *v_sal;
   const int32_t *sal_idx, *sal_cnt;
   const uint32_t *fine_mask;  // [B][T_cap/32] or null: fine halves of 4-bit tokens stored as row pairs
+  const uint16_t *k_win, *v_win;  // recent-window rings (null: none), win_len slots
+  int win_len;
+  int t_win;                  // first row read from the rings (= T_len without a window)
   const uint16_t *q;  // [B][Hq][128] binary16
   float *partial;     // [B*Hq][n_split][kPartialStride] fp32
   float *out;         // [B][Hq][128]

@@ -285,30 +285,41 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
         }
     }
 
-    // ---- bfloat16 overlay for salient rows (Section III-C.1: salient tokens keep 16-bit precision) ----
-    if (valid[h] && slots[h] >= 0) {
-      const int slot = slots[h];
+    // ---- bfloat16 copies: the overlay slot of a salient row (Section III-C.1: salient tokens keep 16-bit
+    // precision) and the ring slot of a row inside the recent window (the last win_len appended rows) ----
+    auto store_bf16_row = [&](uint16_t *k_rows, uint16_t *v_plane, int slot, bool token) {
+      const float scale = kappa_s;
       if (tensor == 0) {
-        uint16_t *dst = a.k_sal + ((size_t)bh * a.S_cap + slot) * kD;
+        uint16_t *dst = k_rows + (size_t)slot * kD;
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
           u32x4 o;
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            o[w] = pack_bf16x2(__fmul_rn(u[m][2 * w], kappa_s), __fmul_rn(u[m][2 * w + 1], kappa_s));
+            o[w] = token ? pack_bf16x2(__fmul_rn(u[m][2 * w], scale), __fmul_rn(u[m][2 * w + 1], scale)) : 0u;
           *reinterpret_cast<u32x4 *>(dst + 32 * m + 8 * j) = o;
         }
       } else {
-        uint16_t *plane = a.v_sal + (size_t)bh * a.S_cap * kD;
         const int sb = slot >> 5, sh = (slot & 31) >> 4, sr = slot & 15, sq = sr >> 2, sii = sr & 3;
 #pragma unroll
         for (int m = 0; m < 4; ++m)
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const int e = 32 * m + 8 * j + i, nb = e >> 4, n = e & 15;
-            plane[(size_t)sb * 4096 + nb * 512 + (16 * sq + n) * 8 + 2 * sii + sh] =
-                (uint16_t)pack_bf16x2(__fmul_rn(u[m][i], kappa_s), 0.0f);
+            v_plane[(size_t)sb * 4096 + nb * 512 + (16 * sq + n) * 8 + 2 * sii + sh] =
+                token ? (uint16_t)pack_bf16x2(__fmul_rn(u[m][i], scale), 0.0f) : (uint16_t)0;
           }
+      }
+    };
+    if (valid[h] && slots[h] >= 0)
+      store_bf16_row(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, slots[h], true);
+    if (a.win_len > 0) {
+      const int t = t0 + 16 * h + r;
+      if (valid[h] && t >= t_end - a.win_len) {
+        // fine halves and padding rows carry no token: their ring slots are zeroed
+        const bool token = !TIERED || (tier[h] != AKVQ_TIER_4BIT_FINE && tier[h] != AKVQ_TIER_PAD);
+        store_bf16_row(a.k_win + (size_t)bh * a.win_len * kD, a.v_win + (size_t)bh * a.win_len * kD,
+                       t % a.win_len, token);
       }
     }
 
@@ -347,8 +358,8 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           mw = float_to_half_bits_rne(4.0f * half_bits_to_float(gq[g].s16)) | ((uint32_t)((gq[g].z >> 2) & 0xFFFF) << 16);
         else if (tier[h] == AKVQ_TIER_4BIT_FINE)  // scale s, zero z4 mod 4
           mw = gq[g].s16 | ((uint32_t)(gq[g].z & 3) << 16);
-        else if (tier[h] == AKVQ_TIER_PAD)  // ignored by decode: salient bit without an overlay slot
-          mw = 0x3C00u | 0x8000u;
+        else if (tier[h] == AKVQ_TIER_PAD)  // ignored by decode: salient bit with scale bits 0, a marker no real row has
+          mw = 0x8000u;
         meta_out[h][g] = mw;
       }
       gq[g].rcpu *= lane_sign;  // codes are taken from the signed values this lane holds

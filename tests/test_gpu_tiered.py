@@ -117,3 +117,99 @@ def test_tiered_decode_gqa(orc, Hq, Hkv, G):
 def test_tiered_cfg1(orc):
     w = synth.WORKLOADS["cfg1"]
     _decode_case(orc, w, 341, (0,))
+
+
+# ---------------------------------------------------------------------------------------- recent window
+def _assert_rings_equal(oc, gc, what):
+    torch.cuda.synchronize()
+    for name in ("k_win", "v_win"):
+        got = getattr(gc, name).cpu().numpy().view(np.uint16).reshape(-1)
+        assert np.array_equal(got, getattr(oc, name).reshape(-1)), f"{what} {name}"
+
+
+def _check_decode(oc, gc, d, w, what, n_splits=(0,)):
+    ref, lse_ref = oc.decode(d["q"], w.sm_scale)
+    q = _dev(d["q"])
+    for ns in n_splits:
+        out, lse = akvq.decode_attention(gc, q, w.sm_scale, n_split=ns)
+        torch.cuda.synchronize()
+        got = out.cpu().numpy().astype(np.float64)
+        rel = np.abs(got - ref).max(axis=-1) / np.maximum(np.abs(ref).max(axis=-1), 1e-6)
+        assert rel.max() <= ATTN_TOL, f"{what} n_split={ns}: {rel.max():.3e}"
+        assert np.abs(lse.cpu().numpy() - lse_ref).max() <= 2e-3, what
+
+
+@pytest.mark.parametrize("Hq,Hkv,G,W", [(3, 3, 128, 64), (3, 3, 64, 128), (8, 2, 128, 64), (14, 2, 64, 128)])
+def test_window_prefill_then_decode_steps(orc, Hq, Hkv, G, W):
+    """Prefill with a 16-bit recent window, then append rows one at a time: each step's attention must match the
+    oracle, the rings must match bit for bit, and rows that left the window must be read from their codes."""
+    w = synth.small(f"win{Hq}{G}", B=2, Hq=Hq, Hkv=Hkv, T=300, G=G, n_text_head=12, n_text_tail=8, top_k=6, W=16)
+    d = _np(synth.generate(w, seed=401 + Hq + G))
+    T0 = 230
+    oc = orc.OracleCache(w.B, w.Hkv, w.G, 320, 64, fill=0)
+    gc = akvq.Cache(w.B, w.Hkv, w.G, 320, 64, fill=0)
+    oc.enable_window(W); gc.enable_window(W)
+    oc.select_psa(d["q_tail"], d["k"][:, :, :T0], w.top_k, w.sm_scale)   # pivots of the prompt stay 16-bit as well
+    gc.sal_idx.copy_(_dev(oc.sal_idx)); gc.counts().copy_(_dev(oc.sal_cnt))
+    k0, v0 = d["k"][:, :, :T0], d["v"][:, :, :T0]
+    oc.quantize_append_tiered(k0, v0, None, None, 0.8, 1.0)
+    akvq.quantize_append_tiered(gc, _dev(k0), _dev(v0), None, None, 0.8, 1.0)
+    _assert_equal_plain(oc, gc, "prefill")
+    _assert_rings_equal(oc, gc, "prefill")
+    _check_decode(oc, gc, d, w, "after prefill", (1, 3))
+    for t in range(T0, w.T):
+        kt, vt = d["k"][:, :, t:t + 1], d["v"][:, :, t:t + 1]
+        oc.quantize_append_tiered(kt, vt, None, None, 0.8, 1.0)
+        akvq.quantize_append_tiered(gc, _dev(kt), _dev(vt), None, None, 0.8, 1.0)
+        if t in (T0, T0 + 1, T0 + 37, w.T - 1):
+            _assert_rings_equal(oc, gc, f"step {t}")
+            _check_decode(oc, gc, d, w, f"step {t}")
+    _assert_equal_plain(oc, gc, "after the steps")
+
+
+def _assert_equal_plain(oc, gc, what):
+    torch.cuda.synchronize()
+    T = oc.T_len
+    assert gc.T_len == T
+    for name in ("k_codes", "v_codes"):
+        assert np.array_equal(_u32(getattr(gc, name)), getattr(oc, name)), f"{what} {name}"
+    for name in ("k_meta", "v_meta"):
+        assert np.array_equal(_u32(getattr(gc, name))[:, :, :T], getattr(oc, name)[:, :, :T]), f"{what} {name}"
+    for name in ("k_sal", "v_sal"):
+        got = getattr(gc, name).cpu().numpy().view(np.uint16).reshape(-1)
+        assert np.array_equal(got, getattr(oc, name).reshape(-1)), f"{what} {name}"
+
+
+def test_window_shorter_context_than_window(orc):
+    w = synth.small("winshort", B=1, Hq=2, Hkv=2, T=50, G=128, W=16)
+    d = _np(synth.generate(w, seed=431))
+    oc = orc.OracleCache(w.B, w.Hkv, w.G, 64, 64, fill=0); gc = akvq.Cache(w.B, w.Hkv, w.G, 64, 64, fill=0)
+    oc.enable_window(64); gc.enable_window(64)
+    oc.quantize_append_tiered(d["k"], d["v"], None, None, 0.8, 1.0)
+    akvq.quantize_append_tiered(gc, _dev(d["k"]), _dev(d["v"]), None, None, 0.8, 1.0)
+    _assert_rings_equal(oc, gc, "short")
+    _check_decode(oc, gc, d, w, "context shorter than the window")
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(3, 3), (8, 2)])
+def test_window_with_four_bit_tier(orc, Hq, Hkv):
+    """Tiers and window together: pairs inside the window are read once from the ring, pairs outside from their two
+    rows; then a few decode steps with a text token (a pair) and a plain token appended."""
+    w = synth.small(f"wint{Hq}", B=2, Hq=Hq, Hkv=Hkv, T=260, G=128, n_text_head=15, n_text_tail=30, W=16)
+    d, row_src, row_tier, oc, gc = _case(orc, w, seed=441 + Hq)
+    oc.enable_window(64); gc.enable_window(64)
+    n_rows = row_src.shape[1]
+    n0 = n_rows - 8
+    a, b = np.ascontiguousarray(row_src[:, :n0]), np.ascontiguousarray(row_tier[:, :n0])
+    oc.quantize_append_tiered(d["k"], d["v"], a, b, 0.8, 1.0)
+    akvq.quantize_append_tiered(gc, _dev(d["k"]), _dev(d["v"]), _dev(a), _dev(b), 0.8, 1.0)
+    _assert_equal(oc, gc, "tiered prefill")
+    _assert_rings_equal(oc, gc, "tiered prefill")
+    _check_decode(oc, gc, d, w, "tiered prefill", (1, 2))
+    for lo in range(n0, n_rows, 2):      # two rows at a time: a pair, or two plain / padding rows
+        a, b = np.ascontiguousarray(row_src[:, lo:lo + 2]), np.ascontiguousarray(row_tier[:, lo:lo + 2])
+        oc.quantize_append_tiered(d["k"], d["v"], a, b, 0.8, 1.0)
+        akvq.quantize_append_tiered(gc, _dev(d["k"]), _dev(d["v"]), _dev(a), _dev(b), 0.8, 1.0)
+        _assert_rings_equal(oc, gc, f"rows {lo}")
+        _check_decode(oc, gc, d, w, f"rows {lo}")
+    _assert_equal(oc, gc, "tiered steps")
