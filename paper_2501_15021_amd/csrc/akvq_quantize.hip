@@ -178,7 +178,8 @@ constexpr uint32_t kPack4Bias = (uint32_t)(0x4B400000ull * 0x01010101ull);    //
 
 // TIERED: rows carry a tier and a source-row index (akvq_quantize_append_tiered); the plain instantiation is the
 // two-bit path with identity row mapping and none of the per-row tier arithmetic.
-template <int G, bool TIERED>
+// WINDOW: the last win_len appended rows also go to the recent-window rings.
+template <int G, bool TIERED, bool WINDOW>
 __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   __shared__ int slot_of_lds[4][kTokBlock];
   const int wave = threadIdx.x >> 6;
@@ -313,7 +314,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
     };
     if (valid[h] && slots[h] >= 0)
       store_bf16_row(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, slots[h], true);
-    if (a.win_len > 0) {
+    if constexpr (WINDOW) {
       const int t = t0 + 16 * h + r;
       if (valid[h] && t >= t_end - a.win_len) {
         // fine halves and padding rows carry no token: their ring slots are zeroed
@@ -482,13 +483,16 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream) {
   dim3 grid((a.n_blk + 3) / 4, B * a.Hkv, 2), block(256);
-  if (a.row_tier) {
-    if (G == 128) hipLaunchKernelGGL((quantize_append_kernel<128, true>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((quantize_append_kernel<64, true>), grid, block, 0, stream, a);
+  const bool tiered = a.row_tier != nullptr, window = a.win_len > 0;
+#define AKVQ_LAUNCH_Q(GG, TT, WW) hipLaunchKernelGGL((quantize_append_kernel<GG, TT, WW>), grid, block, 0, stream, a)
+  if (G == 128) {
+    if (tiered) { if (window) AKVQ_LAUNCH_Q(128, true, true); else AKVQ_LAUNCH_Q(128, true, false); }
+    else { if (window) AKVQ_LAUNCH_Q(128, false, true); else AKVQ_LAUNCH_Q(128, false, false); }
   } else {
-    if (G == 128) hipLaunchKernelGGL((quantize_append_kernel<128, false>), grid, block, 0, stream, a);
-    else hipLaunchKernelGGL((quantize_append_kernel<64, false>), grid, block, 0, stream, a);
+    if (tiered) { if (window) AKVQ_LAUNCH_Q(64, true, true); else AKVQ_LAUNCH_Q(64, true, false); }
+    else { if (window) AKVQ_LAUNCH_Q(64, false, true); else AKVQ_LAUNCH_Q(64, false, false); }
   }
+#undef AKVQ_LAUNCH_Q
   return hipGetLastError();
 }
 
