@@ -80,6 +80,9 @@ def phase_bench(args, w, akvq, synth, torch, np):
         cache = akvq.Cache(w.B, w.Hkv, w.G, t_cap, w.s_cap(layer))
         sets.append((d, cache))
 
+    if args.window:
+        for _, cache in sets:
+            cache.enable_window(args.window)
     tiered = None
     if args.tiered:
         # Section III-C.1 tiers: text tokens (all but position 0, a planted pivot) 4-bit as row pairs, pivot tokens
@@ -92,6 +95,9 @@ def phase_bench(args, w, akvq, synth, torch, np):
                   "row_of": torch.from_numpy(row_of).cuda().long(), "n_rows": n_rows,
                   "plain": torch.from_numpy(((mask == 0) | (np.arange(w.T)[None, :] == 0))).cuda()}
         sets = [(d, akvq.Cache(w.B, w.Hkv, w.G, t_cap, w.s_cap(layer))) for d, _ in sets]
+        if args.window:
+            for _, cache in sets:
+                cache.enable_window(args.window)
         n_pairs = int((row_tier == 2).sum(axis=1).max())
         per_row = 2 * (32 + 4 * (128 // w.G))
         per_set = dict(per_set)
@@ -112,6 +118,8 @@ def phase_bench(args, w, akvq, synth, torch, np):
     def append(d, cache):
         if tiered:
             akvq.quantize_append_tiered(cache, d["k"], d["v"], tiered["row_src"], tiered["row_tier"], w.clip, 1.0)
+        elif args.window:
+            akvq.quantize_append_tiered(cache, d["k"], d["v"], None, None, w.clip, 1.0)
         else:
             akvq.quantize_append(cache, d["k"], d["v"], w.clip)
 
@@ -154,9 +162,12 @@ def phase_bench(args, w, akvq, synth, torch, np):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / n_calls
     nbytes = per_set[args.phase]
+    if args.window:  # window rows are read (decode) / also written (quantize) as 16-bit instead of / besides their codes
+        per_row = 2 * (32 + 4 * (128 // w.G))
+        nbytes += w.B * w.Hkv * args.window * (512 - per_row if args.phase == "decode" else 512)
     gbps = nbytes / (ms * 1e-3) / 1e9
     out = {"metric": f"{args.phase} call alone" + (" (4-bit text tier as row pairs)" if tiered else ""),
-           "cache_rows": tiered["n_rows"] if tiered else w.T, "workload": w.name, "layer_mode": w.mode(layer), "ms_per_call": round(ms, 5),
+           "cache_rows": tiered["n_rows"] if tiered else w.T, "recent_window": args.window, "workload": w.name, "layer_mode": w.mode(layer), "ms_per_call": round(ms, 5),
            "kv_tokens_per_s": w.B * w.T / (ms * 1e-3), "n_sets": n_sets, "calls": n_calls,
            "n_split": args.n_split or akvq.lib().akvq_decode_default_splits(w.B, w.Hkv, w.T),
            "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -175,6 +186,8 @@ def main():
     ap.add_argument("--workload", default="cfg2")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (debugging)")
     ap.add_argument("--layer", type=int, default=-1, help="layer whose mode (TSA/PSA) a --phase run uses")
+    ap.add_argument("--window", type=int, default=0,
+                    help="--phase decode|quantize with a 16-bit recent window of this many rows (multiple of 64)")
     ap.add_argument("--tiered", action="store_true",
                     help="--phase decode|quantize with the 4-bit text tier (text tokens as row pairs, pivots 16-bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

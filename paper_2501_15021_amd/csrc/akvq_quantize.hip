@@ -182,6 +182,7 @@ constexpr uint32_t kPack4Bias = (uint32_t)(0x4B400000ull * 0x01010101ull);    //
 template <int G, bool TIERED, bool WINDOW>
 __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   __shared__ int slot_of_lds[4][kTokBlock];
+  __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[WINDOW ? 4 : 1][WINDOW ? 1024 : 4];  // half a V ring tile per wavefront
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int blk_rel = blockIdx.x * 4 + wave;
@@ -263,6 +264,11 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   }
   wave_lds_sync();
 
+  // recent window: is this whole block new and inside the window?  (uniform over the wavefront)
+  bool win_block = false;
+  uint32_t vwin_h0[16];
+  if constexpr (WINDOW)
+    win_block = t0 >= a.T_len && t0 + kTokBlock <= t_end && t0 >= t_end - a.win_len;
   uint32_t kw[2][2];         // K words of token half h: [h][group-of-64 word]
   uint32_t vcode[2][8];      // V: [mpair][i]: raw patterns of (X, Y) x (half 0, half 1) in the four byte lanes
   uint32_t vmask_part = 0;
@@ -316,9 +322,52 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
       store_bf16_row(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, slots[h], true);
     if constexpr (WINDOW) {
       const int t = t0 + 16 * h + r;
-      if (valid[h] && t >= t_end - a.win_len) {
-        // fine halves and padding rows carry no token: their ring slots are zeroed
-        const bool token = !TIERED || (tier[h] != AKVQ_TIER_4BIT_FINE && tier[h] != AKVQ_TIER_PAD);
+      // fine halves and padding rows carry no token: their ring slots are zeroed
+      const bool token = !TIERED || (tier[h] != AKVQ_TIER_4BIT_FINE && tier[h] != AKVQ_TIER_PAD);
+      if (win_block && tensor == 1) {
+        // The whole block lies in the window (the prefill case): its 32 rows fill one 32-slot tile of the V ring, in
+        // which the values of rows r and r+16 of one channel are neighbours.  This lane owns both rows, so it keeps
+        // the first half's values and assembles (row r, row r+16) pairs as 32-bit words of the tile in LDS, half a
+        // tile at a time; each half goes out as four fully coalesced 1 KB stores.  (Scattered partial-line stores, as in the row-at-a-time
+        // path below, are several times slower and would dominate the tail of a prefill launch.)
+        uint32_t pk[16];
+#pragma unroll
+        for (int m = 0; m < 4; ++m)
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            pk[4 * m + w] = token ? pack_bf16x2(__fmul_rn(u[m][2 * w], kappa_s), __fmul_rn(u[m][2 * w + 1], kappa_s)) : 0u;
+        if (h == 0) {
+#pragma unroll
+          for (int x = 0; x < 16; ++x) vwin_h0[x] = pk[x];
+        } else {
+          const int slot0 = t0 % a.win_len;  // multiple of 32
+          uint32_t *tile_out = reinterpret_cast<uint32_t *>(a.v_win + (size_t)bh * a.win_len * kD + (size_t)(slot0 >> 5) * 4096);
+          uint32_t *half_tile = vtile_lds[wave];  // half a tile (channel blocks 4*mh .. 4*mh+3) at a time
+          const int sq = r >> 2, sii = r & 3;
+#pragma unroll
+          for (int mh = 0; mh < 2; ++mh) {
+#pragma unroll
+            for (int m = 2 * mh; m < 2 * mh + 2; ++m)
+#pragma unroll
+              for (int w = 0; w < 4; ++w) {
+                const uint32_t a0 = vwin_h0[4 * m + w], a1 = pk[4 * m + w];   // channels (2w, 2w+1) of rows r, r+16
+                const uint32_t even = __builtin_amdgcn_perm(a1, a0, 0x05040100u);  // (row r, row r+16) of channel 2w
+                const uint32_t odd = __builtin_amdgcn_perm(a1, a0, 0x07060302u);   // ... of channel 2w+1
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                  const int e = 32 * m + 8 * j + 2 * w + c, nb = (e >> 4) - 4 * mh, n = e & 15;
+                  half_tile[(nb * 512 + (16 * sq + n) * 8 + 2 * sii) >> 1] = c == 0 ? even : odd;
+                }
+              }
+            wave_lds_sync();
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+              *reinterpret_cast<u32x4 *>(tile_out + 1024 * mh + 256 * x + 4 * lane) =
+                  *reinterpret_cast<const u32x4 *>(half_tile + 256 * x + 4 * lane);
+            wave_lds_sync();
+          }
+        }
+      } else if (valid[h] && t >= t_end - a.win_len) {
         store_bf16_row(a.k_win + (size_t)bh * a.win_len * kD, a.v_win + (size_t)bh * a.win_len * kD,
                        t % a.win_len, token);
       }
@@ -481,9 +530,9 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 
 }  // namespace
 
-hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream) {
+static void launch_blocks(const QuantArgs &a, int B, int G, bool window, hipStream_t stream) {
   dim3 grid((a.n_blk + 3) / 4, B * a.Hkv, 2), block(256);
-  const bool tiered = a.row_tier != nullptr, window = a.win_len > 0;
+  const bool tiered = a.row_tier != nullptr;
 #define AKVQ_LAUNCH_Q(GG, TT, WW) hipLaunchKernelGGL((quantize_append_kernel<GG, TT, WW>), grid, block, 0, stream, a)
   if (G == 128) {
     if (tiered) { if (window) AKVQ_LAUNCH_Q(128, true, true); else AKVQ_LAUNCH_Q(128, true, false); }
@@ -493,6 +542,31 @@ hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t 
     else { if (window) AKVQ_LAUNCH_Q(64, false, true); else AKVQ_LAUNCH_Q(64, false, false); }
   }
 #undef AKVQ_LAUNCH_Q
+}
+
+hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream) {
+  if (a.win_len <= 0) {
+    launch_blocks(a, B, G, false, stream);
+    return hipGetLastError();
+  }
+  // Recent window: only the blocks that hold the last win_len new rows write ring slots.  A long append (prefill)
+  // runs the plain instantiation over the blocks before them, so that the ring stores (and the registers and LDS
+  // they need) stay out of the bulk of the work, then the windowed instantiation over the few window blocks.
+  const int t_end = a.T_len + a.n_new;
+  const int t_w0 = t_end - a.win_len > a.T_len ? t_end - a.win_len : a.T_len;
+  const int win_first_blk = t_w0 / kTokBlock;
+  if (win_first_blk > a.first_blk) {
+    QuantArgs head = a;
+    head.n_blk = win_first_blk - a.first_blk;
+    head.win_len = 0;
+    launch_blocks(head, B, G, false, stream);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  QuantArgs tail = a;
+  tail.first_blk = win_first_blk;
+  tail.n_blk = a.first_blk + a.n_blk - win_first_blk;
+  launch_blocks(tail, B, G, true, stream);
   return hipGetLastError();
 }
 
