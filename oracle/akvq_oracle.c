@@ -363,6 +363,44 @@ void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Pivot tokens from massive activations (Section III-B.2: tokens whose residual-stream activations are massive
+ * attract the attention of the following layers; their indices are the pivot tokens).
+ * reading (the paper gives neither a threshold nor a count rule; its ablation keeps 15 pivots): the score of a
+ * token is the largest magnitude among its hidden-state channels; pivots are the top_k positions by score among
+ * those whose score is at least `floor`; equal scores go to the lower position; the list is per batch element and
+ * copied to every kv-head.  pinned by: planted activations are found; full sort; floor and tie cases.
+ * parity unpinned by the paper (threshold, count).
+ * ---------------------------------------------------------------------------------------- */
+void orc_select_massive(orc_cache *c, const uint16_t *hidden, int T, int d_model, int top_k, float floor_,
+                        double *score_out) {
+  for (int b = 0; b < c->B; ++b) {
+    mass_item *items = (mass_item *)malloc(sizeof(mass_item) * (size_t)T);
+    int n = 0;
+    for (int t = 0; t < T; ++t) {
+      const uint16_t *row = hidden + ((size_t)b * T + t) * d_model;
+      double mx = 0.0;
+      for (int ch = 0; ch < d_model; ++ch) {
+        double v = fabs((double)orc_half_to_float(row[ch]));
+        if (v > mx) mx = v;
+      }
+      if (score_out) score_out[(size_t)b * T + t] = mx;
+      if (mx >= (double)floor_ && mx > 0.0) { items[n].mass = mx; items[n].idx = t; ++n; }
+    }
+    qsort(items, (size_t)n, sizeof(mass_item), mass_cmp);
+    int kk = top_k < n ? top_k : n;
+    int *sel = (int *)malloc(sizeof(int) * (size_t)(kk > 0 ? kk : 1));
+    for (int s_ = 0; s_ < kk; ++s_) sel[s_] = items[s_].idx;
+    qsort(sel, (size_t)kk, sizeof(int), int_cmp);
+    for (int h = 0; h < c->Hkv; ++h) {
+      int32_t *idx = c->sal_idx + bh_index(c, b, h) * c->S_cap;
+      for (int s_ = 0; s_ < kk && s_ < c->S_cap; ++s_) idx[s_] = sel[s_];
+      c->sal_cnt[bh_index(c, b, h)] = kk;
+    }
+    free(sel); free(items);
+  }
+}
+
+/* ------------------------------------------------------------------------------------------
  * Write path: rotate, quantize (Eq. 3-6), pack; salient rows also keep a bfloat16 copy.
  * Every row gets 2-bit codes and meta; a row listed in sal_idx additionally gets an overlay row at the
  * slot equal to its rank in the list, and bit 15 of its meta words is set.

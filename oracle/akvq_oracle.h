@@ -79,6 +79,11 @@ void orc_select_tsa(orc_cache *c, const uint8_t *is_text, int T);
  * both binary16, un-rotated.  mass_out (optional) [B][Hkv][T] fp64.  Writes sal_idx / sal_cnt. */
 void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
                     double sm_scale, double *mass_out);
+/* Pivots from massive activations (Section III-B.2): hidden [B][T][d_model] binary16 (a block's residual-stream output);
+ * score = max |channel| per token; the top_k positions with score >= floor (ties -> lower position), the same list for
+ * every kv-head.  score_out (optional) [B][T] fp64.  Writes sal_idx / sal_cnt. */
+void orc_select_massive(orc_cache *c, const uint16_t *hidden, int T, int d_model, int top_k, float floor_,
+                        double *score_out);
 /* Write path: rows [T_len, T_len+n_new) of K and V ([B][Hkv][n_new][128] binary16).  Does not change T_len. */
 void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_new, int n_new, float clip,
                          int rotate_v);

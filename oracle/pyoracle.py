@@ -72,6 +72,8 @@ def lib():
                                            C.c_void_p]
         L.orc_decode_attention_one.argtypes = [C.POINTER(_Cache), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_double,
                                                C.c_int, C.c_void_p, C.c_void_p]
+        L.orc_select_massive.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
+                                         C.c_void_p]
         L.orc_quantize_row_bits.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_void_p]
         L.orc_quantize_append_tiered.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
@@ -162,6 +164,16 @@ class OracleCache:
         c = self._c()
         lib().orc_quantize_append(C.byref(c), _p(k_new), _p(v_new), n_new, clip, int(rotate_v))
         self.T_len += n_new
+
+    def select_massive(self, hidden, top_k: int, floor: float = 0.0, want_score: bool = False):
+        """Pivots = top_k tokens by largest hidden-state magnitude (>= floor); hidden [B, T, d_model] fp16."""
+        hidden = _u16(hidden)
+        B, T, d_model = hidden.shape
+        assert B == self.B
+        score = np.zeros((B, T), dtype=np.float64) if want_score else None
+        c = self._c()
+        lib().orc_select_massive(C.byref(c), _p(hidden), T, d_model, top_k, floor, _p(score))
+        return score
 
     def enable_window(self, W: int):
         """Keep the most recent W rows 16-bit (ring buffers, zero-initialised)."""

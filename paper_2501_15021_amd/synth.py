@@ -181,3 +181,29 @@ def tiered_rows(is_text: np.ndarray, keep_plain=None):
         row_tier[b, :len(tier)] = tier
         row_of_token[b] = row_of
     return row_src, row_tier, row_of_token
+
+
+def hidden_states(w: Workload, pivots, d_model: int = 4096, seed: int = BASE_SEED, layer: int = 0,
+                  device: str = "cpu"):
+    """A block's residual-stream output with massive activations planted at the pivot tokens: N(0,1) everywhere, two
+    fixed channels of every pivot token raised to distinct magnitudes between 300 and 2500 (the pattern the paper's
+    pivot identification relies on), and a sprinkling of merely large values (around 40) elsewhere.
+
+    pivots [B, n] int64 (as returned by generate()).  Returns [B, T, d_model] fp16 on `device`."""
+    dev = torch.device(device)
+    g = torch.Generator(device=dev)
+    g.manual_seed(int(seed) * 1000003 + 7919 * int(layer) + 5)
+    h = torch.randn(w.B, w.T, d_model, generator=g, device=dev, dtype=torch.float32)
+    cpu_g = torch.Generator(device="cpu")
+    cpu_g.manual_seed(int(seed) * 1000003 + 7919 * int(layer) + 6)
+    ch = torch.randperm(d_model, generator=cpu_g)[:2]
+    piv = torch.as_tensor(pivots).long()
+    for b in range(w.B):
+        for i, t in enumerate(piv[b].tolist()):
+            h[b, t, ch[0]] = 300.0 + 173.0 * i + 37.0 * b
+            h[b, t, ch[1]] = -(2500.0 - 211.0 * i - 29.0 * b)
+    n_large = max(1, w.T // 50)
+    pos = torch.randint(0, w.T, (w.B, n_large), generator=cpu_g)
+    for b in range(w.B):
+        h[b, pos[b], ch[0]] = 40.0
+    return h.to(torch.float16)
