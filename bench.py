@@ -192,7 +192,7 @@ def main():
                     help="--phase decode|quantize with the 4-bit text tier (text tokens as row pairs, pivots 16-bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
-    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "copy"],
+    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "copy"],
                     help="time one call only (per-kernel studies; the default 'all' is the benchmark line)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through in --phase runs")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (sweeps)")
@@ -228,6 +228,33 @@ def main():
         ms = e0.elapsed_time(e1) / args.steps
         print(json.dumps({"metric": "plain copy", "bytes_read": n, "bytes_written": n, "ms_per_call": round(ms, 4),
                           "GBps_read_plus_write": round(2 * n / (ms * 1e-3) / 1e9, 1)}))
+        return
+    if args.phase == "massive":
+        # pivot identification from massive activations on a synthetic residual stream (d_model 4096)
+        d_model = 4096
+        sets = []
+        for i in range(2):
+            d = synth.generate(w, layer=2 + 100 * i, device="cuda")
+            hid = synth.hidden_states(w, d["pivots"].cpu(), d_model=d_model, layer=2 + 100 * i, device="cuda")
+            sets.append((hid, akvq.Cache(w.B, w.Hkv, w.G, (w.T + 63) // 64 * 64, 64)))
+            del d
+        for i in range(args.warmup * 2):
+            akvq.select_massive(sets[i % 2][1], sets[i % 2][0], 15, 100.0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(args.steps * 2):
+            akvq.select_massive(sets[i % 2][1], sets[i % 2][0], 15, 100.0)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / (args.steps * 2)
+        nbytes = w.B * w.T * d_model * 2
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        print(json.dumps({"metric": "select_massive call alone", "workload": w.name, "d_model": d_model,
+                          "ms_per_call": round(ms, 5),
+                          "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                       "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
+                                       "algorithmic_bytes_per_launch": nbytes}}))
         return
     if args.phase != "all":
         return phase_bench(args, w, akvq, synth, torch, np)

@@ -121,6 +121,18 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * akvq_select_massive -- Section III-B.2 as the paper states it: pivot tokens are the tokens whose residual-stream
+ *   activations are massive.  hidden: device, [B][T][d_model] binary16 (a Transformer block's output), d_model a
+ *   multiple of 512.  score[b][t] = max over channels of |hidden|; the salient list of every kv-head of batch element b
+ *   is the top_k positions by score among those with score >= floor (and > 0), equal scores to the lower position,
+ *   ascending.  c->sal_cnt receives the number kept (<= top_k).  score_out: optional device [B][T] fp32.
+ *   workspace: device, akvq_massive_workspace_bytes(B, T) bytes.
+ */
+size_t akvq_massive_workspace_bytes(int B, int T);
+int akvq_select_massive(const akvq_cache *c, const void *hidden, int T, int d_model, int top_k, float floor,
+                        float *score_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * akvq_quantize_append -- Section III-C write path for rows [T_len, T_len + n_new).
  *   k_new, v_new: device, [B][Hkv][n_new][128] binary16 (K post-RoPE, un-rotated).
  *   Each row is rotated (fp32 butterfly, stride 1..64, then 2^-3.5), its groups get scale / zero-point

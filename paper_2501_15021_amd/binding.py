@@ -22,7 +22,8 @@ V_PREROTATED, OUT_ROTATED = 1, 2
 EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
            "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention",
-           "akvq_quantize_append_tiered", "akvq_decode_attention_tiered"]
+           "akvq_quantize_append_tiered", "akvq_decode_attention_tiered",
+           "akvq_massive_workspace_bytes", "akvq_select_massive"]
 TIER_2BIT, TIER_4BIT_COARSE, TIER_4BIT_FINE, TIER_PAD = 0, 1, 2, 3
 
 
@@ -74,6 +75,11 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention.restype = C.c_int
         L.akvq_decode_attention.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+        L.akvq_massive_workspace_bytes.restype = C.c_size_t
+        L.akvq_massive_workspace_bytes.argtypes = [C.c_int, C.c_int]
+        L.akvq_select_massive.restype = C.c_int
+        L.akvq_select_massive.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
+                                          C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.akvq_quantize_append_tiered.restype = C.c_int
         L.akvq_quantize_append_tiered.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                                   C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_void_p,
@@ -181,6 +187,17 @@ def select_salient(cache: Cache, mode: int, *, is_text: Optional[torch.Tensor] =
         st = lib().akvq_select_salient(C.byref(c), mode, None, _ptr(q_tail), Hq, _ptr(k), T, W, top_k, sm_scale,
                                        _ptr(mass_out), _ptr(ws), ws.numel(), _stream())
     _check(st, "akvq_select_salient")
+
+
+def select_massive(cache: Cache, hidden: torch.Tensor, top_k: int, floor: float = 0.0,
+                   score_out: Optional[torch.Tensor] = None) -> None:
+    """akvq_select_massive: pivots = top_k tokens by largest hidden-state magnitude (>= floor); hidden [B,T,d_model]."""
+    assert hidden.dtype == torch.float16 and hidden.is_contiguous()
+    B, T, d_model = hidden.shape
+    ws = cache.workspace("massive", lib().akvq_massive_workspace_bytes(B, T))
+    c = cache.struct()
+    _check(lib().akvq_select_massive(C.byref(c), _ptr(hidden), T, d_model, top_k, floor, _ptr(score_out), _ptr(ws),
+                                     ws.numel(), _stream()), "akvq_select_massive")
 
 
 def quantize_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, clip: float, flags: int = 0) -> None:

@@ -133,6 +133,34 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
   return hip_status(akvq::launch_select_psa(a, s));
 }
 
+size_t akvq_massive_workspace_bytes(int B, int T) {
+  if (B <= 0 || T <= 0) return 0;
+  return round_up((size_t)B * T * sizeof(float), 256);
+}
+
+int akvq_select_massive(const akvq_cache *c, const void *hidden, int T, int d_model, int top_k, float floor,
+                        float *score_out, void *workspace, size_t workspace_bytes, void *stream) {
+  int st = check_cache_shape(c);
+  if (st != AKVQ_OK) return st;
+  if (!c->sal_idx || !c->sal_cnt || !aligned16(c->sal_idx) || !aligned16(c->sal_cnt)) return AKVQ_ERR_INVALID_ARG;
+  if (!hidden || !aligned16(hidden) || T <= 0 || T > c->T_cap || top_k <= 0 || d_model <= 0) return AKVQ_ERR_INVALID_ARG;
+  if (d_model % 512 != 0) return AKVQ_ERR_UNSUPPORTED;
+  if (top_k > c->S_cap) return AKVQ_ERR_CAPACITY;
+  if (!(floor >= 0.0f)) return AKVQ_ERR_INVALID_ARG;
+  if (score_out && !aligned16(score_out)) return AKVQ_ERR_INVALID_ARG;
+  if (!score_out) {
+    if (!workspace || !aligned16(workspace)) return AKVQ_ERR_INVALID_ARG;
+    if (workspace_bytes < akvq_massive_workspace_bytes(c->B, T)) return AKVQ_ERR_WORKSPACE;
+  }
+  akvq::SelectArgs a{};
+  a.sal_idx = c->sal_idx; a.sal_cnt = c->sal_cnt;
+  a.B = c->B; a.Hkv = c->Hkv; a.Hq = c->Hkv; a.T = T; a.S_cap = c->S_cap; a.top_k = top_k;
+  a.hidden = static_cast<const uint16_t *>(hidden);
+  a.d_model = d_model; a.floor = floor; a.mass_per_batch = 1; a.skip_zero = 1;
+  a.mass = score_out ? score_out : static_cast<float *>(workspace);
+  return hip_status(akvq::launch_select_massive(a, static_cast<hipStream_t>(stream)));
+}
+
 static int check_window(const akvq_window *win) {
   if (!win) return AKVQ_OK;
   if (!win->k_win || !win->v_win || !aligned16(win->k_win) || !aligned16(win->v_win)) return AKVQ_ERR_INVALID_ARG;

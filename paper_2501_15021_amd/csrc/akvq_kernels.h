@@ -55,9 +55,16 @@ struct SelectArgs {
   float *row_stats;          // workspace: [B][Hq][n_chunk][W][2]
   int B, Hq, Hkv, T, W, top_k, S_cap, n_chunk;
   float sm_scale;
+  // massive-activation mode: hidden states, one score row per batch element, zero keys are never selected
+  const uint16_t *hidden;    // [B][T][d_model] binary16
+  int d_model;
+  float floor;
+  int mass_per_batch;        // top-k reads mass[b][T] (shared by the batch element's kv-heads) instead of mass[b][hkv][T]
+  int skip_zero;
 };
 constexpr int kScoreChunk = 2048;  // keys per scoring workgroup
 hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream);
+hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream);
 
 }  // namespace akvq

@@ -348,9 +348,10 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   __shared__ int list_n;
   __shared__ int list[kTopkListMax];
   const int bh = blockIdx.x, lane = threadIdx.x & 63;
-  const float *mass = a.mass + (size_t)bh * a.T;
+  const float *mass = a.mass + (size_t)(a.mass_per_batch ? bh / a.Hkv : bh) * a.T;
   int32_t *out = a.sal_idx + (size_t)bh * a.S_cap;
   const int k = min(a.top_k, a.T);
+  const uint32_t lowest = a.skip_zero ? 1u : 0u;  // keys below this bit pattern (i.e. +0) are never selected
   if (STAGED) {
     for (int t = threadIdx.x; t < a.T; t += 256) keys_lds[t] = mass[t];
     if (threadIdx.x == 0) list_n = 0;
@@ -397,16 +398,19 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   const int n_equal = hist[0];
   if (STAGED && k <= kTopkListMax && n_equal == need) {
     // every key >= prefix is taken: gather their positions in any order, then order the short list by rank
-    for (int t = threadIdx.x; t < a.T; t += 256)
-      if (__float_as_uint(keys[t]) >= prefix) list[atomicAdd(&list_n, 1)] = t;
+    for (int t = threadIdx.x; t < a.T; t += 256) {
+      const uint32_t bits = __float_as_uint(keys[t]);
+      if (bits >= prefix && bits >= lowest) list[atomicAdd(&list_n, 1)] = t;
+    }
     __syncthreads();
-    if ((int)threadIdx.x < k) {
+    const int n_kept = list_n;  // k, or fewer when zero keys are excluded
+    if ((int)threadIdx.x < n_kept) {
       const int mine = list[threadIdx.x];
       int rank = 0;
-      for (int j = 0; j < k; ++j) rank += list[j] < mine;
+      for (int j = 0; j < n_kept; ++j) rank += list[j] < mine;
       if (rank < a.S_cap) out[rank] = mine;
     }
-    if (threadIdx.x == 0) a.sal_cnt[bh] = k;
+    if (threadIdx.x == 0) a.sal_cnt[bh] = n_kept;
     return;
   }
   // general case: each thread owns a contiguous run of positions, so two workgroup scans (equal keys, taken keys)
@@ -422,7 +426,7 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
     int r = eq_rank;
     for (int t = t0; t < t1; ++t) {
       const uint32_t bits = __float_as_uint(keys[t]);
-      n_take += bits > prefix || (bits == prefix && r++ < need);
+      n_take += (bits > prefix || (bits == prefix && r++ < need)) && bits >= lowest;
     }
   }
   int tot_take;
@@ -430,7 +434,7 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   if (n_take > 0) {
     for (int t = t0; t < t1; ++t) {
       const uint32_t bits = __float_as_uint(keys[t]);
-      if (bits > prefix || (bits == prefix && eq_rank++ < need)) {
+      if ((bits > prefix || (bits == prefix && eq_rank++ < need)) && bits >= lowest) {
         if (pos < a.S_cap) out[pos] = t;
         ++pos;
       }
@@ -439,7 +443,50 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   if (threadIdx.x == 0) a.sal_cnt[bh] = tot_take;
 }
 
+// ---- massive-activation score (Section III-B.2): largest channel magnitude of every token's hidden state ----
+// One wavefront per token; magnitudes of binary16 values order like their low 15 bits, so the row maximum is taken on
+// integers; scores below the floor are written as 0 (the top-k never selects a zero key).
+__global__ __launch_bounds__(256) void massive_score_kernel(SelectArgs a) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long row = (long)blockIdx.x * 4 + wave;
+  if (row >= (long)a.B * a.T) return;
+  const uint16_t *src = a.hidden + (size_t)row * a.d_model;
+  uint32_t m0 = 0u, m1 = 0u;  // running maxima of the low and the high binary16 of every word, as 15-bit integers
+  for (int c0 = 0; c0 < a.d_model; c0 += 512) {  // 64 lanes x 8 channels
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(src + c0 + 8 * lane);
+    const uint32_t w0 = v[0], w1 = v[1], w2 = v[2], w3 = v[3];
+    m0 = max(m0, max(max(w0 & 0x7FFFu, w1 & 0x7FFFu), max(w2 & 0x7FFFu, w3 & 0x7FFFu)));
+    m1 = max(m1, max(max((w0 >> 16) & 0x7FFFu, (w1 >> 16) & 0x7FFFu), max((w2 >> 16) & 0x7FFFu, (w3 >> 16) & 0x7FFFu)));
+  }
+  uint32_t m2 = max(m0, m1);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m2 = max(m2, (uint32_t)__shfl_xor((int)m2, off, kWave));
+  if (lane == 0) {
+    const float score = half_bits_to_float(m2);
+    a.mass[row] = score >= a.floor ? score : 0.0f;
+  }
+}
+
 }  // namespace
+
+hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream) {
+  const long rows = (long)a.B * a.T;
+  hipLaunchKernelGGL(massive_score_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  if (a.T <= kTopkStageMax) {
+    const size_t lds = (size_t)a.T * sizeof(float);
+    if (lds > 48 * 1024) {
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, a);
+  } else {
+    hipLaunchKernelGGL(topk_kernel<false>, dim3(a.B * a.Hkv), dim3(256), 0, stream, a);
+  }
+  return hipGetLastError();
+}
 
 hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream) {
   hipLaunchKernelGGL(select_tsa_kernel, dim3(a.B * a.Hkv), dim3(256), 0, stream, a);

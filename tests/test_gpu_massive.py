@@ -1,0 +1,49 @@
+"""GPU parity of akvq_select_massive (Section III-B.2: pivots from massive activations): index sets and counts are
+compared exactly with the oracle (scores are exact maxima of binary16 magnitudes, so nothing is approximate)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2501_15021_amd import binding as akvq
+from paper_2501_15021_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _compare(orc, w, hid, top_k, floor, t_cap):
+    oc = orc.OracleCache(w.B, w.Hkv, w.G, t_cap, 64)
+    gc = akvq.Cache(w.B, w.Hkv, w.G, t_cap, 64)
+    ref = oc.select_massive(hid.cpu().numpy(), top_k, floor, want_score=True)
+    score = torch.zeros(w.B, w.T, dtype=torch.float32, device="cuda")
+    akvq.select_massive(gc, hid.cuda(), top_k, floor, score_out=score)
+    torch.cuda.synchronize()
+    got = score.cpu().numpy().astype(np.float64)
+    assert np.array_equal(got, np.where(ref >= floor, ref, 0.0))
+    assert np.array_equal(gc.counts().cpu().numpy(), oc.sal_cnt)
+    idx = gc.sal_idx.cpu().numpy()
+    for b in range(w.B):
+        for h in range(w.Hkv):
+            n = int(oc.sal_cnt[b, h])
+            assert np.array_equal(idx[b, h, :n], oc.sal_idx[b, h, :n]), (b, h)
+    akvq.select_massive(gc, hid.cuda(), top_k, floor)          # scores in the workspace instead
+    torch.cuda.synchronize()
+    assert np.array_equal(gc.sal_idx.cpu().numpy()[:, :, :top_k], idx[:, :, :top_k])
+    return oc
+
+
+@pytest.mark.parametrize("top_k,floor", [(15, 100.0), (4, 0.0), (15, 0.0), (3, 1000.0), (64, 41.0)])
+def test_massive_small(orc, top_k, floor):
+    w = synth.small("mag", B=3, Hq=4, Hkv=2, T=333)
+    d = synth.generate(w, seed=11)
+    hid = synth.hidden_states(w, d["pivots"], d_model=512, seed=11)
+    hid[0, 17, 5] = hid[0, 200, 9] = 77.0     # equal scores: the lower position first
+    _compare(orc, w, hid, top_k, floor, 384)
+
+
+def test_massive_cfg2_shape(orc):
+    w = synth.WORKLOADS["cfg2"]
+    d = synth.generate(w, layer=3, device="cuda")
+    hid = synth.hidden_states(w, d["pivots"].cpu(), d_model=4096, layer=3, device="cuda")
+    oc = _compare(orc, w, hid, 15, 100.0, 4096)
+    for b in range(w.B):
+        assert sorted(set(int(x) for x in d["pivots"][b])) == oc.sal_idx[b, 0, :oc.sal_cnt[b, 0]].tolist()
