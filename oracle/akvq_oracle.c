@@ -363,6 +363,41 @@ void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t
 }
 
 /* ------------------------------------------------------------------------------------------
+ * Offline fold of the rotation into projection weights (Section III-C.2 / Fig. 7: H is merged into W_V and W_O so that
+ * the value rotation and the output un-rotation cost nothing online).  w [rows][cols] binary16, row-major.
+ *   axis 1: every aligned run of 128 columns of a row is rotated: out[r][128g..] = in[r][128g..] * H   (W_V, used as x*W_V)
+ *   axis 0: every aligned run of 128 rows is rotated column-wise: out[128g..][c] = H * in[128g..][c]    (W_O, used as o*W_O)
+ * Arithmetic as for cached rows: fp32 butterfly (stride 1..64), times 2^-3.5, rounded to binary16 (nearest even).
+ * pinned by: equals the dense H product within binary16 rounding; folding twice returns the input within rounding;
+ * (x*W_V)*H equals x*(W_V folded) within rounding.
+ * ---------------------------------------------------------------------------------------- */
+void orc_fold_hadamard(const uint16_t *w, uint16_t *out, int rows, int cols, int axis) {
+  const float kappa = bits_to_float(ORC_INV_SQRT128_BITS);
+  float x[ORC_D], u[ORC_D];
+  if (axis == 1) {
+    for (int r = 0; r < rows; ++r)
+      for (int g = 0; g < cols / ORC_D; ++g) {
+        for (int e = 0; e < ORC_D; ++e) x[e] = orc_half_to_float(w[(size_t)r * cols + g * ORC_D + e]);
+        orc_fwht128_f32(x, u);
+        for (int e = 0; e < ORC_D; ++e) {
+          volatile float y = u[e] * kappa;
+          out[(size_t)r * cols + g * ORC_D + e] = orc_float_to_half_rne(y);
+        }
+      }
+  } else {
+    for (int g = 0; g < rows / ORC_D; ++g)
+      for (int c = 0; c < cols; ++c) {
+        for (int e = 0; e < ORC_D; ++e) x[e] = orc_half_to_float(w[(size_t)(g * ORC_D + e) * cols + c]);
+        orc_fwht128_f32(x, u);
+        for (int e = 0; e < ORC_D; ++e) {
+          volatile float y = u[e] * kappa;
+          out[(size_t)(g * ORC_D + e) * cols + c] = orc_float_to_half_rne(y);
+        }
+      }
+  }
+}
+
+/* ------------------------------------------------------------------------------------------
  * Pivot tokens from massive activations (Section III-B.2: tokens whose residual-stream activations are massive
  * attract the attention of the following layers; their indices are the pivot tokens).
  * reading (the paper gives neither a threshold nor a count rule; its ablation keeps 15 pivots): the score of a

@@ -72,6 +72,7 @@ def lib():
                                            C.c_void_p]
         L.orc_decode_attention_one.argtypes = [C.POINTER(_Cache), C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_double,
                                                C.c_int, C.c_void_p, C.c_void_p]
+        L.orc_fold_hadamard.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int]
         L.orc_select_massive.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_float,
                                          C.c_void_p]
         L.orc_quantize_row_bits.argtypes = [C.c_void_p, C.c_int, C.c_float, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -271,6 +272,16 @@ def quantize_row_bits(x_f16, G: int, clip: float, n_bits: int, rotate: bool = Tr
     ybf = np.zeros(D, dtype=np.uint16)
     lib().orc_quantize_row_bits(_p(x), G, clip, int(rotate), n_bits, _p(codes), _p(sb), _p(z), _p(ybf))
     return codes, sb, z, ybf
+
+
+def fold_hadamard(w_f16, axis: int) -> np.ndarray:
+    """Fold H_128 into a projection matrix [rows, cols] fp16 (axis 1: column runs of every row; axis 0: row runs)."""
+    w = _u16(w_f16)
+    rows, cols = w.shape
+    assert (cols if axis == 1 else rows) % D == 0
+    out = np.zeros_like(w)
+    lib().orc_fold_hadamard(_p(w), _p(out), rows, cols, axis)
+    return out.view(np.float16)
 
 
 def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
