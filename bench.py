@@ -192,7 +192,7 @@ def main():
                     help="--phase decode|quantize with the 4-bit text tier (text tokens as row pairs, pivots 16-bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
-    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "copy"],
+    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "fold", "copy"],
                     help="time one call only (per-kernel studies; the default 'all' is the benchmark line)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through in --phase runs")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (sweeps)")
@@ -255,6 +255,31 @@ def main():
                           "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                                        "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                                        "algorithmic_bytes_per_launch": nbytes}}))
+        return
+    if args.phase == "fold":
+        # offline fold of the rotation into one layer's W_V (output columns) and W_O (input rows), d_model 4096
+        d_model = 4096
+        g = torch.Generator(device="cuda").manual_seed(11)
+        wv = (torch.randn(d_model, w.Hkv * 128, generator=g, device="cuda") / 64).half()
+        wo = (torch.randn(w.Hq * 128, d_model, generator=g, device="cuda") / 64).half()
+        ov, oo = torch.empty_like(wv), torch.empty_like(wo)
+        res = {}
+        for name, src, dst, axis in (("W_V columns", wv, ov, 1), ("W_O rows", wo, oo, 0)):
+            for _ in range(args.warmup):
+                akvq.fold_hadamard(src, axis, out=dst)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                akvq.fold_hadamard(src, axis, out=dst)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / args.steps
+            nbytes = 2 * src.numel() * 2
+            res[name] = {"shape": list(src.shape), "ms_per_call": round(ms, 5), "algorithmic_bytes": nbytes,
+                         "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                         "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+        print(json.dumps({"metric": "fold_hadamard call alone", "workload": w.name, "d_model": d_model, **res}))
         return
     if args.phase != "all":
         return phase_bench(args, w, akvq, synth, torch, np)

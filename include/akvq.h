@@ -121,6 +121,16 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
                         void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * akvq_fold_hadamard -- offline mode of Section III-C.2 (Fig. 7): fold H_128 into a projection matrix once, so that
+ *   values arrive rotated (AKVQ_V_PREROTATED) and the rotated attention output (AKVQ_OUT_ROTATED) is consumed as is.
+ *   w_in, w_out: device, [rows][cols] binary16, row-major (w_out may equal w_in only for axis 1).
+ *   axis 1: every aligned run of 128 columns of each row becomes run * H_128   (W_V used as x * W_V; cols % 128 == 0);
+ *   axis 0: every aligned run of 128 rows becomes H_128 * run, column by column (W_O used as o * W_O; rows % 128 == 0).
+ *   fp32 butterfly (strides 1..64), times 2^-3.5, rounded to binary16.
+ */
+int akvq_fold_hadamard(const void *w_in, void *w_out, int rows, int cols, int axis, void *stream);
+
+/*
  * akvq_select_massive -- Section III-B.2 as the paper states it: pivot tokens are the tokens whose residual-stream
  *   activations are massive.  hidden: device, [B][T][d_model] binary16 (a Transformer block's output), d_model a
  *   multiple of 512.  score[b][t] = max over channels of |hidden|; the salient list of every kv-head of batch element b

@@ -23,7 +23,7 @@ EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_b
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
            "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention",
            "akvq_quantize_append_tiered", "akvq_decode_attention_tiered",
-           "akvq_massive_workspace_bytes", "akvq_select_massive"]
+           "akvq_massive_workspace_bytes", "akvq_select_massive", "akvq_fold_hadamard"]
 TIER_2BIT, TIER_4BIT_COARSE, TIER_4BIT_FINE, TIER_PAD = 0, 1, 2, 3
 
 
@@ -75,6 +75,8 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention.restype = C.c_int
         L.akvq_decode_attention.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+        L.akvq_fold_hadamard.restype = C.c_int
+        L.akvq_fold_hadamard.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.akvq_massive_workspace_bytes.restype = C.c_size_t
         L.akvq_massive_workspace_bytes.argtypes = [C.c_int, C.c_int]
         L.akvq_select_massive.restype = C.c_int
@@ -187,6 +189,16 @@ def select_salient(cache: Cache, mode: int, *, is_text: Optional[torch.Tensor] =
         st = lib().akvq_select_salient(C.byref(c), mode, None, _ptr(q_tail), Hq, _ptr(k), T, W, top_k, sm_scale,
                                        _ptr(mass_out), _ptr(ws), ws.numel(), _stream())
     _check(st, "akvq_select_salient")
+
+
+def fold_hadamard(w: torch.Tensor, axis: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """akvq_fold_hadamard: fold H_128 into a projection matrix [rows, cols] fp16 (axis 1: W_V, axis 0: W_O)."""
+    assert w.dtype == torch.float16 and w.is_contiguous() and w.dim() == 2
+    if out is None:
+        out = torch.empty_like(w)
+    assert out.dtype == torch.float16 and out.is_contiguous() and out.shape == w.shape
+    _check(lib().akvq_fold_hadamard(_ptr(w), _ptr(out), w.shape[0], w.shape[1], axis, _stream()), "akvq_fold_hadamard")
+    return out
 
 
 def select_massive(cache: Cache, hidden: torch.Tensor, top_k: int, floor: float = 0.0,

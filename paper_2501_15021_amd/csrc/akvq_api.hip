@@ -133,6 +133,15 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
   return hip_status(akvq::launch_select_psa(a, s));
 }
 
+int akvq_fold_hadamard(const void *w_in, void *w_out, int rows, int cols, int axis, void *stream) {
+  if (!w_in || !w_out || !aligned16(w_in) || !aligned16(w_out) || rows <= 0 || cols <= 0) return AKVQ_ERR_INVALID_ARG;
+  if (axis != 0 && axis != 1) return AKVQ_ERR_INVALID_ARG;
+  if ((axis == 1 ? cols : rows) % 128 != 0) return AKVQ_ERR_INVALID_ARG;
+  if (axis == 0 && w_in == w_out) return AKVQ_ERR_INVALID_ARG;
+  return hip_status(akvq::launch_fold_hadamard(static_cast<const uint16_t *>(w_in), static_cast<uint16_t *>(w_out), rows,
+                                               cols, axis, static_cast<hipStream_t>(stream)));
+}
+
 size_t akvq_massive_workspace_bytes(int B, int T) {
   if (B <= 0 || T <= 0) return 0;
   return round_up((size_t)B * T * sizeof(float), 256);

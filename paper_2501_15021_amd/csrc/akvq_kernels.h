@@ -67,4 +67,7 @@ hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream);
 
+// offline fold of H_128 into a projection matrix w [rows][cols] binary16 (axis 1: runs of 128 columns, axis 0: of rows)
+hipError_t launch_fold_hadamard(const uint16_t *w, uint16_t *out, int rows, int cols, int axis, hipStream_t stream);
+
 }  // namespace akvq
