@@ -441,7 +441,7 @@ void orc_select_massive(orc_cache *c, const uint16_t *hidden, int T, int d_model
  * slot equal to its rank in the list, and bit 15 of its meta words is set.
  * ---------------------------------------------------------------------------------------- */
 void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_new, int n_new, float clip,
-                         int rotate_v) {
+                         int rot) {
   const int ng = ORC_D / c->G;
   const int nbh = c->B * c->Hkv;
 #pragma omp parallel for schedule(dynamic)
@@ -453,7 +453,7 @@ void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_
       for (int tensor = 0; tensor < 2; ++tensor) {
         const uint16_t *row = (tensor == 0 ? k_new : v_new) + ((size_t)bh * n_new + i) * ORC_D;
         uint8_t codes[ORC_D]; uint16_t sb[2]; int16_t z[2]; uint16_t ybf[ORC_D];
-        orc_quantize_row(row, c->G, clip, tensor == 0 ? 1 : rotate_v, codes, sb, z, ybf);
+        orc_quantize_row(row, c->G, clip, (rot & (tensor == 0 ? ORC_ROT_K : ORC_ROT_V)) != 0, codes, sb, z, ybf);
         for (int e = 0; e < ORC_D; ++e) put_code(c, tensor, b, h, t, e, codes[e]);
         uint32_t *meta = (tensor == 0 ? c->k_meta : c->v_meta) + ((size_t)bh * c->T_cap + t) * ng;
         for (int g = 0; g < ng; ++g)
@@ -487,7 +487,7 @@ void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_
  * ---------------------------------------------------------------------------------------- */
 void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint16_t *v_src, int n_src,
                                 const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
-                                float clip4, int rotate_v, uint32_t *fine_mask, uint16_t *k_win, uint16_t *v_win,
+                                float clip4, int rot, uint32_t *fine_mask, uint16_t *k_win, uint16_t *v_win,
                                 int W) {
   const int ng = ORC_D / c->G;
   const int nbh = c->B * c->Hkv;
@@ -525,15 +525,15 @@ void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint1
         }
         const uint16_t *row = (tensor == 0 ? k_src : v_src) + ((size_t)bh * n_src + src) * ORC_D;
         uint8_t codes[ORC_D]; uint16_t sb[2]; int16_t z[2]; uint16_t ybf[ORC_D];
-        const int rot = tensor == 0 ? 1 : rotate_v;
+        const int rotate = (rot & (tensor == 0 ? ORC_ROT_K : ORC_ROT_V)) != 0;
         if (in_win && tier != 2) { /* ybf does not depend on the bit width */
           uint16_t yb[ORC_D]; uint8_t cc[ORC_D]; uint16_t s2[2]; int16_t z2[2];
-          orc_quantize_row_bits(row, c->G, clip2, rot, 2, cc, s2, z2, yb);
+          orc_quantize_row_bits(row, c->G, clip2, rotate, 2, cc, s2, z2, yb);
           if (tensor == 0) memcpy(k_win + ((size_t)bh * W + t % W) * ORC_D, yb, sizeof(yb));
           else for (int e = 0; e < ORC_D; ++e) v_win[(size_t)bh * W * ORC_D + orc_vsal_pos(t % W, e)] = yb[e];
         }
         if (tier == 0) {
-          orc_quantize_row_bits(row, c->G, clip2, rot, 2, codes, sb, z, ybf);
+          orc_quantize_row_bits(row, c->G, clip2, rotate, 2, codes, sb, z, ybf);
           for (int e = 0; e < ORC_D; ++e) put_code(c, tensor, b, h, t, e, codes[e]);
           for (int g = 0; g < ng; ++g)
             meta[g] = (uint32_t)sb[g] | (slot >= 0 ? 0x8000u : 0u) | ((uint32_t)(uint16_t)z[g] << 16);
@@ -545,7 +545,7 @@ void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint1
             }
           }
         } else {
-          orc_quantize_row_bits(row, c->G, clip4, rot, 4, codes, sb, z, ybf);
+          orc_quantize_row_bits(row, c->G, clip4, rotate, 4, codes, sb, z, ybf);
           for (int e = 0; e < ORC_D; ++e)
             put_code(c, tensor, b, h, t, e, tier == 1 ? (uint8_t)(codes[e] >> 2) : (uint8_t)(codes[e] & 3));
           for (int g = 0; g < ng; ++g) {
@@ -569,7 +569,7 @@ void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint1
  * Read path: softmax attention of one decode query over the cached rows (Section II-A, Eq. 2 context),
  * using the dequantized (Eq. 4) or bfloat16 rows, all in fp64, dense, two-pass softmax.
  * The query is rotated with the dense H_128 (Section III-C: rotate Q and K after RoPE); the output is
- * rotated back (H is its own inverse) unless unrotate == 0.
+ * rotated back (H is its own inverse); rot selects which of the two happen (ORC_ROT_Q | ORC_ROT_OUT is the method).
  * pinned by: a numpy brute-force attention over independently dequantized rows; T=1; equal scores give
  * the mean; shift invariance; an all-salient cache matches attention over the original K,V up to
  * bfloat16 rounding; GQA equals MHA with repeated KV heads.
@@ -595,8 +595,8 @@ static void cached_row(const orc_cache *c, int tensor, int b, int h, int t, int 
 }
 
 void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const uint16_t *q_row, double sm_scale,
-                              int unrotate, double *out, double *lse) {
-  orc_decode_attention_one_tiered(c, NULL, NULL, NULL, 0, Hq, b, hq, q_row, sm_scale, unrotate, out, lse);
+                              int rot, double *out, double *lse) {
+  orc_decode_attention_one_tiered(c, NULL, NULL, NULL, 0, Hq, b, hq, q_row, sm_scale, rot, out, lse);
 }
 
 /* first row of the recent window: the last W rows, the boundary moved up to an even row so that a (coarse, fine)
@@ -622,13 +622,14 @@ static void window_row(const uint16_t *k_win, const uint16_t *v_win, int W, size
  * it are one token whose value is the sum of the two dequantized rows (Eq. 4 applied to each half). */
 void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
                                      const uint16_t *v_win, int W, int Hq, int b, int hq, const uint16_t *q_row,
-                                     double sm_scale, int unrotate, double *out, double *lse) {
+                                     double sm_scale, int rot, double *out, double *lse) {
   const int r = Hq / c->Hkv;
   const int h = hq / r;
   const int T = c->T_len;
   double qd[ORC_D], qrot[ORC_D];
   for (int d = 0; d < ORC_D; ++d) qd[d] = (double)orc_half_to_float(q_row[d]);
-  orc_wht_dense_f64(ORC_D, qd, qrot);
+  if (rot & ORC_ROT_Q) orc_wht_dense_f64(ORC_D, qd, qrot);
+  else memcpy(qrot, qd, sizeof(qrot));
   int *slot_of = (int *)malloc(sizeof(int) * (size_t)T);
   for (int t = 0; t < T; ++t) slot_of[t] = -1;
   {
@@ -683,25 +684,25 @@ void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_ma
     for (int e = 0; e < ORC_D; ++e) orot[e] += p * row[e];
   }
 #undef ORC_IS_FINE
-  if (unrotate) orc_wht_dense_f64(ORC_D, orot, out);
+  if (rot & ORC_ROT_OUT) orc_wht_dense_f64(ORC_D, orot, out);
   else memcpy(out, orot, sizeof(orot));
   if (lse) *lse = mx + log(den);
   free(score); free(slot_of);
 }
 
-void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int unrotate,
+void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int rot,
                           double *out, double *lse) {
-  orc_decode_attention_tiered(c, NULL, NULL, NULL, 0, Hq, q, sm_scale, unrotate, out, lse);
+  orc_decode_attention_tiered(c, NULL, NULL, NULL, 0, Hq, q, sm_scale, rot, out, lse);
 }
 
 void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
                                  const uint16_t *v_win, int W, int Hq, const uint16_t *q, double sm_scale,
-                                 int unrotate, double *out, double *lse) {
+                                 int rot, double *out, double *lse) {
   const int n = c->B * Hq;
 #pragma omp parallel for schedule(dynamic)
   for (int x = 0; x < n; ++x) {
     int b = x / Hq, hq = x % Hq;
-    orc_decode_attention_one_tiered(c, fine_mask, k_win, v_win, W, Hq, b, hq, q + (size_t)x * ORC_D, sm_scale, unrotate,
+    orc_decode_attention_one_tiered(c, fine_mask, k_win, v_win, W, Hq, b, hq, q + (size_t)x * ORC_D, sm_scale, rot,
                                     out + (size_t)x * ORC_D, lse ? lse + x : NULL);
   }
 }

@@ -87,34 +87,39 @@ void orc_fold_hadamard(const uint16_t *w, uint16_t *out, int rows, int cols, int
  * every kv-head.  score_out (optional) [B][T] fp64.  Writes sal_idx / sal_cnt. */
 void orc_select_massive(orc_cache *c, const uint16_t *hidden, int T, int d_model, int top_k, float floor_,
                         double *score_out);
+/* Which rotations a call applies.  The method is ORC_ROT_K | ORC_ROT_V on the write path and ORC_ROT_Q | ORC_ROT_OUT on
+ * the read path; a cleared bit means the tensor is already in (or stays in) the rotated domain -- the offline fold of
+ * Section III-C.2 clears ORC_ROT_V and ORC_ROT_OUT; all four cleared is plain round-to-nearest quantization without the
+ * rotation (the ablation baseline of Table III). */
+enum { ORC_ROT_K = 1, ORC_ROT_V = 2, ORC_ROT_Q = 1, ORC_ROT_OUT = 2 };
 /* Write path: rows [T_len, T_len+n_new) of K and V ([B][Hkv][n_new][128] binary16).  Does not change T_len. */
 void orc_quantize_append(orc_cache *c, const uint16_t *k_new, const uint16_t *v_new, int n_new, float clip,
-                         int rotate_v);
+                         int rot);
 /* Tiered write path: cache row T_len + r of batch b takes source token row_src[b][r] (index into k_src / v_src,
  * [B][Hkv][n_src][128]) with tier row_tier[b][r]: 0 = 2-bit, 1 / 2 = coarse / fine half of a 4-bit token (two 2-bit
  * rows), 3 = padding.  fine_mask [B][T_cap/32] marks the fine halves.  Does not change T_len. */
 void orc_quantize_append_tiered(orc_cache *c, const uint16_t *k_src, const uint16_t *v_src, int n_src,
                                 const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
-                                float clip4, int rotate_v, uint32_t *fine_mask, uint16_t *k_win, uint16_t *v_win,
+                                float clip4, int rot, uint32_t *fine_mask, uint16_t *k_win, uint16_t *v_win,
                                 int W);
 /* row_src / row_tier / fine_mask may be NULL (plain rows, identity mapping).  Recent window (W > 0): k_win
  * [B][Hkv][W][128] and v_win [B][Hkv][W/32][4096] (tiled like v_sal) bfloat16 rings, zero-initialised by the caller;
  * the last W appended rows are also written to slot t % W.  Decode then reads rows t >= window start from the ring. */
 /* Read path: decode attention (Eq. 2 with the dequantized cache), fp64.  q [B][Hq][128] binary16.
- * out [B][Hq][128]; lse (optional) [B][Hq].  unrotate!=0: out = o~ * H_128. */
-void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int unrotate,
+ * out [B][Hq][128]; lse (optional) [B][Hq].  rot & ORC_ROT_Q: q is rotated first; rot & ORC_ROT_OUT: out = o~ * H_128. */
+void orc_decode_attention(const orc_cache *c, int Hq, const uint16_t *q, double sm_scale, int rot,
                           double *out, double *lse);
 /* One (b,hq) output only -- used to spot-check full-size runs. */
 void orc_decode_attention_one(const orc_cache *c, int Hq, int b, int hq, const uint16_t *q_row, double sm_scale,
-                              int unrotate, double *out, double *lse);
+                              int rot, double *out, double *lse);
 
 /* The same over a cache with 4-bit tokens stored as row pairs (fine_mask may be NULL: no such tokens). */
 void orc_decode_attention_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
                                  const uint16_t *v_win, int W, int Hq, const uint16_t *q, double sm_scale,
-                                 int unrotate, double *out, double *lse);
+                                 int rot, double *out, double *lse);
 void orc_decode_attention_one_tiered(const orc_cache *c, const uint32_t *fine_mask, const uint16_t *k_win,
                                      const uint16_t *v_win, int W, int Hq, int b, int hq, const uint16_t *q_row,
-                                     double sm_scale, int unrotate, double *out, double *lse);
+                                     double sm_scale, int rot, double *out, double *lse);
 
 #ifdef __cplusplus
 }

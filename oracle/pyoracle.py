@@ -157,13 +157,13 @@ class OracleCache:
         lib().orc_select_psa(C.byref(c), Hq, _p(q_tail), _p(k), T, W, top_k, sm_scale, _p(mass))
         return mass
 
-    def quantize_append(self, k_new, v_new, clip: float, rotate_v: bool = True):
+    def quantize_append(self, k_new, v_new, clip: float, rotate_v: bool = True, rotate_k: bool = True):
         k_new, v_new = _u16(k_new), _u16(v_new)
         n_new = k_new.shape[2]
         assert k_new.shape == (self.B, self.Hkv, n_new, D) == v_new.shape
         assert self.T_len + n_new <= self.T_cap
         c = self._c()
-        lib().orc_quantize_append(C.byref(c), _p(k_new), _p(v_new), n_new, clip, int(rotate_v))
+        lib().orc_quantize_append(C.byref(c), _p(k_new), _p(v_new), n_new, clip, int(rotate_k) + 2 * int(rotate_v))
         self.T_len += n_new
 
     def select_massive(self, hidden, top_k: int, floor: float = 0.0, want_score: bool = False):
@@ -184,7 +184,7 @@ class OracleCache:
         self.v_win = np.zeros((self.B, self.Hkv, W // 32, 4096), dtype=np.uint16)
 
     def quantize_append_tiered(self, k_src, v_src, row_src, row_tier, clip2: float, clip4: float,
-                               rotate_v: bool = True):
+                               rotate_v: bool = True, rotate_k: bool = True):
         """Rows [T_len, T_len + n_rows): row r of batch b takes source token row_src[b, r] with tier row_tier[b, r]
         (0 = 2-bit, 1 / 2 = coarse / fine half of a 4-bit token, 3 = padding); updates self.fine_mask."""
         k_src, v_src = _u16(k_src), _u16(v_src)
@@ -203,26 +203,27 @@ class OracleCache:
         assert self.T_len + n_rows <= self.T_cap
         c = self._c()
         lib().orc_quantize_append_tiered(C.byref(c), _p(k_src), _p(v_src), n_src, _p(row_src), _p(row_tier), n_rows,
-                                         clip2, clip4, int(rotate_v), _p(self.fine_mask if row_src is not None else None),
+                                         clip2, clip4, int(rotate_k) + 2 * int(rotate_v), _p(self.fine_mask if row_src is not None else None),
                                          _p(self.k_win), _p(self.v_win), self.W)
         self.T_len += n_rows
 
-    def decode(self, q, sm_scale: float, unrotate: bool = True):
+    def decode(self, q, sm_scale: float, unrotate: bool = True, rotate_q: bool = True):
         q = _u16(q)
         B, Hq, _ = q.shape
         out = np.zeros((B, Hq, D), dtype=np.float64)
         lse = np.zeros((B, Hq), dtype=np.float64)
         c = self._c()
         lib().orc_decode_attention_tiered(C.byref(c), _p(self.fine_mask), _p(self.k_win), _p(self.v_win), self.W, Hq,
-                                          _p(q), sm_scale, int(unrotate), _p(out), _p(lse))
+                                          _p(q), sm_scale, int(rotate_q) + 2 * int(unrotate), _p(out), _p(lse))
         return out, lse
 
-    def decode_one(self, b: int, hq: int, Hq: int, q_row, sm_scale: float, unrotate: bool = True):
+    def decode_one(self, b: int, hq: int, Hq: int, q_row, sm_scale: float, unrotate: bool = True,
+                   rotate_q: bool = True):
         q_row = _u16(q_row)
         out = np.zeros(D, dtype=np.float64)
         lse = np.zeros(1, dtype=np.float64)
         c = self._c()
-        lib().orc_decode_attention_one(C.byref(c), Hq, b, hq, _p(q_row), sm_scale, int(unrotate), _p(out), _p(lse))
+        lib().orc_decode_attention_one(C.byref(c), Hq, b, hq, _p(q_row), sm_scale, int(rotate_q) + 2 * int(unrotate), _p(out), _p(lse))
         return out, float(lse[0])
 
     def get_code(self, tensor: int, b: int, h: int, t: int, e: int) -> int:

@@ -267,3 +267,44 @@ def test_workload_shapes_and_structure():
     ch = d["outlier_channels"][0]
     assert k[0, 0, 1:, ch].abs().mean() > 5 * k[0, 0, 1:, :].abs().mean() / 2
     assert d["pivots"][:, 0].eq(0).all()
+
+
+def test_no_rotation_mode_is_plain_quantized_attention(orc):
+    """All four rotation bits cleared (the ablation baseline of Table III, and the mode in which every tensor already
+    sits in the rotated domain): rows are quantized as they arrive and attention uses q and the output as they are.
+    Checked against Eq. 3-6 written out in numpy on the raw rows plus brute-force softmax attention."""
+    w = synth.small("norot", B=1, Hq=4, Hkv=2, T=45, G=64)
+    d = _gen(w, seed=5)
+    c = orc.OracleCache(1, 2, 64, 64, 64)
+    c.select_tsa(d["is_text"])
+    c.quantize_append(d["k"], d["v"], 0.8, rotate_v=False, rotate_k=False)
+    out, lse = c.decode(d["q"], w.sm_scale, unrotate=False, rotate_q=False)
+    text = np.flatnonzero(d["is_text"][0])
+
+    def plain(x):                                     # one row, groups of 64 raw channels
+        x = x.astype(np.float64)
+        y = np.empty(D)
+        for g in range(2):
+            u = x[64 * g: 64 * g + 64]
+            lo, hi = 0.8 * u.min(), 0.8 * u.max()
+            s = float(np.float16(np.float32(hi - lo) * np.float32(1 / 3)))
+            while s < float(np.float32(hi - lo) * np.float32(1 / 3)):          # stored scale is rounded up
+                s = float(np.nextafter(np.float16(s), np.float16(np.inf)))
+            if hi == lo:
+                s = 1.0
+            z = np.rint(-lo / s)
+            q = np.clip(np.rint(u / s + z), 0, 3)
+            y[64 * g: 64 * g + 64] = s * (q - z)
+        return y
+
+    def bf16(x):
+        b = x.astype(np.float32).view(np.uint32).astype(np.uint64)
+        b = (b + 0x7FFF + ((b >> 16) & 1)) >> 16 << 16
+        return b.astype(np.uint32).view(np.float32).astype(np.float64)
+
+    for hq in range(4):
+        K = np.stack([bf16(d["k"][0, hq // 2, t]) if t in text else plain(d["k"][0, hq // 2, t]) for t in range(w.T)])
+        V = np.stack([bf16(d["v"][0, hq // 2, t]) if t in text else plain(d["v"][0, hq // 2, t]) for t in range(w.T)])
+        o, l = _softmax_attention(d["q"][0, hq].astype(np.float64), K, V, w.sm_scale)
+        assert np.allclose(out[0, hq], o, rtol=1e-9, atol=1e-11)
+        assert abs(lse[0, hq] - l) < 1e-9
