@@ -178,6 +178,123 @@ def phase_bench(args, w, akvq, synth, torch, np):
     print(json.dumps(out))
 
 
+def capacity_bench(args, w, akvq, synth, torch, np):
+    """One-GPU analogue of the paper's capacity / throughput comparison (Section IV-D, Table IV): at a fixed HBM budget
+    for the KV cache, the largest batch a 16-bit cache and the mixed 2-bit cache hold at this context length, and the
+    decode-attention rate of each at its largest batch.  One layer's share of the budget is allocated and timed (all
+    layers have the same shape); the 16-bit cache is this library's own format with every row in the 16-bit window."""
+    import ctypes as C
+    import dataclasses
+    L, T = args.layers or w.n_layers, w.T
+    t_cap = (T + 63) // 64 * 64
+    layer = 2 if w.tsa_layers else 0                     # a pivot-token layer (all but two layers of cfg2)
+    budget = args.budget_gb * 1e9 / L
+    sizes = (C.c_size_t * 8)()
+    shape = akvq.akvq_cache(1, w.Hkv, w.G, t_cap, w.s_cap(layer), 0)
+    assert akvq.lib().akvq_cache_bytes(C.byref(shape), sizes) == 0
+    bytes2 = sum(sizes)
+    bytes16 = 2 * w.Hkv * t_cap * 256
+    b16, b2 = int(budget // bytes16), int(budget // bytes2)
+    chunk = min(8, b16)
+    wc = dataclasses.replace(w, B=chunk)
+
+    def build(B, sixteen):
+        big = akvq.Cache(B, w.Hkv, w.G, t_cap, w.s_cap(layer))
+        if sixteen:
+            big.enable_window(t_cap)
+        smalls = []
+        for i in range(3):                               # three distinct chunks, dealt round-robin over the batch
+            d = synth.generate(wc, layer=layer + 100 * i, device="cuda")
+            c = akvq.Cache(chunk, w.Hkv, w.G, t_cap, w.s_cap(layer))
+            if sixteen:
+                c.enable_window(t_cap)
+                akvq.quantize_append_tiered(c, d["k"], d["v"], None, None, w.clip, 1.0)
+            else:
+                akvq.select_salient(c, akvq.MODE_PSA, q_tail=d["q_tail"], k=d["k"], top_k=w.top_k, sm_scale=w.sm_scale)
+                akvq.quantize_append(c, d["k"], d["v"], w.clip)
+            smalls.append(c)
+            del d
+        names = ["k_codes", "v_codes", "k_meta", "v_meta", "k_sal", "v_sal", "sal_idx"] + (["k_win", "v_win"] if sixteen else [])
+        for i, b0 in enumerate(range(0, B, chunk)):
+            n = min(chunk, B - b0)
+            src = smalls[i % 3]
+            for name in names:
+                getattr(big, name)[b0:b0 + n].copy_(getattr(src, name)[:n])
+            big.counts()[b0:b0 + n].copy_(src.counts()[:n])
+        big.T_len = T
+        return big
+
+    def time_decode(cache):
+        g = torch.Generator(device="cuda").manual_seed(5)
+        q = torch.randn(cache.B, w.Hq, 128, generator=g, device="cuda").half()
+        for _ in range(args.warmup):
+            akvq.decode_attention(cache, q, w.sm_scale)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            akvq.decode_attention(cache, q, w.sm_scale)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / args.steps
+
+    res = {}
+    for name, B, sixteen in (("16-bit cache, its largest batch", b16, True), ("2-bit cache, the same batch", b16, False),
+                             ("2-bit cache, its largest batch", b2, False)):
+        cache = build(B, sixteen)
+        ms = time_decode(cache)
+        per_row = 2 * (32 + 4 * (128 // w.G))
+        nbytes = B * w.Hkv * (T * 512 if sixteen else (T - w.top_k) * per_row + w.top_k * 512)
+        res[name] = {"batch": B, "cache_GB_all_layers": round(B * (bytes16 if sixteen else bytes2) * L / 1e9, 1),
+                     "ms_per_layer": round(ms, 4), "decode_tokens_per_s_attention_only": round(B / (L * ms * 1e-3), 1),
+                     "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1)}
+        del cache
+        torch.cuda.empty_cache()
+    r16, r2 = res["16-bit cache, its largest batch"], res["2-bit cache, its largest batch"]
+    ideal16 = b16 / (L * (b16 * w.Hkv * T * 512) / (HBM_PEAK_GBPS * 1e9))
+    print(json.dumps({"metric": "capacity and decode-attention rate at a fixed KV-cache budget", "workload": w.name,
+                      "context": T, "layers": L, "budget_GB": args.budget_gb,
+                      "bytes_per_sequence_per_layer": {"16-bit": bytes16, "2-bit mixed": bytes2},
+                      "max_batch_ratio": round(b2 / b16, 3), **res,
+                      "throughput_ratio_at_max_batch": round(r2["decode_tokens_per_s_attention_only"] /
+                                                             r16["decode_tokens_per_s_attention_only"], 3),
+                      "16-bit cache at the HBM peak (bound, not measured)": round(ideal16, 1),
+                      "throughput_ratio_vs_that_bound": round(r2["decode_tokens_per_s_attention_only"] / ideal16, 3)}))
+
+
+def ablation_bench(args, w, akvq, synth, torch, np):
+    """Synthetic-data analogue of the paper's ablation (Section IV-C, Table III): error of the decode-attention output
+    against exact attention over the unquantized K and V, with and without the rotation and the 16-bit salient tokens.
+    The inputs are this build's synthetic ones (outlier channels in K, planted pivot rows), not the paper's benchmark."""
+    import dataclasses
+    w = dataclasses.replace(w, B=min(w.B, 4))
+    layer = 2 if w.tsa_layers else 0
+    d = synth.generate(w, layer=layer, device="cuda")
+    t_cap = (w.T + 63) // 64 * 64
+    r = w.Hq // w.Hkv
+    k64 = d["k"].double().repeat_interleave(r, dim=1)
+    v64 = d["v"].double().repeat_interleave(r, dim=1)
+    logits = torch.einsum("bhd,bhtd->bht", d["q"].double(), k64) * w.sm_scale
+    ref = torch.einsum("bht,bhtd->bhd", torch.softmax(logits, dim=-1), v64)
+    rot_off = akvq.K_PREROTATED | akvq.V_PREROTATED, akvq.Q_PREROTATED | akvq.OUT_ROTATED
+    res = {}
+    for name, rotate, salient in (("rotation + salient tokens (the method)", True, "psa"),
+                                  ("rotation + text tokens salient", True, "tsa"),
+                                  ("rotation only", True, None), ("salient tokens only", False, "psa"),
+                                  ("plain 2-bit round-to-nearest", False, None)):
+        cache = akvq.Cache(w.B, w.Hkv, w.G, t_cap, max(64, (w.n_text + 63) // 64 * 64))
+        if salient == "psa":
+            akvq.select_salient(cache, akvq.MODE_PSA, q_tail=d["q_tail"], k=d["k"], top_k=w.top_k, sm_scale=w.sm_scale)
+        elif salient == "tsa":
+            akvq.select_salient(cache, akvq.MODE_TSA, is_text=d["is_text"])
+        akvq.quantize_append(cache, d["k"], d["v"], w.clip, flags=0 if rotate else rot_off[0])
+        out, _ = akvq.decode_attention(cache, d["q"], w.sm_scale, flags=0 if rotate else rot_off[1])
+        err = (out.double() - ref).norm(dim=-1) / ref.norm(dim=-1)
+        res[name] = {"mean_rel_err": round(err.mean().item(), 4), "max_rel_err": round(err.max().item(), 4)}
+    print(json.dumps({"metric": "decode-attention output error vs exact attention on unquantized K, V",
+                      "workload": f"{w.name}(B={w.B})", "data": "synthetic", **res}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -192,10 +309,12 @@ def main():
                     help="--phase decode|quantize with the 4-bit text tier (text tokens as row pairs, pivots 16-bit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
-    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "fold", "copy"],
+    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "fold", "capacity", "ablation", "copy"],
                     help="time one call only (per-kernel studies; the default 'all' is the benchmark line)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through in --phase runs")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (sweeps)")
+    ap.add_argument("--budget-gb", type=float, default=256.0,
+                    help="--phase capacity: HBM set aside for the KV cache of all layers together")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -256,6 +375,10 @@ def main():
                                        "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                                        "algorithmic_bytes_per_launch": nbytes}}))
         return
+    if args.phase == "ablation":
+        return ablation_bench(args, w, akvq, synth, torch, np)
+    if args.phase == "capacity":
+        return capacity_bench(args, w, akvq, synth, torch, np)
     if args.phase == "fold":
         # offline fold of the rotation into one layer's W_V (output columns) and W_O (input rows), d_model 4096
         d_model = 4096

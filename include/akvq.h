@@ -61,7 +61,11 @@ enum { AKVQ_MODE_TSA = 0, AKVQ_MODE_PSA = 1 };
 enum {
   AKVQ_V_PREROTATED = 1u, /* quantize_append: V rows arrive already rotated (H folded into W_V offline,
                              Section III-C.2 / Fig. 7); skip the transform on V */
-  AKVQ_OUT_ROTATED = 2u   /* decode_attention: leave the output in the rotated domain (H folded into W_O) */
+  AKVQ_OUT_ROTATED = 2u,  /* decode_attention: leave the output in the rotated domain (H folded into W_O) */
+  AKVQ_K_PREROTATED = 4u, /* quantize_append: K rows arrive already rotated; skip the transform on K */
+  AKVQ_Q_PREROTATED = 8u  /* decode_attention: q arrives already rotated; skip the transform on q.
+                             All four together make the library transform nothing: with inputs that were never
+                             rotated this is plain round-to-nearest quantization, the ablation baseline of Table III */
 };
 
 /* Tier of a cache row written by akvq_quantize_append_tiered (Section III-C.1: text tokens 4-bit, the rest 2-bit).

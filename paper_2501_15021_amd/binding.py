@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libakvq.so")
 
 D = 128
 MODE_TSA, MODE_PSA = 0, 1
-V_PREROTATED, OUT_ROTATED = 1, 2
+V_PREROTATED, OUT_ROTATED, K_PREROTATED, Q_PREROTATED = 1, 2, 4, 8
 
 EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",

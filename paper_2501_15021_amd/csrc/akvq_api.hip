@@ -200,6 +200,7 @@ static int quantize_common(const akvq_cache *c, const void *k_new, const void *v
   a.first_blk = c->T_len / 32;
   a.n_blk = (c->T_len + n_new - 1) / 32 - a.first_blk + 1;
   a.clip = clip;
+  a.rotate_k = (flags & AKVQ_K_PREROTATED) ? 0 : 1;
   a.rotate_v = (flags & AKVQ_V_PREROTATED) ? 0 : 1;
   return hip_status(akvq::launch_quantize_append(a, c->B, c->G, static_cast<hipStream_t>(stream)));
 }
@@ -261,6 +262,7 @@ int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask,
   a.out = out; a.lse = lse_out;
   a.B = c->B; a.Hq = Hq; a.Hkv = c->Hkv; a.T_cap = c->T_cap; a.S_cap = c->S_cap; a.T_len = c->T_len;
   a.n_split = n_split; a.sm_scale = sm_scale;
+  a.q_rotated = (flags & AKVQ_Q_PREROTATED) ? 1 : 0;
   a.out_rotated = (flags & AKVQ_OUT_ROTATED) ? 1 : 0;
   return hip_status(akvq::launch_decode_attention(a, c->G, static_cast<hipStream_t>(stream)));
 }

@@ -15,7 +15,7 @@ struct QuantArgs {
   int Hkv, T_cap, S_cap, T_len, n_new;
   int first_blk, n_blk;  // 32-token blocks touched by rows [T_len, T_len + n_new)
   float clip;
-  int rotate_v;
+  int rotate_k, rotate_v;
   // tiered append (all null / zero for the plain call): source row and tier of every new cache row, per batch element
   const int32_t *row_src;   // [B][n_new]
   const uint8_t *row_tier;  // [B][n_new]
@@ -41,7 +41,7 @@ struct DecodeArgs {
   float *lse;         // optional [B][Hq]
   int B, Hq, Hkv, T_cap, S_cap, T_len, n_split;
   float sm_scale;
-  int out_rotated;
+  int q_rotated, out_rotated;
 };
 constexpr int kPartialStride = 132;  // m, l, 2 pad, 128 accumulators
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream);

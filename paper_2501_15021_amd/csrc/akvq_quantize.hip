@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   constexpr int NG = kD / G;
 
   const uint16_t *src = tensor == 0 ? a.k_new : a.v_new;
-  const bool rotate = tensor == 0 ? true : (a.rotate_v != 0);
+  const bool rotate = (tensor == 0 ? a.rotate_k : a.rotate_v) != 0;
   const float kappa = rotate ? inv_sqrt128() : 1.0f;
   const float lane_sign = rotate ? quad_sign(j) : 1.0f;  // this lane holds lane_sign * (transformed values)
   const float kappa_s = lane_sign * kappa;

@@ -65,7 +65,7 @@ def assert_cache_equal(oc, gc, what=""):
         assert bad.size == 0, f"{what} {name}: {len(bad)} values differ, first at {bad[0]}"
 
 
-def assert_attention_close(out_gpu, lse_gpu, out_ref, lse_ref, what=""):
+def assert_attention_close(out_gpu, lse_gpu, out_ref, lse_ref, what="", lse_tol=2e-3):
     out_gpu = out_gpu.cpu().numpy().astype(np.float64)
     err = np.abs(out_gpu - out_ref).max(axis=-1)
     scale = np.maximum(np.abs(out_ref).max(axis=-1), 1e-6)
@@ -73,7 +73,7 @@ def assert_attention_close(out_gpu, lse_gpu, out_ref, lse_ref, what=""):
     worst = np.unravel_index(np.argmax(rel), rel.shape)
     assert rel.max() <= ATTN_TOL, f"{what}: worst relative error {rel.max():.3e} at (b,h)={worst}"
     if lse_gpu is not None:
-        assert np.abs(lse_gpu.cpu().numpy() - lse_ref).max() <= 2e-3, what
+        assert np.abs(lse_gpu.cpu().numpy() - lse_ref).max() <= lse_tol, what
     return rel.max()
 
 
@@ -265,7 +265,7 @@ def test_select_psa_cfg1(orc):
 
 
 # ------------------------------------------------------------------------------------------- decode attention
-def run_decode_case(orc, w, d, mode, top_k, n_splits=(0,), T=None, clip=0.8, flags=0):
+def run_decode_case(orc, w, d, mode, top_k, n_splits=(0,), T=None, clip=0.8, flags=0, lse_tol=2e-3):
     T = T or w.T
     k, v = d["k"][:, :, :T], d["v"][:, :, :T]
     n_sal = T if mode == "all" else max(top_k, w.n_text)
@@ -277,16 +277,20 @@ def run_decode_case(orc, w, d, mode, top_k, n_splits=(0,), T=None, clip=0.8, fla
     elif mode == "all":
         oc.select_tsa(np.ones((w.B, T), dtype=np.uint8))
     copy_salient_to_gpu(oc, gc)
-    oc.quantize_append(k, v, clip)
-    akvq.quantize_append(gc, _dev(k), _dev(v), clip)
+    wflags = flags & (akvq.K_PREROTATED | akvq.V_PREROTATED)
+    oc.quantize_append(k, v, clip, rotate_v=not (flags & akvq.V_PREROTATED), rotate_k=not (flags & akvq.K_PREROTATED))
+    akvq.quantize_append(gc, _dev(k), _dev(v), clip, flags=wflags)
     assert_cache_equal(oc, gc, "decode case cache")
-    out_ref, lse_ref = oc.decode(d["q"], w.sm_scale, unrotate=not (flags & akvq.OUT_ROTATED))
+    out_ref, lse_ref = oc.decode(d["q"], w.sm_scale, unrotate=not (flags & akvq.OUT_ROTATED),
+                                 rotate_q=not (flags & akvq.Q_PREROTATED))
+    flags &= akvq.OUT_ROTATED | akvq.Q_PREROTATED
     q = _dev(d["q"])
     worst = 0.0
     for ns in n_splits:
         out, lse = akvq.decode_attention(gc, q, w.sm_scale, n_split=ns, flags=flags)
         torch.cuda.synchronize()
-        worst = max(worst, assert_attention_close(out, lse, out_ref, lse_ref, f"{w.name} {mode} T={T} n_split={ns}"))
+        worst = max(worst, assert_attention_close(out, lse, out_ref, lse_ref, f"{w.name} {mode} T={T} n_split={ns}",
+                                                  lse_tol=lse_tol))
     return worst
 
 
@@ -325,6 +329,21 @@ def test_decode_rotated_output_flag(orc):
     w = synth.small("rotout", B=1, Hq=2, Hkv=2, T=100, W=16)
     d = _np(synth.generate(w, seed=110))
     run_decode_case(orc, w, d, "psa", 4, n_splits=(2,), flags=akvq.OUT_ROTATED)
+
+
+@pytest.mark.parametrize("Hq,Hkv,G", [(3, 3, 128), (2, 2, 64), (6, 2, 128)])
+def test_no_rotation_mode(orc, Hq, Hkv, G):
+    """All four rotation flags: rows are quantized as they arrive, q and the output are used as given (plain
+    round-to-nearest quantization, the ablation baseline of Table III)."""
+    w = synth.small(f"norot{Hq}_{G}", B=2, Hq=Hq, Hkv=Hkv, T=170, G=G, n_text_head=9, n_text_tail=5, top_k=6, W=16)
+    d = _np(synth.generate(w, seed=141))
+    allf = akvq.K_PREROTATED | akvq.V_PREROTATED | akvq.Q_PREROTATED | akvq.OUT_ROTATED
+    # An un-rotated query keeps its outlier channel, and one product then carries most of a logit (here up to 118 in
+    # the base-e domain).  The grouped-query kernel stages queries as two bfloat16 terms (16 bits), so a logit, and with
+    # it the log-sum-exp, can be off by 2^-16 of that product; the output bar is unchanged.
+    lse_tol = 2e-3 if Hq == Hkv else 6e-3
+    run_decode_case(orc, w, d, "tsa", 6, n_splits=(1, 3), flags=allf, lse_tol=lse_tol)
+    run_decode_case(orc, w, d, "psa", 6, n_splits=(2,), flags=akvq.K_PREROTATED | akvq.Q_PREROTATED, lse_tol=lse_tol)
 
 
 @pytest.mark.parametrize("mode,clip", [("tsa", 0.8), ("psa", 0.8), ("tsa", 1.0), ("psa", 1.0)])
