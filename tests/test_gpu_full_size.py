@@ -100,3 +100,71 @@ def test_cfg4(orc):
 
 def test_cfg5_gqa(orc):
     _run(orc, "cfg5", 0, [(0, 0), (31, 3)])
+
+
+# --------------------------------------------------------------- 4-bit text tier + recent window at full size
+def _run_tiered(orc, name, layer, units, W):
+    """Section III-C.1 tiers at the benchmark's size: text tokens 4-bit (row pairs) except position 0, the pivots of
+    the GPU's own selection 16-bit, the last W rows in the 16-bit window; sampled (batch, kv-head) units are recomputed
+    by the oracle from the same inputs and the same salient rows."""
+    w = synth.WORKLOADS[name]
+    d = synth.generate(w, layer=layer, device="cuda")
+    mask = d["is_text"].cpu().numpy()
+    row_src, row_tier, row_of = synth.tiered_rows(mask, [[0]] * w.B)
+    n_rows = row_src.shape[1]
+    t_cap = (n_rows + 63) // 64 * 64
+    cache = akvq.Cache(w.B, w.Hkv, w.G, t_cap, 64, fill=0)
+    cache.enable_window(W)
+    akvq.select_salient(cache, akvq.MODE_PSA, q_tail=d["q_tail"], k=d["k"], top_k=w.top_k, sm_scale=w.sm_scale)
+    # token positions -> cache rows; tokens stored 4-bit are dropped from the list (ascending order is kept)
+    idx = cache.sal_idx.cpu().numpy()
+    cnt = cache.counts().cpu().numpy()
+    plain = (mask == 0) | (np.arange(w.T)[None, :] == 0)
+    new_idx = np.full_like(idx, -1)
+    new_cnt = np.zeros_like(cnt)
+    for b in range(w.B):
+        for h in range(w.Hkv):
+            rows = [int(row_of[b, t]) for t in idx[b, h, :cnt[b, h]] if plain[b, t]]
+            new_idx[b, h, :len(rows)] = rows
+            new_cnt[b, h] = len(rows)
+    cache.sal_idx.copy_(torch.from_numpy(new_idx).cuda())
+    cache.counts().copy_(torch.from_numpy(new_cnt).cuda())
+    akvq.quantize_append_tiered(cache, d["k"], d["v"], torch.from_numpy(row_src).cuda(),
+                                torch.from_numpy(row_tier).cuda(), w.clip, 1.0)
+    out, _ = akvq.decode_attention(cache, d["q"], w.sm_scale)
+    torch.cuda.synchronize()
+    R = w.Hq // w.Hkv
+    for (b, h) in units:
+        print(f"tiered unit b={b} kv-head={h}", flush=True)
+        oc = orc.OracleCache(1, 1, w.G, t_cap, 64, fill=0)
+        oc.enable_window(W)
+        n = int(new_cnt[b, h])
+        oc.sal_idx[0, 0, :n] = new_idx[b, h, :n]
+        oc.sal_cnt[0, 0] = n
+        oc.quantize_append_tiered(d["k"][b:b + 1, h:h + 1].cpu().numpy(), d["v"][b:b + 1, h:h + 1].cpu().numpy(),
+                                  row_src[b:b + 1], row_tier[b:b + 1], w.clip, 1.0)
+        nb = (n_rows + 31) // 32
+        for nm in ("k_codes", "v_codes"):
+            got = getattr(cache, nm)[b, h].cpu().numpy().view(np.uint32)[:nb]
+            assert np.array_equal(got, getattr(oc, nm)[0, 0, :nb]), f"{nm} differ at unit {(b, h)}"
+        for nm in ("k_meta", "v_meta"):
+            got = getattr(cache, nm)[b, h].cpu().numpy().view(np.uint32)[:n_rows]
+            assert np.array_equal(got, getattr(oc, nm)[0, 0, :n_rows]), f"{nm} differ at unit {(b, h)}"
+        for nm in ("k_sal", "v_sal", "k_win", "v_win"):
+            got = getattr(cache, nm)[b, h].cpu().numpy().view(np.uint16).reshape(-1)
+            assert np.array_equal(got, getattr(oc, nm)[0, 0].reshape(-1)), f"{nm} differ at unit {(b, h)}"
+        assert np.array_equal(cache.fine_mask[b].cpu().numpy().view(np.uint32)[:nb], oc.fine_mask[0, :nb])
+        heads = slice(h * R, (h + 1) * R)
+        ref, _ = oc.decode(d["q"][b:b + 1, heads].cpu().numpy(), w.sm_scale)
+        got = out[b, heads].cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref[0]).max(axis=-1)
+        scale = np.maximum(np.abs(ref[0]).max(axis=-1), 1e-6)
+        assert (err / scale).max() <= ATTN_TOL, f"tiered attention at unit {(b, h)}: {(err / scale).max():.3e}"
+
+
+def test_cfg2_tiered_window(orc):
+    _run_tiered(orc, "cfg2", 2, [(0, 0), (7, 13), (15, 31)], W=128)
+
+
+def test_cfg5_tiered_window_gqa(orc):
+    _run_tiered(orc, "cfg5", 0, [(0, 0), (31, 3)], W=128)
