@@ -58,3 +58,75 @@ def test_argument_errors_launch_nothing(L):
     assert L.akvq_quantize_append(C.byref(c), None, None, 1, 0.8, 0, None) == -1
     assert L.akvq_decode_attention(C.byref(c), None, 1, 0.1, None, None, 1, None, 0, 0, None) == -1
     assert L.akvq_select_salient(C.byref(c), 0, None, None, 1, None, 64, 0, 0, 0.0, None, None, 0, None) == -1
+
+
+def test_every_error_code_of_every_entry_point(L):
+    """Each documented rejection, reached with well-formed fake device addresses: all of these return on the host before
+    anything is launched or dereferenced, so they are safe without a GPU."""
+    from paper_2501_15021_amd.binding import akvq_cache, akvq_window
+    P = 0x7F0000001000                      # 16-byte aligned, never dereferenced
+    INVALID, UNSUPPORTED, CAPACITY, WORKSPACE = -1, -2, -3, -4
+
+    def cache(B=2, Hkv=2, G=128, T_cap=128, S_cap=64, T_len=0, **ptr):
+        c = akvq_cache(B, Hkv, G, T_cap, S_cap, T_len, P, P, P, P, P, P, P, P)
+        for k, v in ptr.items():
+            setattr(c, k, v)
+        return c
+
+    big = 1 << 30
+    # ---- write path
+    q = L.akvq_quantize_append
+    assert q(C.byref(cache(T_len=120)), P, P, 9, 0.8, 0, None) == CAPACITY
+    assert q(C.byref(cache()), P, P, 0, 0.8, 0, None) == INVALID                 # no rows
+    assert q(C.byref(cache()), P + 2, P, 4, 0.8, 0, None) == INVALID             # misaligned input
+    assert q(C.byref(cache()), P, P, 4, 0.0, 0, None) == INVALID                 # clip outside (0, 1]
+    assert q(C.byref(cache()), P, P, 4, 1.5, 0, None) == INVALID
+    assert q(C.byref(cache(G=32)), P, P, 4, 0.8, 0, None) == UNSUPPORTED
+    assert q(C.byref(cache(k_codes=None)), P, P, 4, 0.8, 0, None) == INVALID
+    qt = L.akvq_quantize_append_tiered
+    win = akvq_window(P, P, 96)                                                  # not a multiple of 64
+    assert qt(C.byref(cache()), P, P, 4, None, None, 4, 0.8, 1.0, None, C.byref(win), 0, None) == INVALID
+    win = akvq_window(None, P, 64)
+    assert qt(C.byref(cache()), P, P, 4, None, None, 4, 0.8, 1.0, None, C.byref(win), 0, None) == INVALID
+    assert qt(C.byref(cache()), P, P, 4, None, None, 4, 0.8, 1.5, None, None, 0, None) == INVALID   # 4-bit clip
+    assert qt(C.byref(cache(T_len=100)), P, P, 4, P, P, 40, 0.8, 1.0, P, None, 0, None) == CAPACITY
+    # ---- read path
+    d = L.akvq_decode_attention
+    assert d(C.byref(cache(T_len=0)), P, 2, 0.1, P, None, 1, P, big, 0, None) == INVALID            # empty cache
+    assert d(C.byref(cache(T_len=5)), P, 3, 0.1, P, None, 1, P, big, 0, None) == INVALID            # Hq % Hkv
+    assert d(C.byref(cache(T_len=5)), P, 18, 0.1, P, None, 1, P, big, 0, None) == UNSUPPORTED       # 9 heads per KV head
+    assert d(C.byref(cache(T_len=5)), P, 2, 0.1, P, None, 2000, P, big, 0, None) == INVALID         # too many splits
+    assert d(C.byref(cache(T_len=5)), P, 2, 0.1, P, None, 4, P, 64, 0, None) == WORKSPACE
+    assert d(C.byref(cache(T_len=5)), P, 2, 0.1, P, None, 4, None, big, 0, None) == INVALID
+    assert d(C.byref(cache(T_len=5)), P, 2, 0.1, P, P + 4, 1, P, big, 0, None) == INVALID           # misaligned lse
+    dt = L.akvq_decode_attention_tiered
+    assert dt(C.byref(cache(T_len=5)), P + 4, None, P, 2, 0.1, P, None, 1, P, big, 0, None) == INVALID
+    win = akvq_window(P, P, 0)
+    assert dt(C.byref(cache(T_len=5)), None, C.byref(win), P, 2, 0.1, P, None, 1, P, big, 0, None) == INVALID
+    # ---- selection
+    s = L.akvq_select_salient
+    assert s(C.byref(cache()), 0, None, None, 2, None, 64, 0, 0, 0.0, None, None, 0, None) == INVALID      # no mask
+    assert s(C.byref(cache()), 7, P, P, 2, P, 64, 16, 4, 0.1, None, P, big, None) == INVALID               # unknown mode
+    assert s(C.byref(cache()), 1, None, P, 2, P, 200, 16, 4, 0.1, None, P, big, None) == INVALID           # T > T_cap
+    assert s(C.byref(cache()), 1, None, P, 2, P, 64, 24, 4, 0.1, None, P, big, None) == UNSUPPORTED        # W % 16
+    assert s(C.byref(cache()), 1, None, P, 2, P, 128, 128, 4, 0.1, None, P, big, None) == UNSUPPORTED      # W > 64
+    assert s(C.byref(cache()), 1, None, P, 2, P, 64, 16, 65, 0.1, None, P, big, None) == CAPACITY
+    assert s(C.byref(cache()), 1, None, P, 2, P, 64, 16, 4, 0.1, None, P, 16, None) == WORKSPACE
+    assert s(C.byref(cache()), 1, None, P, 2, P, 8, 16, 4, 0.1, None, P, big, None) == INVALID             # W > T
+    m = L.akvq_select_massive
+    assert m(C.byref(cache()), P, 64, 1000, 4, 0.0, None, P, big, None) == UNSUPPORTED                     # d_model % 512
+    assert m(C.byref(cache()), P, 64, 1024, 65, 0.0, None, P, big, None) == CAPACITY
+    assert m(C.byref(cache()), P, 64, 1024, 4, -1.0, None, P, big, None) == INVALID
+    assert m(C.byref(cache()), P, 64, 1024, 4, float("nan"), None, P, big, None) == INVALID
+    assert m(C.byref(cache()), P, 64, 1024, 4, 0.0, None, P, 16, None) == WORKSPACE
+    assert m(C.byref(cache()), P, 64, 1024, 4, 0.0, None, None, 0, None) == INVALID
+    assert m(C.byref(cache()), P, 300, 1024, 4, 0.0, None, P, big, None) == INVALID                        # T > T_cap
+    # ---- offline fold
+    f = L.akvq_fold_hadamard
+    assert f(P, P, 4, 100, 1, None) == INVALID                                   # columns not in runs of 128
+    assert f(P, P + 4096, 100, 4, 0, None) == INVALID                            # rows not in runs of 128
+    assert f(P, P, 128, 4, 0, None) == INVALID                                   # row fold cannot run in place
+    assert f(P, P, 4, 128, 2, None) == INVALID
+    assert f(None, P, 4, 128, 1, None) == INVALID
+    for code in (0, -1, -2, -3, -4, -5):
+        assert len(L.akvq_strerror(code)) > 0
