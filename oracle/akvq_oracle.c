@@ -435,6 +435,38 @@ void orc_select_massive(orc_cache *c, const uint16_t *hidden, int T, int d_model
   }
 }
 
+/* ----------------------------------------------------------------------------------------
+ * Rotary position embedding in front of the rotation (Section III-C.2, Fig. 6: Q and K are rotated by H after RoPE).
+ * Convention of the LLaMA family the paper evaluates (RoFormer, Su et al. 2021, in its "rotate half" form): channel i
+ * pairs with channel i + 64, angle pos * theta_i:
+ *     out[i]      = x[i] * cos_i - x[i + 64] * sin_i
+ *     out[i + 64] = x[i + 64] * cos_i + x[i] * sin_i
+ * The caller supplies cos and sin as binary16 tables (what an fp16 model holds), one row of 64 per position.
+ * reading (the paper does not state the arithmetic): both products of binary16 numbers are exact in binary32; their
+ * sum or difference is rounded once to binary32 and then to binary16, the format in which the model hands K and q
+ * on.  Evaluated here in double (exact for these operands up to the one rounding that follows).
+ * x, out: [B][H][n][128]; cos, sin: [n][64], batch b at b * batch_stride (0: one table for every batch entry).
+ * ---------------------------------------------------------------------------------------- */
+void orc_rope_rows(const uint16_t *x, uint16_t *out, int B, int H, int n, const uint16_t *cos_t, const uint16_t *sin_t,
+                   long batch_stride) {
+  for (int b = 0; b < B; ++b)
+    for (int h = 0; h < H; ++h)
+      for (int r = 0; r < n; ++r) {
+        const uint16_t *xr = x + (((size_t)b * H + h) * n + r) * ORC_D;
+        uint16_t *o = out + (((size_t)b * H + h) * n + r) * ORC_D;
+        const uint16_t *cr = cos_t + (size_t)b * batch_stride + (size_t)r * 64;
+        const uint16_t *sr = sin_t + (size_t)b * batch_stride + (size_t)r * 64;
+        for (int i = 0; i < 64; ++i) {
+          const double lo = orc_half_to_float(xr[i]), hi = orc_half_to_float(xr[i + 64]);
+          const double c = orc_half_to_float(cr[i]), sn = orc_half_to_float(sr[i]);
+          const float a = (float)(lo * c - hi * sn);
+          const float bb = (float)(hi * c + lo * sn);
+          o[i] = orc_float_to_half_rne(a);
+          o[i + 64] = orc_float_to_half_rne(bb);
+        }
+      }
+}
+
 /* ------------------------------------------------------------------------------------------
  * Write path: rotate, quantize (Eq. 3-6), pack; salient rows also keep a bfloat16 copy.
  * Every row gets 2-bit codes and meta; a row listed in sal_idx additionally gets an overlay row at the

@@ -87,6 +87,11 @@ void orc_fold_hadamard(const uint16_t *w, uint16_t *out, int rows, int cols, int
  * every kv-head.  score_out (optional) [B][T] fp64.  Writes sal_idx / sal_cnt. */
 void orc_select_massive(orc_cache *c, const uint16_t *hidden, int T, int d_model, int top_k, float floor_,
                         double *score_out);
+/* Rotary position embedding ("rotate half" pairing, channel i with i + 64) of rows x [B][H][n][128] binary16 with
+ * binary16 tables cos, sin [n][64] (batch b at b * batch_stride; 0 = shared); result rounded to binary16.  Runs in front
+ * of the write path (on K) and of decode (on q) when the caller hands over pre-RoPE tensors (Section III-C.2, Fig. 6). */
+void orc_rope_rows(const uint16_t *x, uint16_t *out, int B, int H, int n, const uint16_t *cos_t, const uint16_t *sin_t,
+                   long batch_stride);
 /* Which rotations a call applies.  The method is ORC_ROT_K | ORC_ROT_V on the write path and ORC_ROT_Q | ORC_ROT_OUT on
  * the read path; a cleared bit means the tensor is already in (or stays in) the rotated domain -- the offline fold of
  * Section III-C.2 clears ORC_ROT_V and ORC_ROT_OUT; all four cleared is plain round-to-nearest quantization without the

@@ -285,5 +285,20 @@ def fold_hadamard(w_f16, axis: int) -> np.ndarray:
     return out.view(np.float16)
 
 
+def rope_rows(x_f16, cos_f16, sin_f16) -> np.ndarray:
+    """Rotary position embedding (channel i pairs with i + 64) of x [B, H, n, 128] fp16 with fp16 tables cos, sin
+    [n, 64] (shared) or [B, n, 64]; rounded to fp16.  Applied to pre-RoPE K before the write path / q before decode."""
+    x = _u16(x_f16)
+    B, H, n, d = x.shape
+    assert d == D
+    cos, sin = _u16(cos_f16), _u16(sin_f16)
+    assert cos.shape == sin.shape and cos.shape[-2:] == (n, 64)
+    stride = n * 64 if cos.ndim == 3 else 0
+    assert cos.ndim == 2 or cos.shape[0] == B
+    out = np.zeros_like(x)
+    lib().orc_rope_rows(_p(x), _p(out), B, H, n, _p(cos), _p(sin), C.c_long(stride))
+    return out.view(np.float16)
+
+
 def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

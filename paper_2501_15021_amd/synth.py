@@ -207,3 +207,12 @@ def hidden_states(w: Workload, pivots, d_model: int = 4096, seed: int = BASE_SEE
     for b in range(w.B):
         h[b, pos[b], ch[0]] = 40.0
     return h.to(torch.float16)
+
+
+def rope_tables(positions, theta: float = 10000.0):
+    """cos / sin tables of a rotary position embedding as an fp16 model holds them: [..., 64] fp16 for integer positions
+    [...], angle pos * theta^(-i/64), i < 64 (inputs of the fused RoPE entry points; both sides read the same bits)."""
+    pos = np.asarray(positions, dtype=np.float64)
+    inv_freq = theta ** (-np.arange(64, dtype=np.float64) / 64.0)
+    ang = pos[..., None] * inv_freq
+    return np.cos(ang).astype(np.float16), np.sin(ang).astype(np.float16)
