@@ -115,11 +115,16 @@ def phase_bench(args, w, akvq, synth, torch, np):
         cache.sal_idx.copy_(torch.where(rows < (1 << 30), rows, torch.full_like(rows, -1)).int())
         cache.counts().copy_(ok.sum(-1).int())
 
+    rope = None
+    if args.rope:  # K rows are taken as pre-RoPE and embedded inside the write path (timing only: same bytes)
+        rope = tuple(torch.from_numpy(t).cuda() for t in synth.rope_tables(np.arange(w.T)))
+
     def append(d, cache):
         if tiered:
-            akvq.quantize_append_tiered(cache, d["k"], d["v"], tiered["row_src"], tiered["row_tier"], w.clip, 1.0)
-        elif args.window:
-            akvq.quantize_append_tiered(cache, d["k"], d["v"], None, None, w.clip, 1.0)
+            akvq.quantize_append_tiered(cache, d["k"], d["v"], tiered["row_src"], tiered["row_tier"], w.clip, 1.0,
+                                        rope=rope)
+        elif args.window or rope:
+            akvq.quantize_append_tiered(cache, d["k"], d["v"], None, None, w.clip, 1.0, rope=rope)
         else:
             akvq.quantize_append(cache, d["k"], d["v"], w.clip)
 
@@ -167,7 +172,7 @@ def phase_bench(args, w, akvq, synth, torch, np):
         nbytes += w.B * w.Hkv * args.window * (512 - per_row if args.phase == "decode" else 512)
     gbps = nbytes / (ms * 1e-3) / 1e9
     out = {"metric": f"{args.phase} call alone" + (" (4-bit text tier as row pairs)" if tiered else ""),
-           "cache_rows": tiered["n_rows"] if tiered else w.T, "recent_window": args.window, "workload": w.name, "layer_mode": w.mode(layer), "ms_per_call": round(ms, 5),
+           "cache_rows": tiered["n_rows"] if tiered else w.T, "recent_window": args.window, "fused_rope": bool(args.rope), "workload": w.name, "layer_mode": w.mode(layer), "ms_per_call": round(ms, 5),
            "kv_tokens_per_s": w.B * w.T / (ms * 1e-3), "n_sets": n_sets, "calls": n_calls,
            "n_split": args.n_split or akvq.lib().akvq_decode_default_splits(w.B, w.Hkv, w.T),
            "roofline": {"bound": "hbm", "achieved": round(gbps, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
@@ -307,6 +312,8 @@ def main():
                     help="--phase decode|quantize with a 16-bit recent window of this many rows (multiple of 64)")
     ap.add_argument("--tiered", action="store_true",
                     help="--phase decode|quantize with the 4-bit text tier (text tokens as row pairs, pivots 16-bit)")
+    ap.add_argument("--rope", action="store_true",
+                    help="--phase quantize with the rotary position embedding fused into the write path")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
     ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "fold", "capacity", "ablation", "copy"],

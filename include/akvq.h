@@ -84,6 +84,18 @@ typedef struct akvq_window {
   int32_t W;
 } akvq_window;
 
+/* Rotary position embedding applied by the library in front of the rotation (Section III-C.2, Fig. 6: Q and K are
+ * rotated by H after RoPE), for callers that hand over pre-RoPE K rows / queries and save the separate pass.
+ * Pairing of the LLaMA family ("rotate half"): out[i] = x[i]*cos_i - x[i+64]*sin_i, out[i+64] = x[i+64]*cos_i +
+ * x[i]*sin_i, i < 64.  cos / sin: device, binary16 (the tables an fp16 model holds), one row of 64 per position, 16-byte
+ * aligned; batch element b reads its rows at b * batch_stride elements (0: one table for every batch element; else a
+ * multiple of 8).  Arithmetic: the two products are exact in fp32, their sum is rounded once to fp32 and then to
+ * binary16 (the format a separate RoPE pass would have stored); the rotation then starts from those binary16 values. */
+typedef struct akvq_rope {
+  const uint16_t *cos, *sin; /* device */
+  int64_t batch_stride;
+} akvq_rope;
+
 /* One layer's cache.  Plain data; every pointer is device memory owned by the caller (layout above).
  * T_len is the number of valid rows; the caller advances it after akvq_quantize_append. */
 typedef struct akvq_cache {
@@ -199,6 +211,22 @@ int akvq_quantize_append_tiered(const akvq_cache *c, const void *k_src, const vo
 int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win,
                                  const void *q, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
                                  void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
+
+/*
+ * akvq_quantize_append_rope / akvq_decode_attention_rope -- the tiered entry points with the rotary position embedding
+ *   fused in front of the rotation (Section III-C.2, Fig. 6).  k_src holds pre-RoPE rows; source token s of batch
+ *   element b uses table row s (rope->cos/sin hold n_src rows per batch element).  q holds pre-RoPE queries; batch
+ *   element b uses table row 0 of its table (one position per decode step).  V and everything else as in the tiered
+ *   entry points; rope == NULL makes them identical to those.  AKVQ_K_PREROTATED / AKVQ_Q_PREROTATED cannot be
+ *   combined with a table (the embedding precedes the rotation): AKVQ_ERR_INVALID_ARG.
+ */
+int akvq_quantize_append_rope(const akvq_cache *c, const void *k_src, const void *v_src, int n_src,
+                              const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2, float clip4,
+                              uint32_t *fine_mask, const akvq_window *win, const akvq_rope *rope, uint32_t flags,
+                              void *stream);
+int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
+                               const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                               void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 
 #ifdef __cplusplus
 }

@@ -22,7 +22,8 @@ V_PREROTATED, OUT_ROTATED, K_PREROTATED, Q_PREROTATED = 1, 2, 4, 8
 EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
            "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention",
-           "akvq_quantize_append_tiered", "akvq_decode_attention_tiered",
+           "akvq_quantize_append_tiered", "akvq_decode_attention_tiered", "akvq_quantize_append_rope",
+           "akvq_decode_attention_rope",
            "akvq_massive_workspace_bytes", "akvq_select_massive", "akvq_fold_hadamard"]
 TIER_2BIT, TIER_4BIT_COARSE, TIER_4BIT_FINE, TIER_PAD = 0, 1, 2, 3
 
@@ -33,6 +34,10 @@ class AkvqError(RuntimeError):
 
 class akvq_window(C.Structure):
     _fields_ = [("k_win", C.c_void_p), ("v_win", C.c_void_p), ("W", C.c_int32)]
+
+
+class akvq_rope(C.Structure):
+    _fields_ = [("cos", C.c_void_p), ("sin", C.c_void_p), ("batch_stride", C.c_int64)]
 
 
 class akvq_cache(C.Structure):
@@ -90,8 +95,25 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention_tiered.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.POINTER(akvq_window),
                                                    C.c_void_p, C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_int,
                                                    C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+        L.akvq_quantize_append_rope.restype = C.c_int
+        L.akvq_quantize_append_rope.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
+                                                C.c_void_p, C.c_int, C.c_float, C.c_float, C.c_void_p,
+                                                C.POINTER(akvq_window), C.POINTER(akvq_rope), C.c_uint32, C.c_void_p]
+        L.akvq_decode_attention_rope.restype = C.c_int
+        L.akvq_decode_attention_rope.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.POINTER(akvq_window), C.c_void_p,
+                                                 C.POINTER(akvq_rope), C.c_int, C.c_float, C.c_void_p, C.c_void_p,
+                                                 C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         _lib = L
     return _lib
+
+
+def _rope_struct(rope, B: int, n: int):
+    """(cos, sin) fp16 tensors [n, 64] (one table for the batch) or [B, n, 64] -> akvq_rope (tensors stay referenced)."""
+    cos, sin = rope
+    assert cos.dtype == torch.float16 and sin.dtype == torch.float16 and cos.is_contiguous() and sin.is_contiguous()
+    assert cos.shape == sin.shape and tuple(cos.shape[-2:]) == (n, 64)
+    assert cos.dim() == 2 or (cos.dim() == 3 and cos.shape[0] == B)
+    return akvq_rope(cos.data_ptr(), sin.data_ptr(), n * 64 if cos.dim() == 3 else 0)
 
 
 def _check(status: int, what: str):
@@ -224,9 +246,10 @@ def quantize_append(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, clip
 
 
 def quantize_append_tiered(cache: Cache, k_src: torch.Tensor, v_src: torch.Tensor, row_src: torch.Tensor,
-                           row_tier: torch.Tensor, clip2: float, clip4: float, flags: int = 0) -> None:
+                           row_tier: torch.Tensor, clip2: float, clip4: float, flags: int = 0, rope=None) -> None:
     """akvq_quantize_append_tiered: cache rows [T_len, T_len + n_rows) from source tokens row_src [B, n_rows] int32
-    with tiers row_tier [B, n_rows] uint8; keeps the fine-half mask in cache.fine_mask; advances cache.T_len."""
+    with tiers row_tier [B, n_rows] uint8; keeps the fine-half mask in cache.fine_mask; advances cache.T_len.
+    rope = (cos, sin): k_src holds pre-RoPE rows (akvq_quantize_append_rope)."""
     assert k_src.dtype == torch.float16 and v_src.dtype == torch.float16
     assert k_src.is_contiguous() and v_src.is_contiguous() and k_src.shape == v_src.shape
     n_src = k_src.shape[2]
@@ -242,16 +265,24 @@ def quantize_append_tiered(cache: Cache, k_src: torch.Tensor, v_src: torch.Tenso
         mask = cache.fine_mask
     c = cache.struct()
     win = cache.window_struct()
-    _check(lib().akvq_quantize_append_tiered(C.byref(c), _ptr(k_src), _ptr(v_src), n_src, _ptr(row_src),
-                                             _ptr(row_tier), n_rows, clip2, clip4, _ptr(mask),
-                                             C.byref(win) if win else None, flags, _stream()),
-           "akvq_quantize_append_tiered")
+    if rope is not None:
+        rs = _rope_struct(rope, cache.B, n_src)
+        _check(lib().akvq_quantize_append_rope(C.byref(c), _ptr(k_src), _ptr(v_src), n_src, _ptr(row_src),
+                                               _ptr(row_tier), n_rows, clip2, clip4, _ptr(mask),
+                                               C.byref(win) if win else None, C.byref(rs), flags, _stream()),
+               "akvq_quantize_append_rope")
+    else:
+        _check(lib().akvq_quantize_append_tiered(C.byref(c), _ptr(k_src), _ptr(v_src), n_src, _ptr(row_src),
+                                                 _ptr(row_tier), n_rows, clip2, clip4, _ptr(mask),
+                                                 C.byref(win) if win else None, flags, _stream()),
+               "akvq_quantize_append_tiered")
     cache.T_len += n_rows
 
 
 def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: int = 0, flags: int = 0,
-                     out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None):
-    """akvq_decode_attention: returns (out [B,Hq,128] fp32, lse [B,Hq] fp32)."""
+                     out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None, rope=None):
+    """akvq_decode_attention: returns (out [B,Hq,128] fp32, lse [B,Hq] fp32).
+    rope = (cos, sin) [1, 64] or [B, 1, 64]: q holds pre-RoPE queries (akvq_decode_attention_rope)."""
     assert q.dtype == torch.float16 and q.is_contiguous()
     B, Hq, _ = q.shape
     if n_split <= 0:
@@ -262,6 +293,13 @@ def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: in
     if lse is None:
         lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
     c = cache.struct()
+    if rope is not None:
+        win = cache.window_struct()
+        rs = _rope_struct(rope, B, 1)
+        _check(lib().akvq_decode_attention_rope(C.byref(c), _ptr(cache.fine_mask), C.byref(win) if win else None,
+                                                _ptr(q), C.byref(rs), Hq, sm_scale, _ptr(out), _ptr(lse), n_split,
+                                                _ptr(ws), ws.numel(), flags, _stream()), "akvq_decode_attention_rope")
+        return out, lse
     if cache.fine_mask is not None or cache.W:
         win = cache.window_struct()
         _check(lib().akvq_decode_attention_tiered(C.byref(c), _ptr(cache.fine_mask), C.byref(win) if win else None,

@@ -177,10 +177,21 @@ static int check_window(const akvq_window *win) {
   return AKVQ_OK;
 }
 
+static int check_rope(const akvq_rope *rope, uint32_t prerotated) {
+  if (!rope) return AKVQ_OK;
+  if (prerotated) return AKVQ_ERR_INVALID_ARG;  // the embedding precedes the rotation
+  if (!rope->cos || !rope->sin || !aligned16(rope->cos) || !aligned16(rope->sin)) return AKVQ_ERR_INVALID_ARG;
+  if (rope->batch_stride < 0 || rope->batch_stride % 8 != 0) return AKVQ_ERR_INVALID_ARG;
+  return AKVQ_OK;
+}
+
 static int quantize_common(const akvq_cache *c, const void *k_new, const void *v_new, int n_src, int n_new,
                            float clip, float clip4, const int32_t *row_src, const uint8_t *row_tier,
-                           uint32_t *fine_mask, const akvq_window *win, uint32_t flags, void *stream) {
-  int st = check_cache_shape(c);
+                           uint32_t *fine_mask, const akvq_window *win, const akvq_rope *rope, uint32_t flags,
+                           void *stream) {
+  int st = check_rope(rope, flags & AKVQ_K_PREROTATED);
+  if (st != AKVQ_OK) return st;
+  st = check_cache_shape(c);
   if (st != AKVQ_OK) return st;
   st = check_cache_pointers(c);
   if (st != AKVQ_OK) return st;
@@ -192,6 +203,7 @@ static int quantize_common(const akvq_cache *c, const void *k_new, const void *v
   st = check_window(win);
   if (st != AKVQ_OK) return st;
   if (win) { a.k_win = win->k_win; a.v_win = win->v_win; a.win_len = win->W; }
+  if (rope) { a.rope_cos = rope->cos; a.rope_sin = rope->sin; a.rope_stride = rope->batch_stride; }
   a.k_new = static_cast<const uint16_t *>(k_new);
   a.v_new = static_cast<const uint16_t *>(v_new);
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
@@ -207,33 +219,51 @@ static int quantize_common(const akvq_cache *c, const void *k_new, const void *v
 
 int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_new, int n_new, float clip,
                          uint32_t flags, void *stream) {
-  return quantize_common(c, k_new, v_new, n_new, n_new, clip, 1.0f, nullptr, nullptr, nullptr, nullptr, flags, stream);
+  return quantize_common(c, k_new, v_new, n_new, n_new, clip, 1.0f, nullptr, nullptr, nullptr, nullptr, nullptr, flags,
+                         stream);
 }
 
 int akvq_quantize_append_tiered(const akvq_cache *c, const void *k_src, const void *v_src, int n_src,
                                 const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2,
                                 float clip4, uint32_t *fine_mask, const akvq_window *win, uint32_t flags,
                                 void *stream) {
+  return akvq_quantize_append_rope(c, k_src, v_src, n_src, row_src, row_tier, n_rows, clip2, clip4, fine_mask, win,
+                                   nullptr, flags, stream);
+}
+
+int akvq_quantize_append_rope(const akvq_cache *c, const void *k_src, const void *v_src, int n_src,
+                              const int32_t *row_src, const uint8_t *row_tier, int n_rows, float clip2, float clip4,
+                              uint32_t *fine_mask, const akvq_window *win, const akvq_rope *rope, uint32_t flags,
+                              void *stream) {
   const bool mapped = row_src || row_tier || fine_mask;  // all three or none
   if (mapped && (!row_src || !row_tier || !fine_mask || !aligned16(row_src) || !aligned16(row_tier) ||
                  !aligned16(fine_mask)))
     return AKVQ_ERR_INVALID_ARG;
   if (!mapped && n_rows != n_src) return AKVQ_ERR_INVALID_ARG;
-  return quantize_common(c, k_src, v_src, n_src, n_rows, clip2, clip4, row_src, row_tier, fine_mask, win, flags,
+  return quantize_common(c, k_src, v_src, n_src, n_rows, clip2, clip4, row_src, row_tier, fine_mask, win, rope, flags,
                          stream);
 }
 
 int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
                           int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
-  return akvq_decode_attention_tiered(c, nullptr, nullptr, q, Hq, sm_scale, out, lse_out, n_split, workspace,
-                                      workspace_bytes, flags, stream);
+  return akvq_decode_attention_rope(c, nullptr, nullptr, q, nullptr, Hq, sm_scale, out, lse_out, n_split, workspace,
+                                    workspace_bytes, flags, stream);
 }
 
 int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win,
                                  const void *q, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
                                  void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
+  return akvq_decode_attention_rope(c, fine_mask, win, q, nullptr, Hq, sm_scale, out, lse_out, n_split, workspace,
+                                    workspace_bytes, flags, stream);
+}
+
+int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
+                               const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                               void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
   if (fine_mask && !aligned16(fine_mask)) return AKVQ_ERR_INVALID_ARG;
-  int st = check_window(win);
+  int st = check_rope(rope, flags & AKVQ_Q_PREROTATED);
+  if (st != AKVQ_OK) return st;
+  st = check_window(win);
   if (st != AKVQ_OK) return st;
   st = check_cache_shape(c);
   if (st != AKVQ_OK) return st;
@@ -262,6 +292,7 @@ int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask,
   a.out = out; a.lse = lse_out;
   a.B = c->B; a.Hq = Hq; a.Hkv = c->Hkv; a.T_cap = c->T_cap; a.S_cap = c->S_cap; a.T_len = c->T_len;
   a.n_split = n_split; a.sm_scale = sm_scale;
+  if (rope) { a.rope_cos = rope->cos; a.rope_sin = rope->sin; a.rope_stride = rope->batch_stride; }
   a.q_rotated = (flags & AKVQ_Q_PREROTATED) ? 1 : 0;
   a.out_rotated = (flags & AKVQ_OUT_ROTATED) ? 1 : 0;
   return hip_status(akvq::launch_decode_attention(a, c->G, static_cast<hipStream_t>(stream)));

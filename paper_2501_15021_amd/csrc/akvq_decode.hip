@@ -36,8 +36,19 @@ __device__ __forceinline__ void wht128_wave(float &x0, float &x1, int lane) {
   x1 = d * inv_sqrt128();
 }
 // rotate a query row inside one wavefront (unless it arrives rotated) and leave it in LDS (the caller synchronises before other waves read it)
-__device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *qf, bool q_rotated, int lane) {
+// A pre-RoPE query (cos_row != null) first takes its rotary position embedding: channel i pairs with i + 64, both held
+// by this lane; exact fp32 products, one rounding of their sum to fp32, then to binary16 (kept apart by the barrier).
+__device__ __forceinline__ void rotate_query_lds(const uint16_t *q_row, float *qf, bool q_rotated,
+                                                 const uint16_t *cos_row, const uint16_t *sin_row, int lane) {
   float x0 = half_bits_to_float(q_row[lane]), x1 = half_bits_to_float(q_row[lane + 64]);
+  if (cos_row != nullptr) {
+    const float c = half_bits_to_float(cos_row[lane]), sn = half_bits_to_float(sin_row[lane]);
+    float r0 = __fmaf_rn(x0, c, -__fmul_rn(x1, sn)), r1 = __fmaf_rn(x1, c, __fmul_rn(x0, sn));
+    asm("" : "+v"(r0));
+    asm("" : "+v"(r1));
+    x0 = half_bits_to_float(float_to_half_bits_rne(r0));
+    x1 = half_bits_to_float(float_to_half_bits_rne(r1));
+  }
   if (!q_rotated) wht128_wave(x0, x1, lane);
   qf[lane] = x0;
   qf[lane + 64] = x1;
@@ -205,7 +216,9 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
 
   if (tid < 64) zero16[tid] = 0;
   if (tid < kD) { q_digit[3][tid] = 0; q_plain[3][tid] = 0; }
-  if (wave == 0) rotate_query_lds(a.q + (size_t)bh * kD, qf, a.q_rotated != 0, lane);
+  if (wave == 0) rotate_query_lds(a.q + (size_t)bh * kD, qf, a.q_rotated != 0,
+                                  a.rope_cos ? a.rope_cos + (size_t)(bh / a.Hkv) * a.rope_stride : nullptr,
+                                  a.rope_sin ? a.rope_sin + (size_t)(bh / a.Hkv) * a.rope_stride : nullptr, lane);
   __syncthreads();
   // fixed-point unit of the query: U = 2^ceil(log2 max|q~|) / 2^20 (the digits then cover it exactly, 21 bits)
   float q_unit_inv;
@@ -554,7 +567,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 
   for (int x = tid; x < 16 * kD; x += 64 * kWaves) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
   for (int x = lane; x < NG * 16 * kTokBlock; x += 64) (&w_lds[0][0][0])[x] = 0;
-  for (int h = wave; h < R; h += kWaves) rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf[h], a.q_rotated != 0, lane);
+  for (int h = wave; h < R; h += kWaves) rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf[h], a.q_rotated != 0,
+                     a.rope_cos ? a.rope_cos + (size_t)b * a.rope_stride : nullptr,
+                     a.rope_sin ? a.rope_sin + (size_t)b * a.rope_stride : nullptr, lane);
   __syncthreads();
   // sm_scale * log2(e) is folded into the staged queries (and through them into the bias and group sums), so the
   // products already are base-2 logits

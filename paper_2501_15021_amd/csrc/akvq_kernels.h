@@ -24,6 +24,8 @@ struct QuantArgs {
   float clip4;
   uint16_t *k_win, *v_win;  // recent-window rings (null: none)
   int win_len;
+  const uint16_t *rope_cos, *rope_sin;  // rotary tables for pre-RoPE K rows (null: rows arrive embedded), [n_src][64] binary16
+  long long rope_stride;                // elements between the tables of consecutive batch elements
 };
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream);
 
@@ -42,6 +44,8 @@ struct DecodeArgs {
   int B, Hq, Hkv, T_cap, S_cap, T_len, n_split;
   float sm_scale;
   int q_rotated, out_rotated;
+  const uint16_t *rope_cos, *rope_sin;  // rotary tables for pre-RoPE queries (null: none), one row of 64 per batch element
+  long long rope_stride;
 };
 constexpr int kPartialStride = 132;  // m, l, 2 pad, 128 accumulators
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream);

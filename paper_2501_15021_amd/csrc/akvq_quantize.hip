@@ -104,6 +104,39 @@ __device__ __forceinline__ void wht128_quad(const u32x4 (&raw)[4], float (&u)[4]
         }
 }
 
+// Rotary position embedding of one row held as raw[m] (see wht128_quad): channel e pairs with e + 64, i.e. raw[mm] with
+// raw[mm + 2] word by word, both in this lane; cw / sw hold the binary16 cos / sin of channels 32*mm + 8*j .. + 7.
+// Both products are exact in fp32 and the multiply-add rounds their sum once; the result is then rounded to binary16.
+// The mixed-precision instructions read the binary16 halves in place (HI selects the upper half of every word); being
+// assembly, they also keep the compiler from merging the two roundings into one.
+template <int HI>
+__device__ __forceinline__ float rope_mix(uint32_t x, uint32_t c, uint32_t xp, uint32_t sn, bool subtract) {
+  float t, r;
+  const float neg_zero = -0.0f;  // product + (-0) is the product itself, signed zeros included
+  if (HI) asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(t) : "v"(xp), "v"(sn), "v"(neg_zero));
+  else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,1,0]" : "=v"(t) : "v"(xp), "v"(sn), "v"(neg_zero));
+  if (subtract) {
+    if (HI) asm("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(r) : "v"(x), "v"(c), "v"(t));
+    else asm("v_fma_mix_f32 %0, %1, %2, -%3 op_sel:[0,0,0] op_sel_hi:[1,1,0]" : "=v"(r) : "v"(x), "v"(c), "v"(t));
+  } else {
+    if (HI) asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,1,0] op_sel_hi:[1,1,0]" : "=v"(r) : "v"(x), "v"(c), "v"(t));
+    else asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,1,0]" : "=v"(r) : "v"(x), "v"(c), "v"(t));
+  }
+  return r;
+}
+__device__ __forceinline__ void rope_row_quad(u32x4 (&raw)[4], const u32x4 (&cw)[2], const u32x4 (&sw)[2]) {
+#pragma unroll
+  for (int mm = 0; mm < 2; ++mm)
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const uint32_t lo = raw[mm][w], hi = raw[mm + 2][w], c = cw[mm][w], sn = sw[mm][w];
+      raw[mm][w] = float_to_half_bits_rne(rope_mix<0>(lo, c, hi, sn, true)) |
+                   (float_to_half_bits_rne(rope_mix<1>(lo, c, hi, sn, true)) << 16);
+      raw[mm + 2][w] = float_to_half_bits_rne(rope_mix<0>(hi, c, lo, sn, false)) |
+                       (float_to_half_bits_rne(rope_mix<1>(hi, c, lo, sn, false)) << 16);
+    }
+}
+
 struct GroupQ {
   uint32_t meta;      // scale bits | zero << 16 (salient flag added by the caller)
   float rcpu;         // kappa / scale
@@ -179,7 +212,8 @@ constexpr uint32_t kPack4Bias = (uint32_t)(0x4B400000ull * 0x01010101ull);    //
 // TIERED: rows carry a tier and a source-row index (akvq_quantize_append_tiered); the plain instantiation is the
 // two-bit path with identity row mapping and none of the per-row tier arithmetic.
 // WINDOW: the last win_len appended rows also go to the recent-window rings.
-template <int G, bool TIERED, bool WINDOW>
+// ROPE: K rows arrive without their rotary position embedding; it is applied here, in front of the rotation.
+template <int G, bool TIERED, bool WINDOW, bool ROPE>
 __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   __shared__ int slot_of_lds[4][kTokBlock];
   __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[WINDOW ? 4 : 1][WINDOW ? 1024 : 4];  // half a V ring tile per wavefront
@@ -217,6 +251,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   bool valid[2];
   int tier[2] = {AKVQ_TIER_2BIT, AKVQ_TIER_2BIT};
   u32x4 raw[2][4];
+  u32x4 rope_c[ROPE ? 2 : 1][2], rope_s[ROPE ? 2 : 1][2];
 #pragma unroll
   for (int h = 0; h < 2; ++h) {
     const int t = t0 + 16 * h + r;
@@ -232,6 +267,16 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
     const uint16_t *row = src + ((size_t)bh * a.n_src + src_row) * kD;
 #pragma unroll
     for (int m = 0; m < 4; ++m) raw[h][m] = *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j);
+    if constexpr (ROPE) {
+      if (tensor == 0) {
+        const size_t at = (size_t)(bh / a.Hkv) * a.rope_stride + (size_t)src_row * 64 + 8 * j;
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+          rope_c[h][mm] = *reinterpret_cast<const u32x4 *>(a.rope_cos + at + 32 * mm);
+          rope_s[h][mm] = *reinterpret_cast<const u32x4 *>(a.rope_sin + at + 32 * mm);
+        }
+      }
+    }
   }
   if constexpr (TIERED) {
     // fine-half mask of this block (one word per batch element): lane L < 32 looks at row t0 + L
@@ -280,6 +325,9 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
     slots[h] = slot_of[16 * h + r];
     if (TIERED && tier[h] != AKVQ_TIER_2BIT) slots[h] = -1;  // only plain rows can be salient
     float u[4][8];  // lane_sign times the (rotated) row
+    if constexpr (ROPE) {
+      if (tensor == 0) rope_row_quad(raw[h], rope_c[h], rope_s[h]);
+    }
     if (rotate) {
       wht128_quad(raw[h], u, j);
     } else {
@@ -533,14 +581,19 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 static void launch_blocks(const QuantArgs &a, int B, int G, bool window, hipStream_t stream) {
   dim3 grid((a.n_blk + 3) / 4, B * a.Hkv, 2), block(256);
   const bool tiered = a.row_tier != nullptr;
-#define AKVQ_LAUNCH_Q(GG, TT, WW) hipLaunchKernelGGL((quantize_append_kernel<GG, TT, WW>), grid, block, 0, stream, a)
+  const bool rope = a.rope_cos != nullptr;
+#define AKVQ_LAUNCH_Q(GG, TT, WW, RR) \
+  hipLaunchKernelGGL((quantize_append_kernel<GG, TT, WW, RR>), grid, block, 0, stream, a)
+#define AKVQ_LAUNCH_QR(GG, TT, WW) \
+  do { if (rope) AKVQ_LAUNCH_Q(GG, TT, WW, true); else AKVQ_LAUNCH_Q(GG, TT, WW, false); } while (0)
   if (G == 128) {
-    if (tiered) { if (window) AKVQ_LAUNCH_Q(128, true, true); else AKVQ_LAUNCH_Q(128, true, false); }
-    else { if (window) AKVQ_LAUNCH_Q(128, false, true); else AKVQ_LAUNCH_Q(128, false, false); }
+    if (tiered) { if (window) AKVQ_LAUNCH_QR(128, true, true); else AKVQ_LAUNCH_QR(128, true, false); }
+    else { if (window) AKVQ_LAUNCH_QR(128, false, true); else AKVQ_LAUNCH_QR(128, false, false); }
   } else {
-    if (tiered) { if (window) AKVQ_LAUNCH_Q(64, true, true); else AKVQ_LAUNCH_Q(64, true, false); }
-    else { if (window) AKVQ_LAUNCH_Q(64, false, true); else AKVQ_LAUNCH_Q(64, false, false); }
+    if (tiered) { if (window) AKVQ_LAUNCH_QR(64, true, true); else AKVQ_LAUNCH_QR(64, true, false); }
+    else { if (window) AKVQ_LAUNCH_QR(64, false, true); else AKVQ_LAUNCH_QR(64, false, false); }
   }
+#undef AKVQ_LAUNCH_QR
 #undef AKVQ_LAUNCH_Q
 }
 

@@ -121,6 +121,17 @@ def test_every_error_code_of_every_entry_point(L):
     assert m(C.byref(cache()), P, 64, 1024, 4, 0.0, None, P, 16, None) == WORKSPACE
     assert m(C.byref(cache()), P, 64, 1024, 4, 0.0, None, None, 0, None) == INVALID
     assert m(C.byref(cache()), P, 300, 1024, 4, 0.0, None, P, big, None) == INVALID                        # T > T_cap
+    # ---- fused rotary position embedding
+    from paper_2501_15021_amd.binding import akvq_rope
+    qr, dr = L.akvq_quantize_append_rope, L.akvq_decode_attention_rope
+    ok, odd, nul = akvq_rope(P, P, 0), akvq_rope(P, P, 12), akvq_rope(P, None, 0)
+    assert qr(C.byref(cache()), P, P, 4, None, None, 4, 0.8, 1.0, None, None, C.byref(ok), 4, None) == INVALID   # K pre-rotated
+    assert qr(C.byref(cache()), P, P, 4, None, None, 4, 0.8, 1.0, None, None, C.byref(odd), 0, None) == INVALID  # stride % 8
+    assert qr(C.byref(cache()), P, P, 4, None, None, 4, 0.8, 1.0, None, None, C.byref(nul), 0, None) == INVALID
+    assert qr(C.byref(cache(T_len=126)), P, P, 4, None, None, 4, 0.8, 1.0, None, None, C.byref(ok), 0, None) == CAPACITY
+    assert dr(C.byref(cache(T_len=5)), None, None, P, C.byref(ok), 2, 0.1, P, None, 1, P, big, 8, None) == INVALID  # q pre-rotated
+    assert dr(C.byref(cache(T_len=5)), None, None, P, C.byref(nul), 2, 0.1, P, None, 1, P, big, 0, None) == INVALID
+    assert dr(C.byref(cache(T_len=5)), None, None, P, C.byref(ok), 2, 0.1, P, None, 4, P, 64, 0, None) == WORKSPACE
     # ---- offline fold
     f = L.akvq_fold_hadamard
     assert f(P, P, 4, 100, 1, None) == INVALID                                   # columns not in runs of 128
