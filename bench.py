@@ -267,6 +267,69 @@ def capacity_bench(args, w, akvq, synth, torch, np):
                       "throughput_ratio_vs_that_bound": round(r2["decode_tokens_per_s_attention_only"] / ideal16, 3)}))
 
 
+def decode_step_bench(args, w, akvq, synth, torch, np):
+    """One generated token through the cache of every layer: per layer, append the new token's K and V (rotary
+    embedding fused in) and run decode attention over the cache.  Launch-bound at small batch; --graph replays the
+    whole step as one HIP graph (the library allocates nothing and records no memset, so it can be captured)."""
+    L = args.layers or w.n_layers
+    t_cap = (w.T + 64) // 64 * 64
+    caches, qs, news = [], [], []
+    rope_all = tuple(torch.from_numpy(t).cuda() for t in synth.rope_tables(np.arange(w.T)))
+    rope_new = tuple(torch.from_numpy(t).cuda() for t in synth.rope_tables(np.array([w.T])))
+    for layer in range(L):
+        d = synth.generate(w, layer=layer, device="cuda")
+        c = akvq.Cache(w.B, w.Hkv, w.G, t_cap, w.s_cap(layer))
+        if w.mode(layer) == "tsa":
+            akvq.select_salient(c, akvq.MODE_TSA, is_text=d["is_text"])
+        else:
+            akvq.select_salient(c, akvq.MODE_PSA, q_tail=d["q_tail"], k=d["k"], top_k=w.top_k, sm_scale=w.sm_scale)
+        akvq.quantize_append_tiered(c, d["k"], d["v"], None, None, w.clip, 1.0, rope=rope_all)
+        caches.append(c)
+        qs.append(d["q"])
+        news.append((d["k"][:, :, :1].contiguous(), d["v"][:, :, :1].contiguous()))
+        del d
+    out = torch.empty(w.B, w.Hq, 128, device="cuda")
+    lse = torch.empty(w.B, w.Hq, device="cuda")
+
+    def step():
+        for c, q, (k1, v1) in zip(caches, qs, news):
+            c.T_len = w.T
+            akvq.quantize_append_tiered(c, k1, v1, None, None, w.clip, 1.0, rope=rope_new)
+            akvq.decode_attention(c, q, w.sm_scale, out=out, lse=lse, rope=rope_new)
+
+    for _ in range(max(args.warmup, 1)):
+        step()
+    torch.cuda.synchronize()
+    run = step
+    if args.graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        run = graph.replay
+        run()
+        torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    per_row = 2 * (32 + 4 * (128 // w.G))
+    nbytes = sum(w.B * w.Hkv * ((w.T + 1 - min(w.s_cap(l), w.n_text if w.mode(l) == "tsa" else w.top_k)) * per_row
+                                + (w.n_text if w.mode(l) == "tsa" else w.top_k) * 512) for l in range(L))
+    print(json.dumps({"metric": "decode step over all layers (append one token + decode attention)",
+                      "workload": w.name, "layers": L, "batch": w.B, "context": w.T + 1, "hip_graph": bool(args.graph),
+                      "ms_per_step": round(ms, 4), "launches_per_step": 2 * L,
+                      "generated_tokens_per_s_attention_path": round(w.B / (ms * 1e-3), 1),
+                      "cache_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                      "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}))
+
+
 def ablation_bench(args, w, akvq, synth, torch, np):
     """Synthetic-data analogue of the paper's ablation (Section IV-C, Table III): error of the decode-attention output
     against exact attention over the unquantized K and V, with and without the rotation and the 16-bit salient tokens.
@@ -314,9 +377,10 @@ def main():
                     help="--phase decode|quantize with the 4-bit text tier (text tokens as row pairs, pivots 16-bit)")
     ap.add_argument("--rope", action="store_true",
                     help="--phase quantize with the rotary position embedding fused into the write path")
+    ap.add_argument("--graph", action="store_true", help="--phase decode_step replayed as one HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
-    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "fold", "capacity", "ablation", "copy"],
+    ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "fold", "capacity", "ablation", "decode_step", "copy"],
                     help="time one call only (per-kernel studies; the default 'all' is the benchmark line)")
     ap.add_argument("--sets", type=int, default=0, help="distinct buffer sets to rotate through in --phase runs")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (sweeps)")
@@ -382,6 +446,8 @@ def main():
                                        "frac": round(gbps / HBM_PEAK_GBPS, 4), "traffic": None,
                                        "algorithmic_bytes_per_launch": nbytes}}))
         return
+    if args.phase == "decode_step":
+        return decode_step_bench(args, w, akvq, synth, torch, np)
     if args.phase == "ablation":
         return ablation_bench(args, w, akvq, synth, torch, np)
     if args.phase == "capacity":

@@ -292,6 +292,19 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
     }
   }
 
+  // A block that is only partly new (a decode step appends one row) keeps the other tokens' bits of its V words: the
+  // words this lane will rewrite are requested now, with the rows, instead of after the arithmetic.
+  const size_t blk_word = ((size_t)bh * (a.T_cap / kTokBlock) + blk) * kBlockWords;
+  const bool partial_blk = t0 < a.T_len || t0 + kTokBlock > t_end;  // uniform over the wavefront
+  u32x2 v_old[2] = {{0u, 0u}, {0u, 0u}};
+  if (tensor == 1 && partial_blk) {
+    const int ii = r & 3, q = r >> 2;
+#pragma unroll
+    for (int c = 0; c < 2; ++c)
+      v_old[c] = *reinterpret_cast<const u32x2 *>(a.v_codes + blk_word + (size_t)(16 * q + 8 * (j & 1) + 2 * ii + c) * 4 +
+                                                  2 * (j >> 1));
+  }
+
   if (lane < kTokBlock) slot_of[lane] = -1;
   wave_lds_sync();
   if (stride <= 1) {
@@ -517,7 +530,6 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
       }
   }
 
-  const size_t blk_word = ((size_t)bh * (a.T_cap / kTokBlock) + blk) * kBlockWords;
   if (tensor == 0) {
     // chunk 16*j + r: words {2h, 2h+1} belong to token half h
     uint32_t *chunk = a.k_codes + blk_word + (size_t)(16 * j + r) * 4;
@@ -565,15 +577,155 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
       for (int c = 0; c < 2; ++c) {
         uint32_t *dst = a.v_codes + blk_word + (size_t)(16 * q + 8 * (j & 1) + 2 * ii + c) * 4 + 2 * (j >> 1);
         uint32_t w0 = sel[c][0], w1 = sel[c][1];
-        if (mask != 0xFFFFFFFFu) {  // block only partly new: keep the other tokens' bits
-          w0 = (dst[0] & ~mask) | (w0 & mask);
-          w1 = (dst[1] & ~mask) | (w1 & mask);
+        if (mask != 0xFFFFFFFFu) {  // block only partly new: keep the other tokens' bits (read at the top)
+          w0 = (v_old[c][0] & ~mask) | (w0 & mask);
+          w1 = (v_old[c][1] & ~mask) | (w1 & mask);
         }
         u32x2 o = {w0, w1};
         *reinterpret_cast<u32x2 *>(dst) = o;
       }
     }
   }
+}
+
+// ------------------------------------------------------------------------------------------------
+// One new row per (batch, kv-head): the decode step.  The block kernel above spends a whole wavefront, and a few
+// thousand instructions fetched once, on a 32-token block that holds a single new token; here one wavefront owns one
+// row of one tensor: lane l holds channels l and l + 64, so the stride-64 butterfly (and the rotary pair) is inside
+// the lane and the other six strides are lane exchanges.  Same arithmetic as the block kernel: every butterfly is
+// (lower + upper, lower - upper) on the same pairs in the same stride order, so the stored bits are identical.
+// Codes are gathered through LDS into the words of the packed planes; V words (two codes of this token each, 64
+// words) and K words (16 codes each, 8 words) are read, merged and written back.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float xor_butterfly(float v, int s, int lane) {
+  const float p = __shfl_xor(v, s, kWave);
+  return (lane & s) ? (p - v) : (v + p);
+}
+__device__ __forceinline__ float wave_min_all(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+__device__ __forceinline__ float wave_max_all(float v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
+  return v;
+}
+
+template <int G>
+__global__ __launch_bounds__(64) void append_row_kernel(QuantArgs a) {
+  constexpr int NG = kD / G;
+  __shared__ __attribute__((aligned(16))) uint8_t code_lds[kD];
+  __shared__ __attribute__((aligned(16))) uint16_t row_lds[kD];
+  const int lane = threadIdx.x;
+  const int bh = blockIdx.x;
+  const int tensor = blockIdx.y;  // 0 = K, 1 = V
+  const int t = a.T_len;          // the row being written
+  const int blk = t / kTokBlock, half = (t % kTokBlock) >> 4, n16 = t & 15;
+  const bool rotate = (tensor == 0 ? a.rotate_k : a.rotate_v) != 0;
+  const float kappa = rotate ? inv_sqrt128() : 1.0f;
+
+  // everything that has to come from memory is requested first
+  const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+  int cnt = a.sal_cnt[bh];
+  const uint16_t *row = (tensor == 0 ? a.k_new : a.v_new) + (size_t)bh * kD;
+  float x0 = half_bits_to_float(row[lane]), x1 = half_bits_to_float(row[lane + 64]);
+  const size_t blk_word = ((size_t)bh * (a.T_cap / kTokBlock) + blk) * kBlockWords;
+  uint32_t *v_word = a.v_codes + blk_word + 64 * (n16 >> 2) + lane;                       // tensor 1: lane's word
+  uint32_t *k_word = a.k_codes + blk_word + (size_t)(16 * (lane >> 1) + n16) * 4 + 2 * half + (lane & 1);  // lanes 0..7
+  uint32_t old_word = 0u;  // a V word also holds seven other tokens; a K word holds this token only
+  if (tensor == 1) old_word = *v_word;
+  if (tensor == 0 && a.rope_cos != nullptr) {
+    const size_t at = (size_t)(bh / a.Hkv) * a.rope_stride + lane;
+    const float c = half_bits_to_float(a.rope_cos[at]), sn = half_bits_to_float(a.rope_sin[at]);
+    float r0 = __fmaf_rn(x0, c, -__fmul_rn(x1, sn)), r1 = __fmaf_rn(x1, c, __fmul_rn(x0, sn));
+    asm("" : "+v"(r0));  // keeps the rounding to fp32 and the one to binary16 apart
+    asm("" : "+v"(r1));
+    x0 = half_bits_to_float(float_to_half_bits_rne(r0));
+    x1 = half_bits_to_float(float_to_half_bits_rne(r1));
+  }
+
+  // is the row listed as salient, and at which rank?
+  cnt = min(max(cnt, 0), a.S_cap);
+  int slot = -1;
+  for (int base = 0; base < cnt; base += kWave) {
+    const int e = base + lane < cnt ? sidx[base + lane] : -1;
+    const unsigned long long hit = __ballot(e == t);
+    if (hit != 0ull) slot = base + __builtin_ctzll(hit);
+  }
+
+  if (rotate) {
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      x0 = xor_butterfly(x0, s, lane);
+      x1 = xor_butterfly(x1, s, lane);
+    }
+    const float lo = x0 + x1, hi = x0 - x1;
+    x0 = lo;
+    x1 = hi;
+  }
+
+  GroupQ gq[2];
+  if constexpr (NG == 1) {
+    const float mn = wave_min_all(fminf(x0, x1)), mx = wave_max_all(fmaxf(x0, x1));
+    gq[0] = gq[1] = group_params(mn, mx, kappa, a.clip, tier_two_bit());
+  } else {
+    gq[0] = group_params(wave_min_all(x0), wave_max_all(x0), kappa, a.clip, tier_two_bit());
+    gq[1] = group_params(wave_min_all(x1), wave_max_all(x1), kappa, a.clip, tier_two_bit());
+  }
+  const uint32_t c0 = code_bits(x0, gq[0]) & 3u, c1 = code_bits(x1, gq[1]) & 3u;
+  code_lds[lane] = (uint8_t)c0;
+  code_lds[lane + 64] = (uint8_t)c1;
+  const uint32_t y0 = pack_bf16x2(__fmul_rn(x0, kappa), 0.0f) & 0xFFFFu, y1 = pack_bf16x2(__fmul_rn(x1, kappa), 0.0f) & 0xFFFFu;
+  row_lds[lane] = (uint16_t)y0;
+  row_lds[lane + 64] = (uint16_t)y1;
+  wave_lds_sync();
+
+  if (lane == 0) {
+    uint32_t *meta = (tensor == 0 ? a.k_meta : a.v_meta) + ((size_t)bh * a.T_cap + t) * NG;
+    meta[0] = gq[0].meta | (slot >= 0 ? 0x8000u : 0u);
+    if constexpr (NG == 2) meta[1] = gq[1].meta | (slot >= 0 ? 0x8000u : 0u);
+  }
+
+  if (tensor == 0) {
+    if (lane < 8) {
+      // word (j, mh) = lane (j = lane / 2, mh = lane % 2): slot 8*ml + i holds channel 64*mh + 32*ml + 8*j + i
+      const int j = lane >> 1, mh = lane & 1;
+      uint32_t word = 0u;
+#pragma unroll
+      for (int ml = 0; ml < 2; ++ml) {
+        const u32x2 eight = *reinterpret_cast<const u32x2 *>(&code_lds[64 * mh + 32 * ml + 8 * j]);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+          word |= ((eight[i >> 2] >> (8 * (i & 3))) & 3u) << (2 * (8 * ml + i));
+      }
+      *k_word = word;  // the word holds this token's codes only
+    }
+  } else {
+    // word lane: n = lane / 4, nb = (lane / 2) % 2 + 2 * XY + 4 * (lane % 2); XY = 0, 1 sit 8 bits apart
+    const int n = lane >> 2, nb_lo = ((lane >> 1) & 1) + 4 * (lane & 1);
+    const uint32_t cx = code_lds[16 * nb_lo + n], cy = code_lds[16 * (nb_lo + 2) + n];
+    const int bit = 16 * half + 2 * (n16 & 3);
+    const uint32_t mask = (3u << bit) | (3u << (bit + 8));
+    *v_word = (old_word & ~mask) | (cx << bit) | (cy << (bit + 8));
+  }
+
+  // 16-bit copies: overlay slot of a salient row, ring slot of the recent window (the new row is always inside it)
+  auto store_row16 = [&](uint16_t *k_rows, uint16_t *v_plane, int s16) {
+    if (tensor == 0) {
+      reinterpret_cast<uint32_t *>(k_rows + (size_t)s16 * kD)[lane] = reinterpret_cast<const uint32_t *>(row_lds)[lane];
+    } else {
+      const int sb = s16 >> 5, sh = (s16 & 31) >> 4, sr = s16 & 15, sq = sr >> 2, sii = sr & 3;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int e = lane + 64 * k, nb = e >> 4, n = e & 15;
+        v_plane[(size_t)sb * 4096 + nb * 512 + (16 * sq + n) * 8 + 2 * sii + sh] = (uint16_t)(k == 0 ? y0 : y1);
+      }
+    }
+  };
+  if (slot >= 0) store_row16(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, slot);
+  if (a.win_len > 0)
+    store_row16(a.k_win + (size_t)bh * a.win_len * kD, a.v_win + (size_t)bh * a.win_len * kD, t % a.win_len);
 }
 
 }  // namespace
@@ -598,6 +750,12 @@ static void launch_blocks(const QuantArgs &a, int B, int G, bool window, hipStre
 }
 
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream) {
+  if (a.n_new == 1 && a.n_src == 1 && a.row_tier == nullptr) {  // the decode step: one plain row per (batch, kv-head)
+    dim3 grid(B * a.Hkv, 2), block(64);
+    if (G == 128) hipLaunchKernelGGL(append_row_kernel<128>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(append_row_kernel<64>, grid, block, 0, stream, a);
+    return hipGetLastError();
+  }
   if (a.win_len <= 0) {
     launch_blocks(a, B, G, false, stream);
     return hipGetLastError();

@@ -392,6 +392,28 @@ def test_decode_then_append_then_decode(orc):
     assert_cache_equal(oc, gc, "after decode steps")
 
 
+@pytest.mark.parametrize("G,flags", [(128, 0), (64, 0), (128, akvq.V_PREROTATED), (64, akvq.K_PREROTATED | akvq.V_PREROTATED)])
+def test_single_row_appends(orc, G, flags):
+    """The decode step's append (one row per (batch, kv-head)) over 45 consecutive positions across block boundaries,
+    some of the new rows listed as salient beforehand; the cache is compared bit for bit after every row."""
+    w = synth.small(f"one{G}", B=2, Hq=3, Hkv=3, T=90, G=G, n_text_head=7, n_text_tail=4, top_k=5, W=16)
+    d = _np(synth.generate(w, seed=151))
+    T0 = 45
+    oc, gc = make_pair(orc, w, t_cap=128, s_cap=64)
+    listed = np.array([3, 17, 44, 45, 46, 63, 64, 70, 89], dtype=np.int32)     # rows before and after the prefill end
+    oc.sal_idx[:, :, :len(listed)] = listed
+    oc.sal_cnt[:] = len(listed)
+    copy_salient_to_gpu(oc, gc)
+    rk, rv = not (flags & akvq.K_PREROTATED), not (flags & akvq.V_PREROTATED)
+    oc.quantize_append(d["k"][:, :, :T0], d["v"][:, :, :T0], w.clip, rotate_v=rv, rotate_k=rk)
+    akvq.quantize_append(gc, _dev(d["k"][:, :, :T0]), _dev(d["v"][:, :, :T0]), w.clip, flags=flags)
+    for t in range(T0, w.T):
+        k1, v1 = d["k"][:, :, t:t + 1], d["v"][:, :, t:t + 1]
+        oc.quantize_append(k1, v1, w.clip, rotate_v=rv, rotate_k=rk)
+        akvq.quantize_append(gc, _dev(k1), _dev(v1), w.clip, flags=flags)
+        assert_cache_equal(oc, gc, f"after row {t}")
+
+
 # ------------------------------------------------------------------------------------------- error paths (no launch)
 def test_argument_errors():
     L = akvq.lib()
