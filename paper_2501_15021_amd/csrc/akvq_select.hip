@@ -116,7 +116,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // pass 1: per (b, hq, chunk): running max and sum of exponentials (base 2) of every tail row
 template <int NRB>
-__global__ __launch_bounds__(256) void psa_row_stats_kernel(SelectArgs a) {
+__global__ __launch_bounds__(256, 4) void psa_row_stats_kernel(SelectArgs a) {  // 4 wavefronts per SIMD: at most 128 registers
   __shared__ float st_m[4][64], st_l[4][64];
   const int chunk = blockIdx.x, bhq = blockIdx.y;
   const int b = bhq / a.Hq, hq = bhq % a.Hq, hkv = hq / (a.Hq / a.Hkv);
