@@ -22,10 +22,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E, published
+ALU_PEAK_GLANEOPS = 256 * 64 * 2.4   # fp32 vector lane-operations per ns without packed fp32 (= 78.6 TFLOP/s as FMAs)
 # HBM bytes per launch counted by rocprofv3 (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, factors from a 1 GiB copy),
 # mean over the 32 layers of cfg2; the runs and the raw figures are in profiles/bench_cfg2_kernel_trace.md.
 # Reported as roofline.traffic for that workload only; other workloads report null.
-MEASURED_TRAFFIC_CFG2 = {"quantize": 1253893530, "select": 1127269786, "decode": 168239104}
+MEASURED_TRAFFIC_CFG2 = {"quantize": 1253567283, "select": 1127683277, "decode": 168192000}
 METRIC = "decode-attn KV tokens/s/GPU + achieved HBM GB/s (% peak); quantize GB/s"
 
 
@@ -548,6 +549,15 @@ def main():
         "decode": roof("decode", dec_bytes, tot["decode"], "decode_mha_kernel/decode_gqa_kernel (+combine)"),
         "quantize": roof("quantize", q_bytes, tot["quantize"], "quantize_append_kernel"),
     }
+    # quantize_append is bound by vector-instruction issue, not by HBM (counters: vector unit busy 97 % of the kernel):
+    # the same launch against the vector peak without packed fp32 (256 CUs x 64 lanes x 2.4 GHz lane-operations/s),
+    # counting the method's arithmetic only: per element 7 butterflies, one min/max step, three for the code
+    # (multiply-add to an integer, clamp, pack).
+    q_lane_ops = 11 * 2 * w.B * w.Hkv * w.T * 128 * L
+    q_alu = q_lane_ops / (tot["quantize"] * 1e-3) / 1e9
+    rooflines["quantize"]["alu"] = {"bound": "alu", "achieved": round(q_alu, 1), "peak": ALU_PEAK_GLANEOPS,
+                                    "unit": "G lane-op/s", "frac": round(q_alu / ALU_PEAK_GLANEOPS, 4),
+                                    "algorithmic_lane_ops_per_launch": q_lane_ops // L}
     if sel_bytes:
         rooflines["select"] = roof("select", sel_bytes, tot["select"], "psa_row_stats_kernel+psa_mass_kernel(+topk)")
     dominant = max(("decode", "quantize", "select"), key=lambda n: tot[n])
@@ -556,7 +566,7 @@ def main():
         "value": kv_tokens / (tot["decode"] * 1e-3),
         "unit": "KV tokens/s (decode attention; whole-path and quantize rates in 'extra')",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u2 codes; int8 and bf16 MFMA; f32 accumulate",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u2 codes; int8, bf16 and f16 MFMA; f32 accumulate",
         "data": "synthetic (seeded; LLaVA-1.5-shaped prompt layout, outlier channels and pivot tokens planted)",
         "config": {"workload": f"{w.name}: {L} layers x B={w.B} x Hq={w.Hq}/Hkv={w.Hkv} x T={w.T}, G={w.G}, "
                                f"TSA layers {list(w.tsa_layers)}, PSA top-{w.top_k}, clip {w.clip}",
