@@ -218,7 +218,7 @@ __global__ __launch_bounds__(256, 4) void psa_row_stats_kernel(SelectArgs a) {  
 
 // pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads and the tail rows of 2^(s - m_row) / l_row
 template <int NRB>
-__global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
+__global__ __launch_bounds__(256, 4) void psa_mass_kernel(SelectArgs a) {  // registers and LDS sized for 4 workgroups per CU
   __shared__ __attribute__((aligned(16))) float row_m[64], row_il[64];
   __shared__ u32x4 q_lds[NRB * 4 * 64];
   const int chunk = blockIdx.x, bh = blockIdx.y;
@@ -227,10 +227,11 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
   const uint16_t *k_rows = a.k + (size_t)bh * a.T * kD;
   const float scale2 = a.sm_scale * kLog2e;
   const int t_wave = chunk * kScoreChunk + wave * (kScoreChunk / 4);
-  // column sums of the chunk, one slot per (row quarter qd, key): every slot has a single owning lane, so the sums
-  // over key groups and over the heads of the group are plain read-add-write in a fixed order
-  __shared__ float col_lds[4 * kScoreChunk];
-  for (int i = threadIdx.x; i < 4 * kScoreChunk; i += 256) col_lds[i] = 0.0f;
+  // column sums of the chunk, one slot per (pair of row quarters, key): the two quarters of a pair are added across
+  // lanes first, every slot then has a single owning lane, so the sums over key groups and over the heads of the
+  // group are plain read-add-write in a fixed order
+  __shared__ float col_lds[2 * kScoreChunk];
+  for (int i = threadIdx.x; i < 2 * kScoreChunk; i += 256) col_lds[i] = 0.0f;
   for (int h = 0; h < R; ++h) {
     const int bhq = b * a.Hq + hkv * R + h;
     KeyGroup ring[kKeyDepth + 1];  // first keys requested before the row statistics and query rows are staged
@@ -289,16 +290,19 @@ __global__ __launch_bounds__(256) void psa_mass_kernel(SelectArgs a) {
               c = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[i])), ril[i], c);
         }
       }
-      float *slot = col_lds + qd * kScoreChunk + (t_first - chunk * kScoreChunk) + mrow;
-      *slot += c0 + c1;
+      float c = c0 + c1;
+      c += __shfl_xor(c, 16, kWave);  // quarters qd and qd ^ 1
+      if ((qd & 1) == 0) {
+        float *slot = col_lds + (qd >> 1) * kScoreChunk + (t_first - chunk * kScoreChunk) + mrow;
+        *slot += c;
+      }
     }
   }
   __syncthreads();
   for (int i = threadIdx.x; i < kScoreChunk; i += 256) {
     const int t = chunk * kScoreChunk + i;
     if (t < a.T)
-      a.mass[(size_t)bh * a.T + t] =
-          (col_lds[i] + col_lds[kScoreChunk + i]) + (col_lds[2 * kScoreChunk + i] + col_lds[3 * kScoreChunk + i]);
+      a.mass[(size_t)bh * a.T + t] = col_lds[i] + col_lds[kScoreChunk + i];
   }
 }
 
