@@ -161,9 +161,12 @@ void orc_quantize_row_bits(const uint16_t *x_f16, int G, float clip, int rotate,
     memcpy(u, xf, sizeof(u));
     kappa = 1.0f;
   }
-  /* the rotated row y = u * kappa; salient rows keep it as bfloat16 (Section III-C.1: salient tokens stay 16-bit) */
+  /* the rotated row y = u * kappa; salient rows keep it as bfloat16 (Section III-C.1: salient tokens stay 16-bit).
+   * reading: a zero is stored as +0.  The sign of a zero carries no information for attention, and an implementation
+   * is free to hold intermediate butterfly values negated (b - a for a - b), which loses it. */
   for (int e = 0; e < ORC_D; ++e) {
     volatile float y = u[e] * kappa;
+    if (y == 0.0f) y = 0.0f;
     y_bf16[e] = orc_float_to_bf16_rne(y);
   }
   const float third = bits_to_float(n_bits == 2 ? ORC_ONE_THIRD_BITS : ORC_ONE_FIFTEENTH_BITS);

@@ -244,3 +244,18 @@ def test_wht_reduces_2bit_error_on_outlier_keys(orc):
         e_raw += np.sum((row.astype(np.float64) - _dequant(c, sb, z, 128)) ** 2)
         n += np.sum(row.astype(np.float64) ** 2)
     assert e_rot < 0.9 * e_raw and e_raw < n
+
+
+def test_stored_16bit_rows_hold_positive_zeros(orc):
+    """Zeros of the rotated row are stored as +0 whatever their IEEE sign: a row of -0 inputs (every butterfly sum is
+    -0), a row whose pairs cancel exactly (+0 from x - x), and an un-rotated row that already holds -0."""
+    neg_zero = np.full(D, -0.0, dtype=np.float16)
+    _, _, _, ybf = orc.quantize_row(neg_zero, 128, 0.8)
+    assert np.all(ybf == 0)                           # bit pattern 0x0000, not 0x8000
+    x = np.zeros(D, dtype=np.float16)
+    x[0], x[1] = 1.5, 1.5                             # stride-1 difference is exactly zero -> many exact zeros
+    _, _, _, ybf = orc.quantize_row(x, 128, 0.8)
+    y = orc.bf16_bits_to_f64(ybf)
+    assert np.count_nonzero(y == 0) == 64 and np.all(ybf[y == 0] == 0)
+    _, _, _, ybf = orc.quantize_row(neg_zero, 64, 1.0, rotate=False)
+    assert np.all(ybf == 0)
