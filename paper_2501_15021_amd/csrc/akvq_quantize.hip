@@ -137,6 +137,10 @@ __device__ __forceinline__ void rope_row_quad(u32x4 (&raw)[4], const u32x4 (&cw)
     }
 }
 
+// value of a stored 16-bit row before its conversion: u * scale rounded once, with a zero product stored as +0
+// (lanes that hold negated butterfly values cannot know the sign of a zero; x * y + (+0) is +0 for either sign)
+__device__ __forceinline__ float scaled_row_value(float u, float scale) { return __fmaf_rn(u, scale, 0.0f); }
+
 struct GroupQ {
   uint32_t meta;      // scale bits | zero << 16 (salient flag added by the caller)
   float rcpu;         // kappa / scale
@@ -364,7 +368,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           u32x4 o;
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            o[w] = token ? pack_bf16x2(__fmul_rn(u[m][2 * w], scale), __fmul_rn(u[m][2 * w + 1], scale)) : 0u;
+            o[w] = token ? pack_bf16x2(scaled_row_value(u[m][2 * w], scale), scaled_row_value(u[m][2 * w + 1], scale)) : 0u;
           *reinterpret_cast<u32x4 *>(dst + 32 * m + 8 * j) = o;
         }
       } else {
@@ -375,7 +379,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           for (int i = 0; i < 8; ++i) {
             const int e = 32 * m + 8 * j + i, nb = e >> 4, n = e & 15;
             v_plane[(size_t)sb * 4096 + nb * 512 + (16 * sq + n) * 8 + 2 * sii + sh] =
-                token ? (uint16_t)pack_bf16x2(__fmul_rn(u[m][i], scale), 0.0f) : (uint16_t)0;
+                token ? (uint16_t)pack_bf16x2(scaled_row_value(u[m][i], scale), 0.0f) : (uint16_t)0;
           }
       }
     };
@@ -396,7 +400,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
         for (int m = 0; m < 4; ++m)
 #pragma unroll
           for (int w = 0; w < 4; ++w)
-            pk[4 * m + w] = token ? pack_bf16x2(__fmul_rn(u[m][2 * w], kappa_s), __fmul_rn(u[m][2 * w + 1], kappa_s)) : 0u;
+            pk[4 * m + w] = token ? pack_bf16x2(scaled_row_value(u[m][2 * w], kappa_s), scaled_row_value(u[m][2 * w + 1], kappa_s)) : 0u;
         if (h == 0) {
 #pragma unroll
           for (int x = 0; x < 16; ++x) vwin_h0[x] = pk[x];
@@ -676,7 +680,7 @@ __global__ __launch_bounds__(64) void append_row_kernel(QuantArgs a) {
   const uint32_t c0 = code_bits(x0, gq[0]) & 3u, c1 = code_bits(x1, gq[1]) & 3u;
   code_lds[lane] = (uint8_t)c0;
   code_lds[lane + 64] = (uint8_t)c1;
-  const uint32_t y0 = pack_bf16x2(__fmul_rn(x0, kappa), 0.0f) & 0xFFFFu, y1 = pack_bf16x2(__fmul_rn(x1, kappa), 0.0f) & 0xFFFFu;
+  const uint32_t y0 = pack_bf16x2(scaled_row_value(x0, kappa), 0.0f) & 0xFFFFu, y1 = pack_bf16x2(scaled_row_value(x1, kappa), 0.0f) & 0xFFFFu;
   row_lds[lane] = (uint16_t)y0;
   row_lds[lane + 64] = (uint16_t)y1;
   wave_lds_sync();
