@@ -43,7 +43,7 @@ def _one_case(orc, case):
     Hq = Hkv * R
     B = int(rng.integers(1, 4))
     G = int(rng.choice([64, 128]))
-    T = int(rng.integers(3, 260))
+    T = int(rng.integers(3, 260)) if case % 5 else int(rng.integers(260, 700))
     n_head = int(rng.integers(1, max(2, min(20, T - 2))))
     n_tail = int(rng.integers(1, max(2, min(12, T - n_head))))
     W_score = 16
@@ -133,7 +133,7 @@ def _one_case(orc, case):
         assert np.abs(lse.cpu().numpy() - lse_ref).max() <= 2e-3, what
 
 
-@pytest.mark.parametrize("block", range(6))
+@pytest.mark.parametrize("block", range(12))
 def test_random_configurations(orc, block):
     for case in range(block * 8, block * 8 + 8):
         _one_case(orc, case)
