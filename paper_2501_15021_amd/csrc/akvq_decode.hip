@@ -260,8 +260,8 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   }
 
   // ---- A operands for the code stream, per token group g: row 4g+digit carries that digit, other rows are zero.
-  // They stay in LDS (two 128-bit reads per product) instead of 32 registers: the kernel then fits four
-  // wavefronts per SIMD, which is what keeps enough loads in flight.
+  // They stay in LDS (two 128-bit reads per product) instead of 32 registers: the kernel then fits three
+  // wavefronts per SIMD instead of two, which is what keeps enough loads in flight.
   uint32_t a_off[4];  // byte offset of this lane's operand row inside q_digit, per token group
 #pragma unroll
   for (int g = 0; g < 4; ++g) {
