@@ -47,3 +47,12 @@ def test_massive_cfg2_shape(orc):
     oc = _compare(orc, w, hid, 15, 100.0, 4096)
     for b in range(w.B):
         assert sorted(set(int(x) for x in d["pivots"][b])) == oc.sal_idx[b, 0, :oc.sal_cnt[b, 0]].tolist()
+
+
+def test_massive_longer_than_the_staged_topk(orc):
+    """More than 32768 tokens: the top-k reads the scores from memory instead of LDS."""
+    w = synth.small("ma_long", B=2, Hq=2, Hkv=2, T=40001, n_text_head=20, n_text_tail=11)
+    piv = np.array([[0, 5, 33000, 40000], [0, 17, 32768, 39999]])
+    hid = synth.hidden_states(w, piv, d_model=512, seed=77)
+    oc = _compare(orc, w, hid, 15, 100.0, 40064)
+    assert set(piv[0]) <= set(oc.sal_idx[0, 0, :int(oc.sal_cnt[0, 0])].tolist())

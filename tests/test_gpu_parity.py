@@ -252,6 +252,15 @@ def test_select_psa_small(orc):
     check_psa(orc, w, d, 8)
 
 
+def test_select_psa_longer_than_the_staged_topk(orc):
+    """More than 32768 keys: 17 score chunks per head and the top-k that reads its keys from memory instead of LDS;
+    top_k above the short-list limit takes the general ordering path as well."""
+    w = synth.small("psa_long", B=1, Hq=2, Hkv=1, T=33111, W=16, top_k=12, n_text_head=40, n_text_tail=31)
+    d = _np(synth.generate(w, seed=161))
+    check_psa(orc, w, d, 12)
+    check_psa(orc, w, d, 300)
+
+
 def test_select_psa_cfg1(orc):
     w = synth.WORKLOADS["cfg1"]
     d = _np(synth.generate(w))
@@ -323,6 +332,15 @@ def test_decode_gqa_small(orc, Hq, Hkv, G, mode):
     w = synth.small(f"dgqa{Hq}_{Hkv}", B=2, Hq=Hq, Hkv=Hkv, T=333, G=G, n_text_head=33, n_text_tail=12, top_k=9, W=16)
     d = _np(synth.generate(w, seed=109))
     run_decode_case(orc, w, d, mode, 9, n_splits=(1, 4, 5))
+
+
+@pytest.mark.parametrize("Hq,Hkv,G", [(1, 1, 128), (7, 1, 64)])
+def test_decode_long_context_small_batch(orc, Hq, Hkv, G):
+    """33 thousand rows in one (batch, kv-head): more than a thousand tiles per workgroup without a split, and the
+    default and a large split count."""
+    w = synth.small(f"long{Hq}", B=1, Hq=Hq, Hkv=Hkv, T=33050, G=G, n_text_head=30, n_text_tail=21, top_k=5, W=16)
+    d = _np(synth.generate(w, seed=163))
+    run_decode_case(orc, w, d, "tsa", 5, n_splits=(1, 0, 37))
 
 
 def test_decode_rotated_output_flag(orc):
