@@ -168,3 +168,36 @@ def test_cfg2_tiered_window(orc):
 
 def test_cfg5_tiered_window_gqa(orc):
     _run_tiered(orc, "cfg5", 0, [(0, 0), (31, 3)], W=128)
+
+
+@pytest.mark.parametrize("Hq,G", [(8, 128), (16, 64)])
+def test_planes_larger_than_4_gib(Hq, G):
+    """Addressing beyond 32 bits: code planes of 4.8 GB each (300 x 8 kv-heads x 65536 rows).  64 rows are appended at
+    the end of the last batch elements' planes and decode runs over the whole length; a one-sequence cache holding the
+    same rows must give the same words and, with the same split, the same output bits."""
+    B, Hkv, T_cap = 300, 8, 65536
+    T0, n_new = T_cap - 64, 64
+    big = akvq.Cache(B, Hkv, G, T_cap, 64, fill=0)
+    assert big.k_codes.numel() * 4 > (1 << 32)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    k = torch.randn(B, Hkv, n_new, 128, generator=g, device="cuda").half()
+    v = torch.randn(B, Hkv, n_new, 128, generator=g, device="cuda").half()
+    q = torch.randn(B, Hq, 128, generator=g, device="cuda").half()
+    big.T_len = T0
+    big.sal_idx[:, :, 0] = T0 + 3                       # one of the new rows is kept 16-bit
+    big.counts().fill_(1)
+    akvq.quantize_append(big, k, v, 0.8)
+    out_big, lse_big = akvq.decode_attention(big, q, 0.0884, n_split=8)
+    torch.cuda.synchronize()
+    for b in (0, B - 1):
+        small = akvq.Cache(1, Hkv, G, T_cap, 64, fill=0)
+        small.T_len = T0
+        small.sal_idx[:, :, 0] = T0 + 3
+        small.counts().fill_(1)
+        akvq.quantize_append(small, k[b:b + 1].contiguous(), v[b:b + 1].contiguous(), 0.8)
+        out, lse = akvq.decode_attention(small, q[b:b + 1].contiguous(), 0.0884, n_split=8)
+        torch.cuda.synchronize()
+        for name in ("k_codes", "v_codes", "k_meta", "v_meta", "k_sal", "v_sal"):
+            assert torch.equal(getattr(big, name)[b], getattr(small, name)[0]), f"{name} of batch element {b}"
+        assert int(big.k_codes[b, -1, -2:].ne(0).sum()) > 0                # the appended blocks were written
+        assert torch.equal(out_big[b], out[0]) and torch.equal(lse_big[b], lse[0]), f"decode of batch element {b}"
