@@ -28,7 +28,8 @@
  *   k_meta, v_meta [B][Hkv][T_cap][128/G] uint32
  *       bits 0-14 scale (IEEE binary16, positive), bit 15 = row is salient (its 2-bit copy is ignored
  *       by decode), bits 16-31 zero-point (int16).  Dequantized value = scale * (code - zero)  (Eq. 4).
- *   k_sal [B][Hkv][S_cap][128] bfloat16: rotated salient rows, natural channel order.
+ *   k_sal [B][Hkv][S_cap][128] bfloat16: rotated salient rows, natural channel order (round to nearest even of the
+ *       fp32 value; a zero is stored as +0).
  *   v_sal [B][Hkv][S_cap/32][4096] bfloat16: rotated salient rows, tiled: slot s: blk=s/32,
  *       half=(s%32)/16, r=s%16, q=r/4, ii=r%4; channel e: nb=e/16, n=e%16;
  *       index = blk*4096 + nb*512 + (16*q+n)*8 + 2*ii + half.
