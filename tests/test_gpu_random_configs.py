@@ -137,3 +137,23 @@ def _one_case(orc, case):
 def test_random_configurations(orc, block):
     for case in range(block * 8, block * 8 + 8):
         _one_case(orc, case)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_pivot_selection(orc, block):
+    """Seeded draws for the attention-mass pivot selection: scoring rows 16..64, 1 to 8 query heads per kv-head,
+    context lengths around the 2048-key chunk and 16-key group boundaries, top-k from 1 to 64."""
+    from test_gpu_parity import check_psa
+    for case in range(block * 6, block * 6 + 6):
+        rng = np.random.default_rng(8100 + case)
+        Hkv = int(rng.integers(1, 3))
+        R = int(rng.choice([1, 2, 3, 7, 8]))
+        W = int(rng.choice([16, 32, 48, 64]))
+        T = int(rng.choice([W, W + 1, 2047, 2048, 2049, 4096 + 17, int(rng.integers(W, 3000))]))
+        top_k = int(min(T, rng.choice([1, 4, 16, 64])))
+        n_head = max(1, min(8, T // 4))
+        w = synth.small(f"psa_rnd{case}", B=int(rng.integers(1, 3)), Hq=Hkv * R, Hkv=Hkv, T=max(T, 3), W=W, top_k=top_k,
+                        n_text_head=n_head, n_text_tail=1)
+        print(f"case {case}: B={w.B} Hq={w.Hq} Hkv={Hkv} T={w.T} W={W} top_k={top_k}", flush=True)
+        d = {k: (v.numpy() if hasattr(v, "numpy") else v) for k, v in synth.generate(w, seed=950 + case).items()}
+        check_psa(orc, w, d, top_k)
