@@ -220,7 +220,7 @@ constexpr uint32_t kPack4Bias = (uint32_t)(0x4B400000ull * 0x01010101ull);    //
 template <int G, bool TIERED, bool WINDOW, bool ROPE>
 __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   __shared__ int slot_of_lds[4][kTokBlock];
-  __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[WINDOW ? 4 : 1][WINDOW ? 1024 : 4];  // half a V ring tile per wavefront
+  __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[WINDOW ? 4 : 1][WINDOW ? 2048 : 4];  // one V tile (32 slots x 128 channels, bf16) per wavefront
   const int wave = threadIdx.x >> 6;
   const int lane = threadIdx.x & 63;
   const int blk_rel = blockIdx.x * 4 + wave;
@@ -328,9 +328,20 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 
   // recent window: is this whole block new and inside the window?  (uniform over the wavefront)
   bool win_block = false;
-  uint32_t vwin_h0[16];
-  if constexpr (WINDOW)
+  // salient overlay: is this whole block new, salient, and does it fill one 32-slot tile of the V overlay exactly
+  // (slots s0 .. s0+31 with s0 a multiple of 32)?  Text runs in front of and between 576-token images do.
+  bool sal_block = false;
+  int sal_tile = 0;
+  if constexpr (WINDOW) {
     win_block = t0 >= a.T_len && t0 + kTokBlock <= t_end && t0 >= t_end - a.win_len;
+    if constexpr (!TIERED) {
+      const int s0 = slot_of[0];
+      const bool in_run = slot_of[lane & (kTokBlock - 1)] == s0 + (lane & (kTokBlock - 1));
+      sal_block = s0 >= 0 && (s0 & (kTokBlock - 1)) == 0 && t0 >= a.T_len && t0 + kTokBlock <= t_end &&
+                  __ballot(!in_run) == 0ull;
+      sal_tile = s0 >> 5;
+    }
+  }
   uint32_t kw[2][2];         // K words of token half h: [h][group-of-64 word]
   uint32_t vcode[2][8];      // V: [mpair][i]: raw patterns of (X, Y) x (half 0, half 1) in the four byte lanes
   uint32_t vmask_part = 0;
@@ -383,58 +394,50 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
           }
       }
     };
-    if (valid[h] && slots[h] >= 0)
+    if (valid[h] && slots[h] >= 0 && !(sal_block && tensor == 1))  // a tile-filling block stores its V tile below
       store_bf16_row(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, slots[h], true);
     if constexpr (WINDOW) {
       const int t = t0 + 16 * h + r;
       // fine halves and padding rows carry no token: their ring slots are zeroed
       const bool token = !TIERED || (tier[h] != AKVQ_TIER_4BIT_FINE && tier[h] != AKVQ_TIER_PAD);
-      if (win_block && tensor == 1) {
-        // The whole block lies in the window (the prefill case): its 32 rows fill one 32-slot tile of the V ring, in
-        // which the values of rows r and r+16 of one channel are neighbours.  This lane owns both rows, so it keeps
-        // the first half's values and assembles (row r, row r+16) pairs as 32-bit words of the tile in LDS, half a
-        // tile at a time; each half goes out as four fully coalesced 1 KB stores.  (Scattered partial-line stores, as in the row-at-a-time
-        // path below, are several times slower and would dominate the tail of a prefill launch.)
-        uint32_t pk[16];
+      if ((win_block || sal_block) && tensor == 1) {
+        // The whole block fills one 32-slot tile of the V ring (the prefill case) and / or of the salient overlay.  In a
+        // tile the values of rows r and r+16 of one channel are neighbours; this lane owns both rows and writes its 16-bit
+        // values into the wavefront's tile in LDS, half 0 and then half 1, and the finished tile goes out as eight fully
+        // coalesced 1 KB stores.  (Scattered partial-line stores, as in the row-at-a-time path, are several times slower
+        // and would dominate the tail of a prefill launch.)
+        uint16_t *tile16 = reinterpret_cast<uint16_t *>(vtile_lds[wave]);
+        const int sq = r >> 2, sii = r & 3;
 #pragma unroll
         for (int m = 0; m < 4; ++m)
 #pragma unroll
-          for (int w = 0; w < 4; ++w)
-            pk[4 * m + w] = token ? pack_bf16x2(scaled_row_value(u[m][2 * w], kappa_s), scaled_row_value(u[m][2 * w + 1], kappa_s)) : 0u;
-        if (h == 0) {
+          for (int w = 0; w < 4; ++w) {
+            const uint32_t pk = token ? pack_bf16x2(scaled_row_value(u[m][2 * w], kappa_s), scaled_row_value(u[m][2 * w + 1], kappa_s)) : 0u;
 #pragma unroll
-          for (int x = 0; x < 16; ++x) vwin_h0[x] = pk[x];
-        } else {
-          const int slot0 = t0 % a.win_len;  // multiple of 32
-          uint32_t *tile_out = reinterpret_cast<uint32_t *>(a.v_win + (size_t)bh * a.win_len * kD + (size_t)(slot0 >> 5) * 4096);
-          uint32_t *half_tile = vtile_lds[wave];  // half a tile (channel blocks 4*mh .. 4*mh+3) at a time
-          const int sq = r >> 2, sii = r & 3;
-#pragma unroll
-          for (int mh = 0; mh < 2; ++mh) {
-#pragma unroll
-            for (int m = 2 * mh; m < 2 * mh + 2; ++m)
-#pragma unroll
-              for (int w = 0; w < 4; ++w) {
-                const uint32_t a0 = vwin_h0[4 * m + w], a1 = pk[4 * m + w];   // channels (2w, 2w+1) of rows r, r+16
-                const uint32_t even = __builtin_amdgcn_perm(a1, a0, 0x05040100u);  // (row r, row r+16) of channel 2w
-                const uint32_t odd = __builtin_amdgcn_perm(a1, a0, 0x07060302u);   // ... of channel 2w+1
-#pragma unroll
-                for (int c = 0; c < 2; ++c) {
-                  const int e = 32 * m + 8 * j + 2 * w + c, nb = (e >> 4) - 4 * mh, n = e & 15;
-                  half_tile[(nb * 512 + (16 * sq + n) * 8 + 2 * sii) >> 1] = c == 0 ? even : odd;
-                }
-              }
-            wave_lds_sync();
-#pragma unroll
-            for (int x = 0; x < 4; ++x)
-              *reinterpret_cast<u32x4 *>(tile_out + 1024 * mh + 256 * x + 4 * lane) =
-                  *reinterpret_cast<const u32x4 *>(half_tile + 256 * x + 4 * lane);
-            wave_lds_sync();
+            for (int c = 0; c < 2; ++c) {
+              const int e = 32 * m + 8 * j + 2 * w + c, nb = e >> 4, n = e & 15;
+              tile16[nb * 512 + (16 * sq + n) * 8 + 2 * sii + h] = (uint16_t)(c == 0 ? pk : pk >> 16);
+            }
           }
+        if (h == 1) {
+          // the same tile goes to the ring (slot = row mod W, a multiple of 32 here) and / or to the salient overlay
+          uint32_t *ring_out = !win_block ? nullptr : reinterpret_cast<uint32_t *>(
+              a.v_win + (size_t)bh * a.win_len * kD + (size_t)((t0 % max(a.win_len, 1)) >> 5) * 4096);
+          uint32_t *sal_out = !sal_block ? nullptr : reinterpret_cast<uint32_t *>(
+              a.v_sal + (size_t)bh * a.S_cap * kD + (size_t)sal_tile * 4096);
+          wave_lds_sync();
+#pragma unroll
+          for (int x = 0; x < 8; ++x) {
+            const u32x4 piece = *reinterpret_cast<const u32x4 *>(vtile_lds[wave] + 256 * x + 4 * lane);
+            if (ring_out != nullptr) *reinterpret_cast<u32x4 *>(ring_out + 256 * x + 4 * lane) = piece;
+            if (sal_out != nullptr) *reinterpret_cast<u32x4 *>(sal_out + 256 * x + 4 * lane) = piece;
+          }
+          wave_lds_sync();
         }
-      } else if (valid[h] && t >= t_end - a.win_len) {
+      }
+      if (!(win_block && tensor == 1) && valid[h] && t >= t_end - a.win_len) {
         store_bf16_row(a.k_win + (size_t)bh * a.win_len * kD, a.v_win + (size_t)bh * a.win_len * kD,
-                       t % a.win_len, token);
+                       t % max(a.win_len, 1), token);
       }
     }
 
@@ -760,8 +763,11 @@ hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t 
     else hipLaunchKernelGGL(append_row_kernel<64>, grid, block, 0, stream, a);
     return hipGetLastError();
   }
+  // The instantiation with the tile path also stores salient V rows of tile-filling blocks as whole tiles: worth its
+  // extra registers when the salient lists are long (text-salient layers), not for a handful of pivots.
+  const bool dense_salient = a.S_cap > 64;
   if (a.win_len <= 0) {
-    launch_blocks(a, B, G, false, stream);
+    launch_blocks(a, B, G, dense_salient, stream);
     return hipGetLastError();
   }
   // Recent window: only the blocks that hold the last win_len new rows write ring slots.  A long append (prefill)
@@ -774,7 +780,7 @@ hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t 
     QuantArgs head = a;
     head.n_blk = win_first_blk - a.first_blk;
     head.win_len = 0;
-    launch_blocks(head, B, G, false, stream);
+    launch_blocks(head, B, G, dense_salient, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
