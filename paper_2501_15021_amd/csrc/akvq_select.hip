@@ -332,6 +332,7 @@ __device__ __forceinline__ int block_inclusive_scan(int v, int *wave_tot, int &t
 // STAGED: the row of keys is copied to LDS once and every pass reads it from there.
 constexpr int kTopkStageMax = 32768;  // keys (128 KB of LDS)
 constexpr int kTopkListMax = 256;     // selected positions ordered through LDS when k is at most this
+constexpr int kTopkCandMax = 512;     // candidates the short cut ranks among themselves
 template <bool STAGED>
 __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   extern __shared__ float keys_lds[];
@@ -341,15 +342,72 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   __shared__ int sh_need;
   __shared__ int list_n;
   __shared__ int list[kTopkListMax];
+  __shared__ uint32_t thread_max[256];
+  __shared__ int cand_n;
+  __shared__ uint32_t cand_key[kTopkCandMax];
+  __shared__ int cand_pos[kTopkCandMax];
   const int bh = blockIdx.x, lane = threadIdx.x & 63;
   const float *mass = a.mass + (size_t)(a.mass_per_batch ? bh / a.Hkv : bh) * a.T;
   int32_t *out = a.sal_idx + (size_t)bh * a.S_cap;
   const int k = min(a.top_k, a.T);
   const uint32_t lowest = a.skip_zero ? 1u : 0u;  // keys below this bit pattern (i.e. +0) are never selected
   if (STAGED) {
-    for (int t = threadIdx.x; t < a.T; t += 256) keys_lds[t] = mass[t];
-    if (threadIdx.x == 0) list_n = 0;
+    uint32_t mine = 0u;  // largest key this thread staged (bit patterns of non-negative floats order like the floats)
+    for (int t = threadIdx.x; t < a.T; t += 256) {
+      const float x = mass[t];
+      keys_lds[t] = x;
+      mine = max(mine, __float_as_uint(x));
+    }
+    if (threadIdx.x == 0) { list_n = 0; cand_n = 0; }
+    thread_max[threadIdx.x] = mine;
     __syncthreads();
+    if (k <= 128) {
+      // Short cut for the usual case (a few pivots out of thousands of keys): the k-th largest of the 256 per-thread
+      // maxima is a lower bound of the k-th largest key, and few keys reach it.  They are collected and ranked among
+      // themselves (key descending, position ascending: the order of the radix path).  Too many candidates (many equal
+      // keys): the radix passes below take over.  Every wavefront finds the bound for itself (four maxima per lane),
+      // bit by bit from the top: the largest x with at least k maxima >= x.
+      const uint32_t m0 = thread_max[lane], m1 = thread_max[lane + 64], m2 = thread_max[lane + 128],
+                     m3 = thread_max[lane + 192];
+      uint32_t bound = 0u;
+      for (int bit = 31; bit >= 0; --bit) {
+        const uint32_t cand = bound | (1u << bit);
+        const int n_ge = __popcll(__ballot(m0 >= cand)) + __popcll(__ballot(m1 >= cand)) +
+                         __popcll(__ballot(m2 >= cand)) + __popcll(__ballot(m3 >= cand));
+        if (n_ge >= k) bound = cand;
+      }
+      for (int t = threadIdx.x; t < a.T; t += 256) {
+        const uint32_t bits = __float_as_uint(keys_lds[t]);
+        if (bits >= bound && bits >= lowest) {
+          const int at = atomicAdd(&cand_n, 1);
+          if (at < kTopkCandMax) { cand_key[at] = bits; cand_pos[at] = t; }
+        }
+      }
+      __syncthreads();
+      const int n_cand = cand_n;
+      if (n_cand <= kTopkCandMax) {  // uniform
+        for (int c = threadIdx.x; c < n_cand; c += 256) {
+          const uint32_t key = cand_key[c];
+          const int pos = cand_pos[c];
+          int beaten_by = 0;
+          for (int j = 0; j < n_cand; ++j) beaten_by += (cand_key[j] > key) || (cand_key[j] == key && cand_pos[j] < pos);
+          if (beaten_by < k) list[atomicAdd(&list_n, 1)] = pos;
+        }
+        __syncthreads();
+        const int n_kept = list_n;  // k, or fewer when zero keys are excluded
+        if ((int)threadIdx.x < n_kept) {
+          const int mine_pos = list[threadIdx.x];
+          int rank = 0;
+          for (int j = 0; j < n_kept; ++j) rank += list[j] < mine_pos;
+          if (rank < a.S_cap) out[rank] = mine_pos;
+        }
+        if (threadIdx.x == 0) a.sal_cnt[bh] = n_kept;
+        return;
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) list_n = 0;
+      __syncthreads();
+    }
   }
   const float *keys = STAGED ? keys_lds : mass;
   uint32_t prefix = 0;

@@ -56,3 +56,19 @@ def test_massive_longer_than_the_staged_topk(orc):
     hid = synth.hidden_states(w, piv, d_model=512, seed=77)
     oc = _compare(orc, w, hid, 15, 100.0, 40064)
     assert set(piv[0]) <= set(oc.sal_idx[0, 0, :int(oc.sal_cnt[0, 0])].tolist())
+
+
+@pytest.mark.parametrize("T,top_k", [(2000, 15), (700, 64), (300, 60)])
+def test_massive_many_equal_scores(orc, T, top_k):
+    """Nearly all tokens share one score: far more candidates than the top-k short cut ranks among themselves, so the
+    radix passes take over; equal keys go to the lower positions."""
+    w = synth.small("ma_ties", B=2, Hq=2, Hkv=2, T=T, n_text_head=5, n_text_tail=3)
+    hid = torch.full((2, T, 512), 0.5, dtype=torch.float16)
+    hid[:, :, 7] = 3.0                       # every token's score is 3 ...
+    hid[0, 41, 100] = -9.0                   # ... except a few larger ones
+    hid[0, T - 1, 3] = 8.0
+    hid[1, 5, 511] = 3.5
+    oc = _compare(orc, w, hid, top_k, 0.0, (T + 63) // 64 * 64)
+    n = int(oc.sal_cnt[0, 0])
+    assert n == top_k and 41 in oc.sal_idx[0, 0, :n] and T - 1 in oc.sal_idx[0, 0, :n]
+    assert list(oc.sal_idx[1, 0, :top_k]) == list(range(top_k))       # 5 is among the first positions anyway
