@@ -26,7 +26,7 @@ ALU_PEAK_GLANEOPS = 256 * 64 * 2.4   # fp32 vector lane-operations per ns withou
 # HBM bytes per launch counted by rocprofv3 (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 KiB, factors from a 1 GiB copy),
 # mean over the 32 layers of cfg2; the runs and the raw figures are in profiles/bench_cfg2_kernel_trace.md.
 # Reported as roofline.traffic for that workload only; other workloads report null.
-MEASURED_TRAFFIC_CFG2 = {"quantize": 1253581926, "select": 1133632512, "decode": 168192000}
+MEASURED_TRAFFIC_CFG2 = {"quantize": 1270545830, "select": 1133459865, "decode": 168193024}
 METRIC = "decode-attn KV tokens/s/GPU + achieved HBM GB/s (% peak); quantize GB/s"
 
 
