@@ -295,8 +295,11 @@ def decode_step_bench(args, w, akvq, synth, torch, np):
     def step():
         for c, q, (k1, v1) in zip(caches, qs, news):
             c.T_len = w.T
-            akvq.quantize_append_tiered(c, k1, v1, None, None, w.clip, 1.0, rope=rope_new)
-            akvq.decode_attention(c, q, w.sm_scale, out=out, lse=lse, rope=rope_new)
+            if args.fused:   # akvq_decode_step: the append runs inside the decode launch
+                akvq.decode_step(c, k1, v1, q, w.clip, w.sm_scale, out=out, lse=lse, rope=rope_new)
+            else:
+                akvq.quantize_append_tiered(c, k1, v1, None, None, w.clip, 1.0, rope=rope_new)
+                akvq.decode_attention(c, q, w.sm_scale, out=out, lse=lse, rope=rope_new)
 
     for _ in range(max(args.warmup, 1)):
         step()
@@ -324,8 +327,8 @@ def decode_step_bench(args, w, akvq, synth, torch, np):
     nbytes = sum(w.B * w.Hkv * ((w.T + 1 - min(w.s_cap(l), w.n_text if w.mode(l) == "tsa" else w.top_k)) * per_row
                                 + (w.n_text if w.mode(l) == "tsa" else w.top_k) * 512) for l in range(L))
     print(json.dumps({"metric": "decode step over all layers (append one token + decode attention)",
-                      "workload": w.name, "layers": L, "batch": w.B, "context": w.T + 1, "hip_graph": bool(args.graph),
-                      "ms_per_step": round(ms, 4), "launches_per_step": 2 * L,
+                      "workload": w.name, "layers": L, "batch": w.B, "context": w.T + 1, "hip_graph": bool(args.graph), "fused_append": bool(args.fused),
+                      "ms_per_step": round(ms, 4), "launches_per_step": (1 if args.fused else 2) * L,
                       "generated_tokens_per_s_attention_path": round(w.B / (ms * 1e-3), 1),
                       "cache_GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
                       "frac_of_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}))
@@ -379,6 +382,7 @@ def main():
     ap.add_argument("--rope", action="store_true",
                     help="--phase quantize with the rotary position embedding fused into the write path")
     ap.add_argument("--graph", action="store_true", help="--phase decode_step replayed as one HIP graph")
+    ap.add_argument("--fused", action="store_true", help="--phase decode_step through akvq_decode_step (one launch per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--n-split", type=int, default=0)
     ap.add_argument("--phase", default="all", choices=["all", "decode", "quantize", "select", "massive", "fold", "capacity", "ablation", "decode_step", "copy"],

@@ -229,6 +229,23 @@ int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, c
                                const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
                                void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 
+/*
+ * akvq_decode_step -- one generated token in one launch: the new token's K and V rows (k_new, v_new: device,
+ *   [B][Hkv][1][128] binary16) are written to cache row T_len exactly as akvq_quantize_append_rope would write a single
+ *   plain row (codes, meta, the recent-window rings, the overlay if the row is listed in c->sal_idx), then decode
+ *   attention runs over the T_len + 1 rows as akvq_decode_attention_rope would: the cache holds the bits of the
+ *   separate append, the output those of the separate decode call when n_split is 1 (with more splits the 16-bit rows
+ *   are all read by the last split, so they enter the sums in another order).  The new row is written by the
+ *   workgroups of the last KV split before they read it; no other workgroup reads it.
+ *   c->T_len is the number of rows already cached (0 is allowed); advance it by one
+ *   afterwards.  rope (may be NULL): one table row per batch element, used for the new K row and for q.  clip: the
+ *   2-bit clip ratio.  flags: write- and read-path flags together.  Everything else as in the two entry points.
+ */
+int akvq_decode_step(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *k_new,
+                     const void *v_new, const void *q, const akvq_rope *rope, int Hq, float clip, float sm_scale,
+                     float *out, float *lse_out, int n_split, void *workspace, size_t workspace_bytes, uint32_t flags,
+                     void *stream);
+
 #ifdef __cplusplus
 }
 #endif

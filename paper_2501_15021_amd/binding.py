@@ -23,7 +23,7 @@ EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_b
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
            "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention",
            "akvq_quantize_append_tiered", "akvq_decode_attention_tiered", "akvq_quantize_append_rope",
-           "akvq_decode_attention_rope",
+           "akvq_decode_attention_rope", "akvq_decode_step",
            "akvq_massive_workspace_bytes", "akvq_select_massive", "akvq_fold_hadamard"]
 TIER_2BIT, TIER_4BIT_COARSE, TIER_4BIT_FINE, TIER_PAD = 0, 1, 2, 3
 
@@ -103,6 +103,10 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention_rope.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.POINTER(akvq_window), C.c_void_p,
                                                  C.POINTER(akvq_rope), C.c_int, C.c_float, C.c_void_p, C.c_void_p,
                                                  C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+        L.akvq_decode_step.restype = C.c_int
+        L.akvq_decode_step.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.POINTER(akvq_window), C.c_void_p, C.c_void_p,
+                                       C.c_void_p, C.POINTER(akvq_rope), C.c_int, C.c_float, C.c_float, C.c_void_p,
+                                       C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
         _lib = L
     return _lib
 
@@ -308,4 +312,31 @@ def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: in
         return out, lse
     _check(lib().akvq_decode_attention(C.byref(c), _ptr(q), Hq, sm_scale, _ptr(out), _ptr(lse), n_split, _ptr(ws),
                                        ws.numel(), flags, _stream()), "akvq_decode_attention")
+    return out, lse
+
+
+def decode_step(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, clip: float, sm_scale: float,
+                n_split: int = 0, flags: int = 0, out: Optional[torch.Tensor] = None,
+                lse: Optional[torch.Tensor] = None, rope=None):
+    """akvq_decode_step: append one row per (batch, kv-head) and run decode attention over the cache including it, in
+    one launch; advances cache.T_len.  Returns (out, lse)."""
+    assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16 and q.dtype == torch.float16
+    assert k_new.is_contiguous() and v_new.is_contiguous() and q.is_contiguous()
+    assert tuple(k_new.shape) == (cache.B, cache.Hkv, 1, D) and k_new.shape == v_new.shape
+    B, Hq, _ = q.shape
+    if n_split <= 0:
+        n_split = lib().akvq_decode_default_splits(cache.B, cache.Hkv, cache.T_len + 1)
+    ws = cache.workspace("decode", lib().akvq_decode_workspace_bytes(B, Hq, n_split))
+    if out is None:
+        out = torch.empty(B, Hq, D, dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
+    c = cache.struct()
+    win = cache.window_struct()
+    rs = _rope_struct(rope, B, 1) if rope is not None else None
+    _check(lib().akvq_decode_step(C.byref(c), _ptr(cache.fine_mask), C.byref(win) if win else None, _ptr(k_new),
+                                  _ptr(v_new), _ptr(q), C.byref(rs) if rs is not None else None, Hq, clip, sm_scale,
+                                  _ptr(out), _ptr(lse), n_split, _ptr(ws), ws.numel(), flags, _stream()),
+           "akvq_decode_step")
+    cache.T_len += 1
     return out, lse

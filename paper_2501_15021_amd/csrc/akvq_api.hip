@@ -188,10 +188,10 @@ static int check_rope(const akvq_rope *rope, uint32_t prerotated) {
   return AKVQ_OK;
 }
 
-static int quantize_common(const akvq_cache *c, const void *k_new, const void *v_new, int n_src, int n_new,
-                           float clip, float clip4, const int32_t *row_src, const uint8_t *row_tier,
-                           uint32_t *fine_mask, const akvq_window *win, const akvq_rope *rope, uint32_t flags,
-                           void *stream) {
+static int quantize_args(const akvq_cache *c, const void *k_new, const void *v_new, int n_src, int n_new,
+                         float clip, float clip4, const int32_t *row_src, const uint8_t *row_tier,
+                         uint32_t *fine_mask, const akvq_window *win, const akvq_rope *rope, uint32_t flags,
+                         akvq::QuantArgs &a) {
   int st = check_rope(rope, flags & AKVQ_K_PREROTATED);
   if (st != AKVQ_OK) return st;
   st = check_cache_shape(c);
@@ -201,7 +201,7 @@ static int quantize_common(const akvq_cache *c, const void *k_new, const void *v
   if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new <= 0 || n_src <= 0) return AKVQ_ERR_INVALID_ARG;
   if (!(clip > 0.0f) || clip > 1.0f || !(clip4 > 0.0f) || clip4 > 1.0f) return AKVQ_ERR_INVALID_ARG;
   if ((long)c->T_len + n_new > c->T_cap) return AKVQ_ERR_CAPACITY;
-  akvq::QuantArgs a{};
+  a = akvq::QuantArgs{};
   a.row_src = row_src; a.row_tier = row_tier; a.fine_mask = fine_mask; a.n_src = n_src; a.clip4 = clip4;
   st = check_window(win);
   if (st != AKVQ_OK) return st;
@@ -217,6 +217,17 @@ static int quantize_common(const akvq_cache *c, const void *k_new, const void *v
   a.clip = clip;
   a.rotate_k = (flags & AKVQ_K_PREROTATED) ? 0 : 1;
   a.rotate_v = (flags & AKVQ_V_PREROTATED) ? 0 : 1;
+  return AKVQ_OK;
+}
+
+static int quantize_common(const akvq_cache *c, const void *k_new, const void *v_new, int n_src, int n_new,
+                           float clip, float clip4, const int32_t *row_src, const uint8_t *row_tier,
+                           uint32_t *fine_mask, const akvq_window *win, const akvq_rope *rope, uint32_t flags,
+                           void *stream) {
+  akvq::QuantArgs a;
+  const int st = quantize_args(c, k_new, v_new, n_src, n_new, clip, clip4, row_src, row_tier, fine_mask, win, rope,
+                               flags, a);
+  if (st != AKVQ_OK) return st;
   return hip_status(akvq::launch_quantize_append(a, c->B, c->G, static_cast<hipStream_t>(stream)));
 }
 
@@ -260,9 +271,9 @@ int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask,
                                     workspace_bytes, flags, stream);
 }
 
-int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
-                               const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
-                               void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
+static int decode_args(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
+                       const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                       void *workspace, size_t workspace_bytes, uint32_t flags, akvq::DecodeArgs &a) {
   if (fine_mask && !aligned16(fine_mask)) return AKVQ_ERR_INVALID_ARG;
   int st = check_rope(rope, flags & AKVQ_Q_PREROTATED);
   if (st != AKVQ_OK) return st;
@@ -281,7 +292,7 @@ int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, c
   if (n_split > 1024) return AKVQ_ERR_INVALID_ARG;
   if (!workspace || !aligned16(workspace)) return AKVQ_ERR_INVALID_ARG;
   if (workspace_bytes < akvq_decode_workspace_bytes(c->B, Hq, n_split)) return AKVQ_ERR_WORKSPACE;
-  akvq::DecodeArgs a{};
+  a = akvq::DecodeArgs{};
   a.k_codes = c->k_codes; a.v_codes = c->v_codes; a.k_meta = c->k_meta; a.v_meta = c->v_meta;
   a.k_sal = c->k_sal; a.v_sal = c->v_sal; a.sal_idx = c->sal_idx; a.sal_cnt = c->sal_cnt;
   a.fine_mask = fine_mask;
@@ -298,6 +309,35 @@ int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, c
   if (rope) { a.rope_cos = rope->cos; a.rope_sin = rope->sin; a.rope_stride = rope->batch_stride; }
   a.q_rotated = (flags & AKVQ_Q_PREROTATED) ? 1 : 0;
   a.out_rotated = (flags & AKVQ_OUT_ROTATED) ? 1 : 0;
+  return AKVQ_OK;
+}
+
+int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
+                               const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                               void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
+  akvq::DecodeArgs a;
+  const int st = decode_args(c, fine_mask, win, q, rope, Hq, sm_scale, out, lse_out, n_split, workspace,
+                             workspace_bytes, flags, a);
+  if (st != AKVQ_OK) return st;
+  return hip_status(akvq::launch_decode_attention(a, c->G, static_cast<hipStream_t>(stream)));
+}
+
+int akvq_decode_step(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *k_new,
+                     const void *v_new, const void *q, const akvq_rope *rope, int Hq, float clip, float sm_scale,
+                     float *out, float *lse_out, int n_split, void *workspace, size_t workspace_bytes, uint32_t flags,
+                     void *stream) {
+  if (!c) return AKVQ_ERR_INVALID_ARG;
+  akvq::QuantArgs qa;
+  int st = quantize_args(c, k_new, v_new, 1, 1, clip, 1.0f, nullptr, nullptr, nullptr, win, rope, flags, qa);
+  if (st != AKVQ_OK) return st;
+  akvq_cache after = *c;  // what decode attends over: the cached rows and the new one
+  after.T_len = c->T_len + 1;
+  akvq::DecodeArgs a;
+  st = decode_args(&after, fine_mask, win, q, rope, Hq, sm_scale, out, lse_out, n_split, workspace, workspace_bytes,
+                   flags, a);
+  if (st != AKVQ_OK) return st;
+  a.fused_append = 1;
+  a.step = qa;
   return hip_status(akvq::launch_decode_attention(a, c->G, static_cast<hipStream_t>(stream)));
 }
 

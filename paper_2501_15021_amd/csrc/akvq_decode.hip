@@ -13,6 +13,7 @@
 // tile's loads are issued before the current tile is consumed.
 #include "akvq_device.h"
 #include "akvq_kernels.h"
+#include "akvq_rowquant.h"
 
 namespace akvq {
 
@@ -209,9 +210,21 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
   auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
   MhaTile<NG> tb[3];
-  if (n_mine > 0) {
+  // Fused decode step: the workgroups of the last split first write the new row (wavefront 1 the K row, wavefront 2
+  // the V row, while wavefront 0 stages the query); the barrier below orders those stores before this workgroup's
+  // loads of the tile that holds the row.  A wavefront whose first two tiles include that tile asks for them after
+  // the barrier instead of here.
+  const bool appends = a.fused_append != 0 && split == a.n_split - 1;  // uniform over the workgroup
+  const bool defer_loads = appends && a.t_win == a.T_len && n_mine > 0 &&
+                           (tile_at(0) == n_tiles - 1 || tile_at(1) == n_tiles - 1);
+  if (n_mine > 0 && !defer_loads) {
     load_tile(tile_at(0), tb[0]);
     load_tile(tile_at(1), tb[1]);
+  }
+  if (appends && (wave == 1 || wave == 2)) {
+    __shared__ __attribute__((aligned(16))) uint8_t step_codes[2][kD];
+    __shared__ __attribute__((aligned(16))) uint16_t step_row[2][kD];
+    append_row_wave<G>(a.step, bh, wave - 1, lane, step_codes[wave - 1], step_row[wave - 1]);
   }
 
   if (tid < 64) zero16[tid] = 0;
@@ -220,6 +233,10 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
                                   a.rope_cos ? a.rope_cos + (size_t)(bh / a.Hkv) * a.rope_stride : nullptr,
                                   a.rope_sin ? a.rope_sin + (size_t)(bh / a.Hkv) * a.rope_stride : nullptr, lane);
   __syncthreads();
+  if (defer_loads) {
+    load_tile(tile_at(0), tb[0]);
+    load_tile(tile_at(1), tb[1]);
+  }
   // fixed-point unit of the query: U = 2^ceil(log2 max|q~|) / 2^20 (the digits then cover it exactly, 21 bits)
   float q_unit_inv;
   {
@@ -402,7 +419,10 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   // Used twice: the salient overlay (slot = rank in the salient list) and the recent-window rings (slot = row mod W).
   auto bf16_units = [&](const uint16_t *ks_base, const uint16_t *vs_base, int cnt, auto &&row_ok) {
     const int n_units = (cnt + 63) / 64;
-    for (int unit = split + wave * a.n_split; unit < n_units; unit += kWaves * a.n_split) {
+    // fused decode step: the 16-bit rows (one of which may be the new row) are read by the last split only
+    const int unit_step = a.fused_append ? kWaves : kWaves * a.n_split;
+    const int unit_first = a.fused_append ? (appends ? wave : n_units) : split + wave * a.n_split;
+    for (int unit = unit_first; unit < n_units; unit += unit_step) {
       const int s_lane = unit * 64 + lane;
       // only the token groups (16 slots) and blocks (32 slots) that hold rows are touched; the first block of value
       // rows and the row's validity are requested together with the key rows so that the phase costs one round trip
@@ -567,6 +587,14 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 
   for (int x = tid; x < 16 * kD; x += 64 * kWaves) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
   for (int x = lane; x < NG * 16 * kTokBlock; x += 64) (&w_lds[0][0][0])[x] = 0;
+  // Fused decode step: the workgroups of the last split first write the new row (wavefront 3 the K row, wavefront 2
+  // the V row); the barrier below orders those stores before this workgroup's loads, which all come later.
+  const bool appends = a.fused_append != 0 && split == a.n_split - 1;  // uniform over the workgroup
+  if (appends && wave >= 2) {
+    __shared__ __attribute__((aligned(16))) uint8_t step_codes[2][kD];
+    __shared__ __attribute__((aligned(16))) uint16_t step_row[2][kD];
+    append_row_wave<G>(a.step, bh, 3 - wave, lane, step_codes[3 - wave], step_row[3 - wave]);
+  }
   for (int h = wave; h < R; h += kWaves) rotate_query_lds(a.q + ((size_t)b * a.Hq + hkv * R + h) * kD, qf[h], a.q_rotated != 0,
                      a.rope_cos ? a.rope_cos + (size_t)b * a.rope_stride : nullptr,
                      a.rope_sin ? a.rope_sin + (size_t)b * a.rope_stride : nullptr, lane);
@@ -833,13 +861,15 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   // Used twice: the salient overlay (slot = rank in the salient list) and the recent-window rings (slot = row mod W).
   auto bf16_units = [&](const uint16_t *ks_base, const uint16_t *vs_base, int cnt, auto &&row_ok) {
     const int n_units = (cnt + 31) / 32;
-    const int first_unit = split + wave * a.n_split;
+    // fused decode step: the 16-bit rows (one of which may be the new row) are read by the last split only
+    const int unit_step = a.fused_append ? kWaves : kWaves * a.n_split;
+    const int first_unit = a.fused_append ? (appends ? wave : n_units) : split + wave * a.n_split;
     if (first_unit >= n_units) return;
     bf16x8 a_s[4];
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
       a_s[kc] = *reinterpret_cast<const bf16x8 *>(&q_plain[mrow][32 * kc + 8 * qd]);
-    for (int unit = first_unit; unit < n_units; unit += kWaves * a.n_split) {
+    for (int unit = first_unit; unit < n_units; unit += unit_step) {
       // the value rows and the rows' validity are requested together with the key rows (one round trip for the
       // phase); a token group (16 slots) without rows is not read
       const int n_grp = min(2, (cnt - unit * 32 + 15) >> 4);

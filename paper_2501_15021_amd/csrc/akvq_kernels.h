@@ -44,6 +44,10 @@ struct DecodeArgs {
   int B, Hq, Hkv, T_cap, S_cap, T_len, n_split;
   float sm_scale;
   int q_rotated, out_rotated;
+  // the decode step in one launch: row T_len - 1 is first quantized from step.k_new / step.v_new (step.T_len is that
+  // row) by the workgroups of the last KV split, which are also the only ones to read 16-bit rows then
+  int fused_append;
+  QuantArgs step;
   const uint16_t *rope_cos, *rope_sin;  // rotary tables for pre-RoPE queries (null: none), one row of 64 per batch element
   long long rope_stride;
 };

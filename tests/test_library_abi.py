@@ -132,6 +132,14 @@ def test_every_error_code_of_every_entry_point(L):
     assert dr(C.byref(cache(T_len=5)), None, None, P, C.byref(ok), 2, 0.1, P, None, 1, P, big, 8, None) == INVALID  # q pre-rotated
     assert dr(C.byref(cache(T_len=5)), None, None, P, C.byref(nul), 2, 0.1, P, None, 1, P, big, 0, None) == INVALID
     assert dr(C.byref(cache(T_len=5)), None, None, P, C.byref(ok), 2, 0.1, P, None, 4, P, 64, 0, None) == WORKSPACE
+    # ---- fused decode step
+    ds = L.akvq_decode_step
+    assert ds(C.byref(cache(T_len=128)), None, None, P, P, P, None, 2, 0.8, 0.1, P, None, 1, P, big, 0, None) == CAPACITY
+    assert ds(C.byref(cache(T_len=5)), None, None, None, P, P, None, 2, 0.8, 0.1, P, None, 1, P, big, 0, None) == INVALID
+    assert ds(C.byref(cache(T_len=5)), None, None, P, P, P, None, 2, 1.5, 0.1, P, None, 1, P, big, 0, None) == INVALID
+    assert ds(C.byref(cache(T_len=5)), None, None, P, P, P, None, 3, 0.8, 0.1, P, None, 1, P, big, 0, None) == INVALID
+    assert ds(C.byref(cache(T_len=5)), None, None, P, P, P, None, 2, 0.8, 0.1, P, None, 4, P, 64, 0, None) == WORKSPACE
+    assert ds(C.byref(cache(T_len=5)), None, None, P, P, P, C.byref(ok), 2, 0.8, 0.1, P, None, 1, P, big, 4, None) == INVALID
     # ---- offline fold
     f = L.akvq_fold_hadamard
     assert f(P, P, 4, 100, 1, None) == INVALID                                   # columns not in runs of 128
