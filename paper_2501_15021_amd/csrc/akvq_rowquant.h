@@ -116,6 +116,7 @@ __device__ __forceinline__ void append_row_wave(const QuantArgs &a, int bh, int 
   // everything that has to come from memory is requested first
   const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
   int cnt = a.sal_cnt[bh];
+  const int first_entry = sidx[lane];  // S_cap >= 64: asked for together with the count instead of after it
   const uint16_t *row = (tensor == 0 ? a.k_new : a.v_new) + (size_t)bh * kD;
   float x0 = half_bits_to_float(row[lane]), x1 = half_bits_to_float(row[lane + 64]);
   const size_t blk_word = ((size_t)bh * (a.T_cap / kTokBlock) + blk) * kBlockWords;
@@ -137,7 +138,7 @@ __device__ __forceinline__ void append_row_wave(const QuantArgs &a, int bh, int 
   cnt = min(max(cnt, 0), a.S_cap);
   int slot = -1;
   for (int base = 0; base < cnt; base += kWave) {
-    const int e = base + lane < cnt ? sidx[base + lane] : -1;
+    const int e = base + lane < cnt ? (base == 0 ? first_entry : sidx[base + lane]) : -1;
     const unsigned long long hit = __ballot(e == t);
     if (hit != 0ull) slot = base + __builtin_ctzll(hit);
   }
