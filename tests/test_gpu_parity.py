@@ -455,3 +455,25 @@ def test_argument_errors():
     qt = torch.zeros(1, 4, 16, D, dtype=torch.float16, device="cuda")
     with pytest.raises(akvq.AkvqError, match="capacity"):
         akvq.select_salient(gc, akvq.MODE_PSA, q_tail=qt, k=kk, top_k=65, sm_scale=0.1)     # top_k > S_cap
+
+
+def test_results_do_not_depend_on_the_run():
+    """The same inputs twice (fresh caches, other work in between): index sets, cache bytes, masses and attention
+    outputs are bit-identical -- no result depends on the order in which workgroups or atomics happen to run."""
+    w = synth.small("det", B=3, Hq=14, Hkv=2, T=2300, G=64, n_text_head=40, n_text_tail=25, top_k=24, W=32)
+    d = synth.generate(w, seed=201, device="cuda")
+    runs = []
+    for rep in range(2):
+        c = akvq.Cache(w.B, w.Hkv, w.G, 2304, 64, fill=0)
+        c.enable_window(64)
+        mass = torch.zeros(w.B, w.Hkv, w.T, device="cuda")
+        akvq.select_salient(c, akvq.MODE_PSA, q_tail=d["q_tail"], k=d["k"], top_k=w.top_k, sm_scale=w.sm_scale,
+                            mass_out=mass)
+        akvq.quantize_append_tiered(c, d["k"], d["v"], None, None, w.clip, 1.0)
+        out, lse = akvq.decode_attention(c, d["q"], w.sm_scale, n_split=5)
+        torch.cuda.synchronize()
+        runs.append([t.clone() for t in (mass, c.sal_idx, c.k_codes, c.v_codes, c.k_meta, c.v_meta, c.k_sal, c.v_sal,
+                                         c.k_win, c.v_win, out, lse)])
+        torch.randn(1 << 22, device="cuda").sort()          # unrelated work between the two runs
+    for a, b in zip(*runs):
+        assert torch.equal(a, b)
