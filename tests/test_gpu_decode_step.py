@@ -115,3 +115,27 @@ def test_decode_step_after_tiered_prefill(orc):
         got = out.cpu().numpy().astype(np.float64)
         rel = np.abs(got - ref).max(axis=-1) / np.maximum(np.abs(ref).max(axis=-1), 1e-6)
         assert rel.max() <= ATTN_TOL, f"tiered step {t}: {rel.max():.3e}"
+
+
+def test_decode_step_with_offline_fold_flags(orc):
+    """V arrives rotated and the output stays rotated (Section III-C.2 offline mode): the fused step passes the write-
+    and the read-path flags together."""
+    w = synth.small("step_flags", B=2, Hq=4, Hkv=2, T=80, G=128, n_text_head=3, n_text_tail=2, top_k=4, W=16)
+    d = {k: (v.numpy() if hasattr(v, "numpy") else v) for k, v in synth.generate(w, seed=197).items()}
+    T0 = 75
+    oc = orc.OracleCache(w.B, w.Hkv, 128, 128, 64, fill=0)
+    gc = akvq.Cache(w.B, w.Hkv, 128, 128, 64, fill=0)
+    oc.quantize_append(d["k"][:, :, :T0], d["v"][:, :, :T0], w.clip, rotate_v=False)
+    akvq.quantize_append(gc, _dev(d["k"][:, :, :T0]), _dev(d["v"][:, :, :T0]), w.clip, flags=akvq.V_PREROTATED)
+    rng = np.random.default_rng(9)
+    for t in range(T0, w.T):
+        k1, v1 = d["k"][:, :, t:t + 1], d["v"][:, :, t:t + 1]
+        q = rng.standard_normal((w.B, w.Hq, 128)).astype(np.float16)
+        oc.quantize_append(k1, v1, w.clip, rotate_v=False)
+        ref, _ = oc.decode(q, w.sm_scale, unrotate=False)
+        out, _ = akvq.decode_step(gc, _dev(k1), _dev(v1), _dev(q), w.clip, w.sm_scale, n_split=2,
+                                  flags=akvq.V_PREROTATED | akvq.OUT_ROTATED)
+        _compare_cache(oc, gc, f"flags step {t}")
+        got = out.cpu().numpy().astype(np.float64)
+        rel = np.abs(got - ref).max(axis=-1) / np.maximum(np.abs(ref).max(axis=-1), 1e-6)
+        assert rel.max() <= ATTN_TOL, f"flags step {t}: {rel.max():.3e}"
