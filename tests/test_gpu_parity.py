@@ -498,3 +498,39 @@ def test_decode_softmax_scales(orc, Hq, Hkv, sm_scale):
         # of the grouped-query kernel are at that magnitude (the output bar is unchanged)
         assert_attention_close(out, lse, ref, lse_ref, f"sm_scale={sm_scale} n_split={ns}",
                                lse_tol=max(2e-3, 5e-5 * float(np.abs(lse_ref).max())))
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(3, 3), (8, 2)])
+def test_non_finite_inputs_stay_in_their_unit(orc, Hq, Hkv):
+    """NaN and infinities in the rows of one (batch, kv-head): its results are unspecified, nothing faults, and every
+    other unit is exactly what it is without them (selection, cache bytes, attention)."""
+    w = synth.small(f"nonfinite{Hq}", B=2, Hq=Hq, Hkv=Hkv, T=200, G=128, n_text_head=9, n_text_tail=5, top_k=6, W=16)
+    d = _np(synth.generate(w, seed=211))
+    k, v = d["k"].copy(), d["v"].copy()
+    k[0, 0, 5, :] = np.nan
+    k[0, 0, 9, 0] = -np.inf
+    v[0, 0, 7, 3] = np.inf
+    v[0, 0, 150, 64:] = np.nan
+    oc, gc = make_pair(orc, w, t_cap=256, s_cap=64)
+    clean = orc.OracleCache(w.B, w.Hkv, w.G, 256, 64, fill=0)
+    clean.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale)
+    clean.quantize_append(d["k"], d["v"], w.clip)
+    ref, lse_ref = clean.decode(d["q"], w.sm_scale)
+    akvq.select_salient(gc, akvq.MODE_PSA, q_tail=_dev(d["q_tail"]), k=_dev(k), top_k=w.top_k, sm_scale=w.sm_scale)
+    akvq.quantize_append(gc, _dev(k), _dev(v), w.clip)
+    out, lse = akvq.decode_attention(gc, _dev(d["q"]), w.sm_scale, n_split=2)
+    torch.cuda.synchronize()
+    R = Hq // Hkv
+    for b in range(w.B):
+        for h in range(Hkv):
+            if (b, h) == (0, 0):
+                continue
+            n = int(clean.sal_cnt[b, h])
+            assert int(gc.counts()[b, h]) == n
+            assert np.array_equal(gc.sal_idx[b, h, :n].cpu().numpy(), clean.sal_idx[b, h, :n])
+            for name in ("k_codes", "v_codes", "k_meta", "v_meta"):
+                got = _u32(getattr(gc, name)[b, h])
+                assert np.array_equal(got, getattr(clean, name)[b, h]), (name, b, h)
+            heads = slice(h * R, (h + 1) * R)
+            assert_attention_close(out[b:b + 1, heads], lse[b:b + 1, heads], ref[b:b + 1, heads], lse_ref[b:b + 1, heads],
+                                   f"unit {(b, h)}")
