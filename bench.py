@@ -570,7 +570,7 @@ def main():
         "value": kv_tokens / (tot["decode"] * 1e-3),
         "unit": "KV tokens/s (decode attention; whole-path and quantize rates in 'extra')",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u2 codes; int8, bf16 and f16 MFMA; f32 accumulate",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u2 codes; int8 and bf16 MFMA; f32 accumulate",
         "data": "synthetic (seeded; LLaVA-1.5-shaped prompt layout, outlier channels and pivot tokens planted)",
         "config": {"workload": f"{w.name}: {L} layers x B={w.B} x Hq={w.Hq}/Hkv={w.Hkv} x T={w.T}, G={w.G}, "
                                f"TSA layers {list(w.tsa_layers)}, PSA top-{w.top_k}, clip {w.clip}",

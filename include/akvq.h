@@ -127,7 +127,7 @@ int akvq_decode_default_splits(int B, int Hkv, int T_len);
  *   mode AKVQ_MODE_PSA (III-B.2): salient = the top_k positions by attention-column mass
  *       mass[b][hkv][t] = sum over the Hq/Hkv query heads of the group and the W last prompt rows i of
  *       softmax_t( sm_scale * q_i . k_t )[t], row i sitting at position T-W+i and seeing keys t <= T-W+i.
- *       Operands are taken as stored (binary16), products accumulate in fp32 on the matrix cores, softmax in fp32.
+ *       Operands are rounded to bfloat16, products accumulate in fp32 on the matrix cores, softmax in fp32.
  *       Needs q_tail (device, [B][Hq][W][128] binary16, post-RoPE) and k (device, [B][Hkv][T][128] binary16,
  *       post-RoPE, un-rotated).  Ties go to the lower position.  W must be a multiple of 16, W <= T, W <= 64.
  *   Output: c->sal_idx (ascending) and c->sal_cnt.  mass_out (device, [B][Hkv][T] fp32) is optional (PSA).

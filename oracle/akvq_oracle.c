@@ -314,9 +314,9 @@ static int int_cmp(const void *a, const void *b) {
   return (x > y) - (x < y);
 }
 
-static double score_operand(uint16_t h) {
-  /* reading: the score takes q and K as the model holds them (binary16), with no further rounding */
-  return (double)orc_half_to_float(h);
+static double bf16_round_of_half(uint16_t h) {
+  /* reading: scoring uses bfloat16 operands (inputs arrive as binary16 and are rounded once) */
+  return (double)orc_bf16_to_float(orc_float_to_bf16_rne(orc_half_to_float(h)));
 }
 
 void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
@@ -330,14 +330,14 @@ void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t
     double *kd = (double *)malloc(sizeof(double) * (size_t)T * ORC_D);
     double *logit = (double *)malloc(sizeof(double) * (size_t)T);
     const uint16_t *kp = k + ((size_t)bh * T) * ORC_D;
-    for (size_t x = 0; x < (size_t)T * ORC_D; ++x) kd[x] = score_operand(kp[x]);
+    for (size_t x = 0; x < (size_t)T * ORC_D; ++x) kd[x] = bf16_round_of_half(kp[x]);
     for (int hh = 0; hh < r; ++hh) {
       int hq = h * r + hh;
       for (int i = 0; i < W; ++i) {
         int pos = T - W + i;                     /* absolute position of this query row */
         const uint16_t *qp = q_tail + (((size_t)b * Hq + hq) * W + i) * ORC_D;
         double qd[ORC_D];
-        for (int d = 0; d < ORC_D; ++d) qd[d] = score_operand(qp[d]);
+        for (int d = 0; d < ORC_D; ++d) qd[d] = bf16_round_of_half(qp[d]);
         double mx = -INFINITY;
         for (int t = 0; t <= pos; ++t) {          /* causal: keys up to and including the row's position */
           double acc = 0.0;

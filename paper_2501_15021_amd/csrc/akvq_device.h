@@ -136,10 +136,5 @@ struct ExpandI8 {
 __device__ __forceinline__ f32x4 mfma_bf16(bf16x8 a, bf16x8 b, f32x4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
-// the same shape on binary16 operands (products of binary16 numbers are exact in the fp32 accumulator's format)
-__device__ __forceinline__ f32x4 mfma_f16(f16x8 a, f16x8 b, f32x4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
-}
 
 } // namespace akvq

@@ -1,7 +1,7 @@
 // Salient-token identification (Section III-B of arXiv 2501.15021).
 //   TSA layers: the salient set is the text positions -> ordered stream compaction of the modality mask.
 //   PSA layers: pivot tokens are the few tokens that receive most of the attention (Section I / III-A.3); the score
-//   is the attention-column mass of the last W prompt rows, computed on the matrix cores (binary16 operands as stored, fp32
+//   is the attention-column mass of the last W prompt rows, computed on the matrix cores (bfloat16 operands, fp32
 //   accumulate, fp32 softmax) in two streaming passes over K (row statistics, then column sums), followed by an
 //   exact top-k (radix select on the fp32 bit patterns, ties to the lower position).
 #include "akvq_device.h"
@@ -57,6 +57,14 @@ constexpr int kGroupsPerWave = kScoreChunk / (4 * 16);
 constexpr int kKeyDepth = 1;  // key groups in flight ahead of the one being scored
 static_assert(kGroupsPerWave % (kKeyDepth + 1) == 0, "the scoring loop is unrolled over the key ring");
 
+// binary16 pair (packed) -> bfloat16 pair (packed), each rounded to nearest even
+__device__ __forceinline__ uint32_t half2_to_bf16x2(uint32_t hh) {
+  return pack_bf16x2(half_bits_to_float(hh & 0xFFFFu), half_bits_to_float(hh >> 16));
+}
+__device__ __forceinline__ bf16x8 rows8_as_bf16(u32x4 raw) {
+  u32x4 r = {half2_to_bf16x2(raw[0]), half2_to_bf16x2(raw[1]), half2_to_bf16x2(raw[2]), half2_to_bf16x2(raw[3])};
+  return __builtin_bit_cast(bf16x8, r);
+}
 __device__ __forceinline__ float row_max16(float v) {
 #pragma unroll
   for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
@@ -85,13 +93,15 @@ __device__ __forceinline__ void score_16keys(const u32x4 *q_lds, const KeyGroup 
   // not hoisted out of the caller's loop into 64 registers (which would cost a wavefront of occupancy).
   uint32_t lane_off = (uint32_t)(qd * 16 + mrow);
   asm volatile("" : "+v"(lane_off));
+  bf16x8 kb[4];
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) kb[kc] = rows8_as_bf16(g.raw[kc]);
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
     acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
-      acc[rb] = mfma_f16(__builtin_bit_cast(f16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]),
-                         __builtin_bit_cast(f16x8, g.raw[kc]), acc[rb]);
+      acc[rb] = mfma_bf16(__builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), kb[kc], acc[rb]);
   }
 }
 // causal visibility of key t for tail row `row` (the row sits at position T-W+row); keys past the end are never seen
@@ -100,14 +110,14 @@ __device__ __forceinline__ bool key_seen(int t, int row, int T, int W) { return 
 __device__ __forceinline__ bool group_has_masked(int t_first, int T, int W) { return t_first + 15 > T - W; }
 
 // the W tail rows of one query head as matrix-core A operands in LDS: slot (rb, kc, lane) is what lane (mrow, qd)
-// feeds for row block rb and channel step kc; wavefront w copies row blocks w, w+4, ...
+// feeds for row block rb and channel step kc; wavefront w converts row blocks w, w+4, ...
 template <int NRB>
 __device__ __forceinline__ void stage_query_rows(const uint16_t *q_head, int wave, int mrow, int qd, u32x4 *q_lds) {
   for (int rb = wave; rb < NRB; rb += 4)
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
-      q_lds[(rb * 4 + kc) * 64 + qd * 16 + mrow] =
-          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd);
+      q_lds[(rb * 4 + kc) * 64 + qd * 16 + mrow] = __builtin_bit_cast(u32x4, rows8_as_bf16(
+          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd)));
 }
 
 constexpr float kLog2e = 1.4426950408889634f;

@@ -104,8 +104,10 @@ def test_psa_mass_invariants_and_topk(orc):
     assert (mass >= 0).all()
     # causal: the last key is seen only by the last row (of each of the 2 query heads of the group)
     assert (mass[..., -1] <= 2.0).all()
-    # independent numpy evaluation of the definition (operands as stored, fp64 softmax)
-    q, k = d["q_tail"].astype(np.float64), d["k"].astype(np.float64)
+    # independent numpy evaluation of the definition (bf16-rounded operands, fp64 softmax)
+    import torch
+    rb = lambda a: torch.from_numpy(a).to(torch.bfloat16).to(torch.float64).numpy()
+    q, k = rb(d["q_tail"]), rb(d["k"])
     for b in range(2):
         for h in range(2):
             ref = np.zeros(w.T)
