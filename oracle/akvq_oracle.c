@@ -319,8 +319,29 @@ static double bf16_round_of_half(uint16_t h) {
   return (double)orc_bf16_to_float(orc_float_to_bf16_rne(orc_half_to_float(h)));
 }
 
-void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
-                    double sm_scale, double *mass_out) {
+/* top_k positions of one mass row (mass descending, then position ascending), written ascending to every list in
+ * lists[0..n_lists) */
+static void select_top_positions(const orc_cache *c, const double *mass, int T, int top_k, int32_t **lists,
+                                 int32_t **counts, int n_lists) {
+  mass_item *items = (mass_item *)malloc(sizeof(mass_item) * (size_t)T);
+  for (int t = 0; t < T; ++t) { items[t].mass = mass[t]; items[t].idx = t; }
+  qsort(items, (size_t)T, sizeof(mass_item), mass_cmp);
+  int kk = top_k < T ? top_k : T;
+  int *sel = (int *)malloc(sizeof(int) * (size_t)(kk > 0 ? kk : 1));
+  for (int s = 0; s < kk; ++s) sel[s] = items[s].idx;
+  qsort(sel, (size_t)kk, sizeof(int), int_cmp);
+  for (int l = 0; l < n_lists; ++l) {
+    for (int s = 0; s < kk && s < c->S_cap; ++s) lists[l][s] = sel[s];
+    *counts[l] = kk;
+  }
+  free(sel); free(items);
+}
+
+/* share_heads != 0: the masses of the kv-heads of a batch element are added (head 0 first) and every head gets the
+ * same list -- token-level pivots, as the paper has them (Section III-B.2: one pivot set per layer). */
+static void select_psa_impl(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
+                            double sm_scale, double *mass_out, int share_heads) {
+  double *mass_all = (double *)malloc(sizeof(double) * (size_t)c->B * c->Hkv * T);
   const int r = Hq / c->Hkv;
   const int nbh = c->B * c->Hkv;
 #pragma omp parallel for schedule(dynamic)
@@ -350,19 +371,42 @@ void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t
         for (int t = 0; t <= pos; ++t) mass[t] += exp(logit[t] - mx) / den;
       }
     }
-    if (mass_out) memcpy(mass_out + (size_t)bh * T, mass, sizeof(double) * (size_t)T);
-    mass_item *items = (mass_item *)malloc(sizeof(mass_item) * (size_t)T);
-    for (int t = 0; t < T; ++t) { items[t].mass = mass[t]; items[t].idx = t; }
-    qsort(items, (size_t)T, sizeof(mass_item), mass_cmp);
-    int kk = top_k < T ? top_k : T;
-    int *sel = (int *)malloc(sizeof(int) * (size_t)(kk > 0 ? kk : 1));
-    for (int s = 0; s < kk; ++s) sel[s] = items[s].idx;
-    qsort(sel, (size_t)kk, sizeof(int), int_cmp);
-    int32_t *idx = c->sal_idx + (size_t)bh * c->S_cap;
-    for (int s = 0; s < kk && s < c->S_cap; ++s) idx[s] = sel[s];
-    c->sal_cnt[bh] = kk;
-    free(sel); free(items); free(logit); free(kd); free(mass);
+    memcpy(mass_all + (size_t)bh * T, mass, sizeof(double) * (size_t)T);
+    free(logit); free(kd); free(mass);
   }
+  if (mass_out) memcpy(mass_out, mass_all, sizeof(double) * (size_t)c->B * c->Hkv * T);
+  if (!share_heads) {
+    for (int bh = 0; bh < nbh; ++bh) {
+      int32_t *list = c->sal_idx + (size_t)bh * c->S_cap, *cnt = c->sal_cnt + bh;
+      select_top_positions(c, mass_all + (size_t)bh * T, T, top_k, &list, &cnt, 1);
+    }
+  } else {
+    double *sum = (double *)malloc(sizeof(double) * (size_t)T);
+    int32_t **lists = (int32_t **)malloc(sizeof(int32_t *) * (size_t)c->Hkv);
+    int32_t **cnts = (int32_t **)malloc(sizeof(int32_t *) * (size_t)c->Hkv);
+    for (int b = 0; b < c->B; ++b) {
+      for (int t = 0; t < T; ++t) sum[t] = 0.0;
+      for (int h = 0; h < c->Hkv; ++h) {
+        const double *m = mass_all + ((size_t)b * c->Hkv + h) * T;
+        for (int t = 0; t < T; ++t) sum[t] += m[t];
+        lists[h] = c->sal_idx + ((size_t)b * c->Hkv + h) * c->S_cap;
+        cnts[h] = c->sal_cnt + ((size_t)b * c->Hkv + h);
+      }
+      select_top_positions(c, sum, T, top_k, lists, cnts, c->Hkv);
+    }
+    free(sum); free(lists); free(cnts);
+  }
+  free(mass_all);
+}
+
+void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
+                    double sm_scale, double *mass_out) {
+  select_psa_impl(c, Hq, q_tail, k, T, W, top_k, sm_scale, mass_out, 0);
+}
+
+void orc_select_psa_shared(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
+                           double sm_scale, double *mass_out) {
+  select_psa_impl(c, Hq, q_tail, k, T, W, top_k, sm_scale, mass_out, 1);
 }
 
 /* ------------------------------------------------------------------------------------------

@@ -79,6 +79,10 @@ void orc_select_tsa(orc_cache *c, const uint8_t *is_text, int T);
  * both binary16, un-rotated.  mass_out (optional) [B][Hkv][T] fp64.  Writes sal_idx / sal_cnt. */
 void orc_select_psa(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
                     double sm_scale, double *mass_out);
+/* The same with token-level pivots (Section III-B.2: one pivot set per layer): the masses of a batch element's kv-heads
+ * are added and every kv-head gets the same list.  mass_out stays per kv-head. */
+void orc_select_psa_shared(orc_cache *c, int Hq, const uint16_t *q_tail, const uint16_t *k, int T, int W, int top_k,
+                           double sm_scale, double *mass_out);
 /* Offline fold of H_128 into a projection matrix w [rows][cols] binary16 (Section III-C.2, Fig. 7): axis 1 rotates every
  * aligned run of 128 columns of each row (W_V), axis 0 every aligned run of 128 rows column-wise (W_O). */
 void orc_fold_hadamard(const uint16_t *w, uint16_t *out, int rows, int cols, int axis);

@@ -67,6 +67,7 @@ def lib():
         L.orc_select_tsa.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_int]
         L.orc_select_psa.argtypes = [C.POINTER(_Cache), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int,
                                      C.c_double, C.c_void_p]
+        L.orc_select_psa_shared.argtypes = L.orc_select_psa.argtypes
         L.orc_quantize_append.argtypes = [C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_int, C.c_float, C.c_int]
         L.orc_decode_attention.argtypes = [C.POINTER(_Cache), C.c_int, C.c_void_p, C.c_double, C.c_int, C.c_void_p,
                                            C.c_void_p]
@@ -147,14 +148,15 @@ class OracleCache:
         c = self._c()
         lib().orc_select_tsa(C.byref(c), _p(is_text), is_text.shape[1])
 
-    def select_psa(self, q_tail, k, top_k: int, sm_scale: float, want_mass: bool = False):
+    def select_psa(self, q_tail, k, top_k: int, sm_scale: float, want_mass: bool = False, share_heads: bool = False):
         q_tail, k = _u16(q_tail), _u16(k)
         B, Hq, W, _ = q_tail.shape
         T = k.shape[2]
         assert k.shape[:2] == (self.B, self.Hkv) and B == self.B
         mass = np.zeros((self.B, self.Hkv, T), dtype=np.float64) if want_mass else None
         c = self._c()
-        lib().orc_select_psa(C.byref(c), Hq, _p(q_tail), _p(k), T, W, top_k, sm_scale, _p(mass))
+        fn = lib().orc_select_psa_shared if share_heads else lib().orc_select_psa
+        fn(C.byref(c), Hq, _p(q_tail), _p(k), T, W, top_k, sm_scale, _p(mass))
         return mass
 
     def quantize_append(self, k_new, v_new, clip: float, rotate_v: bool = True, rotate_k: bool = True):

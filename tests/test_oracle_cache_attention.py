@@ -308,3 +308,28 @@ def test_no_rotation_mode_is_plain_quantized_attention(orc):
         o, l = _softmax_attention(d["q"][0, hq].astype(np.float64), K, V, w.sm_scale)
         assert np.allclose(out[0, hq], o, rtol=1e-9, atol=1e-11)
         assert abs(lse[0, hq] - l) < 1e-9
+
+
+def test_psa_token_level_pivots_share_the_heads(orc):
+    """Section III-B.2 has one pivot set per layer: with shared heads the masses of a batch element's kv-heads are added
+    and every head gets the top-k of the sum (checked against numpy on the per-head masses, which are pinned above)."""
+    w = synth.small("psa_sh", B=2, Hq=6, Hkv=3, T=90, W=8, top_k=5)
+    d = _gen(w, seed=31)
+    per_head = orc.OracleCache(2, 3, 128, 128, 64)
+    mass = per_head.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale, want_mass=True)
+    shared = orc.OracleCache(2, 3, 128, 128, 64)
+    mass2 = shared.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale, want_mass=True, share_heads=True)
+    assert np.array_equal(mass, mass2)                       # the masses themselves are the per-head ones
+    for b in range(2):
+        total = mass[b].sum(axis=0)
+        want = sorted(sorted(range(w.T), key=lambda t: (-total[t], t))[:w.top_k])
+        for h in range(3):
+            assert shared.sal_cnt[b, h] == w.top_k
+            assert list(shared.sal_idx[b, h, :w.top_k]) == want
+    # a single kv-head: nothing to share
+    w1 = synth.small("psa_sh1", B=1, Hq=2, Hkv=1, T=60, W=8, top_k=4)
+    d1 = _gen(w1, seed=32)
+    a, b_ = orc.OracleCache(1, 1, 128, 64, 64), orc.OracleCache(1, 1, 128, 64, 64)
+    a.select_psa(d1["q_tail"], d1["k"], 4, w1.sm_scale)
+    b_.select_psa(d1["q_tail"], d1["k"], 4, w1.sm_scale, share_heads=True)
+    assert np.array_equal(a.sal_idx, b_.sal_idx) and np.array_equal(a.sal_cnt, b_.sal_cnt)
