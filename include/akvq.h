@@ -56,7 +56,7 @@ typedef enum {
   AKVQ_ERR_HIP = -5          /* a kernel launch failed; see akvq_last_hip_error() */
 } akvq_status;
 
-enum { AKVQ_MODE_TSA = 0, AKVQ_MODE_PSA = 1 };
+enum { AKVQ_MODE_TSA = 0, AKVQ_MODE_PSA = 1, AKVQ_MODE_PSA_SHARED = 2 };
 
 /* flags */
 enum {
@@ -130,6 +130,8 @@ int akvq_decode_default_splits(int B, int Hkv, int T_len);
  *       Operands are rounded to bfloat16, products accumulate in fp32 on the matrix cores, softmax in fp32.
  *       Needs q_tail (device, [B][Hq][W][128] binary16, post-RoPE) and k (device, [B][Hkv][T][128] binary16,
  *       post-RoPE, un-rotated).  Ties go to the lower position.  W must be a multiple of 16, W <= T, W <= 64.
+ *   mode AKVQ_MODE_PSA_SHARED: token-level pivots as in the paper (one pivot set per layer): the masses of a batch
+ *       element's kv-heads are added (head order, fp32) and every kv-head gets the top_k positions of the sum.
  *   Output: c->sal_idx (ascending) and c->sal_cnt.  mass_out (device, [B][Hkv][T] fp32) is optional (PSA).
  *   workspace: device, akvq_select_workspace_bytes() bytes (PSA only; may be NULL for TSA).
  */

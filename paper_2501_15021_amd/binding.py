@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libakvq.so")
 
 D = 128
-MODE_TSA, MODE_PSA = 0, 1
+MODE_TSA, MODE_PSA, MODE_PSA_SHARED = 0, 1, 2
 V_PREROTATED, OUT_ROTATED, K_PREROTATED, Q_PREROTATED = 1, 2, 4, 8
 
 EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",

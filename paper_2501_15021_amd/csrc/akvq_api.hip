@@ -77,7 +77,8 @@ size_t akvq_select_workspace_bytes(int B, int Hq, int Hkv, int T, int W) {
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || W <= 0) return 0;
   const size_t stats = (size_t)B * Hq * select_chunks(T) * W * 2 * sizeof(float);
   const size_t mass = (size_t)B * Hkv * T * sizeof(float);
-  return round_up(stats, 256) + round_up(mass, 256);
+  const size_t shared = (size_t)B * T * sizeof(float);  // AKVQ_MODE_PSA_SHARED: the kv-heads' masses added
+  return round_up(stats, 256) + round_up(mass, 256) + round_up(shared, 256);
 }
 
 size_t akvq_decode_workspace_bytes(int B, int Hq, int n_split) {
@@ -118,7 +119,7 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
     a.Hq = c->Hkv;
     return hip_status(akvq::launch_select_tsa(a, s));
   }
-  if (mode != AKVQ_MODE_PSA) return AKVQ_ERR_INVALID_ARG;
+  if (mode != AKVQ_MODE_PSA && mode != AKVQ_MODE_PSA_SHARED) return AKVQ_ERR_INVALID_ARG;
   if (!q_tail || !k || !aligned16(q_tail) || !aligned16(k)) return AKVQ_ERR_INVALID_ARG;
   if (Hq <= 0 || Hq % c->Hkv != 0 || W <= 0 || W > T || top_k <= 0) return AKVQ_ERR_INVALID_ARG;
   if (W % 16 != 0 || W > 64) return AKVQ_ERR_UNSUPPORTED;
@@ -132,7 +133,10 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
   a.n_chunk = select_chunks(T);
   a.row_stats = static_cast<float *>(workspace);
   const size_t stats = round_up((size_t)c->B * Hq * a.n_chunk * W * 2 * sizeof(float), 256);
+  const size_t mass_bytes = round_up((size_t)c->B * c->Hkv * T * sizeof(float), 256);
   a.mass = mass_out ? mass_out : reinterpret_cast<float *>(static_cast<char *>(workspace) + stats);
+  if (mode == AKVQ_MODE_PSA_SHARED)
+    a.mass_shared = reinterpret_cast<float *>(static_cast<char *>(workspace) + stats + mass_bytes);
   return hip_status(akvq::launch_select_psa(a, s));
 }
 

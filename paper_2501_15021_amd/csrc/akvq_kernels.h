@@ -69,6 +69,7 @@ struct SelectArgs {
   float floor;
   int mass_per_batch;        // top-k reads mass[b][T] (shared by the batch element's kv-heads) instead of mass[b][hkv][T]
   int skip_zero;
+  float *mass_shared;        // token-level pivots: [B][T] sums of the kv-heads' masses (workspace), null: per-head lists
 };
 constexpr int kScoreChunk = 2048;  // keys per scoring workgroup
 hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream);

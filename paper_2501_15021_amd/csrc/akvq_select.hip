@@ -555,6 +555,20 @@ hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream) {
   return hipGetLastError();
 }
 
+namespace {
+
+// token-level pivots: the masses of a batch element's kv-heads added in head order (one thread per position)
+__global__ __launch_bounds__(256) void sum_heads_kernel(SelectArgs a) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long)a.B * a.T) return;
+  const int b = (int)(i / a.T), t = (int)(i % a.T);
+  float sum = 0.0f;
+  for (int h = 0; h < a.Hkv; ++h) sum += a.mass[((size_t)b * a.Hkv + h) * a.T + t];
+  a.mass_shared[i] = sum;
+}
+
+}  // namespace
+
 template <int NRB>
 static void launch_psa_passes(const SelectArgs &a, hipStream_t stream) {
   const dim3 block(256);
@@ -571,6 +585,14 @@ hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream) {
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  SelectArgs k = a;  // what the top-k reads
+  if (a.mass_shared != nullptr) {
+    hipLaunchKernelGGL(sum_heads_kernel, dim3((unsigned)(((long)a.B * a.T + 255) / 256)), dim3(256), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    k.mass = a.mass_shared;
+    k.mass_per_batch = 1;
+  }
   if (a.T <= kTopkStageMax) {
     const size_t lds = (size_t)a.T * sizeof(float);
     if (lds > 48 * 1024) {  // large dynamic LDS has to be opted into
@@ -578,9 +600,9 @@ hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream) {
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
       if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, a);
+    hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, k);
   } else
-    hipLaunchKernelGGL(topk_kernel<false>, dim3(a.B * a.Hkv), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(topk_kernel<false>, dim3(a.B * a.Hkv), dim3(256), 0, stream, k);
   return hipGetLastError();
 }
 

@@ -534,3 +534,32 @@ def test_non_finite_inputs_stay_in_their_unit(orc, Hq, Hkv):
             heads = slice(h * R, (h + 1) * R)
             assert_attention_close(out[b:b + 1, heads], lse[b:b + 1, heads], ref[b:b + 1, heads], lse_ref[b:b + 1, heads],
                                    f"unit {(b, h)}")
+
+
+@pytest.mark.parametrize("Hq,Hkv,T,top_k", [(6, 3, 500, 7), (8, 8, 2100, 16), (14, 2, 333, 4)])
+def test_select_psa_token_level(orc, Hq, Hkv, T, top_k):
+    """AKVQ_MODE_PSA_SHARED: the kv-heads' masses are added and every head of a batch element gets the same list."""
+    w = synth.small(f"psa_sh{Hq}", B=2, Hq=Hq, Hkv=Hkv, T=T, W=16, top_k=top_k, n_text_head=9, n_text_tail=4)
+    d = _np(synth.generate(w, seed=221))
+    oc, gc = make_pair(orc, w, s_cap=64)
+    mass_ref = oc.select_psa(d["q_tail"], d["k"], top_k, w.sm_scale, want_mass=True, share_heads=True)
+    mass = torch.zeros(w.B, Hkv, T, dtype=torch.float32, device="cuda")
+    akvq.select_salient(gc, akvq.MODE_PSA_SHARED, q_tail=_dev(d["q_tail"]), k=_dev(d["k"]), top_k=top_k,
+                        sm_scale=w.sm_scale, mass_out=mass)
+    torch.cuda.synchronize()
+    idx, cnt = gc.sal_idx.cpu().numpy(), gc.counts().cpu().numpy()
+    assert (cnt == top_k).all()
+    m = mass.cpu().numpy()
+    for b in range(w.B):
+        total = np.zeros(T, dtype=np.float32)
+        for h in range(Hkv):
+            total = total + m[b, h]                                # head order, fp32: what the kernel adds
+        order = sorted(range(T), key=lambda t: (-total[t], t))[:top_k]
+        for h in range(Hkv):
+            assert list(idx[b, h, :top_k]) == sorted(order), f"list of {(b, h)}"
+        ref = oc.sal_idx[b, 0, :top_k]
+        if not np.array_equal(idx[b, 0, :top_k], ref):             # near-ties at the boundary only
+            tot_ref = mass_ref[b].sum(axis=0)
+            kth = np.sort(tot_ref)[::-1][top_k - 1]
+            for t in set(idx[b, 0, :top_k].tolist()) ^ set(ref.tolist()):
+                assert abs(tot_ref[t] - kth) <= 2e-4 * max(1.0, tot_ref.max())
