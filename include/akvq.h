@@ -10,7 +10,8 @@
  *   - Every pointer named "device" is GPU memory owned by the caller.  The library allocates nothing,
  *     frees nothing and never synchronises: each call validates its arguments on the host, enqueues
  *     kernels on `stream` (a hipStream_t passed as void*, NULL = default stream) and returns.
- *   - All device pointers must be 16-byte aligned.
+ *   - All device pointers must be 16-byte aligned, except is_text (bytes, any alignment).
+ *   - B * Hkv (and B * Hq for the pivot score) must not exceed 65535 (a launch-grid limit): AKVQ_ERR_UNSUPPORTED.
  *   - Return value: AKVQ_OK or a negative akvq_status.  Argument errors launch nothing.
  *   - head_dim is fixed to 128, codes are 2-bit, the quantization group G is 64 or 128 channels of
  *     the rotated head vector.
@@ -120,6 +121,12 @@ size_t akvq_select_workspace_bytes(int B, int Hq, int Hkv, int T, int W);
 size_t akvq_decode_workspace_bytes(int B, int Hq, int n_split);
 /* Host helper: number of KV splits akvq_decode_attention uses when n_split <= 0 is passed. */
 int akvq_decode_default_splits(int B, int Hkv, int T_len);
+
+/* Host helper: how the decode kernels deal the n_tiles tiles of the code stream (64 rows each when Hq == Hkv, else 32)
+ * to n_split KV splits: split `split` reads tiles [*begin, *end) (equal runs of ceil(n_tiles / n_split); trailing
+ * splits can be empty).  Returns the split whose run holds the last tile, which in akvq_decode_step is the one that
+ * writes the new row (0 when n_tiles is 0), or AKVQ_ERR_INVALID_ARG. */
+int akvq_decode_split_range(int n_tiles, int n_split, int split, int *begin, int *end);
 
 /*
  * akvq_select_salient -- Section III-B: write the salient-token list of every (batch, kv-head).
@@ -237,8 +244,9 @@ int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, c
  *   plain row (codes, meta, the recent-window rings, the overlay if the row is listed in c->sal_idx), then decode
  *   attention runs over the T_len + 1 rows as akvq_decode_attention_rope would: the cache holds the bits of the
  *   separate append, the output those of the separate decode call when n_split is 1 (with more splits the 16-bit rows
- *   are all read by the last split, so they enter the sums in another order).  The new row is written by the
- *   workgroups of the last KV split before they read it; no other workgroup reads it.
+ *   are all read by one split, so they enter the sums in another order).  The new row is written by the workgroups
+ *   of the KV split that holds the row's tile (akvq_decode_split_range) before they read it; no other workgroup
+ *   reads it.
  *   c->T_len is the number of rows already cached (0 is allowed); advance it by one
  *   afterwards.  rope (may be NULL): one table row per batch element, used for the new K row and for q.  clip: the
  *   2-bit clip ratio.  flags: write- and read-path flags together.  Everything else as in the two entry points.

@@ -21,6 +21,7 @@ V_PREROTATED, OUT_ROTATED, K_PREROTATED, Q_PREROTATED = 1, 2, 4, 8
 
 EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
+           "akvq_decode_split_range",
            "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention",
            "akvq_quantize_append_tiered", "akvq_decode_attention_tiered", "akvq_quantize_append_rope",
            "akvq_decode_attention_rope", "akvq_decode_step",
@@ -70,6 +71,8 @@ def lib() -> C.CDLL:
         L.akvq_decode_workspace_bytes.argtypes = [C.c_int] * 3
         L.akvq_decode_default_splits.restype = C.c_int
         L.akvq_decode_default_splits.argtypes = [C.c_int] * 3
+        L.akvq_decode_split_range.restype = C.c_int
+        L.akvq_decode_split_range.argtypes = [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_int), C.POINTER(C.c_int)]
         L.akvq_select_salient.restype = C.c_int
         L.akvq_select_salient.argtypes = [C.POINTER(akvq_cache), C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p,
                                           C.c_int, C.c_int, C.c_int, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,

@@ -29,6 +29,10 @@ int check_cache_pointers(const akvq_cache *c) {
   return AKVQ_OK;
 }
 
+// (batch, head) units index the second grid dimension of the streaming kernels, which the runtime caps at 65535
+constexpr long kMaxGridUnits = 65535;
+inline bool too_many_units(long units) { return units > kMaxGridUnits; }
+
 int hip_status(hipError_t e) {
   if (e == hipSuccess) return AKVQ_OK;
   g_last_hip_error = (int)e;
@@ -102,6 +106,12 @@ int akvq_decode_default_splits(int B, int Hkv, int T_len) {
   return (int)want;
 }
 
+int akvq_decode_split_range(int n_tiles, int n_split, int split, int *begin, int *end) {
+  if (n_tiles < 0 || n_split <= 0 || split < 0 || split >= n_split || !begin || !end) return AKVQ_ERR_INVALID_ARG;
+  akvq::decode_split_range(n_tiles, n_split, split, *begin, *end);
+  return akvq::decode_last_tile_split(n_tiles, n_split);
+}
+
 int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, const void *q_tail, int Hq,
                         const void *k, int T, int W, int top_k, float sm_scale, float *mass_out,
                         void *workspace, size_t workspace_bytes, void *stream) {
@@ -123,6 +133,7 @@ int akvq_select_salient(const akvq_cache *c, int mode, const uint8_t *is_text, c
   if (!q_tail || !k || !aligned16(q_tail) || !aligned16(k)) return AKVQ_ERR_INVALID_ARG;
   if (Hq <= 0 || Hq % c->Hkv != 0 || W <= 0 || W > T || top_k <= 0) return AKVQ_ERR_INVALID_ARG;
   if (W % 16 != 0 || W > 64) return AKVQ_ERR_UNSUPPORTED;
+  if (too_many_units((long)c->B * Hq)) return AKVQ_ERR_UNSUPPORTED;
   if (top_k > c->S_cap) return AKVQ_ERR_CAPACITY;
   if (mass_out && !aligned16(mass_out)) return AKVQ_ERR_INVALID_ARG;
   if (!workspace || !aligned16(workspace)) return AKVQ_ERR_INVALID_ARG;
@@ -145,6 +156,7 @@ int akvq_fold_hadamard(const void *w_in, void *w_out, int rows, int cols, int ax
   if (axis != 0 && axis != 1) return AKVQ_ERR_INVALID_ARG;
   if ((axis == 1 ? cols : rows) % 128 != 0) return AKVQ_ERR_INVALID_ARG;
   if (axis == 0 && w_in == w_out) return AKVQ_ERR_INVALID_ARG;
+  if (axis == 0 && too_many_units(rows / 128)) return AKVQ_ERR_UNSUPPORTED;
   return hip_status(akvq::launch_fold_hadamard(static_cast<const uint16_t *>(w_in), static_cast<uint16_t *>(w_out), rows,
                                                cols, axis, static_cast<hipStream_t>(stream)));
 }
@@ -204,6 +216,7 @@ static int quantize_args(const akvq_cache *c, const void *k_new, const void *v_n
   if (st != AKVQ_OK) return st;
   if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new) || n_new <= 0 || n_src <= 0) return AKVQ_ERR_INVALID_ARG;
   if (!(clip > 0.0f) || clip > 1.0f || !(clip4 > 0.0f) || clip4 > 1.0f) return AKVQ_ERR_INVALID_ARG;
+  if (too_many_units((long)c->B * c->Hkv)) return AKVQ_ERR_UNSUPPORTED;
   if ((long)c->T_len + n_new > c->T_cap) return AKVQ_ERR_CAPACITY;
   a = akvq::QuantArgs{};
   a.row_src = row_src; a.row_tier = row_tier; a.fine_mask = fine_mask; a.n_src = n_src; a.clip4 = clip4;
@@ -292,6 +305,7 @@ static int decode_args(const akvq_cache *c, const uint32_t *fine_mask, const akv
   if (lse_out && !aligned16(lse_out)) return AKVQ_ERR_INVALID_ARG;
   if (Hq <= 0 || Hq % c->Hkv != 0) return AKVQ_ERR_INVALID_ARG;
   if (Hq / c->Hkv > 8) return AKVQ_ERR_UNSUPPORTED;
+  if (too_many_units((long)c->B * c->Hkv)) return AKVQ_ERR_UNSUPPORTED;
   if (n_split <= 0) n_split = akvq_decode_default_splits(c->B, c->Hkv, c->T_len);
   if (n_split > 1024) return AKVQ_ERR_INVALID_ARG;
   if (!workspace || !aligned16(workspace)) return AKVQ_ERR_INVALID_ARG;

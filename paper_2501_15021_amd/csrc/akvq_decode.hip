@@ -178,10 +178,9 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
 
   // ---- tile bookkeeping and the first two tiles' loads come first: they do not depend on the query, so their
   // latency overlaps with the query rotation below ----
-  const int n_tiles = (a.t_win + 63) / 64;  // rows from t_win on are read from the recent-window rings
-  const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
-  const int tile_begin = split * tiles_per_split;
-  const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
+  const int n_tiles = (a.t_win + kMhaTileRows - 1) / kMhaTileRows;  // rows from t_win on are read from the recent-window rings
+  int tile_begin, tile_end;
+  decode_split_range(n_tiles, a.n_split, split, tile_begin, tile_end);
   const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
   const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
   const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
@@ -210,11 +209,11 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
   auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
   MhaTile<NG> tb[3];
-  // Fused decode step: the workgroups of the last split first write the new row (wavefront 1 the K row, wavefront 2
-  // the V row, while wavefront 0 stages the query); the barrier below orders those stores before this workgroup's
-  // loads of the tile that holds the row.  A wavefront whose first two tiles include that tile asks for them after
-  // the barrier instead of here.
-  const bool appends = a.fused_append != 0 && split == a.n_split - 1;  // uniform over the workgroup
+  // Fused decode step: the workgroups of the split that owns the row's tile first write the new row (wavefront 1
+  // the K row, wavefront 2 the V row, while wavefront 0 stages the query); the barrier below orders those stores
+  // before this workgroup's loads of the tile that holds the row, and no other workgroup reads that tile.  A wavefront
+  // whose first two tiles include that tile asks for them after the barrier instead of here.
+  const bool appends = a.fused_append != 0 && split == a.append_split;  // uniform over the workgroup
   const bool defer_loads = appends && a.t_win == a.T_len && n_mine > 0 &&
                            (tile_at(0) == n_tiles - 1 || tile_at(1) == n_tiles - 1);
   if (n_mine > 0 && !defer_loads) {
@@ -419,7 +418,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   // Used twice: the salient overlay (slot = rank in the salient list) and the recent-window rings (slot = row mod W).
   auto bf16_units = [&](const uint16_t *ks_base, const uint16_t *vs_base, int cnt, auto &&row_ok) {
     const int n_units = (cnt + 63) / 64;
-    // fused decode step: the 16-bit rows (one of which may be the new row) are read by the last split only
+    // fused decode step: the 16-bit rows (one of which may be the new row) are read by the appending split only
     const int unit_step = a.fused_append ? kWaves : kWaves * a.n_split;
     const int unit_first = a.fused_append ? (appends ? wave : n_units) : split + wave * a.n_split;
     for (int unit = unit_first; unit < n_units; unit += unit_step) {
@@ -587,9 +586,10 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 
   for (int x = tid; x < 16 * kD; x += 64 * kWaves) { (&q_scaled[0][0])[x] = 0; (&q_plain[0][0])[x] = 0; }
   for (int x = lane; x < NG * 16 * kTokBlock; x += 64) (&w_lds[0][0][0])[x] = 0;
-  // Fused decode step: the workgroups of the last split first write the new row (wavefront 3 the K row, wavefront 2
-  // the V row); the barrier below orders those stores before this workgroup's loads, which all come later.
-  const bool appends = a.fused_append != 0 && split == a.n_split - 1;  // uniform over the workgroup
+  // Fused decode step: the workgroups of the split that owns the row's tile first write the new row (wavefront 3 the
+  // K row, wavefront 2 the V row); the barrier below orders those stores before this workgroup's loads, which all
+  // come later, and no other workgroup reads that tile.
+  const bool appends = a.fused_append != 0 && split == a.append_split;  // uniform over the workgroup
   if (appends && wave >= 2) {
     __shared__ __attribute__((aligned(16))) uint8_t step_codes[2][kD];
     __shared__ __attribute__((aligned(16))) uint16_t step_row[2][kD];
@@ -714,10 +714,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   };
 
   // ================= code stream =================
-  const int n_tiles = (a.t_win + 31) / 32;  // rows from t_win on are read from the recent-window rings
-  const int tiles_per_split = (n_tiles + a.n_split - 1) / a.n_split;
-  const int tile_begin = split * tiles_per_split;
-  const int tile_end = min(n_tiles, tile_begin + tiles_per_split);
+  const int n_tiles = (a.t_win + kGqaTileRows - 1) / kGqaTileRows;  // rows from t_win on are read from the recent-window rings
+  int tile_begin, tile_end;
+  decode_split_range(n_tiles, a.n_split, split, tile_begin, tile_end);
   const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
   const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
   const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
@@ -861,7 +860,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   // Used twice: the salient overlay (slot = rank in the salient list) and the recent-window rings (slot = row mod W).
   auto bf16_units = [&](const uint16_t *ks_base, const uint16_t *vs_base, int cnt, auto &&row_ok) {
     const int n_units = (cnt + 31) / 32;
-    // fused decode step: the 16-bit rows (one of which may be the new row) are read by the last split only
+    // fused decode step: the 16-bit rows (one of which may be the new row) are read by the appending split only
     const int unit_step = a.fused_append ? kWaves : kWaves * a.n_split;
     const int first_unit = a.fused_append ? (appends ? wave : n_units) : split + wave * a.n_split;
     if (first_unit >= n_units) return;
@@ -1028,7 +1027,12 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
 
 }  // namespace
 
-hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream) {
+hipError_t launch_decode_attention(const DecodeArgs &a_in, int G, hipStream_t stream) {
+  DecodeArgs a = a_in;
+  {
+    const int rows = a.Hq == a.Hkv ? kMhaTileRows : kGqaTileRows;
+    a.append_split = decode_last_tile_split((a.t_win + rows - 1) / rows, a.n_split);
+  }
   dim3 grid(a.n_split, a.B * a.Hkv), block(64 * kWaves);
   if (a.Hq == a.Hkv) {
     if (a.fine_mask) {

@@ -45,13 +45,32 @@ struct DecodeArgs {
   float sm_scale;
   int q_rotated, out_rotated;
   // the decode step in one launch: row T_len - 1 is first quantized from step.k_new / step.v_new (step.T_len is that
-  // row) by the workgroups of the last KV split, which are also the only ones to read 16-bit rows then
+  // row) by the workgroups of split append_split: the split whose tile range holds the tile of that row (see
+  // decode_split_range), so that the row is written and read by the same workgroup.  They are also the only ones to
+  // read 16-bit rows then.
   int fused_append;
+  int append_split;
   QuantArgs step;
   const uint16_t *rope_cos, *rope_sin;  // rotary tables for pre-RoPE queries (null: none), one row of 64 per batch element
   long long rope_stride;
 };
 constexpr int kPartialStride = 132;  // m, l, 2 pad, 128 accumulators
+
+// How the code stream's n_tiles tiles are dealt to the n_split KV splits: equal runs of ceil(n_tiles / n_split) tiles,
+// so trailing splits can be short or empty.  Used by the kernels, by the host (append_split) and by the public helper
+// akvq_decode_split_range, so that all three agree by construction.
+__host__ __device__ inline void decode_split_range(int n_tiles, int n_split, int split, int &begin, int &end) {
+  const int per = (n_tiles + n_split - 1) / n_split;
+  begin = split * per < n_tiles ? split * per : n_tiles;
+  end = begin + per < n_tiles ? begin + per : n_tiles;
+}
+// the split whose range holds the last tile (the tile of the row a fused decode step appends); split 0 if there is no tile
+__host__ __device__ inline int decode_last_tile_split(int n_tiles, int n_split) {
+  if (n_tiles <= 0) return 0;
+  const int per = (n_tiles + n_split - 1) / n_split;
+  return (n_tiles - 1) / per;
+}
+constexpr int kMhaTileRows = 64, kGqaTileRows = 32;  // rows per code-stream tile of the two decode kernels
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream);
 
 struct SelectArgs {

@@ -4,6 +4,8 @@
 //   is the attention-column mass of the last W prompt rows, computed on the matrix cores (bfloat16 operands, fp32
 //   accumulate, fp32 softmax) in two streaming passes over K (row statistics, then column sums), followed by an
 //   exact top-k (radix select on the fp32 bit patterns, ties to the lower position).
+#include <atomic>
+
 #include "akvq_device.h"
 #include "akvq_kernels.h"
 
@@ -531,6 +533,20 @@ __global__ __launch_bounds__(256) void massive_score_kernel(SelectArgs a) {
 
 }  // namespace
 
+// Dynamic LDS above 48 KB has to be opted into, per device and process: done on the first launch that needs it on a
+// device (for the largest size the kernel is ever given), not on every call.
+static hipError_t topk_allow_large_lds() {
+  static std::atomic<unsigned long long> done{0};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < 64 && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)(kTopkStageMax * sizeof(float)));
+  if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
+  return e;
+}
+
 hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream) {
   const long rows = (long)a.B * a.T;
   hipLaunchKernelGGL(massive_score_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, a);
@@ -539,8 +555,7 @@ hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream) {
   if (a.T <= kTopkStageMax) {
     const size_t lds = (size_t)a.T * sizeof(float);
     if (lds > 48 * 1024) {
-      e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      e = topk_allow_large_lds();
       if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, a);
@@ -595,9 +610,8 @@ hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream) {
   }
   if (a.T <= kTopkStageMax) {
     const size_t lds = (size_t)a.T * sizeof(float);
-    if (lds > 48 * 1024) {  // large dynamic LDS has to be opted into
-      e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (lds > 48 * 1024) {
+      e = topk_allow_large_lds();
       if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, k);

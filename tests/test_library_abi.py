@@ -51,6 +51,37 @@ def test_host_helpers(L):
         assert 1 <= n <= 64 and n <= max(1, (args[2] + 63) // 64)
 
 
+def test_decode_split_partition(L):
+    """The KV-split partition the decode kernels use (the library exports the very function they call): the runs are
+    disjoint, ordered and cover every tile; the split the fused decode step appends in is the one whose run holds the
+    last tile -- also when trailing splits are empty (n_tiles < n_split, 5 tiles in 4 splits, ...), so the new row is
+    written and read by the same workgroup."""
+    b, e = C.c_int(), C.c_int()
+    for n_tiles in list(range(0, 140)) + [289, 545, 1024, 1033]:
+        for n_split in list(range(1, 70)) + [1024]:
+            nxt, owner_seen = 0, None
+            owner = None
+            for s in range(n_split):
+                owner = L.akvq_decode_split_range(n_tiles, n_split, s, C.byref(b), C.byref(e))
+                assert 0 <= owner < n_split
+                assert b.value == min(nxt, n_tiles) and b.value <= e.value <= n_tiles
+                nxt = e.value
+                if b.value <= n_tiles - 1 < e.value:
+                    owner_seen = s
+            assert nxt == n_tiles
+            assert owner == (owner_seen if n_tiles else 0), (n_tiles, n_split)
+    # the default split count at shapes where the last split is empty: the owner is not the last split
+    for B, Hkv, T, rows in ((1, 28, 18433, 64), (2, 4, 34817, 32)):
+        ns = L.akvq_decode_default_splits(B, Hkv, T)
+        n_tiles = (T + rows - 1) // rows
+        owner = L.akvq_decode_split_range(n_tiles, ns, 0, C.byref(b), C.byref(e))
+        L.akvq_decode_split_range(n_tiles, ns, owner, C.byref(b), C.byref(e))
+        assert b.value <= n_tiles - 1 < e.value
+    assert L.akvq_decode_split_range(4, 0, 0, C.byref(b), C.byref(e)) == -1
+    assert L.akvq_decode_split_range(4, 2, 2, C.byref(b), C.byref(e)) == -1
+    assert L.akvq_decode_split_range(4, 2, 0, None, C.byref(e)) == -1
+
+
 def test_argument_errors_launch_nothing(L):
     """Null pointers are rejected on the host before any launch (safe without a GPU)."""
     from paper_2501_15021_amd.binding import akvq_cache
@@ -83,6 +114,8 @@ def test_every_error_code_of_every_entry_point(L):
     assert q(C.byref(cache()), P, P, 4, 1.5, 0, None) == INVALID
     assert q(C.byref(cache(G=32)), P, P, 4, 0.8, 0, None) == UNSUPPORTED
     assert q(C.byref(cache(k_codes=None)), P, P, 4, 0.8, 0, None) == INVALID
+    assert q(C.byref(cache(B=2048, Hkv=32)), P, P, 4, 0.8, 0, None) == UNSUPPORTED   # 65536 units: beyond the grid limit
+    assert q(C.byref(cache(B=2047, Hkv=32, T_len=126)), P, P, 4, 0.8, 0, None) == CAPACITY   # 65504 units pass that check
     qt = L.akvq_quantize_append_tiered
     win = akvq_window(P, P, 96)                                                  # not a multiple of 64
     assert qt(C.byref(cache()), P, P, 4, None, None, 4, 0.8, 1.0, None, C.byref(win), 0, None) == INVALID
@@ -99,6 +132,7 @@ def test_every_error_code_of_every_entry_point(L):
     assert d(C.byref(cache(T_len=5)), P, 2, 0.1, P, None, 4, P, 64, 0, None) == WORKSPACE
     assert d(C.byref(cache(T_len=5)), P, 2, 0.1, P, None, 4, None, big, 0, None) == INVALID
     assert d(C.byref(cache(T_len=5)), P, 2, 0.1, P, P + 4, 1, P, big, 0, None) == INVALID           # misaligned lse
+    assert d(C.byref(cache(B=16384, Hkv=4, T_len=5)), P, 4, 0.1, P, None, 1, P, 1 << 40, 0, None) == UNSUPPORTED   # grid limit
     dt = L.akvq_decode_attention_tiered
     assert dt(C.byref(cache(T_len=5)), P + 4, None, P, 2, 0.1, P, None, 1, P, big, 0, None) == INVALID
     win = akvq_window(P, P, 0)
@@ -113,6 +147,7 @@ def test_every_error_code_of_every_entry_point(L):
     assert s(C.byref(cache()), 1, None, P, 2, P, 64, 16, 65, 0.1, None, P, big, None) == CAPACITY
     assert s(C.byref(cache()), 1, None, P, 2, P, 64, 16, 4, 0.1, None, P, 16, None) == WORKSPACE
     assert s(C.byref(cache()), 1, None, P, 2, P, 8, 16, 4, 0.1, None, P, big, None) == INVALID             # W > T
+    assert s(C.byref(cache(B=8192, Hkv=1)), 1, None, P, 8, P, 64, 16, 4, 0.1, None, P, 1 << 40, None) == UNSUPPORTED  # B*Hq
     m = L.akvq_select_massive
     assert m(C.byref(cache()), P, 64, 1000, 4, 0.0, None, P, big, None) == UNSUPPORTED                     # d_model % 512
     assert m(C.byref(cache()), P, 64, 1024, 65, 0.0, None, P, big, None) == CAPACITY
