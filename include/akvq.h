@@ -192,6 +192,21 @@ int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_s
                           int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 
 /*
+ * akvq_decode_attention_static -- akvq_decode_attention for callers that cannot allocate or pass device scratch memory:
+ *   code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The split-KV partial results
+ *   go to a fixed array inside the library's device image (akvq_decode_static_scratch_bytes() = 8 MiB per GPU, held
+ *   until the process ends) instead of a caller workspace; the call allocates and frees nothing.  Same kernels, same
+ *   results as akvq_decode_attention with the same n_split.  Requests whose partials do not fit
+ *   (akvq_decode_workspace_bytes(B, Hq, n_split) above the limit, i.e. B * Hq * n_split > 15887) are rejected with
+ *   AKVQ_ERR_WORKSPACE before anything is launched.  Every call on a GPU shares that GPU's array: calls that overlap
+ *   on one GPU (different streams, or threads) race; calls on one stream are ordered.  Nothing in the array needs to
+ *   start at zero: every (head, split) slot is written by the call before its merge pass reads it.
+ */
+size_t akvq_decode_static_scratch_bytes(void);
+int akvq_decode_attention_static(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+                                 int n_split, uint32_t flags, void *stream);
+
+/*
  * akvq_quantize_append_tiered -- the write path with the 4-bit text tier of Section III-C.1.
  *   Cache row T_len + r of batch element b takes source token row_src[b][r] (an index into k_src / v_src, device,
  *   [B][Hkv][n_src][128] binary16) and tier row_tier[b][r] (device, [B][n_rows] uint8, AKVQ_TIER_*):

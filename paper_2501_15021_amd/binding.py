@@ -25,6 +25,7 @@ EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_b
            "akvq_select_salient", "akvq_quantize_append", "akvq_decode_attention",
            "akvq_quantize_append_tiered", "akvq_decode_attention_tiered", "akvq_quantize_append_rope",
            "akvq_decode_attention_rope", "akvq_decode_step",
+           "akvq_decode_static_scratch_bytes", "akvq_decode_attention_static",
            "akvq_massive_workspace_bytes", "akvq_select_massive", "akvq_fold_hadamard"]
 TIER_2BIT, TIER_4BIT_COARSE, TIER_4BIT_FINE, TIER_PAD = 0, 1, 2, 3
 
@@ -83,6 +84,11 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention.restype = C.c_int
         L.akvq_decode_attention.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                             C.c_void_p, C.c_int, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+        L.akvq_decode_static_scratch_bytes.restype = C.c_size_t
+        L.akvq_decode_static_scratch_bytes.argtypes = []
+        L.akvq_decode_attention_static.restype = C.c_int
+        L.akvq_decode_attention_static.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
+                                                   C.c_void_p, C.c_int, C.c_uint32, C.c_void_p]
         L.akvq_fold_hadamard.restype = C.c_int
         L.akvq_fold_hadamard.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.akvq_massive_workspace_bytes.restype = C.c_size_t
@@ -316,6 +322,19 @@ def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: in
     _check(lib().akvq_decode_attention(C.byref(c), _ptr(q), Hq, sm_scale, _ptr(out), _ptr(lse), n_split, _ptr(ws),
                                        ws.numel(), flags, _stream()), "akvq_decode_attention")
     return out, lse
+
+
+def decode_attention_static(cache: Cache, q: torch.Tensor, sm_scale: float, out: torch.Tensor, lse: torch.Tensor,
+                            n_split: int = 0, flags: int = 0) -> None:
+    """akvq_decode_attention_static: the partials live in the library's fixed device array; the caller supplies out
+    [B,Hq,128] fp32 and lse [B,Hq] fp32, and nothing is allocated on the way."""
+    assert q.dtype == torch.float16 and q.is_contiguous()
+    assert out.dtype == torch.float32 and out.is_contiguous() and lse.dtype == torch.float32 and lse.is_contiguous()
+    B, Hq, _ = q.shape
+    assert tuple(out.shape) == (B, Hq, D) and tuple(lse.shape) == (B, Hq)
+    c = cache.struct()
+    _check(lib().akvq_decode_attention_static(C.byref(c), _ptr(q), Hq, sm_scale, _ptr(out), _ptr(lse), n_split, flags,
+                                              _stream()), "akvq_decode_attention_static")
 
 
 def decode_step(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, q: torch.Tensor, clip: float, sm_scale: float,

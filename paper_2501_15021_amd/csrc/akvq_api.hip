@@ -281,6 +281,22 @@ int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_s
                                     workspace_bytes, flags, stream);
 }
 
+size_t akvq_decode_static_scratch_bytes(void) { return akvq::kDecodeStaticScratchBytes; }
+
+int akvq_decode_attention_static(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+                                 int n_split, uint32_t flags, void *stream) {
+  // size check first, on the host, so that an oversize request launches nothing and touches no device state
+  if (!c || c->B <= 0 || c->Hkv <= 0 || Hq <= 0) return AKVQ_ERR_INVALID_ARG;
+  if (n_split <= 0) n_split = akvq_decode_default_splits(c->B, c->Hkv, c->T_len);
+  if (n_split > 1024) return AKVQ_ERR_INVALID_ARG;
+  if (akvq_decode_workspace_bytes(c->B, Hq, n_split) > akvq::kDecodeStaticScratchBytes) return AKVQ_ERR_WORKSPACE;
+  void *ws = nullptr;
+  const hipError_t e = akvq::decode_static_scratch(&ws);
+  if (e != hipSuccess) return hip_status(e);
+  return akvq_decode_attention_rope(c, nullptr, nullptr, q, nullptr, Hq, sm_scale, out, lse_out, n_split, ws,
+                                    akvq::kDecodeStaticScratchBytes, flags, stream);
+}
+
 int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win,
                                  const void *q, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
                                  void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {

@@ -11,11 +11,38 @@
 // (per token for S, per channel-class for O), so the streamed bytes are touched once, by one and-or each.
 // The cache block layout makes each lane's 128-bit load its own matrix-core operand: no shuffles.  The next
 // tile's loads are issued before the current tile is consumed.
+#include <mutex>
+
 #include "akvq_device.h"
 #include "akvq_kernels.h"
 #include "akvq_rowquant.h"
 
 namespace akvq {
+
+// Split-KV partial results for callers that may not allocate (akvq_decode_attention_static): a fixed array in the
+// library's own device image, one copy per GPU, held until the process ends.  In host code this name is only a
+// handle; the device address comes from decode_static_scratch() below and is what the kernels are given.
+static __device__ __align__(256) unsigned char scratch[kDecodeStaticScratchBytes];
+
+hipError_t decode_static_scratch(void **ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void *addr[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (addr[dev] == nullptr) {  // once per device, with that device current: every GPU has its own copy of the array
+    void *p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (p == nullptr) return hipErrorInvalidSymbol;
+    addr[dev] = p;
+  }
+  *ptr = addr[dev];
+  return hipSuccess;
+}
 
 namespace {
 

@@ -72,6 +72,9 @@ __host__ __device__ inline int decode_last_tile_split(int n_tiles, int n_split) 
 }
 constexpr int kMhaTileRows = 64, kGqaTileRows = 32;  // rows per code-stream tile of the two decode kernels
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream);
+// Device address, on the current device, of the library's fixed scratch array for split-KV partials (no allocation).
+constexpr size_t kDecodeStaticScratchBytes = 8u << 20;
+hipError_t decode_static_scratch(void **ptr);
 
 struct SelectArgs {
   const uint8_t *is_text;    // [B][T]
