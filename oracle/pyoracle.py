@@ -302,5 +302,20 @@ def rope_rows(x_f16, cos_f16, sin_f16) -> np.ndarray:
     return out.view(np.float16)
 
 
+def topk_margins(mass: np.ndarray, top_k: int) -> np.ndarray:
+    """Relative gap at the selection boundary of each row of fp64 masses [..., T]: (m_k - m_{k+1}) / m_k with
+    m_1 >= m_2 >= ... the row sorted descending.  A top-k set is unique, and reproducible by an implementation whose
+    masses carry a relative error well below this gap, only when the gap is large enough; inputs for exact index-set
+    comparison are accepted on it.  inf when the row has no (k+1)-th element; 0 when m_k is 0 (a tie among zeros)."""
+    mass = np.asarray(mass, dtype=np.float64)
+    T = mass.shape[-1]
+    if top_k >= T:
+        return np.full(mass.shape[:-1], np.inf)
+    top = -np.partition(-mass, top_k, axis=-1)[..., :top_k + 1]      # the k+1 largest, the (k+1)-th in place
+    m_k, m_next = top[..., :top_k].min(axis=-1), top[..., top_k]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        return np.where(m_k > 0, (m_k - m_next) / m_k, 0.0)
+
+
 def bf16_bits_to_f64(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << 16).view(np.float32).astype(np.float64)

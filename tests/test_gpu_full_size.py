@@ -1,14 +1,15 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times (default KV splits).
 
 The HIP path runs on the whole workload; a few (batch, kv-head) units are then copied to the host and the oracle
-recomputes exactly those units from the same inputs: salient sets equal, codes / meta / overlay rows bit-exact,
-attention within the stated tolerance.  Inputs are drawn on the GPU with the seeded generator (the oracle sees the very
+recomputes exactly those units from the same inputs: salient sets equal (exactly; the inputs pass the margin check of
+psa_inputs on those units), codes / meta / overlay rows bit-exact, attention within the stated tolerance.  Inputs are drawn on the GPU with the seeded generator (the oracle sees the very
 same bits).
 """
 import numpy as np
 import pytest
 import torch
 
+import psa_inputs
 from paper_2501_15021_amd import binding as akvq
 from paper_2501_15021_amd import synth
 
@@ -21,7 +22,37 @@ def _unit_cache(orc, w, layer):
     return orc.OracleCache(1, 1, w.G, (w.T + 63) // 64 * 64, w.s_cap(layer))
 
 
-def _check_units(orc, w, layer, d, cache, out_gpu, units):
+def _unit_selection(orc, w, layer, d, b, h):
+    """The oracle's salient list of one (batch, kv-head) unit from the same inputs, and (pivot layers) the fp64 margin
+    (m_k - m_{k+1}) / m_k of its masses at the selection boundary."""
+    R = w.Hq // w.Hkv
+    oc = _unit_cache(orc, w, layer)
+    if w.mode(layer) == "tsa":
+        oc.select_tsa(d["is_text"][b:b + 1].cpu().numpy())
+        return oc, np.inf
+    k = d["k"][b:b + 1, h:h + 1].cpu().numpy()
+    mass = oc.select_psa(d["q_tail"][b:b + 1, h * R:(h + 1) * R].cpu().numpy(), k, w.top_k, w.sm_scale, want_mass=True)
+    return oc, float(orc.topk_margins(mass, w.top_k)[0, 0])
+
+
+def _margin_checked_inputs(orc, w, layer, units):
+    """Full-size inputs are drawn on the GPU, so the seed search of the index-set protocol runs here, over the sampled
+    units (the ones that are compared): a seed is accepted when each of them has an fp64 margin of at least 1e-4."""
+    for seed in range(synth.BASE_SEED, synth.BASE_SEED + psa_inputs.MAX_TRIES):
+        d = synth.generate(w, seed=seed, layer=layer, device="cuda")
+        sel = {u: _unit_selection(orc, w, layer, d, *u) for u in units}
+        m = np.array([sel[u][1] for u in units])
+        ok = bool((m >= psa_inputs.MIN_MARGIN).all())
+        tight = [f"{u} {x:.2e}" for u, x in zip(units, m) if x < psa_inputs.REPORT_MARGIN]
+        print(f"psa seed search [{w.name} layer {layer}, sampled units {units}]: seed {seed}: min margin {m.min():.3e}"
+              + (f", below {psa_inputs.REPORT_MARGIN:g}: {', '.join(tight)}" if tight else "")
+              + (": accepted" if ok else ": rejected"), flush=True)
+        if ok:
+            return d, sel
+    raise AssertionError("no seed passes the margin check")
+
+
+def _check_units(orc, w, layer, d, cache, out_gpu, units, sel):
     R = w.Hq // w.Hkv
     t_cap = (w.T + 63) // 64 * 64
     n_blocks = t_cap // 32
@@ -30,26 +61,13 @@ def _check_units(orc, w, layer, d, cache, out_gpu, units):
         k = d["k"][b:b + 1, h:h + 1].cpu().numpy()
         v = d["v"][b:b + 1, h:h + 1].cpu().numpy()
         heads = slice(h * R, (h + 1) * R)
-        oc = _unit_cache(orc, w, layer)
-        if w.mode(layer) == "tsa":
-            oc.select_tsa(d["is_text"][b:b + 1].cpu().numpy())
-            mass = None
-        else:
-            mass = oc.select_psa(d["q_tail"][b:b + 1, heads].cpu().numpy(), k, w.top_k, w.sm_scale, want_mass=True)
+        oc, margin = sel[(b, h)]
         cnt = int(oc.sal_cnt[0, 0])
         assert int(cache.counts()[b, h]) == cnt
         got_idx = cache.sal_idx[b, h].cpu().numpy()
-        if not np.array_equal(got_idx[:cnt], oc.sal_idx[0, 0, :cnt]):
-            # several sets are correct when the k-th and (k+1)-th masses differ by less than fp32-vs-fp64 noise:
-            # every disagreeing position must sit that close to the k-th mass; the rest of the unit is then checked
-            # on the GPU's set
-            assert mass is not None, f"text-salient set differs at unit {(b, h)}"
-            m = mass[0, 0]
-            kth = np.sort(m)[-cnt]
-            diff = set(got_idx[:cnt].tolist()) ^ set(oc.sal_idx[0, 0, :cnt].tolist())
-            assert all(abs(m[t] - kth) <= 2e-4 * max(1.0, m.max()) for t in diff), f"salient set differs at {(b, h)}"
-            assert np.all(np.diff(got_idx[:cnt]) > 0)
-            oc.sal_idx[0, 0, :cnt] = got_idx[:cnt]
+        assert np.array_equal(got_idx[:cnt], oc.sal_idx[0, 0, :cnt]), \
+            f"salient set differs at unit {(b, h)} (margin {margin:.2e}): " \
+            f"{sorted(set(got_idx[:cnt].tolist()) ^ set(oc.sal_idx[0, 0, :cnt].tolist()))}"
         oc.quantize_append(k, v, w.clip)
         for name in ("k_codes", "v_codes"):
             got = getattr(cache, name)[b, h].cpu().numpy().view(np.uint32).reshape(-1)
@@ -70,7 +88,7 @@ def _check_units(orc, w, layer, d, cache, out_gpu, units):
 
 def _run(orc, name, layer, units):
     w = synth.WORKLOADS[name]
-    d = synth.generate(w, layer=layer, device="cuda")
+    d, sel = _margin_checked_inputs(orc, w, layer, units)
     cache = akvq.Cache(w.B, w.Hkv, w.G, (w.T + 63) // 64 * 64, w.s_cap(layer))
     if w.mode(layer) == "tsa":
         akvq.select_salient(cache, akvq.MODE_TSA, is_text=d["is_text"])
@@ -79,7 +97,7 @@ def _run(orc, name, layer, units):
     akvq.quantize_append(cache, d["k"], d["v"], w.clip)
     out, _ = akvq.decode_attention(cache, d["q"], w.sm_scale)  # default split heuristic, as in bench.py
     torch.cuda.synchronize()
-    _check_units(orc, w, layer, d, cache, out, units)
+    _check_units(orc, w, layer, d, cache, out, units, sel)
 
 
 def test_cfg2_text_salient_layer(orc):

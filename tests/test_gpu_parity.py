@@ -7,6 +7,7 @@ import numpy as np
 import pytest
 import torch
 
+import psa_inputs
 from paper_2501_15021_amd import binding as akvq
 from paper_2501_15021_amd import synth
 
@@ -213,60 +214,74 @@ def test_select_tsa_exact(orc):
     assert np.array_equal(gc2.sal_idx.cpu().numpy()[:2], oc2.sal_idx[:2])
 
 
-def check_psa(orc, w, d, top_k, seed_note=""):
-    oc, gc = make_pair(orc, w, s_cap=max(64, (top_k + 63) // 64 * 64))
-    mass_ref = oc.select_psa(d["q_tail"], d["k"], top_k, w.sm_scale, want_mass=True)
+# Pivot index sets are compared EXACTLY.  What makes that well-posed: the inputs of every such comparison are accepted
+# by psa_inputs.margin_checked only if the oracle's fp64 masses leave a relative gap of at least 1e-4 between the k-th
+# and the (k+1)-th mass in every (batch, kv-head); the GPU's fp32 masses are held to MASS_RTOL of the oracle's, element
+# by element, relative to the element itself (fp32 logits of magnitude up to ~2^8 in the base-2 domain carry an error
+# of a few 2^-16 ulp-of-256 = 1.5e-5 each, which is the relative error of their exponentials; row sums and the final
+# sums are far more exact), so a swap at the boundary would need an error above half the gap.
+MASS_RTOL = 4e-5
+MASS_ATOL = 1e-12
+
+
+def check_psa(orc, w, seed, top_k, share_heads=False):
+    d, seed, oc, mass_ref, margins = psa_inputs.margin_checked(orc, synth.generate, w, seed, top_k, share_heads)
+    gc = akvq.Cache(w.B, w.Hkv, w.G, (w.T + 63) // 64 * 64, max(64, (top_k + 63) // 64 * 64))
     mass = torch.zeros(w.B, w.Hkv, w.T, dtype=torch.float32, device="cuda")
-    akvq.select_salient(gc, akvq.MODE_PSA, q_tail=_dev(d["q_tail"]), k=_dev(d["k"]), top_k=top_k,
-                        sm_scale=w.sm_scale, mass_out=mass)
+    akvq.select_salient(gc, akvq.MODE_PSA_SHARED if share_heads else akvq.MODE_PSA, q_tail=_dev(d["q_tail"]),
+                        k=_dev(d["k"]), top_k=top_k, sm_scale=w.sm_scale, mass_out=mass)
     torch.cuda.synchronize()
-    mass = mass.cpu().numpy().astype(np.float64)
-    assert np.allclose(mass.sum(-1), w.W * (w.Hq // w.Hkv), rtol=1e-4), "softmax rows must sum to one"
-    assert np.abs(mass - mass_ref).max() <= 2e-4 * max(1.0, mass_ref.max()), np.abs(mass - mass_ref).max()
-    cnt = gc.counts().cpu().numpy()
-    assert (cnt == min(top_k, w.T)).all()
+    mass32 = mass.cpu().numpy()
+    mass = mass32.astype(np.float64)
+    assert np.allclose(mass.sum(-1), w.W * (w.Hq // w.Hkv), rtol=1e-5), "softmax rows must sum to one"
+    err = np.abs(mass - mass_ref)
+    worst = np.unravel_index(np.argmax(err - MASS_RTOL * mass_ref), err.shape)
+    assert (err <= MASS_RTOL * mass_ref + MASS_ATOL).all(), \
+        f"mass at {worst}: {mass[worst]:.9e} vs {mass_ref[worst]:.9e} (rel {err[worst] / mass_ref[worst]:.2e})"
+    n = min(top_k, w.T)
+    assert (gc.counts().cpu().numpy() == n).all()
     idx = gc.sal_idx.cpu().numpy()
-    n_loose = 0
     for b in range(w.B):
+        total = None
+        if share_heads:
+            total = np.zeros(w.T, dtype=np.float32)
+            for h in range(w.Hkv):
+                total = total + mass32[b, h]                       # head order, fp32: what the kernel adds
         for h in range(w.Hkv):
-            got, ref = idx[b, h, :top_k], oc.sal_idx[b, h, :top_k]
+            got, ref = idx[b, h, :n], oc.sal_idx[b, h, :n]
             assert (np.diff(got) > 0).all(), "indices must be ascending and distinct"
-            # the GPU's own masses must make its set a correct top-k (ties to the lower position)
-            gm = mass[b, h]
-            order = sorted(range(w.T), key=lambda t: (-np.float32(gm[t]), t))[:top_k]
+            # the GPU's own masses must make its set a correct top-k (ties to the lower position) ...
+            gm = total if share_heads else mass32[b, h]
+            order = sorted(range(w.T), key=lambda t: (-gm[t], t))[:n]
             assert sorted(order) == list(got), f"top-k of the GPU masses wrong at {(b, h)}"
-            if not np.array_equal(got, ref):
-                # several results can be correct when masses at the k-th boundary differ by less than the
-                # fp32-vs-fp64 noise: every disagreeing element must sit within that noise of the boundary
-                n_loose += 1
-                mr = mass_ref[b, h]
-                kth = np.sort(mr)[::-1][top_k - 1]
-                for t in set(got) ^ set(ref):
-                    assert abs(mr[t] - kth) <= 2e-4 * max(1.0, mass_ref.max()), (b, h, t, mr[t], kth)
-    return n_loose
+            # ... and the set is the oracle's, exactly
+            assert np.array_equal(got, ref), \
+                f"{w.name} seed {seed}: salient set of {(b, h)} differs from the oracle's (margin " \
+                f"{margins[b] if share_heads else margins[b, h]:.2e}): {sorted(set(got) ^ set(ref))}"
+    big = mass_ref > 1e-6                                         # below that the absolute floor decides, not the ratio
+    return float((err[big] / mass_ref[big]).max())
 
 
 def test_select_psa_small(orc):
     w = synth.small("psa", B=2, Hq=4, Hkv=2, T=300, W=16, top_k=8)
-    d = _np(synth.generate(w, seed=106))
-    check_psa(orc, w, d, 8)
+    check_psa(orc, w, 106, 8)
 
 
 def test_select_psa_longer_than_the_staged_topk(orc):
     """More than 32768 keys: 17 score chunks per head and the top-k that reads its keys from memory instead of LDS;
     top_k above the short-list limit takes the general ordering path as well."""
     w = synth.small("psa_long", B=1, Hq=2, Hkv=1, T=33111, W=16, top_k=12, n_text_head=40, n_text_tail=31)
-    d = _np(synth.generate(w, seed=161))
-    check_psa(orc, w, d, 12)
-    check_psa(orc, w, d, 300)
+    check_psa(orc, w, 161, 12)
+    check_psa(orc, w, 161, 300)
 
 
 def test_select_psa_cfg1(orc):
+    """Config 1 (the parity configuration): every head's pivot set equals the oracle's."""
     w = synth.WORKLOADS["cfg1"]
-    d = _np(synth.generate(w))
-    n_loose = check_psa(orc, w, d, w.top_k)
-    assert n_loose <= 2
+    worst = check_psa(orc, w, synth.BASE_SEED, w.top_k)
+    print(f"cfg1: worst relative mass error {worst:.2e}")
     # planted pivots attract the mass (Section III-A.3): all four are in every head's set
+    d = _np(synth.generate(w))
     oc = orc.OracleCache(w.B, w.Hkv, w.G, 640, 64)
     oc.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale)
     hits = [len(set(d["pivots"][0].tolist()) & set(oc.sal_idx[0, h, :w.top_k].tolist())) for h in range(w.Hkv)]
@@ -369,7 +384,10 @@ def test_cfg1_end_to_end(orc, mode, clip):
     """Config 1: one layer, 32 heads, 640 tokens (35 text + 576 vision + 29 text), both salient modes, whole path on
     the GPU: select -> quantize -> decode."""
     w = synth.WORKLOADS["cfg1"]
-    d = _np(synth.generate(w))
+    if mode == "psa":   # the base seed passes the margin check (tests/golden/psa_seed_search.txt); searched again here
+        d, _, _, _, _ = psa_inputs.margin_checked(orc, synth.generate, w, synth.BASE_SEED, w.top_k)
+    else:
+        d = _np(synth.generate(w))
     oc, gc = make_pair(orc, w)
     k, v, q, qt = _dev(d["k"]), _dev(d["v"]), _dev(d["q"]), _dev(d["q_tail"])
     if mode == "tsa":
@@ -379,10 +397,9 @@ def test_cfg1_end_to_end(orc, mode, clip):
         oc.select_psa(d["q_tail"], d["k"], w.top_k, w.sm_scale)
         akvq.select_salient(gc, akvq.MODE_PSA, q_tail=qt, k=k, top_k=w.top_k, sm_scale=w.sm_scale)
     torch.cuda.synchronize()
-    same = np.array_equal(gc.sal_idx.cpu().numpy()[..., :w.top_k if mode == "psa" else 64],
-                          oc.sal_idx[..., :w.top_k if mode == "psa" else 64])
-    if not same:  # a near-tie at the k-th boundary: continue from the oracle's set so that the rest stays comparable
-        copy_salient_to_gpu(oc, gc)
+    n = w.top_k if mode == "psa" else 64
+    assert np.array_equal(gc.counts().cpu().numpy(), oc.sal_cnt)
+    assert np.array_equal(gc.sal_idx.cpu().numpy()[..., :n], oc.sal_idx[..., :n]), f"cfg1 {mode}: salient sets differ"
     oc.quantize_append(d["k"], d["v"], clip)
     akvq.quantize_append(gc, k, v, clip)
     assert_cache_equal(oc, gc, f"cfg1 {mode}")
@@ -540,26 +557,4 @@ def test_non_finite_inputs_stay_in_their_unit(orc, Hq, Hkv):
 def test_select_psa_token_level(orc, Hq, Hkv, T, top_k):
     """AKVQ_MODE_PSA_SHARED: the kv-heads' masses are added and every head of a batch element gets the same list."""
     w = synth.small(f"psa_sh{Hq}", B=2, Hq=Hq, Hkv=Hkv, T=T, W=16, top_k=top_k, n_text_head=9, n_text_tail=4)
-    d = _np(synth.generate(w, seed=221))
-    oc, gc = make_pair(orc, w, s_cap=64)
-    mass_ref = oc.select_psa(d["q_tail"], d["k"], top_k, w.sm_scale, want_mass=True, share_heads=True)
-    mass = torch.zeros(w.B, Hkv, T, dtype=torch.float32, device="cuda")
-    akvq.select_salient(gc, akvq.MODE_PSA_SHARED, q_tail=_dev(d["q_tail"]), k=_dev(d["k"]), top_k=top_k,
-                        sm_scale=w.sm_scale, mass_out=mass)
-    torch.cuda.synchronize()
-    idx, cnt = gc.sal_idx.cpu().numpy(), gc.counts().cpu().numpy()
-    assert (cnt == top_k).all()
-    m = mass.cpu().numpy()
-    for b in range(w.B):
-        total = np.zeros(T, dtype=np.float32)
-        for h in range(Hkv):
-            total = total + m[b, h]                                # head order, fp32: what the kernel adds
-        order = sorted(range(T), key=lambda t: (-total[t], t))[:top_k]
-        for h in range(Hkv):
-            assert list(idx[b, h, :top_k]) == sorted(order), f"list of {(b, h)}"
-        ref = oc.sal_idx[b, 0, :top_k]
-        if not np.array_equal(idx[b, 0, :top_k], ref):             # near-ties at the boundary only
-            tot_ref = mass_ref[b].sum(axis=0)
-            kth = np.sort(tot_ref)[::-1][top_k - 1]
-            for t in set(idx[b, 0, :top_k].tolist()) ^ set(ref.tolist()):
-                assert abs(tot_ref[t] - kth) <= 2e-4 * max(1.0, tot_ref.max())
+    check_psa(orc, w, 221, top_k, share_heads=True)

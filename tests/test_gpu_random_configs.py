@@ -155,5 +155,4 @@ def test_random_pivot_selection(orc, block):
         w = synth.small(f"psa_rnd{case}", B=int(rng.integers(1, 3)), Hq=Hkv * R, Hkv=Hkv, T=max(T, 3), W=W, top_k=top_k,
                         n_text_head=n_head, n_text_tail=1)
         print(f"case {case}: B={w.B} Hq={w.Hq} Hkv={Hkv} T={w.T} W={W} top_k={top_k}", flush=True)
-        d = {k: (v.numpy() if hasattr(v, "numpy") else v) for k, v in synth.generate(w, seed=950 + case).items()}
-        check_psa(orc, w, d, top_k)
+        check_psa(orc, w, 950 + 100 * case, top_k)     # the seed search may move on by a few seeds: keep the cases apart
