@@ -26,7 +26,7 @@ EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_b
            "akvq_quantize_append_tiered", "akvq_decode_attention_tiered", "akvq_quantize_append_rope",
            "akvq_decode_attention_rope", "akvq_decode_step",
            "akvq_decode_static_scratch_bytes", "akvq_decode_attention_static",
-           "akvq_massive_workspace_bytes", "akvq_select_massive", "akvq_fold_hadamard"]
+           "akvq_massive_workspace_bytes", "akvq_select_massive", "akvq_fold_hadamard", "akvq_stream_read"]
 TIER_2BIT, TIER_4BIT_COARSE, TIER_4BIT_FINE, TIER_PAD = 0, 1, 2, 3
 
 
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention_static.restype = C.c_int
         L.akvq_decode_attention_static.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                                    C.c_void_p, C.c_int, C.c_uint32, C.c_void_p]
+        L.akvq_stream_read.restype = C.c_int
+        L.akvq_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         L.akvq_fold_hadamard.restype = C.c_int
         L.akvq_fold_hadamard.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.akvq_massive_workspace_bytes.restype = C.c_size_t
@@ -234,6 +236,13 @@ def fold_hadamard(w: torch.Tensor, axis: int, out: Optional[torch.Tensor] = None
     assert out.dtype == torch.float16 and out.is_contiguous() and out.shape == w.shape
     _check(lib().akvq_fold_hadamard(_ptr(w), _ptr(out), w.shape[0], w.shape[1], axis, _stream()), "akvq_fold_hadamard")
     return out
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    """akvq_stream_read: one plain 128-bit streaming-read pass over src (measurement aid)."""
+    assert src.is_contiguous() and sink.dtype == torch.int32 and sink.numel() >= 1
+    _check(lib().akvq_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()),
+           "akvq_stream_read")
 
 
 def select_massive(cache: Cache, hidden: torch.Tensor, top_k: int, floor: float = 0.0,

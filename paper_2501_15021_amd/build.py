@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libakvq.so")
-SOURCES = ["akvq_api.hip", "akvq_quantize.hip", "akvq_decode.hip", "akvq_select.hip", "akvq_fold.hip"]
+SOURCES = ["akvq_api.hip", "akvq_quantize.hip", "akvq_decode.hip", "akvq_select.hip", "akvq_fold.hip", "akvq_stream.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
