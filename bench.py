@@ -120,22 +120,27 @@ def decode_alone(w, akvq, synth, torch, np, warmup=20, timed=100, n_split=0):
 
 
 def stream_ceiling(akvq, torch, warmup=5, timed=40):
-    """GB/s of the plain 128-bit streaming-read kernel over two 2 GiB buffers (alternating: no reuse in any cache)."""
+    """GB/s of the plain 128-bit streaming-read kernel over two 2 GiB buffers (alternating: no reuse in any cache),
+    with the non-temporal load hint the decode kernels use and without it."""
     n = 1 << 31
     bufs = [torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255) for _ in range(2)]
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
-    for i in range(warmup):
-        akvq.stream_read(bufs[i % 2], sink)
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for i in range(timed):
-        akvq.stream_read(bufs[i % 2], sink)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / timed
-    return {"kernel": "stream_read_kernel", "bytes_per_launch": n, "avg_launch_ms": round(ms, 4),
-            "GBps": round(n / (ms * 1e-3) / 1e9, 1), "frac_of_hbm_peak": round(n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    res = {"kernel": "stream_read_kernel", "bytes_per_launch": n, "launches_timed": timed}
+    for name, nt in (("non_temporal", True), ("plain", False)):
+        for i in range(warmup):
+            akvq.stream_read(bufs[i % 2], sink, nt)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(timed):
+            akvq.stream_read(bufs[i % 2], sink, nt)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / timed
+        res[name] = {"avg_launch_ms": round(ms, 4), "GBps": round(n / (ms * 1e-3) / 1e9, 1),
+                     "frac_of_hbm_peak": round(n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)}
+    res["GBps"] = max(res["non_temporal"]["GBps"], res["plain"]["GBps"])
+    return res
 
 
 def oracle_bench(args, w, synth, torch, np):

@@ -274,10 +274,11 @@ int akvq_decode_step(const akvq_cache *c, const uint32_t *fine_mask, const akvq_
 /*
  * akvq_stream_read -- measurement aid, no part of the method: one pass of plain 128-bit loads over src (device, 16-byte
  *   aligned, `bytes` a multiple of 16), nothing computed but an exclusive-or, nothing stored (sink: device, one
- *   uint32, written only if the data happen to fold to a magic value).  Its rate is the practical streaming-read
+ *   uint32, written only if the data happen to fold to a magic value).  non_temporal != 0: the loads carry the
+ *   non-temporal hint, as the decode kernels' loads of the cache stream do.  Its rate is the practical streaming-read
  *   ceiling of the GPU to hold the cache kernels against, beside the published HBM peak.
  */
-int akvq_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
+int akvq_stream_read(const void *src, size_t bytes, uint32_t *sink, int non_temporal, void *stream);
 
 #ifdef __cplusplus
 }

@@ -90,7 +90,7 @@ def lib() -> C.CDLL:
         L.akvq_decode_attention_static.argtypes = [C.POINTER(akvq_cache), C.c_void_p, C.c_int, C.c_float, C.c_void_p,
                                                    C.c_void_p, C.c_int, C.c_uint32, C.c_void_p]
         L.akvq_stream_read.restype = C.c_int
-        L.akvq_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        L.akvq_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int, C.c_void_p]
         L.akvq_fold_hadamard.restype = C.c_int
         L.akvq_fold_hadamard.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
         L.akvq_massive_workspace_bytes.restype = C.c_size_t
@@ -238,10 +238,10 @@ def fold_hadamard(w: torch.Tensor, axis: int, out: Optional[torch.Tensor] = None
     return out
 
 
-def stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+def stream_read(src: torch.Tensor, sink: torch.Tensor, non_temporal: bool = True) -> None:
     """akvq_stream_read: one plain 128-bit streaming-read pass over src (measurement aid)."""
     assert src.is_contiguous() and sink.dtype == torch.int32 and sink.numel() >= 1
-    _check(lib().akvq_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), _stream()),
+    _check(lib().akvq_stream_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), int(non_temporal), _stream()),
            "akvq_stream_read")
 
 

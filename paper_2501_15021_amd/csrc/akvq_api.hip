@@ -161,10 +161,10 @@ int akvq_fold_hadamard(const void *w_in, void *w_out, int rows, int cols, int ax
                                                cols, axis, static_cast<hipStream_t>(stream)));
 }
 
-int akvq_stream_read(const void *src, size_t bytes, uint32_t *sink, void *stream) {
+int akvq_stream_read(const void *src, size_t bytes, uint32_t *sink, int non_temporal, void *stream) {
   if (!src || !sink || !aligned16(src) || bytes < 16 || bytes % 16 != 0) return AKVQ_ERR_INVALID_ARG;
   if (bytes > ((size_t)1 << 44)) return AKVQ_ERR_UNSUPPORTED;
-  return hip_status(akvq::launch_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+  return hip_status(akvq::launch_stream_read(src, bytes, sink, non_temporal, static_cast<hipStream_t>(stream)));
 }
 
 size_t akvq_massive_workspace_bytes(int B, int T) {

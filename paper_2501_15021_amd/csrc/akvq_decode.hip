@@ -196,7 +196,9 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   __shared__ float mrg_o[kWaves][kD];
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  // the wavefront index as a scalar: everything derived from it (tile indices, tile addresses) then lives in scalar
+  // registers and the loads take a scalar base plus a per-lane offset
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int split = blockIdx.x;
   const int bh = blockIdx.y;  // Hq == Hkv here
   const int mrow = lane & 15, qd = lane >> 4;
@@ -209,23 +211,29 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   int tile_begin, tile_end;
   decode_split_range(n_tiles, a.n_split, split, tile_begin, tile_end);
   const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
-  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
-  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
-  const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + lane) * NG;
-  const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + lane) * NG;
+  // Plane bases and tile indices are uniform over the wavefront (scalar registers); a lane adds a fixed 32-bit offset,
+  // so every load of the stream is "scalar base + lane offset" and needs no per-lane address arithmetic.
+  const gptr_u32 kc_plane = as_global(a.k_codes) + (size_t)bh * plane_blocks * kBlockWords;
+  const gptr_u32 vc_plane = as_global(a.v_codes) + (size_t)bh * plane_blocks * kBlockWords;
+  const gptr_u32 km_plane = as_global(a.k_meta) + (size_t)bh * a.T_cap * NG;
+  const gptr_u32 vm_plane = as_global(a.v_meta) + (size_t)bh * a.T_cap * NG;
   const uint32_t *fm_base = PAIRS ? a.fine_mask + (size_t)(bh / a.Hkv) * plane_blocks + (lane >> 5) : nullptr;
+  const uint32_t lane_code = (uint32_t)lane * 4u, lane_meta = (uint32_t)lane * NG;
 
   auto load_tile = [&](int tile, MhaTile<NG> &t) {
     if constexpr (PAIRS) t.fm = fm_base[2 * tile];
+    gptr_u32 kc_t = kc_plane + (size_t)tile * (2 * kBlockWords), vc_t = vc_plane + (size_t)tile * (2 * kBlockWords);
+    gptr_u32 km_t = km_plane + (size_t)tile * (64 * NG), vm_t = vm_plane + (size_t)tile * (64 * NG);
+    keep_scalar(kc_t); keep_scalar(vc_t); keep_scalar(km_t); keep_scalar(vm_t);
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2) {
-      t.kc[b2] = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)(2 * tile + b2) * kBlockWords);
-      t.vc[b2] = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)(2 * tile + b2) * kBlockWords);
+      t.kc[b2] = stream_load_x4(kc_t + b2 * kBlockWords + lane_code);
+      t.vc[b2] = stream_load_x4(vc_t + b2 * kBlockWords + lane_code);
     }
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      t.km[g] = km_base[(size_t)tile * 64 * NG + g];
-      t.vm[g] = vm_base[(size_t)tile * 64 * NG + g];
+      t.km[g] = stream_load_x1(km_t + lane_meta + g);
+      t.vm[g] = stream_load_x1(vm_t + lane_meta + g);
     }
   };
 
@@ -602,7 +610,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   __shared__ float mrg_o[kWaves][8][kD];
 
   const int tid = threadIdx.x;
-  const int wave = tid >> 6, lane = tid & 63;
+  // the wavefront index as a scalar: everything derived from it (tile indices, tile addresses) then lives in scalar
+  // registers and the loads take a scalar base plus a per-lane offset
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int split = blockIdx.x;
   const int bh = blockIdx.y;  // b * Hkv + hkv
   const int R = a.Hq / a.Hkv;
@@ -745,27 +755,31 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   int tile_begin, tile_end;
   decode_split_range(n_tiles, a.n_split, split, tile_begin, tile_end);
   const size_t plane_blocks = (size_t)a.T_cap / kTokBlock;
-  const uint32_t *kc_base = a.k_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
-  const uint32_t *vc_base = a.v_codes + (size_t)bh * plane_blocks * kBlockWords + lane * 4;
-  const uint32_t *km_base = a.k_meta + ((size_t)bh * a.T_cap + mrow) * NG;
-  const uint32_t *vm_base = a.v_meta + ((size_t)bh * a.T_cap + mrow) * NG;
+  // plane bases and tile indices are uniform (scalar registers); a lane adds a fixed 32-bit offset (see the MHA kernel)
+  const gptr_u32 kc_plane = as_global(a.k_codes) + (size_t)bh * plane_blocks * kBlockWords;
+  const gptr_u32 vc_plane = as_global(a.v_codes) + (size_t)bh * plane_blocks * kBlockWords;
+  const gptr_u32 km_plane = as_global(a.k_meta) + (size_t)bh * a.T_cap * NG;
+  const gptr_u32 vm_plane = as_global(a.v_meta) + (size_t)bh * a.T_cap * NG;
+  const uint32_t lane_code = (uint32_t)lane * 4u, lane_meta = (uint32_t)mrow * NG;
 
   const uint32_t *fm_base = PAIRS ? a.fine_mask + (size_t)b * plane_blocks : nullptr;
   auto load_tile = [&](int tile, GqaTile<NG> &t) {
     if constexpr (PAIRS) t.fm = fm_base[tile];
-    t.kc = *reinterpret_cast<const u32x4 *>(kc_base + (size_t)tile * kBlockWords);
-    t.vc = *reinterpret_cast<const u32x4 *>(vc_base + (size_t)tile * kBlockWords);
+    gptr_u32 kc_t = kc_plane + (size_t)tile * kBlockWords, vc_t = vc_plane + (size_t)tile * kBlockWords;
+    gptr_u32 km_t = km_plane + (size_t)tile * (32 * NG), vm_t = vm_plane + (size_t)tile * (32 * NG);
+    keep_scalar(kc_t); keep_scalar(vc_t); keep_scalar(km_t); keep_scalar(vm_t);
+    t.kc = stream_load_x4(kc_t + lane_code);
+    t.vc = stream_load_x4(vc_t + lane_code);
 #pragma unroll
     for (int tg = 0; tg < 2; ++tg) {
-      const size_t off = ((size_t)tile * 32 + 16 * tg) * NG;
       if constexpr (NG == 2) {
-        const u32x2 k2 = *reinterpret_cast<const u32x2 *>(km_base + off);
-        const u32x2 v2 = *reinterpret_cast<const u32x2 *>(vm_base + off);
+        const u32x2 k2 = stream_load_x2(km_t + 16 * tg * NG + lane_meta);
+        const u32x2 v2 = stream_load_x2(vm_t + 16 * tg * NG + lane_meta);
         t.km[tg][0] = k2[0]; t.km[tg][1] = k2[1];
         t.vm[tg][0] = v2[0]; t.vm[tg][1] = v2[1];
       } else {
-        t.km[tg][0] = km_base[off];
-        t.vm[tg][0] = vm_base[off];
+        t.km[tg][0] = stream_load_x1(km_t + 16 * tg * NG + lane_meta);
+        t.vm[tg][0] = stream_load_x1(vm_t + 16 * tg * NG + lane_meta);
       }
     }
   };

@@ -102,6 +102,6 @@ hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream);
 hipError_t launch_fold_hadamard(const uint16_t *w, uint16_t *out, int rows, int cols, int axis, hipStream_t stream);
 
 // measurement aid: plain 128-bit streaming read of `bytes` bytes (a multiple of 16, at least 16)
-hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t stream);
+hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int non_temporal, hipStream_t stream);
 
 }  // namespace akvq

@@ -517,7 +517,7 @@ __global__ __launch_bounds__(256) void massive_score_kernel(SelectArgs a) {
   const uint16_t *src = a.hidden + (size_t)row * a.d_model;
   uint32_t m0 = 0u, m1 = 0u;  // running maxima of the low and the high binary16 of every word, as 15-bit integers
   for (int c0 = 0; c0 < a.d_model; c0 += 512) {  // 64 lanes x 8 channels
-    const u32x4 v = *reinterpret_cast<const u32x4 *>(src + c0 + 8 * lane);
+    const u32x4 v = stream_load(reinterpret_cast<const u32x4 *>(src + c0 + 8 * lane));
     const uint32_t w0 = v[0], w1 = v[1], w2 = v[2], w3 = v[3];
     m0 = max(m0, max(max(w0 & 0x7FFFu, w1 & 0x7FFFu), max(w2 & 0x7FFFu, w3 & 0x7FFFu)));
     m1 = max(m1, max(max((w0 >> 16) & 0x7FFFu, (w1 >> 16) & 0x7FFFu), max((w2 >> 16) & 0x7FFFu, (w3 >> 16) & 0x7FFFu)));

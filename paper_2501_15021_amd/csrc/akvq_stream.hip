@@ -13,13 +13,16 @@ constexpr int kStreamThreads = 256;
 constexpr int kStreamUnroll = 8;                                         // 16-byte loads in flight per lane
 constexpr size_t kStreamChunk = (size_t)kStreamThreads * 16 * kStreamUnroll;  // 32 KB per workgroup
 
+// NT: loads carry the non-temporal hint (the form the decode kernels use for the cache stream)
+template <bool NT>
 __global__ __launch_bounds__(kStreamThreads) void stream_read_kernel(const u32x4 *src, size_t n_vec, uint32_t *sink) {
   const size_t base = (size_t)blockIdx.x * (kStreamThreads * kStreamUnroll) + threadIdx.x;
   u32x4 v[kStreamUnroll];
 #pragma unroll
   for (int i = 0; i < kStreamUnroll; ++i) {
     const size_t idx = base + (size_t)i * kStreamThreads;
-    v[i] = src[idx < n_vec ? idx : n_vec - 1];  // unconditional loads, clamped address
+    const u32x4 *p = src + (idx < n_vec ? idx : n_vec - 1);  // unconditional loads, clamped address
+    v[i] = NT ? stream_load(p) : *p;
   }
   u32x4 acc = v[0];
 #pragma unroll
@@ -31,11 +34,15 @@ __global__ __launch_bounds__(kStreamThreads) void stream_read_kernel(const u32x4
 
 }  // namespace
 
-hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t stream) {
+hipError_t launch_stream_read(const void *src, size_t bytes, uint32_t *sink, int non_temporal, hipStream_t stream) {
   const size_t n_vec = bytes / 16;
   const size_t n_wg = (bytes + kStreamChunk - 1) / kStreamChunk;
-  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)n_wg), dim3(kStreamThreads), 0, stream,
-                     static_cast<const u32x4 *>(src), n_vec, sink);
+  if (non_temporal)
+    hipLaunchKernelGGL(stream_read_kernel<true>, dim3((unsigned)n_wg), dim3(kStreamThreads), 0, stream,
+                       static_cast<const u32x4 *>(src), n_vec, sink);
+  else
+    hipLaunchKernelGGL(stream_read_kernel<false>, dim3((unsigned)n_wg), dim3(kStreamThreads), 0, stream,
+                       static_cast<const u32x4 *>(src), n_vec, sink);
   return hipGetLastError();
 }
 

@@ -183,7 +183,7 @@ def test_every_error_code_of_every_entry_point(L):
     assert f(P, P, 4, 128, 2, None) == INVALID
     assert f(None, P, 4, 128, 1, None) == INVALID
     sr = L.akvq_stream_read
-    assert sr(None, 64, P, None) == INVALID and sr(P, 8, P, None) == INVALID and sr(P, 40, P, None) == INVALID
-    assert sr(P + 4, 64, P, None) == INVALID and sr(P, 64, None, None) == INVALID
+    assert sr(None, 64, P, 1, None) == INVALID and sr(P, 8, P, 1, None) == INVALID and sr(P, 40, P, 0, None) == INVALID
+    assert sr(P + 4, 64, P, 0, None) == INVALID and sr(P, 64, None, 1, None) == INVALID
     for code in (0, -1, -2, -3, -4, -5):
         assert len(L.akvq_strerror(code)) > 0
