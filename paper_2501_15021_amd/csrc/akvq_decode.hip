@@ -12,6 +12,7 @@
 // The cache block layout makes each lane's 128-bit load its own matrix-core operand: no shuffles.  The next
 // tile's loads are issued before the current tile is consumed.
 #include <mutex>
+#include <type_traits>
 
 #include "akvq_device.h"
 #include "akvq_kernels.h"
@@ -115,6 +116,18 @@ __device__ __forceinline__ Meta unpack_meta(uint32_t w) {
   return m;
 }
 
+// bit 15 of a meta word marks a salient row; read as binary16 the low half is then a negative number (or -0), which one
+// class test detects
+__device__ __forceinline__ bool meta_is_salient(uint32_t w) {
+  return __builtin_amdgcn_classh(__builtin_bit_cast(_Float16, (unsigned short)w), 0x3C | 0x3);  // any negative class or NaN
+}
+// w minus one bfloat16 of `pair`: pair . sel + w in one dot-product instruction, sel = (-1, 0) or (0, -1) as a bfloat16
+// pair held in a register.  Exact: the remainder of a rounding to bfloat16 has at most 16 significant bits.
+__device__ __forceinline__ float minus_bf16(uint32_t pair, uint32_t sel, float w) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, pair), __builtin_bit_cast(bf16x2_t, sel), w, false);
+}
+
 // two-term bfloat16 split, w ~= hi + lo (16 significant bits): hi is w truncated to its upper 16 bits (so storing
 // the upper half of the register stores hi), lo is the exactly representable remainder rounded to bfloat16
 __device__ __forceinline__ void split2(float w, float &hif, float &lof) {
@@ -124,6 +137,7 @@ __device__ __forceinline__ void split2(float w, float &hif, float &lof) {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kLazyMax = 12.0f;  // the softmax reference is raised only when a score exceeds it by 2^12
+constexpr float kNoScore = -1.0e30f;  // softmax reference of the grouped-query kernel before its first score
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // bare v_exp_f32
 
 // ---- DPP reductions over the wavefront (result in every lane) ----
@@ -686,7 +700,10 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   f32x4 acc_o[8];
 #pragma unroll
   for (int nb = 0; nb < 8; ++nb) acc_o[nb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};  // softmax reference (base 2) and partial sums
+  // Softmax reference (base 2) per head, its trigger level, and this lane's share of the sum.  "No score yet" is a large
+  // negative finite number instead of -inf: exp2(x - kNoScore) of a masked score (x = -inf) is 0 and the first real
+  // score raises the reference, so neither the weights nor the rescale factor need a special case.
+  float m_run[2] = {kNoScore, kNoScore}, m_trig[2] = {kNoScore, kNoScore}, l_run[2] = {0.f, 0.f};
   // Per head and group: szx = running sum of w*cx*zero over this lane's tokens; the sum of the weights themselves
   // (what the expansion constant 128 multiplies) comes out of the matrix cores: one extra product per group and tile
   // against an all-ones operand sums exactly the bfloat16 terms the value product uses, over all 32 slots.
@@ -700,28 +717,34 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
     for (int g = 0; g < NG; ++g) szx[hh][g] = 0.0f;
 
+  // The value product wants every weight divided by the 4^k of its token's slot in the code word (k = pair_exp of
+  // the token's position, a per-lane constant).  That factor rides in the exponent of the softmax: weights are taken
+  // as exp2(score - (reference + 2k)), i.e. already divided; the sums kept per lane (l_run, szx) carry the same factor
+  // and are multiplied by 4^k once at the end.
   const int ii = mrow & 3;  // token n = mrow of its group: pair position
-  const float cx = pow4_neg(pair_exp(ii)), rcx = 1.0f / cx;  // exact powers of two
+  const float two_k = 2.0f * (float)pair_exp(ii);
+  const float rcx = 1.0f / pow4_neg(pair_exp(ii));  // 4^k, exact
+  float m_off[2] = {kNoScore, kNoScore};             // reference + 2k
+  uint32_t minus_lo = 0x0000BF80u, minus_hi = 0xBF800000u;  // bfloat16 pairs (-1, 0) and (0, -1), kept in registers
+  asm volatile("" : "+v"(minus_lo), "+v"(minus_hi));
 
-  // scores sc[hh][tg] of heads h0+hh for tokens (16*tg + mrow) of the tile; ok[tg]; returns weights p[hh][tg].
-  // The reference of a head is raised (and its accumulators rescaled) only when one of its scores exceeds it by more
-  // than kLazyMax; the common tile pays one compare and one uniform branch.
-  auto softmax_step = [&](const float (&sc)[2][2], const bool (&ok)[2], const bool (&count)[2], float (&p)[2][2]) {
-    float scm[2][2], top[2];
+  // scm[hh][tg]: scores of heads h0+hh for tokens (16*tg + mrow) of the tile, -inf where the row does not take part;
+  // returns the weights p[hh][tg] (divided by 4^k).  The reference of a head is raised (and its accumulators rescaled)
+  // only when one of its scores exceeds it by more than kLazyMax; the common tile pays one compare and one branch.
+  auto softmax_step = [&](const float (&scm)[2][2], const bool (&count)[2], float (&p)[2][2]) {
+    float top[2];
     bool need = false;
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-#pragma unroll
-      for (int tg = 0; tg < 2; ++tg) scm[hh][tg] = ok[tg] ? sc[hh][tg] : -INFINITY;
       top[hh] = fmaxf(scm[hh][0], scm[hh][1]);
-      need = need || (top[hh] > m_run[hh] + kLazyMax);
+      need = need || (top[hh] > m_trig[hh]);
     }
     if (__ballot(need) != 0ull) {
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         const float mx = row_max_dpp(top[hh]);  // the 16 lanes of a row share a head
-        if (mx > m_run[hh] + kLazyMax) {
-          const float alpha = (m_run[hh] == -INFINITY) ? 0.0f : fast_exp2(m_run[hh] - mx);
+        if (mx > m_trig[hh]) {
+          const float alpha = fast_exp2(m_run[hh] - mx);  // 0 while there was no score
 #pragma unroll
           for (int nb = 0; nb < 8; ++nb) { acc_o[nb][2 * hh] *= alpha; acc_o[nb][2 * hh + 1] *= alpha; }
           l_run[hh] *= alpha;
@@ -732,18 +755,18 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
             szx[hh][g] *= alpha;
           }
           m_run[hh] = mx;
+          m_trig[hh] = mx + kLazyMax;
+          m_off[hh] = mx + two_k;
         }
       }
     }
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-      const float m_ref = (m_run[hh] == -INFINITY) ? 0.0f : m_run[hh];
+    for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
       for (int tg = 0; tg < 2; ++tg) {
-        p[hh][tg] = fast_exp2(scm[hh][tg] - m_ref);
+        p[hh][tg] = fast_exp2(scm[hh][tg] - m_off[hh]);
         l_run[hh] += count[tg] ? p[hh][tg] : 0.0f;  // a fine half carries its token's weight but is not a token
       }
-    }
   };
   // upper halves of two floats packed into one word (two bfloat16 values that are already exact in 16 bits)
   auto pack_hi = [](float lo, float hi) {
@@ -784,8 +807,25 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     }
   };
 
+  // Only the last tile of the stream can hold rows at or beyond t_win, whose meta words are arbitrary bits.  For that
+  // tile the words of such rows are replaced, in registers, by "salient, scale 0" (K) and "scale 0" (V); everything
+  // below then needs no validity mask at all: a salient row gets a score of -inf, hence a weight of exactly 0, and the
+  // scales of written rows are finite.
   auto process = [&](const GqaTile<NG> &cur, int tile) {
-    float sc[2][2];
+    uint32_t km[2][NG], vm[2][NG];
+#pragma unroll
+    for (int tg = 0; tg < 2; ++tg)
+#pragma unroll
+      for (int g = 0; g < NG; ++g) { km[tg][g] = cur.km[tg][g]; vm[tg][g] = cur.vm[tg][g]; }
+    if (tile == n_tiles - 1) {  // uniform over the wavefront
+#pragma unroll
+      for (int tg = 0; tg < 2; ++tg) {
+        const bool beyond = tile * 32 + 16 * tg + mrow >= a.t_win;
+#pragma unroll
+        for (int g = 0; g < NG; ++g) { km[tg][g] = beyond ? 0x8000u : km[tg][g]; vm[tg][g] = beyond ? 0u : vm[tg][g]; }
+      }
+    }
+    float scm[2][2];
     bool ok[2];
 #pragma unroll
     for (int tg = 0; tg < 2; ++tg) {
@@ -797,19 +837,20 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       acc[0] = mfma_bf16(a_k[1], ex.y(w0), acc[0]);
       acc[NG - 1] = mfma_bf16(a_k[2], ex.x(w1), acc[NG - 1]);
       acc[NG - 1] = mfma_bf16(a_k[3], ex.y(w1), acc[NG - 1]);
-      bool salient = false;
-      float s0 = 0.f, s1 = 0.f;
+      // bit 15 of every meta word of a salient row is set: as a binary16 pattern the low half is then negative
+      const bool off = meta_is_salient(km[tg][0]);
+      ok[tg] = !off;
+      const float pen = (PAIRS || !off) ? 0.0f : -INFINITY;
+      float s0 = pen, s1 = pen;
 #pragma unroll
       for (int g = 0; g < NG; ++g) {
-        const Meta mk = unpack_meta(cur.km[tg][g]);
-        salient = salient || mk.salient;
+        const Meta mk = unpack_meta(km[tg][g]);
         // scale * (dot - 128*sum(q') - zero*sum(q)); the accumulators started at -128*sum(q')
         s0 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[0][g], acc[g][0] + acc[g][1]), s0);
         s1 = __builtin_fmaf(mk.scale, __builtin_fmaf(-mk.zero, qsum[1][g], acc[g][2] + acc[g][3]), s1);
       }
-      sc[0][tg] = s0;
-      sc[1][tg] = s1;
-      ok[tg] = (tile * 32 + 16 * tg + mrow < a.t_win) && !salient;
+      scm[0][tg] = s0;
+      scm[1][tg] = s1;
     }
     bool count[2] = {true, true};
     if constexpr (PAIRS) {
@@ -819,37 +860,38 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
         const bool pair = (from_me & 3u) != 0u;               // pairs start on even rows: the partner is lane ^ 1
 #pragma unroll
         for (int hh = 0; hh < 2; ++hh) {
-          const float partner = dpp_f<0xB1>(sc[hh][tg]);
-          sc[hh][tg] = pair ? sc[hh][tg] + partner : sc[hh][tg];
+          const float partner = dpp_f<0xB1>(scm[hh][tg]);
+          const float both = pair ? scm[hh][tg] + partner : scm[hh][tg];
+          scm[hh][tg] = ok[tg] ? both : -INFINITY;
         }
         count[tg] = (from_me & 1u) == 0u;
       }
     }
     float p[2][2];
-    softmax_step(sc, ok, count, p);
+    softmax_step(scm, count, p);
     // weights: rows 4*qd + {0,1,2,3} = (head h0: hi, lo; head h0+1: hi, lo); slots 2*mrow (+1 for the second group)
 #pragma unroll
     for (int g = 0; g < NG; ++g) {
-      float sxc[2], zv[2];
+      float sv[2], zv[2];
 #pragma unroll
       for (int tg = 0; tg < 2; ++tg) {
-        const Meta mv = unpack_meta(cur.vm[tg][g]);
-        sxc[tg] = ok[tg] ? mv.scale * cx : 0.0f;  // rows past T_len hold arbitrary meta
+        const Meta mv = unpack_meta(vm[tg][g]);
+        sv[tg] = mv.scale;
         zv[tg] = mv.zero;
       }
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
-        // hi term = the weight truncated to bfloat16 (the upper half of the register), lo term = the remainder
-        // rounded to bfloat16; the zero-point sum takes the fp32 weight (it differs from hi+lo by 2^-17 relative,
-        // on a term of the size of the result itself)
-        const float w0 = p[hh][0] * sxc[0], w1 = p[hh][1] * sxc[1];
-        const float r0 = w0 - __uint_as_float(__float_as_uint(w0) & 0xFFFF0000u);
-        const float r1 = w1 - __uint_as_float(__float_as_uint(w1) & 0xFFFF0000u);
+        // two bfloat16 terms per weight: hi = the weight rounded to bfloat16, lo = the (exactly representable)
+        // remainder rounded to bfloat16; the zero-point sum takes the fp32 weight (it differs from hi+lo by 2^-17
+        // relative, on a term of the size of the result itself)
+        const float w0 = p[hh][0] * sv[0], w1 = p[hh][1] * sv[1];
         szx[hh][g] = __builtin_fmaf(w0, zv[0], szx[hh][g]);
         szx[hh][g] = __builtin_fmaf(w1, zv[1], szx[hh][g]);
+        const uint32_t hi = pack_bf16x2(w0, w1);
+        const uint32_t lo = pack_bf16x2(minus_bf16(hi, minus_lo, w0), minus_bf16(hi, minus_hi, w1));
         const int row = 4 * qd + 2 * hh;
-        reinterpret_cast<uint32_t *>(&w_lds[g][row][0])[mrow] = pack_hi(w0, w1);
-        reinterpret_cast<uint32_t *>(&w_lds[g][row + 1][0])[mrow] = pack_bf16x2(r0, r1);
+        reinterpret_cast<uint32_t *>(&w_lds[g][row][0])[mrow] = hi;
+        reinterpret_cast<uint32_t *>(&w_lds[g][row + 1][0])[mrow] = lo;
       }
     }
     wave_lds_sync();
@@ -868,7 +910,6 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     }
     wave_lds_sync();
   };
-
   // three tile buffers, two tiles of loads in flight (see the MHA kernel)
   const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
   const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
@@ -937,18 +978,18 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
             acc = mfma_bf16(a_s[kc], kb, acc);
           }
         }
-        sc[0][tg] = acc[0] + acc[1];
-        sc[1][tg] = acc[2] + acc[3];
         ok[tg] = lane_ok[tg];
+        sc[0][tg] = ok[tg] ? acc[0] + acc[1] : -INFINITY;
+        sc[1][tg] = ok[tg] ? acc[2] + acc[3] : -INFINITY;
       }
       float p[2][2];
       const bool count[2] = {true, true};
-      softmax_step(sc, ok, count, p);
+      softmax_step(sc, count, p);
 #pragma unroll
       for (int hh = 0; hh < 2; ++hh) {
         float hif[2], lof[2];
 #pragma unroll
-        for (int tg = 0; tg < 2; ++tg) split2(p[hh][tg], hif[tg], lof[tg]);
+        for (int tg = 0; tg < 2; ++tg) split2(p[hh][tg] * rcx, hif[tg], lof[tg]);  // these rows are plain values: undo the 4^-k
         const int row = 4 * qd + 2 * hh;
         reinterpret_cast<uint32_t *>(&w_lds[0][row][0])[mrow] = pack_hi(hif[0], hif[1]);
         reinterpret_cast<uint32_t *>(&w_lds[0][row + 1][0])[mrow] = pack_hi(lof[0], lof[1]);
@@ -1000,7 +1041,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
   for (int hh = 0; hh < 2; ++hh) {
     const int h = h0 + hh;
-    const float l_tot = row_sum_dpp(l_run[hh]);
+    const float l_tot = row_sum_dpp(l_run[hh] * rcx);
     float corr[NG];
 #pragma unroll
     for (int g = 0; g < NG; ++g)  // acc_one already holds the sum over all slots (every column the same)
@@ -1019,8 +1060,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
       for (int w = 0; w < kWaves; ++w) m_all = fmaxf(m_all, mrg_m[w][h]);
 #pragma unroll
       for (int w = 0; w < kWaves; ++w) {
-        if (mrg_m[w][h] == -INFINITY) continue;
-        const float wgt = fast_exp2(mrg_m[w][h] - m_all);
+        const float wgt = fast_exp2(mrg_m[w][h] - m_all);  // a wavefront without scores has kNoScore and sums of 0
         l_all += wgt * mrg_l[w][h];
         o += wgt * mrg_o[w][h][tid];
       }
