@@ -151,7 +151,9 @@ template <int G, bool TIERED, bool WINDOW, bool ROPE>
 __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   __shared__ int slot_of_lds[4][kTokBlock];
   __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[WINDOW ? 4 : 1][WINDOW ? 2048 : 4];  // one V tile (32 slots x 128 channels, bf16) per wavefront
-  const int wave = threadIdx.x >> 6;
+  // the wavefront index as a scalar: the block index, its first row and every base address derived from them then
+  // live in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   const int blk_rel = blockIdx.x * 4 + wave;
   if (blk_rel >= a.n_blk) return;  // whole wavefront leaves; no block-wide barrier is used below
