@@ -65,9 +65,11 @@ enum {
                              Section III-C.2 / Fig. 7); skip the transform on V */
   AKVQ_OUT_ROTATED = 2u,  /* decode_attention: leave the output in the rotated domain (H folded into W_O) */
   AKVQ_K_PREROTATED = 4u, /* quantize_append: K rows arrive already rotated; skip the transform on K */
-  AKVQ_Q_PREROTATED = 8u  /* decode_attention: q arrives already rotated; skip the transform on q.
+  AKVQ_Q_PREROTATED = 8u, /* decode_attention: q arrives already rotated; skip the transform on q.
                              All four together make the library transform nothing: with inputs that were never
                              rotated this is plain round-to-nearest quantization, the ablation baseline of Table III */
+  AKVQ_OUT_FP16 = 16u     /* decode_attention: out is [B][Hq][128] binary16 (the fp32 result rounded to nearest even)
+                             instead of fp32 */
 };
 
 /* Tier of a cache row written by akvq_quantize_append_tiered (Section III-C.1: text tokens 4-bit, the rest 2-bit).
@@ -185,10 +187,11 @@ int akvq_quantize_append(const akvq_cache *c, const void *k_new, const void *v_n
  *   (Section II-A decode step with the Section III-C cache), q~ = q * H_128, k^/v^ = bfloat16 overlay row if the
  *   row is salient else scale*(code - zero).  Split over T (n_split partial softmaxes merged exactly);
  *   fp32 accumulation.  Output is rotated back by H_128 unless AKVQ_OUT_ROTATED.
- *   q: device [B][Hq][128] binary16.  out: device [B][Hq][128] fp32.  lse_out: optional device [B][Hq] fp32.
+ *   q: device [B][Hq][128] binary16.  out: device [B][Hq][128] fp32 (binary16 with AKVQ_OUT_FP16).  lse_out: optional
+ *   device [B][Hq] fp32.
  *   n_split <= 0 picks akvq_decode_default_splits().  workspace: device, akvq_decode_workspace_bytes() bytes.
  */
-int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, void *out, float *lse_out,
                           int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 
 /*
@@ -203,7 +206,7 @@ int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_s
  *   start at zero: every (head, split) slot is written by the call before its merge pass reads it.
  */
 size_t akvq_decode_static_scratch_bytes(void);
-int akvq_decode_attention_static(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+int akvq_decode_attention_static(const akvq_cache *c, const void *q, int Hq, float sm_scale, void *out, float *lse_out,
                                  int n_split, uint32_t flags, void *stream);
 
 /*
@@ -234,7 +237,7 @@ int akvq_quantize_append_tiered(const akvq_cache *c, const void *k_src, const vo
  *   from the 16-bit rings instead of their codes.  fine_mask and win NULL = akvq_decode_attention.
  */
 int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win,
-                                 const void *q, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                                 const void *q, int Hq, float sm_scale, void *out, float *lse_out, int n_split,
                                  void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 
 /*
@@ -250,7 +253,7 @@ int akvq_quantize_append_rope(const akvq_cache *c, const void *k_src, const void
                               uint32_t *fine_mask, const akvq_window *win, const akvq_rope *rope, uint32_t flags,
                               void *stream);
 int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
-                               const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                               const akvq_rope *rope, int Hq, float sm_scale, void *out, float *lse_out, int n_split,
                                void *workspace, size_t workspace_bytes, uint32_t flags, void *stream);
 
 /*
@@ -268,7 +271,7 @@ int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, c
  */
 int akvq_decode_step(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *k_new,
                      const void *v_new, const void *q, const akvq_rope *rope, int Hq, float clip, float sm_scale,
-                     float *out, float *lse_out, int n_split, void *workspace, size_t workspace_bytes, uint32_t flags,
+                     void *out, float *lse_out, int n_split, void *workspace, size_t workspace_bytes, uint32_t flags,
                      void *stream);
 
 /*

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libakvq.so")
 
 D = 128
 MODE_TSA, MODE_PSA, MODE_PSA_SHARED = 0, 1, 2
-V_PREROTATED, OUT_ROTATED, K_PREROTATED, Q_PREROTATED = 1, 2, 4, 8
+V_PREROTATED, OUT_ROTATED, K_PREROTATED, Q_PREROTATED, OUT_FP16 = 1, 2, 4, 8, 16
 
 EXPORTS = ["akvq_strerror", "akvq_last_hip_error", "akvq_version", "akvq_cache_bytes",
            "akvq_select_workspace_bytes", "akvq_decode_workspace_bytes", "akvq_decode_default_splits",
@@ -310,8 +310,10 @@ def decode_attention(cache: Cache, q: torch.Tensor, sm_scale: float, n_split: in
     if n_split <= 0:
         n_split = lib().akvq_decode_default_splits(cache.B, cache.Hkv, cache.T_len)
     ws = cache.workspace("decode", lib().akvq_decode_workspace_bytes(B, Hq, n_split))
+    out_dtype = torch.float16 if flags & OUT_FP16 else torch.float32
     if out is None:
-        out = torch.empty(B, Hq, D, dtype=torch.float32, device=q.device)
+        out = torch.empty(B, Hq, D, dtype=out_dtype, device=q.device)
+    assert out.dtype == out_dtype and out.is_contiguous()
     if lse is None:
         lse = torch.empty(B, Hq, dtype=torch.float32, device=q.device)
     c = cache.struct()

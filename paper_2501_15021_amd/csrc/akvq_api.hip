@@ -75,7 +75,7 @@ int akvq_cache_bytes(const akvq_cache *shape, size_t out_bytes[8]) {
   return AKVQ_OK;
 }
 
-static int select_chunks(int T) { return (T + akvq::kScoreChunk - 1) / akvq::kScoreChunk; }
+static int select_chunks(int T) { return (int)(((long)T + akvq::kScoreChunk - 1) / akvq::kScoreChunk); }
 
 size_t akvq_select_workspace_bytes(int B, int Hq, int Hkv, int T, int W) {
   if (B <= 0 || Hq <= 0 || Hkv <= 0 || T <= 0 || W <= 0) return 0;
@@ -281,7 +281,7 @@ int akvq_quantize_append_rope(const akvq_cache *c, const void *k_src, const void
                          stream);
 }
 
-int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_scale, void *out, float *lse_out,
                           int n_split, void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
   return akvq_decode_attention_rope(c, nullptr, nullptr, q, nullptr, Hq, sm_scale, out, lse_out, n_split, workspace,
                                     workspace_bytes, flags, stream);
@@ -289,7 +289,7 @@ int akvq_decode_attention(const akvq_cache *c, const void *q, int Hq, float sm_s
 
 size_t akvq_decode_static_scratch_bytes(void) { return akvq::kDecodeStaticScratchBytes; }
 
-int akvq_decode_attention_static(const akvq_cache *c, const void *q, int Hq, float sm_scale, float *out, float *lse_out,
+int akvq_decode_attention_static(const akvq_cache *c, const void *q, int Hq, float sm_scale, void *out, float *lse_out,
                                  int n_split, uint32_t flags, void *stream) {
   // size check first, on the host, so that an oversize request launches nothing and touches no device state
   if (!c || c->B <= 0 || c->Hkv <= 0 || Hq <= 0) return AKVQ_ERR_INVALID_ARG;
@@ -304,14 +304,14 @@ int akvq_decode_attention_static(const akvq_cache *c, const void *q, int Hq, flo
 }
 
 int akvq_decode_attention_tiered(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win,
-                                 const void *q, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                                 const void *q, int Hq, float sm_scale, void *out, float *lse_out, int n_split,
                                  void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
   return akvq_decode_attention_rope(c, fine_mask, win, q, nullptr, Hq, sm_scale, out, lse_out, n_split, workspace,
                                     workspace_bytes, flags, stream);
 }
 
 static int decode_args(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
-                       const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                       const akvq_rope *rope, int Hq, float sm_scale, void *out, float *lse_out, int n_split,
                        void *workspace, size_t workspace_bytes, uint32_t flags, akvq::DecodeArgs &a) {
   if (fine_mask && !aligned16(fine_mask)) return AKVQ_ERR_INVALID_ARG;
   int st = check_rope(rope, flags & AKVQ_Q_PREROTATED);
@@ -349,11 +349,12 @@ static int decode_args(const akvq_cache *c, const uint32_t *fine_mask, const akv
   if (rope) { a.rope_cos = rope->cos; a.rope_sin = rope->sin; a.rope_stride = rope->batch_stride; }
   a.q_rotated = (flags & AKVQ_Q_PREROTATED) ? 1 : 0;
   a.out_rotated = (flags & AKVQ_OUT_ROTATED) ? 1 : 0;
+  a.out_half = (flags & AKVQ_OUT_FP16) ? 1 : 0;
   return AKVQ_OK;
 }
 
 int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *q,
-                               const akvq_rope *rope, int Hq, float sm_scale, float *out, float *lse_out, int n_split,
+                               const akvq_rope *rope, int Hq, float sm_scale, void *out, float *lse_out, int n_split,
                                void *workspace, size_t workspace_bytes, uint32_t flags, void *stream) {
   akvq::DecodeArgs a;
   const int st = decode_args(c, fine_mask, win, q, rope, Hq, sm_scale, out, lse_out, n_split, workspace,
@@ -364,7 +365,7 @@ int akvq_decode_attention_rope(const akvq_cache *c, const uint32_t *fine_mask, c
 
 int akvq_decode_step(const akvq_cache *c, const uint32_t *fine_mask, const akvq_window *win, const void *k_new,
                      const void *v_new, const void *q, const akvq_rope *rope, int Hq, float clip, float sm_scale,
-                     float *out, float *lse_out, int n_split, void *workspace, size_t workspace_bytes, uint32_t flags,
+                     void *out, float *lse_out, int n_split, void *workspace, size_t workspace_bytes, uint32_t flags,
                      void *stream) {
   if (!c) return AKVQ_ERR_INVALID_ARG;
   akvq::QuantArgs qa;

@@ -173,11 +173,20 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
 
 // Final step: `row` (LDS, 128 floats, complete and visible to this wavefront) is the merged, normalised o~; rotate
 // it back (H is its own inverse) unless the caller wants it rotated, and store.  One wavefront does the whole row.
-__device__ __forceinline__ void unrotate_store_wave(const float *row, float *out_row, bool out_rotated, int lane) {
+// `out` is the output array ([B][Hq][128] fp32, or binary16 when out_half), `row_index` the (batch, query-head) row.
+__device__ __forceinline__ void unrotate_store_wave(const float *row, void *out, size_t row_index, bool out_rotated,
+                                                    bool out_half, int lane) {
   float x0 = row[lane], x1 = row[lane + 64];
   if (!out_rotated) wht128_wave(x0, x1, lane);
-  out_row[lane] = x0;
-  out_row[lane + 64] = x1;
+  if (out_half) {
+    uint16_t *o = static_cast<uint16_t *>(out) + row_index * kD;
+    o[lane] = (uint16_t)float_to_half_bits_rne(x0);
+    o[lane + 64] = (uint16_t)float_to_half_bits_rne(x1);
+  } else {
+    float *o = static_cast<float *>(out) + row_index * kD;
+    o[lane] = x0;
+    o[lane + 64] = x1;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -584,7 +593,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     if (tid < kD) qf[tid] = o / l_all;  // the query is no longer needed: its buffer carries the row to wavefront 0
     if (a.lse && tid == 0) a.lse[bh] = (m_all + __log2f(l_all)) * kLn2;
     __syncthreads();
-    if (wave == 0) unrotate_store_wave(qf, a.out + (size_t)bh * kD, a.out_rotated != 0, lane);
+    if (wave == 0) unrotate_store_wave(qf, a.out, (size_t)bh, a.out_rotated != 0, a.out_half != 0, lane);
   } else if (tid < kD) {
     float *dst = a.partial + ((size_t)bh * a.n_split + split) * kPartialStride;
     if (tid == 0) { dst[0] = m_all; dst[1] = l_all; }
@@ -1078,7 +1087,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   if (a.n_split == 1) {
     __syncthreads();
     for (int h = wave; h < R; h += kWaves)
-      unrotate_store_wave(qf[h], a.out + ((size_t)b * a.Hq + hkv * R + h) * kD, a.out_rotated != 0, lane);
+      unrotate_store_wave(qf[h], a.out, (size_t)b * a.Hq + hkv * R + h, a.out_rotated != 0, a.out_half != 0, lane);
   }
 }
 
@@ -1103,7 +1112,7 @@ __global__ __launch_bounds__(128) void decode_combine_kernel(DecodeArgs a) {
   of[d] = o / l_all;
   if (a.lse && d == 0) a.lse[bhq] = (m_all + __log2f(l_all)) * kLn2;
   __syncthreads();
-  if (d < kWave) unrotate_store_wave(of, a.out + (size_t)bhq * kD, a.out_rotated != 0, d);
+  if (d < kWave) unrotate_store_wave(of, a.out, (size_t)bhq, a.out_rotated != 0, a.out_half != 0, d);
 }
 
 }  // namespace

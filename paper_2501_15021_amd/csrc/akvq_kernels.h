@@ -39,11 +39,11 @@ struct DecodeArgs {
   int t_win;                  // first row read from the rings (= T_len without a window)
   const uint16_t *q;  // [B][Hq][128] binary16
   float *partial;     // [B*Hq][n_split][kPartialStride] fp32
-  float *out;         // [B][Hq][128]
+  void *out;          // [B][Hq][128] fp32, or binary16 when out_half
   float *lse;         // optional [B][Hq]
   int B, Hq, Hkv, T_cap, S_cap, T_len, n_split;
   float sm_scale;
-  int q_rotated, out_rotated;
+  int q_rotated, out_rotated, out_half;
   // the decode step in one launch: row T_len - 1 is first quantized from step.k_new / step.v_new (step.T_len is that
   // row) by the workgroups of split append_split: the split whose tile range holds the tile of that row (see
   // decode_split_range), so that the row is written and read by the same workgroup.  They are also the only ones to
@@ -59,16 +59,19 @@ constexpr int kPartialStride = 132;  // m, l, 2 pad, 128 accumulators
 // How the code stream's n_tiles tiles are dealt to the n_split KV splits: equal runs of ceil(n_tiles / n_split) tiles,
 // so trailing splits can be short or empty.  Used by the kernels, by the host (append_split) and by the public helper
 // akvq_decode_split_range, so that all three agree by construction.
+__host__ __device__ inline int decode_tiles_per_split(int n_tiles, int n_split) {
+  return n_tiles > 0 ? (n_tiles - 1) / n_split + 1 : 0;  // ceil(n_tiles / n_split) without overflow
+}
 __host__ __device__ inline void decode_split_range(int n_tiles, int n_split, int split, int &begin, int &end) {
-  const int per = (n_tiles + n_split - 1) / n_split;
-  begin = split * per < n_tiles ? split * per : n_tiles;
-  end = begin + per < n_tiles ? begin + per : n_tiles;
+  const int per = decode_tiles_per_split(n_tiles, n_split);
+  const long long b = (long long)split * per, e = b + per;
+  begin = (int)(b < n_tiles ? b : n_tiles);
+  end = (int)(e < n_tiles ? e : n_tiles);
 }
 // the split whose range holds the last tile (the tile of the row a fused decode step appends); split 0 if there is no tile
 __host__ __device__ inline int decode_last_tile_split(int n_tiles, int n_split) {
   if (n_tiles <= 0) return 0;
-  const int per = (n_tiles + n_split - 1) / n_split;
-  return (n_tiles - 1) / per;
+  return (n_tiles - 1) / decode_tiles_per_split(n_tiles, n_split);
 }
 constexpr int kMhaTileRows = 64, kGqaTileRows = 32;  // rows per code-stream tile of the two decode kernels
 hipError_t launch_decode_attention(const DecodeArgs &a, int G, hipStream_t stream);

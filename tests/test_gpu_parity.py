@@ -358,6 +358,28 @@ def test_decode_long_context_small_batch(orc, Hq, Hkv, G):
     run_decode_case(orc, w, d, "tsa", 5, n_splits=(1, 0, 37))
 
 
+@pytest.mark.parametrize("Hq,Hkv,G", [(3, 3, 128), (14, 2, 64)])
+def test_decode_fp16_output_flag(orc, Hq, Hkv, G):
+    """AKVQ_OUT_FP16: the output is the fp32 result rounded to binary16 (bit for bit), with one split (stored by the
+    attention kernel) and with several (stored by the merge kernel), also combined with a rotated output."""
+    w = synth.small(f"half{Hq}", B=2, Hq=Hq, Hkv=Hkv, T=260, G=G, n_text_head=9, n_text_tail=5, top_k=6, W=16)
+    d = _np(synth.generate(w, seed=231))
+    oc, gc = make_pair(orc, w, t_cap=320, s_cap=64)
+    oc.select_tsa(d["is_text"])
+    copy_salient_to_gpu(oc, gc)
+    oc.quantize_append(d["k"], d["v"], w.clip)
+    akvq.quantize_append(gc, _dev(d["k"]), _dev(d["v"]), w.clip)
+    q = _dev(d["q"])
+    for flags in (0, akvq.OUT_ROTATED):
+        ref, lse_ref = oc.decode(d["q"], w.sm_scale, unrotate=not flags)
+        for ns in (1, 3):
+            full, _ = akvq.decode_attention(gc, q, w.sm_scale, n_split=ns, flags=flags)
+            half, lse = akvq.decode_attention(gc, q, w.sm_scale, n_split=ns, flags=flags | akvq.OUT_FP16)
+            torch.cuda.synchronize()
+            assert half.dtype == torch.float16 and torch.equal(half, full.half()), f"flags={flags} n_split={ns}"
+            assert_attention_close(half.float(), lse, ref, lse_ref, f"fp16 output flags={flags} n_split={ns}")
+
+
 def test_decode_rotated_output_flag(orc):
     w = synth.small("rotout", B=1, Hq=2, Hkv=2, T=100, W=16)
     d = _np(synth.generate(w, seed=110))
