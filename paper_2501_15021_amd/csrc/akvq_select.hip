@@ -320,6 +320,265 @@ __global__ __launch_bounds__(256, 4) void psa_mass_kernel(SelectArgs a) {  // re
   }
 }
 
+// ---- pivot scoring with several query heads per KV head --------------------------------------------------------
+// One workgroup per (batch, kv-head, chunk of kScoreChunk keys) with one wavefront per query head of the group.  The
+// keys are read from HBM and converted to bfloat16 once for the whole group: the wavefronts share the work of bringing
+// blocks of 128 keys into LDS (two buffers, laid out as matrix-core operands) and every wavefront scores all of them
+// against its own head, whose W tail rows it holds in registers as the other operand.  Per block and wavefront: the
+// keys of the block after next are requested into registers, the next block's are converted and stored to LDS, the
+// current block is scored; one barrier per block orders the buffers.
+constexpr int kGqaBlockGroups = 8;                                // groups of 16 keys per block
+constexpr int kGqaBlockKeys = 16 * kGqaBlockGroups;               // 128
+constexpr int kGqaBlocks = kScoreChunk / kGqaBlockKeys;           // blocks per chunk
+constexpr int kGqaItems = kGqaBlockGroups * 4;                    // 1 KB pieces (group, channel step) of a block
+constexpr int kGqaMaxWaves = 8;                                   // query heads per KV head
+static_assert(kScoreChunk % kGqaBlockKeys == 0, "a chunk is a whole number of blocks");
+
+// MAXIT: pieces of a block one wavefront brings in (kGqaItems / heads per KV head, rounded up: only the last can
+// fall past the block).  The loads are unconditional (a piece past the block re-reads the last one), so that they
+// stay in straight-line code and in flight together; only the LDS store is skipped.
+template <int MAXIT>
+struct KeyStage {
+  u32x4 raw[MAXIT];
+};
+template <int MAXIT>
+__device__ __forceinline__ void request_block(const uint16_t *k_rows, int t_block, int T, int wave, int R, int mrow,
+                                              int qd, KeyStage<MAXIT> &st) {
+#pragma unroll
+  for (int it = 0; it < MAXIT; ++it) {
+    const int item = min(wave + it * R, kGqaItems - 1);  // uniform over the wavefront
+    const int g = item >> 2, kc = item & 3;
+    const int t = min(t_block + 16 * g + mrow, T - 1);  // rows past the end repeat the last key; never scored unmasked
+    st.raw[it] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
+  }
+}
+template <int MAXIT>
+__device__ __forceinline__ void deposit_block(const KeyStage<MAXIT> &st, u32x4 *buf, int wave, int R, int lane) {
+#pragma unroll
+  for (int it = 0; it < MAXIT; ++it) {
+    const int item = wave + it * R;
+    const u32x4 piece = __builtin_bit_cast(u32x4, rows8_as_bf16(st.raw[it]));
+    if (it + 1 < MAXIT || item < kGqaItems) buf[item * 64 + lane] = piece;
+  }
+}
+// the W tail rows of one query head as matrix-core operands in registers: q[rb * 4 + kc] is what this lane feeds for
+// row block rb and channel step kc
+template <int NRB>
+__device__ __forceinline__ void load_query_rows(const uint16_t *q_head, int mrow, int qd, bf16x8 (&q)[NRB * 4]) {
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc)
+      q[rb * 4 + kc] = rows8_as_bf16(
+          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd));
+}
+template <int NRB>
+__device__ __forceinline__ void score_block_group(const bf16x8 (&q)[NRB * 4], const u32x4 *buf, int g, int lane,
+                                                  f32x4 (&acc)[4]) {
+  bf16x8 kb[4];
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) acc[rb] = mfma_bf16(q[rb * 4 + kc], kb[kc], acc[rb]);
+  }
+}
+
+// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel
+template <int NRB, int MAXIT>
+__global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(SelectArgs a) {
+  __shared__ u32x4 kbuf[2][kGqaItems * 64];
+  const int chunk = blockIdx.x, bh = blockIdx.y;
+  const int R = a.Hq / a.Hkv, b = bh / a.Hkv, hkv = bh % a.Hkv;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
+  const int bhq = b * a.Hq + hkv * R + wave;
+  const uint16_t *k_rows = a.k + (size_t)bh * a.T * kD;
+  const float scale2 = a.sm_scale * kLog2e;
+  const int t_chunk = chunk * kScoreChunk;
+  const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);  // blocks that hold keys
+  KeyStage<MAXIT> st;
+  request_block(k_rows, t_chunk, a.T, wave, R, mrow, qd, st);
+  bf16x8 q[NRB * 4];
+  load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, q);
+  deposit_block(st, kbuf[0], wave, R, lane);
+  request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
+  float m[4][4], l[4][4];
+#pragma unroll
+  for (int rb = 0; rb < 4; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { m[rb][i] = -INFINITY; l[rb][i] = 0.0f; }
+  __syncthreads();
+  for (int j = 0; j < n_blk; ++j) {
+    if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], wave, R, lane);
+    if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
+    const u32x4 *buf = kbuf[j & 1];
+    for (int g = 0; g < kGqaBlockGroups; ++g) {
+      const int t_first = t_chunk + j * kGqaBlockKeys + 16 * g;
+      if (t_first >= a.T) break;  // uniform over the workgroup
+      f32x4 acc[4];
+      score_block_group<NRB>(q, buf, g, lane, acc);
+      // lazily raised row references, exactly as in psa_row_stats_kernel
+      bool slow = group_has_masked(t_first, a.T, a.W);
+      float x[4][4];
+      if (!slow) {
+        float top = -INFINITY;
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            x[rb][i] = __builtin_fmaf(acc[rb][i], scale2, -m[rb][i]);
+            top = fmaxf(top, x[rb][i]);
+          }
+        slow = __ballot(!(top <= kLazyRaise)) != 0ull;
+      }
+      if (!slow) {
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) l[rb][i] += fast_exp2(x[rb][i]);
+      } else {
+        int t = t_first + mrow;
+        asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const bool seen = key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W);
+            const float sv = seen ? scale2 * acc[rb][i] : -INFINITY;
+            const float top = row_max16(sv);
+            if (top > m[rb][i]) {  // uniform over the row's lanes; a reference of -inf goes with a zero sum
+              l[rb][i] *= fast_exp2(m[rb][i] - top);
+              m[rb][i] = top;
+            }
+            if (seen) l[rb][i] += fast_exp2(sv - m[rb][i]);
+          }
+      }
+    }
+    __syncthreads();
+  }
+  // this wavefront saw every key of the chunk for its head: its statistics are the chunk's
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float lr = row_sum16(l[rb][i]);  // the row's lanes share the reference
+      if (mrow == 0) {
+        float *dst = a.row_stats + (((size_t)bhq * a.n_chunk + chunk) * a.W + 16 * rb + 4 * qd + i) * 2;
+        dst[0] = m[rb][i];
+        dst[1] = lr;
+      }
+    }
+}
+
+// pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads (in head order) and the tail rows of 2^(s - m_row) / l_row
+template <int NRB, int MAXIT>
+__global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectArgs a) {
+  __shared__ u32x4 kbuf[2][kGqaItems * 64];
+  __shared__ float stat_m[kGqaMaxWaves][64], stat_il[kGqaMaxWaves][64];
+  // column sums of a block: one slot per (head, pair of row quarters, key), each written by one lane; two copies, so
+  // that a block's slots are added up (fixed order) while the next block is being scored
+  __shared__ float col_lds[2][kGqaMaxWaves][2][kGqaBlockKeys];
+  const int chunk = blockIdx.x, bh = blockIdx.y;
+  const int R = a.Hq / a.Hkv, b = bh / a.Hkv, hkv = bh % a.Hkv;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
+  const int bhq = b * a.Hq + hkv * R + wave;
+  const uint16_t *k_rows = a.k + (size_t)bh * a.T * kD;
+  const float scale2 = a.sm_scale * kLog2e;
+  const int t_chunk = chunk * kScoreChunk;
+  const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);
+  KeyStage<MAXIT> st;
+  request_block(k_rows, t_chunk, a.T, wave, R, mrow, qd, st);
+  if (lane < a.W) {  // merge the chunk statistics of row `lane` of this wavefront's head
+    const float *src = a.row_stats + ((size_t)bhq * a.n_chunk * a.W + lane) * 2;
+    float mm = -INFINITY;
+    for (int c = 0; c < a.n_chunk; ++c) mm = fmaxf(mm, src[(size_t)c * a.W * 2]);
+    float ll = 0.0f;
+    for (int c = 0; c < a.n_chunk; ++c) {
+      const float mc = src[(size_t)c * a.W * 2];
+      if (mc != -INFINITY) ll += src[(size_t)c * a.W * 2 + 1] * fast_exp2(mc - mm);
+    }
+    stat_m[wave][lane] = mm;
+    stat_il[wave][lane] = 1.0f / ll;
+  }
+  bf16x8 q[NRB * 4];
+  load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, q);
+  deposit_block(st, kbuf[0], wave, R, lane);
+  request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
+  wave_lds_sync();  // the statistics were written by this wavefront
+  f32x4 rm[NRB], ril[NRB];  // rows 16*rb + 4*qd + i
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    rm[rb] = *reinterpret_cast<const f32x4 *>(&stat_m[wave][16 * rb + 4 * qd]);
+    ril[rb] = *reinterpret_cast<const f32x4 *>(&stat_il[wave][16 * rb + 4 * qd]);
+  }
+  // adds up the slots of block j (all heads, head order) and stores the masses of its keys
+  auto flush_block = [&](int j) {
+    if (threadIdx.x < kGqaBlockKeys) {
+      const int t = t_chunk + j * kGqaBlockKeys + threadIdx.x;
+      float sum = 0.0f;
+      for (int h = 0; h < R; ++h) sum += col_lds[j & 1][h][0][threadIdx.x] + col_lds[j & 1][h][1][threadIdx.x];
+      if (t < a.T) a.mass[(size_t)bh * a.T + t] = sum;
+    }
+  };
+  __syncthreads();
+  for (int j = 0; j < n_blk; ++j) {
+    if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], wave, R, lane);
+    if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
+    if (j > 0) flush_block(j - 1);
+    const u32x4 *buf = kbuf[j & 1];
+    const int t_block = t_chunk + j * kGqaBlockKeys;
+    if (t_block + kGqaBlockKeys - 1 <= a.T - a.W) {
+      // Every key of the block is seen by every tail row (all but the last blocks of a context): straight-line code, the
+      // matrix products of group g + 1 issued ahead of the exponentials of group g.  With two wavefronts per SIMD the
+      // overlap of the two pipes has to come from inside a wavefront.
+      f32x4 acc[2][4];
+      score_block_group<NRB>(q, buf, 0, lane, acc[0]);
+#pragma unroll
+      for (int g = 0; g < kGqaBlockGroups; ++g) {
+        const f32x4(&cur)[4] = acc[g & 1];
+        if (g + 1 < kGqaBlockGroups) score_block_group<NRB>(q, buf, g + 1, lane, acc[(g + 1) & 1]);
+        float c0 = 0.0f, c1 = 0.0f;  // two chains: even and odd row blocks
+#pragma unroll
+        for (int rb = 0; rb < NRB; ++rb) {
+          float &cc = (rb & 1) ? c1 : c0;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            cc = __builtin_fmaf(fast_exp2(__builtin_fmaf(cur[rb][i], scale2, -rm[rb][i])), ril[rb][i], cc);
+        }
+        float c = c0 + c1;
+        c += __shfl_xor(c, 16, kWave);  // quarters qd and qd ^ 1
+        if ((qd & 1) == 0) col_lds[j & 1][wave][qd >> 1][16 * g + mrow] = c;
+      }
+    } else {
+      for (int g = 0; g < kGqaBlockGroups; ++g) {
+        const int t_first = t_block + 16 * g;
+        float c = 0.0f;
+        if (t_first < a.T) {  // uniform over the workgroup; groups past the end leave zeros in their slots
+          f32x4 acc[4];
+          score_block_group<NRB>(q, buf, g, lane, acc);
+          float c0 = 0.0f, c1 = 0.0f;
+          const int t = t_first + mrow;
+#pragma unroll
+          for (int rb = 0; rb < NRB; ++rb) {
+            float &cc = (rb & 1) ? c1 : c0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W))
+                cc = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[rb][i])), ril[rb][i], cc);
+          }
+          c = c0 + c1;
+          c += __shfl_xor(c, 16, kWave);
+        }
+        if ((qd & 1) == 0) col_lds[j & 1][wave][qd >> 1][16 * g + mrow] = c;
+      }
+    }
+    __syncthreads();
+  }
+  if (n_blk > 0) flush_block(n_blk - 1);
+}
+
 // inclusive prefix sum of one int per thread over the 256-thread workgroup, plus the workgroup total
 __device__ __forceinline__ int block_inclusive_scan(int v, int *wave_tot, int &total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -586,8 +845,26 @@ __global__ __launch_bounds__(256) void sum_heads_kernel(SelectArgs a) {
 
 }  // namespace
 
+template <int NRB, int MAXIT>
+static void launch_psa_gqa_passes(const SelectArgs &a, hipStream_t stream) {
+  const dim3 grid(a.n_chunk, a.B * a.Hkv), block(64 * (a.Hq / a.Hkv));
+  hipLaunchKernelGGL((psa_row_stats_gqa_kernel<NRB, MAXIT>), grid, block, 0, stream, a);
+  hipLaunchKernelGGL((psa_mass_gqa_kernel<NRB, MAXIT>), grid, block, 0, stream, a);
+}
 template <int NRB>
 static void launch_psa_passes(const SelectArgs &a, hipStream_t stream) {
+  if constexpr (NRB == 4) {  // the grouped-query kernels exist for W = 64 only
+    switch (a.Hq / a.Hkv) {  // pieces per wavefront = ceil(kGqaItems / heads per KV head)
+      case 2: return launch_psa_gqa_passes<NRB, 16>(a, stream);
+      case 3: return launch_psa_gqa_passes<NRB, 11>(a, stream);
+      case 4: return launch_psa_gqa_passes<NRB, 8>(a, stream);
+      case 5: return launch_psa_gqa_passes<NRB, 7>(a, stream);
+      case 6: return launch_psa_gqa_passes<NRB, 6>(a, stream);
+      case 7: return launch_psa_gqa_passes<NRB, 5>(a, stream);
+      case 8: return launch_psa_gqa_passes<NRB, 4>(a, stream);
+      default: break;
+    }
+  }
   const dim3 block(256);
   hipLaunchKernelGGL(psa_row_stats_kernel<NRB>, dim3(a.n_chunk, a.B * a.Hq), block, 0, stream, a);
   hipLaunchKernelGGL(psa_mass_kernel<NRB>, dim3(a.n_chunk, a.B * a.Hkv), block, 0, stream, a);
