@@ -386,7 +386,25 @@ __device__ __forceinline__ void score_block_group(const bf16x8 (&q)[NRB * 4], co
   }
 }
 
-// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel
+// the same products with the operands swapped: acc[rb][i] = key 4*qd + i of the group, tail row 16*rb + mrow
+template <int NRB>
+__device__ __forceinline__ void score_block_group_by_row(const bf16x8 (&q)[NRB * 4], const u32x4 *buf, int g, int lane,
+                                                         f32x4 (&acc)[4]) {
+  bf16x8 kb[4];
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc) acc[rb] = mfma_bf16(kb[kc], q[rb * 4 + kc], acc[rb]);
+  }
+}
+
+// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel.
+// The products are taken key-major (score_block_group_by_row): a lane then holds four keys of ONE tail row per row
+// block, so a row's reference and partial sum are one register each (shared with the three other lanes of the row)
+// instead of four.
 template <int NRB, int MAXIT>
 __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(SelectArgs a) {
   __shared__ u32x4 kbuf[2][kGqaItems * 64];
@@ -404,72 +422,95 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
   load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, q);
   deposit_block(st, kbuf[0], wave, R, lane);
   request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
-  float m[4][4], l[4][4];
+  float m[4], l[4];  // of tail row 16*rb + mrow, over the keys 4*qd .. 4*qd + 3 of every group
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { m[rb][i] = -INFINITY; l[rb][i] = 0.0f; }
+  for (int rb = 0; rb < 4; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0f; }
   __syncthreads();
   for (int j = 0; j < n_blk; ++j) {
     if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], wave, R, lane);
     if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
     const u32x4 *buf = kbuf[j & 1];
-    for (int g = 0; g < kGqaBlockGroups; ++g) {
-      const int t_first = t_chunk + j * kGqaBlockKeys + 16 * g;
-      if (t_first >= a.T) break;  // uniform over the workgroup
-      f32x4 acc[4];
-      score_block_group<NRB>(q, buf, g, lane, acc);
-      // lazily raised row references, exactly as in psa_row_stats_kernel
-      bool slow = group_has_masked(t_first, a.T, a.W);
-      float x[4][4];
-      if (!slow) {
-        float top = -INFINITY;
+    const int t_block = t_chunk + j * kGqaBlockKeys;
+    // A row reference is raised lazily, as in psa_row_stats_kernel: only when a logit exceeds it by more than
+    // kLazyRaise (or at the causal edge) are the references raised to the row maxima of the group and the sums rescaled.
+    auto raise_and_add = [&](const f32x4(&acc)[4], int t_first) {
+      int t = t_first + 4 * qd;
+      asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
 #pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
+      for (int rb = 0; rb < NRB; ++rb) {
+        float sv[4];
+        bool seen[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            x[rb][i] = __builtin_fmaf(acc[rb][i], scale2, -m[rb][i]);
-            top = fmaxf(top, x[rb][i]);
-          }
-        slow = __ballot(!(top <= kLazyRaise)) != 0ull;
+        for (int i = 0; i < 4; ++i) {
+          seen[i] = key_seen(t + i, 16 * rb + mrow, a.T, a.W);
+          sv[i] = seen[i] ? scale2 * acc[rb][i] : -INFINITY;
+        }
+        float top = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+        top = fmaxf(top, __shfl_xor(top, 16, kWave));
+        top = fmaxf(top, __shfl_xor(top, 32, kWave));
+        if (top > m[rb]) {  // uniform over the row's four lanes; a reference of -inf goes with a zero sum
+          l[rb] *= fast_exp2(m[rb] - top);
+          m[rb] = top;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (seen[i]) l[rb] += fast_exp2(sv[i] - m[rb]);
       }
-      if (!slow) {
+    };
+    auto add_group = [&](const f32x4(&cur)[4], int t_first) {
+      float x[4][4];
+      float top = -INFINITY;
+#pragma unroll
+      for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          x[rb][i] = __builtin_fmaf(cur[rb][i], scale2, -m[rb]);
+          top = fmaxf(top, x[rb][i]);
+        }
+      if (__ballot(!(top <= kLazyRaise)) == 0ull) {
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) l[rb][i] += fast_exp2(x[rb][i]);
+          l[rb] += (fast_exp2(x[rb][0]) + fast_exp2(x[rb][1])) + (fast_exp2(x[rb][2]) + fast_exp2(x[rb][3]));
       } else {
-        int t = t_first + mrow;
-        asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const bool seen = key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W);
-            const float sv = seen ? scale2 * acc[rb][i] : -INFINITY;
-            const float top = row_max16(sv);
-            if (top > m[rb][i]) {  // uniform over the row's lanes; a reference of -inf goes with a zero sum
-              l[rb][i] *= fast_exp2(m[rb][i] - top);
-              m[rb][i] = top;
-            }
-            if (seen) l[rb][i] += fast_exp2(sv - m[rb][i]);
-          }
+        raise_and_add(cur, t_first);
+      }
+    };
+    if (t_block + kGqaBlockKeys - 1 <= a.T - a.W) {
+      // Every key of the block is seen by every tail row (all but the last blocks of a context): no masks, and the
+      // matrix products of group g + 1 are issued ahead of the exponentials of group g.  With two wavefronts per SIMD
+      // the overlap of the two pipes has to come from inside a wavefront.
+      f32x4 acc_a[4], acc_b[4];
+      score_block_group_by_row<NRB>(q, buf, 0, lane, acc_a);
+#pragma unroll 1
+      for (int g = 0; g < kGqaBlockGroups; g += 2) {
+        score_block_group_by_row<NRB>(q, buf, g + 1, lane, acc_b);
+        add_group(acc_a, t_block + 16 * g);
+        score_block_group_by_row<NRB>(q, buf, min(g + 2, kGqaBlockGroups - 1), lane, acc_a);  // (the last one is not used)
+        add_group(acc_b, t_block + 16 * g + 16);
+      }
+    } else {
+      for (int g = 0; g < kGqaBlockGroups; ++g) {
+        const int t_first = t_block + 16 * g;
+        if (t_first >= a.T) break;  // uniform over the workgroup
+        f32x4 acc[4];
+        score_block_group_by_row<NRB>(q, buf, g, lane, acc);
+        raise_and_add(acc, t_first);
       }
     }
     __syncthreads();
   }
   // this wavefront saw every key of the chunk for its head: its statistics are the chunk's
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float lr = row_sum16(l[rb][i]);  // the row's lanes share the reference
-      if (mrow == 0) {
-        float *dst = a.row_stats + (((size_t)bhq * a.n_chunk + chunk) * a.W + 16 * rb + 4 * qd + i) * 2;
-        dst[0] = m[rb][i];
-        dst[1] = lr;
-      }
+  for (int rb = 0; rb < NRB; ++rb) {
+    float lr = l[rb];  // the row's four lanes share the reference
+    lr += __shfl_xor(lr, 16, kWave);
+    lr += __shfl_xor(lr, 32, kWave);
+    if (qd == 0) {
+      float *dst = a.row_stats + (((size_t)bhq * a.n_chunk + chunk) * a.W + 16 * rb + mrow) * 2;
+      dst[0] = m[rb];
+      dst[1] = lr;
     }
+  }
 }
 
 // pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads (in head order) and the tail rows of 2^(s - m_row) / l_row
@@ -477,9 +518,9 @@ template <int NRB, int MAXIT>
 __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectArgs a) {
   __shared__ u32x4 kbuf[2][kGqaItems * 64];
   __shared__ float stat_m[kGqaMaxWaves][64], stat_il[kGqaMaxWaves][64];
-  // column sums of a block: one slot per (head, pair of row quarters, key), each written by one lane; two copies, so
-  // that a block's slots are added up (fixed order) while the next block is being scored
-  __shared__ float col_lds[2][kGqaMaxWaves][2][kGqaBlockKeys];
+  // column sums of a block: one slot per (head, row quarter, key), each written by one lane; two copies, so that a
+  // block's slots are added up (fixed order) while the next block is being scored
+  __shared__ float col_lds[2][kGqaMaxWaves][4][kGqaBlockKeys];
   const int chunk = blockIdx.x, bh = blockIdx.y;
   const int R = a.Hq / a.Hkv, b = bh / a.Hkv, hkv = bh % a.Hkv;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
@@ -518,7 +559,9 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
     if (threadIdx.x < kGqaBlockKeys) {
       const int t = t_chunk + j * kGqaBlockKeys + threadIdx.x;
       float sum = 0.0f;
-      for (int h = 0; h < R; ++h) sum += col_lds[j & 1][h][0][threadIdx.x] + col_lds[j & 1][h][1][threadIdx.x];
+      for (int h = 0; h < R; ++h)
+        sum += (col_lds[j & 1][h][0][threadIdx.x] + col_lds[j & 1][h][1][threadIdx.x]) +
+               (col_lds[j & 1][h][2][threadIdx.x] + col_lds[j & 1][h][3][threadIdx.x]);
       if (t < a.T) a.mass[(size_t)bh * a.T + t] = sum;
     }
   };
@@ -547,9 +590,7 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
           for (int i = 0; i < 4; ++i)
             cc = __builtin_fmaf(fast_exp2(__builtin_fmaf(cur[rb][i], scale2, -rm[rb][i])), ril[rb][i], cc);
         }
-        float c = c0 + c1;
-        c += __shfl_xor(c, 16, kWave);  // quarters qd and qd ^ 1
-        if ((qd & 1) == 0) col_lds[j & 1][wave][qd >> 1][16 * g + mrow] = c;
+        col_lds[j & 1][wave][qd][16 * g + mrow] = c0 + c1;
       }
     } else {
       for (int g = 0; g < kGqaBlockGroups; ++g) {
@@ -569,9 +610,8 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
                 cc = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[rb][i])), ril[rb][i], cc);
           }
           c = c0 + c1;
-          c += __shfl_xor(c, 16, kWave);
         }
-        if ((qd & 1) == 0) col_lds[j & 1][wave][qd >> 1][16 * g + mrow] = c;
+        col_lds[j & 1][wave][qd][16 * g + mrow] = c;
       }
     }
     __syncthreads();
