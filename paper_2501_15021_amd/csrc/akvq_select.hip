@@ -323,40 +323,43 @@ __global__ __launch_bounds__(256, 4) void psa_mass_kernel(SelectArgs a) {  // re
 // ---- pivot scoring with several query heads per KV head --------------------------------------------------------
 // One workgroup per (batch, kv-head, chunk of kScoreChunk keys) with one wavefront per query head of the group.  The
 // keys are read from HBM and converted to bfloat16 once for the whole group: the wavefronts share the work of bringing
-// blocks of 128 keys into LDS (two buffers, laid out as matrix-core operands) and every wavefront scores all of them
-// against its own head, whose W tail rows it holds in registers as the other operand.  Per block and wavefront: the
-// keys of the block after next are requested into registers, the next block's are converted and stored to LDS, the
-// current block is scored; one barrier per block orders the buffers.
+// blocks of 128 keys go through LDS (two buffers, laid out as matrix-core operands) and every head's wavefront scores
+// all of them against its own head, whose W tail rows it holds in registers as the other operand.  Per block: the keys
+// of the block after next are requested into registers, the next block's are converted and stored to LDS, the current
+// block is scored; one barrier per block orders the buffers.  With fewer than eight heads per KV head the keys are
+// brought in by a wavefront of their own (the feeder, which also adds up the column sums of the second pass): it
+// takes that work off the scoring wavefronts and evens out the SIMDs; with eight heads the scoring wavefronts share it.
 constexpr int kGqaBlockGroups = 8;                                // groups of 16 keys per block
 constexpr int kGqaBlockKeys = 16 * kGqaBlockGroups;               // 128
 constexpr int kGqaBlocks = kScoreChunk / kGqaBlockKeys;           // blocks per chunk
 constexpr int kGqaItems = kGqaBlockGroups * 4;                    // 1 KB pieces (group, channel step) of a block
 constexpr int kGqaMaxWaves = 8;                                   // query heads per KV head
+constexpr int kGqaFeederItems = kGqaItems;                        // MAXIT of the kernels with a feeder wavefront
 static_assert(kScoreChunk % kGqaBlockKeys == 0, "a chunk is a whole number of blocks");
 
-// MAXIT: pieces of a block one wavefront brings in (kGqaItems / heads per KV head, rounded up: only the last can
-// fall past the block).  The loads are unconditional (a piece past the block re-reads the last one), so that they
+// MAXIT: pieces of a block one wavefront brings in: pieces first, first + stride, ... (all of them for the feeder;
+// kGqaItems / heads per KV head for shared work, where only the last can fall past the block).  The loads are unconditional (a piece past the block re-reads the last one), so that they
 // stay in straight-line code and in flight together; only the LDS store is skipped.
 template <int MAXIT>
 struct KeyStage {
   u32x4 raw[MAXIT];
 };
 template <int MAXIT>
-__device__ __forceinline__ void request_block(const uint16_t *k_rows, int t_block, int T, int wave, int R, int mrow,
+__device__ __forceinline__ void request_block(const uint16_t *k_rows, int t_block, int T, int first, int stride, int mrow,
                                               int qd, KeyStage<MAXIT> &st) {
 #pragma unroll
   for (int it = 0; it < MAXIT; ++it) {
-    const int item = min(wave + it * R, kGqaItems - 1);  // uniform over the wavefront
+    const int item = min(first + it * stride, kGqaItems - 1);  // uniform over the wavefront
     const int g = item >> 2, kc = item & 3;
     const int t = min(t_block + 16 * g + mrow, T - 1);  // rows past the end repeat the last key; never scored unmasked
     st.raw[it] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
   }
 }
 template <int MAXIT>
-__device__ __forceinline__ void deposit_block(const KeyStage<MAXIT> &st, u32x4 *buf, int wave, int R, int lane) {
+__device__ __forceinline__ void deposit_block(const KeyStage<MAXIT> &st, u32x4 *buf, int first, int stride, int lane) {
 #pragma unroll
   for (int it = 0; it < MAXIT; ++it) {
-    const int item = wave + it * R;
+    const int item = first + it * stride;
     const u32x4 piece = __builtin_bit_cast(u32x4, rows8_as_bf16(st.raw[it]));
     if (it + 1 < MAXIT || item < kGqaItems) buf[item * 64 + lane] = piece;
   }
@@ -386,6 +389,22 @@ __device__ __forceinline__ void score_block_group(const bf16x8 (&q)[NRB * 4], co
   }
 }
 
+// the two halves of the above on their own, for loops that read a group's keys one step ahead of its products;
+// BY_ROW swaps the operands: acc[rb][i] = key 4*qd + i of the group, tail row 16*rb + mrow
+__device__ __forceinline__ void read_block_group(const u32x4 *buf, int g, int lane, bf16x8 (&kb)[4]) {
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
+}
+template <int NRB, bool BY_ROW>
+__device__ __forceinline__ void products_of_group(const bf16x8 (&q)[NRB * 4], const bf16x8 (&kb)[4], f32x4 (&acc)[4]) {
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc)
+      acc[rb] = BY_ROW ? mfma_bf16(kb[kc], q[rb * 4 + kc], acc[rb]) : mfma_bf16(q[rb * 4 + kc], kb[kc], acc[rb]);
+  }
+}
 // the same products with the operands swapped: acc[rb][i] = key 4*qd + i of the group, tail row 16*rb + mrow
 template <int NRB>
 __device__ __forceinline__ void score_block_group_by_row(const bf16x8 (&q)[NRB * 4], const u32x4 *buf, int g, int lane,
@@ -416,19 +435,37 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
   const float scale2 = a.sm_scale * kLog2e;
   const int t_chunk = chunk * kScoreChunk;
   const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);  // blocks that hold keys
+  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than heads
+  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : R;
   KeyStage<MAXIT> st;
-  request_block(k_rows, t_chunk, a.T, wave, R, mrow, qd, st);
+  if (kFeeder && wave == R) {  // the feeder: same barriers as the scoring wavefronts below
+    request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
+    deposit_block(st, kbuf[0], first, stride, lane);
+    request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+    __syncthreads();
+    for (int j = 0; j < n_blk; ++j) {
+      if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], first, stride, lane);
+      if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+      __syncthreads();
+    }
+    return;
+  }
+  if constexpr (!kFeeder) request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
   bf16x8 q[NRB * 4];
   load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, q);
-  deposit_block(st, kbuf[0], wave, R, lane);
-  request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
+  if constexpr (!kFeeder) {
+    deposit_block(st, kbuf[0], first, stride, lane);
+    request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+  }
   float m[4], l[4];  // of tail row 16*rb + mrow, over the keys 4*qd .. 4*qd + 3 of every group
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0f; }
   __syncthreads();
   for (int j = 0; j < n_blk; ++j) {
-    if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], wave, R, lane);
-    if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
+    if constexpr (!kFeeder) {
+      if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], first, stride, lane);
+      if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+    }
     const u32x4 *buf = kbuf[j & 1];
     const int t_block = t_chunk + j * kGqaBlockKeys;
     // A row reference is raised lazily, as in psa_row_stats_kernel: only when a logit exceeds it by more than
@@ -480,12 +517,17 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
       // matrix products of group g + 1 are issued ahead of the exponentials of group g.  With two wavefronts per SIMD
       // the overlap of the two pipes has to come from inside a wavefront.
       f32x4 acc_a[4], acc_b[4];
-      score_block_group_by_row<NRB>(q, buf, 0, lane, acc_a);
+      bf16x8 kb_a[4], kb_b[4];  // keys are read from LDS one step ahead of their products
+      read_block_group(buf, 0, lane, kb_a);
+      read_block_group(buf, 1, lane, kb_b);
+      products_of_group<NRB, true>(q, kb_a, acc_a);
 #pragma unroll 1
       for (int g = 0; g < kGqaBlockGroups; g += 2) {
-        score_block_group_by_row<NRB>(q, buf, g + 1, lane, acc_b);
+        read_block_group(buf, min(g + 2, kGqaBlockGroups - 1), lane, kb_a);  // (past the last group: not used)
+        products_of_group<NRB, true>(q, kb_b, acc_b);
         add_group(acc_a, t_block + 16 * g);
-        score_block_group_by_row<NRB>(q, buf, min(g + 2, kGqaBlockGroups - 1), lane, acc_a);  // (the last one is not used)
+        read_block_group(buf, min(g + 3, kGqaBlockGroups - 1), lane, kb_b);
+        products_of_group<NRB, true>(q, kb_a, acc_a);
         add_group(acc_b, t_block + 16 * g + 16);
       }
     } else {
@@ -529,8 +571,36 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
   const float scale2 = a.sm_scale * kLog2e;
   const int t_chunk = chunk * kScoreChunk;
   const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);
+  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than heads
+  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : R;
+  // adds up the slots of block j (all heads in head order, quarters pairwise) and stores the masses of its keys:
+  // key_first, key_first + key_step, ... of the block
+  auto flush_block = [&](int j, int key_first, int key_step) {
+    for (int key = key_first; key < kGqaBlockKeys; key += key_step) {
+      const int t = t_chunk + j * kGqaBlockKeys + key;
+      float sum = 0.0f;
+      for (int h = 0; h < R; ++h)
+        sum += (col_lds[j & 1][h][0][key] + col_lds[j & 1][h][1][key]) +
+               (col_lds[j & 1][h][2][key] + col_lds[j & 1][h][3][key]);
+      if (t < a.T) a.mass[(size_t)bh * a.T + t] = sum;
+    }
+  };
   KeyStage<MAXIT> st;
-  request_block(k_rows, t_chunk, a.T, wave, R, mrow, qd, st);
+  if (kFeeder && wave == R) {  // the feeder: same barriers as the scoring wavefronts below
+    request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
+    deposit_block(st, kbuf[0], first, stride, lane);
+    request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+    __syncthreads();
+    for (int j = 0; j < n_blk; ++j) {
+      if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], first, stride, lane);
+      if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+      if (j > 0) flush_block(j - 1, lane, 64);
+      __syncthreads();
+    }
+    if (n_blk > 0) flush_block(n_blk - 1, lane, 64);
+    return;
+  }
+  if constexpr (!kFeeder) request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
   if (lane < a.W) {  // merge the chunk statistics of row `lane` of this wavefront's head
     const float *src = a.row_stats + ((size_t)bhq * a.n_chunk * a.W + lane) * 2;
     float mm = -INFINITY;
@@ -545,8 +615,10 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
   }
   bf16x8 q[NRB * 4];
   load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, q);
-  deposit_block(st, kbuf[0], wave, R, lane);
-  request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
+  if constexpr (!kFeeder) {
+    deposit_block(st, kbuf[0], first, stride, lane);
+    request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+  }
   wave_lds_sync();  // the statistics were written by this wavefront
   f32x4 rm[NRB], ril[NRB];  // rows 16*rb + 4*qd + i
 #pragma unroll
@@ -554,22 +626,13 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
     rm[rb] = *reinterpret_cast<const f32x4 *>(&stat_m[wave][16 * rb + 4 * qd]);
     ril[rb] = *reinterpret_cast<const f32x4 *>(&stat_il[wave][16 * rb + 4 * qd]);
   }
-  // adds up the slots of block j (all heads, head order) and stores the masses of its keys
-  auto flush_block = [&](int j) {
-    if (threadIdx.x < kGqaBlockKeys) {
-      const int t = t_chunk + j * kGqaBlockKeys + threadIdx.x;
-      float sum = 0.0f;
-      for (int h = 0; h < R; ++h)
-        sum += (col_lds[j & 1][h][0][threadIdx.x] + col_lds[j & 1][h][1][threadIdx.x]) +
-               (col_lds[j & 1][h][2][threadIdx.x] + col_lds[j & 1][h][3][threadIdx.x]);
-      if (t < a.T) a.mass[(size_t)bh * a.T + t] = sum;
-    }
-  };
   __syncthreads();
   for (int j = 0; j < n_blk; ++j) {
-    if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], wave, R, lane);
-    if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, wave, R, mrow, qd, st);
-    if (j > 0) flush_block(j - 1);
+    if constexpr (!kFeeder) {
+      if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], first, stride, lane);
+      if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
+      if (j > 0) flush_block(j - 1, threadIdx.x, blockDim.x);
+    }
     const u32x4 *buf = kbuf[j & 1];
     const int t_block = t_chunk + j * kGqaBlockKeys;
     if (t_block + kGqaBlockKeys - 1 <= a.T - a.W) {
@@ -577,11 +640,15 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
       // matrix products of group g + 1 issued ahead of the exponentials of group g.  With two wavefronts per SIMD the
       // overlap of the two pipes has to come from inside a wavefront.
       f32x4 acc[2][4];
-      score_block_group<NRB>(q, buf, 0, lane, acc[0]);
+      bf16x8 kb[2][4];  // keys are read from LDS one step ahead of their products
+      read_block_group(buf, 0, lane, kb[0]);
+      read_block_group(buf, 1, lane, kb[1]);
+      products_of_group<NRB, false>(q, kb[0], acc[0]);
 #pragma unroll
       for (int g = 0; g < kGqaBlockGroups; ++g) {
         const f32x4(&cur)[4] = acc[g & 1];
-        if (g + 1 < kGqaBlockGroups) score_block_group<NRB>(q, buf, g + 1, lane, acc[(g + 1) & 1]);
+        if (g + 2 < kGqaBlockGroups) read_block_group(buf, g + 2, lane, kb[g & 1]);
+        if (g + 1 < kGqaBlockGroups) products_of_group<NRB, false>(q, kb[(g + 1) & 1], acc[(g + 1) & 1]);
         float c0 = 0.0f, c1 = 0.0f;  // two chains: even and odd row blocks
 #pragma unroll
         for (int rb = 0; rb < NRB; ++rb) {
@@ -616,7 +683,8 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
     }
     __syncthreads();
   }
-  if (n_blk > 0) flush_block(n_blk - 1);
+  if constexpr (!kFeeder)
+    if (n_blk > 0) flush_block(n_blk - 1, threadIdx.x, blockDim.x);
 }
 
 // inclusive prefix sum of one int per thread over the 256-thread workgroup, plus the workgroup total
@@ -887,23 +955,17 @@ __global__ __launch_bounds__(256) void sum_heads_kernel(SelectArgs a) {
 
 template <int NRB, int MAXIT>
 static void launch_psa_gqa_passes(const SelectArgs &a, hipStream_t stream) {
-  const dim3 grid(a.n_chunk, a.B * a.Hkv), block(64 * (a.Hq / a.Hkv));
+  const int R = a.Hq / a.Hkv;
+  const dim3 grid(a.n_chunk, a.B * a.Hkv), block(64 * (MAXIT == kGqaFeederItems ? R + 1 : R));
   hipLaunchKernelGGL((psa_row_stats_gqa_kernel<NRB, MAXIT>), grid, block, 0, stream, a);
   hipLaunchKernelGGL((psa_mass_gqa_kernel<NRB, MAXIT>), grid, block, 0, stream, a);
 }
 template <int NRB>
 static void launch_psa_passes(const SelectArgs &a, hipStream_t stream) {
   if constexpr (NRB == 4) {  // the grouped-query kernels exist for W = 64 only
-    switch (a.Hq / a.Hkv) {  // pieces per wavefront = ceil(kGqaItems / heads per KV head)
-      case 2: return launch_psa_gqa_passes<NRB, 16>(a, stream);
-      case 3: return launch_psa_gqa_passes<NRB, 11>(a, stream);
-      case 4: return launch_psa_gqa_passes<NRB, 8>(a, stream);
-      case 5: return launch_psa_gqa_passes<NRB, 7>(a, stream);
-      case 6: return launch_psa_gqa_passes<NRB, 6>(a, stream);
-      case 7: return launch_psa_gqa_passes<NRB, 5>(a, stream);
-      case 8: return launch_psa_gqa_passes<NRB, 4>(a, stream);
-      default: break;
-    }
+    const int R = a.Hq / a.Hkv;
+    if (R == kGqaMaxWaves) return launch_psa_gqa_passes<NRB, kGqaItems / kGqaMaxWaves>(a, stream);
+    if (R >= 2 && R < kGqaMaxWaves) return launch_psa_gqa_passes<NRB, kGqaFeederItems>(a, stream);
   }
   const dim3 block(256);
   hipLaunchKernelGGL(psa_row_stats_kernel<NRB>, dim3(a.n_chunk, a.B * a.Hq), block, 0, stream, a);
