@@ -16,15 +16,26 @@ namespace akvq {
 namespace {
 
 template <int CTRL>
-__device__ __forceinline__ float dpp_move(float v) {
-  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
-}
-template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_move_u(uint32_t v) {
   return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, 0xF, 0xF, false);
 }
-constexpr int kQuadXor1 = 0xB1;  // quad_perm [1,0,3,2]
-constexpr int kQuadXor2 = 0x4E;  // quad_perm [2,3,0,1]
+// Running extrema, three operands at a time, and their reduction over the four lanes of a quad with the partner's
+// value read through DPP by the min / max itself.  Assembly, because the compiler's fminf / fmaxf first canonicalise
+// operands it cannot prove quiet (one more instruction each) and reach a partner lane through a separate move.
+__device__ __forceinline__ void minmax3(float &mn, float &mx, float a, float b) {
+  asm("v_min3_f32 %0, %0, %1, %2" : "+v"(mn) : "v"(a), "v"(b));
+  asm("v_max3_f32 %0, %0, %1, %2" : "+v"(mx) : "v"(a), "v"(b));
+}
+// (the leading s_nop covers the wait states of a DPP read after a VALU write of its source and after an EXEC write)
+__device__ __forceinline__ void quad_minmax(float &mn, float &mx) {
+  asm volatile("s_nop 4\n\t"
+               "v_min_f32_dpp %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+               "v_max_f32_dpp %1, %1, %1 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\t"
+               "s_nop 1\n\t"
+               "v_min_f32_dpp %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\t"
+               "v_max_f32_dpp %1, %1, %1 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf"
+               : "+v"(mn), "+v"(mx));
+}
 constexpr int kRowRor4 = 0x124;  // rotate right by 4 inside a row of 16 lanes
 constexpr int kRowRor8 = 0x128;
 
@@ -147,10 +158,11 @@ constexpr uint32_t kPack4Bias = (uint32_t)(0x4B400000ull * 0x01010101ull);    //
 // two-bit path with identity row mapping and none of the per-row tier arithmetic.
 // WINDOW: the last win_len appended rows also go to the recent-window rings.
 // ROPE: K rows arrive without their rotary position embedding; it is applied here, in front of the rotation.
-template <int G, bool TIERED, bool WINDOW, bool ROPE>
-__global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
-  __shared__ int slot_of_lds[4][kTokBlock];
-  __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[WINDOW ? 4 : 1][WINDOW ? 2048 : 4];  // one V tile (32 slots x 128 channels, bf16) per wavefront
+// (the tensor, 0 = K or 1 = V, is a template parameter of the body: the two differ in everything after the transform,
+// and the kernel branches once, on blockIdx.z)
+template <int G, bool TIERED, bool WINDOW, bool ROPE, int TENSOR>
+__device__ __forceinline__ void quantize_append_body(const QuantArgs &a, int (*slot_of_lds)[kTokBlock],
+                                                     uint32_t (*vtile_lds)[WINDOW ? 2048 : 4]) {
   // the wavefront index as a scalar: the block index, its first row and every base address derived from them then
   // live in scalar registers
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -159,7 +171,7 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   if (blk_rel >= a.n_blk) return;  // whole wavefront leaves; no block-wide barrier is used below
   const int blk = a.first_blk + blk_rel;
   const int bh = blockIdx.y;
-  const int tensor = blockIdx.z;  // 0 = K, 1 = V
+  constexpr int tensor = TENSOR;
   const int r = lane >> 2, j = lane & 3;
   constexpr int NG = kD / G;
 
@@ -382,19 +394,13 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
 #pragma unroll
       for (int m = g * MPG; m < (g + 1) * MPG; ++m)
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          mn = fminf(mn, u[m][i]);
-          mx = fmaxf(mx, u[m][i]);
-        }
+        for (int i = 0; i < 8; i += 2) minmax3(mn, mx, u[m][i], u[m][i + 1]);
       if (lane_sign < 0.0f) {  // extrema of the true values
         const float t = mn;
         mn = -mx;
         mx = -t;
       }
-      mn = fminf(mn, dpp_move<kQuadXor1>(mn));
-      mx = fmaxf(mx, dpp_move<kQuadXor1>(mx));
-      mn = fminf(mn, dpp_move<kQuadXor2>(mn));
-      mx = fmaxf(mx, dpp_move<kQuadXor2>(mx));
+      quad_minmax(mn, mx);
       if constexpr (!TIERED) {
         gq[g] = group_params(mn, mx, kappa, a.clip, tier_two_bit());
         meta_out[h][g] = gq[g].meta | (slots[h] >= 0 ? 0x8000u : 0u);
@@ -525,6 +531,14 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
       }
     }
   }
+}
+
+template <int G, bool TIERED, bool WINDOW, bool ROPE>
+__global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
+  __shared__ int slot_of_lds[4][kTokBlock];
+  __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[WINDOW ? 4 : 1][WINDOW ? 2048 : 4];  // one V tile (32 slots x 128 channels, bf16) per wavefront
+  if (blockIdx.z == 0) quantize_append_body<G, TIERED, WINDOW, ROPE, 0>(a, slot_of_lds, vtile_lds);
+  else quantize_append_body<G, TIERED, WINDOW, ROPE, 1>(a, slot_of_lds, vtile_lds);
 }
 
 template <int G>

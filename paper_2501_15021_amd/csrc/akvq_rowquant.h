@@ -36,15 +36,16 @@ __device__ __forceinline__ GroupQ group_params(float umin, float umax, float kap
   float cmin = __fmul_rn(clip, gmin), cmax = __fmul_rn(clip, gmax);
   float range = __fsub_rn(cmax, cmin);
   float s32 = __fmul_rn(range, tq.inv_levels);
+  // smallest binary16 >= s32: one conversion with the 16/64-bit rounding mode switched to "toward +infinity" around
+  // it (bits 3:2 of the MODE register; the mode is back to nearest-even before any other instruction runs);
+  // +infinity (0x7C00) and anything above the tier's largest scale end at that largest scale
   uint32_t s16;
-  if (!(s32 > 0.0f)) {
-    s16 = 0x3C00u;
-  } else {
-    s16 = float_to_half_bits_rne(s32);
-    if (s16 > tq.s16_max) s16 = tq.s16_max;
-    else if (half_bits_to_float(s16) < s32) s16 += 1u;
-    if (s16 > tq.s16_max) s16 = tq.s16_max;
-  }
+  asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 1\n\t"
+               "v_cvt_f16_f32 %0, %1\n\t"
+               "s_setreg_imm32_b32 hwreg(HW_REG_MODE, 2, 2), 0"
+               : "=v"(s16) : "v"(s32));
+  s16 = min(s16 & 0xFFFFu, tq.s16_max);
+  if (!(s32 > 0.0f)) s16 = 0x3C00u;
   float s = half_bits_to_float(s16);
   // 1/s correctly rounded: s has an 11-bit significand (binary16), so 1/s is either exact or at least 2^-35 (relative)
   // away from any rounding boundary of fp32, far more than the 2^-45 error left by one Newton step on the hardware
@@ -52,12 +53,13 @@ __device__ __forceinline__ GroupQ group_params(float umin, float umax, float kap
   const float r0 = __builtin_amdgcn_rcpf(s);
   float rcp = __builtin_fmaf(r0, __builtin_fmaf(-s, r0, 1.0f), r0);
   float zr = rintf(__fmul_rn(cmin, rcp));
-  int z = (zr != zr) ? 0 : -(int)fminf(fmaxf(zr, -40000.0f), 40000.0f);
-  z = min(32767, max(-32768, z));
+  zr = (zr != zr) ? 0.0f : zr;
+  const float zf = __builtin_amdgcn_fmed3f(-zr, -32768.0f, 32767.0f);  // the zero-point, saturated to int16, still a float
+  const int z = (int)zf;
   GroupQ g;
-  g.meta = s16 | ((uint32_t)(z & 0xFFFF) << 16);
+  g.meta = s16 | ((uint32_t)z << 16);
   g.rcpu = __fmul_rn(rcp, kappa);
-  g.magic_zero = kMagic + (float)z;
+  g.magic_zero = kMagic + zf;  // exact: an integer below 2^22 on top of 1.5 * 2^23
   g.s16 = s16;
   g.z = z;
   return g;
