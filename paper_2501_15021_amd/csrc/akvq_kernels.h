@@ -26,6 +26,7 @@ struct QuantArgs {
   int win_len;
   const uint16_t *rope_cos, *rope_sin;  // rotary tables for pre-RoPE K rows (null: rows arrive embedded), [n_src][64] binary16
   long long rope_stride;                // elements between the tables of consecutive batch elements
+  int skip_overlay;  // the block kernel leaves the 16-bit overlay rows to the overlay pass that follows it
 };
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream);
 

@@ -272,20 +272,7 @@ __device__ __forceinline__ void quantize_append_body(const QuantArgs &a, int (*s
 
   // recent window: is this whole block new and inside the window?  (uniform over the wavefront)
   bool win_block = false;
-  // salient overlay: is this whole block new, salient, and does it fill one 32-slot tile of the V overlay exactly
-  // (slots s0 .. s0+31 with s0 a multiple of 32)?  Text runs in front of and between 576-token images do.
-  bool sal_block = false;
-  int sal_tile = 0;
-  if constexpr (WINDOW) {
-    win_block = t0 >= a.T_len && t0 + kTokBlock <= t_end && t0 >= t_end - a.win_len;
-    if constexpr (!TIERED) {
-      const int s0 = slot_of[0];
-      const bool in_run = slot_of[lane & (kTokBlock - 1)] == s0 + (lane & (kTokBlock - 1));
-      sal_block = s0 >= 0 && (s0 & (kTokBlock - 1)) == 0 && t0 >= a.T_len && t0 + kTokBlock <= t_end &&
-                  __ballot(!in_run) == 0ull;
-      sal_tile = s0 >> 5;
-    }
-  }
+  if constexpr (WINDOW) win_block = t0 >= a.T_len && t0 + kTokBlock <= t_end && t0 >= t_end - a.win_len;
   uint32_t kw[2][2];         // K words of token half h: [h][group-of-64 word]
   uint32_t vcode[2][8];      // V: [mpair][i]: raw patterns of (X, Y) x (half 0, half 1) in the four byte lanes
   uint32_t vmask_part = 0;
@@ -338,18 +325,18 @@ __device__ __forceinline__ void quantize_append_body(const QuantArgs &a, int (*s
           }
       }
     };
-    if (valid[h] && slots[h] >= 0 && !(sal_block && tensor == 1))  // a tile-filling block stores its V tile below
+    if (valid[h] && slots[h] >= 0 && !a.skip_overlay)  // (long salient lists are stored by overlay_rows_kernel instead)
       store_bf16_row(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, slots[h], true);
     if constexpr (WINDOW) {
       const int t = t0 + 16 * h + r;
       // fine halves and padding rows carry no token: their ring slots are zeroed
       const bool token = !TIERED || (tier[h] != AKVQ_TIER_4BIT_FINE && tier[h] != AKVQ_TIER_PAD);
-      if ((win_block || sal_block) && tensor == 1) {
-        // The whole block fills one 32-slot tile of the V ring (the prefill case) and / or of the salient overlay.  In a
-        // tile the values of rows r and r+16 of one channel are neighbours; this lane owns both rows and writes its 16-bit
-        // values into the wavefront's tile in LDS, half 0 and then half 1, and the finished tile goes out as eight fully
-        // coalesced 1 KB stores.  (Scattered partial-line stores, as in the row-at-a-time path, are several times slower
-        // and would dominate the tail of a prefill launch.)
+      if (win_block && tensor == 1) {
+        // The whole block fills one 32-slot tile of the V ring (the prefill case).  In a tile the values of rows r and
+        // r+16 of one channel are neighbours; this lane owns both rows and writes its 16-bit values into the wavefront's
+        // tile in LDS, half 0 and then half 1, and the finished tile goes out as eight fully coalesced 1 KB stores.
+        // (Scattered partial-line stores, as in the row-at-a-time path, are several times slower and would dominate the
+        // tail of a prefill launch.)
         uint16_t *tile16 = reinterpret_cast<uint16_t *>(vtile_lds[wave]);
         const int sq = r >> 2, sii = r & 3;
 #pragma unroll
@@ -364,18 +351,14 @@ __device__ __forceinline__ void quantize_append_body(const QuantArgs &a, int (*s
             }
           }
         if (h == 1) {
-          // the same tile goes to the ring (slot = row mod W, a multiple of 32 here) and / or to the salient overlay
-          uint32_t *ring_out = !win_block ? nullptr : reinterpret_cast<uint32_t *>(
+          // the tile goes to the ring (slot = row mod W, a multiple of 32 here)
+          uint32_t *ring_out = reinterpret_cast<uint32_t *>(
               a.v_win + (size_t)bh * a.win_len * kD + (size_t)((t0 % max(a.win_len, 1)) >> 5) * 4096);
-          uint32_t *sal_out = !sal_block ? nullptr : reinterpret_cast<uint32_t *>(
-              a.v_sal + (size_t)bh * a.S_cap * kD + (size_t)sal_tile * 4096);
           wave_lds_sync();
 #pragma unroll
-          for (int x = 0; x < 8; ++x) {
-            const u32x4 piece = *reinterpret_cast<const u32x4 *>(vtile_lds[wave] + 256 * x + 4 * lane);
-            if (ring_out != nullptr) *reinterpret_cast<u32x4 *>(ring_out + 256 * x + 4 * lane) = piece;
-            if (sal_out != nullptr) *reinterpret_cast<u32x4 *>(sal_out + 256 * x + 4 * lane) = piece;
-          }
+          for (int x = 0; x < 8; ++x)
+            *reinterpret_cast<u32x4 *>(ring_out + 256 * x + 4 * lane) =
+                *reinterpret_cast<const u32x4 *>(vtile_lds[wave] + 256 * x + 4 * lane);
           wave_lds_sync();
         }
       }
@@ -541,6 +524,119 @@ __global__ __launch_bounds__(256) void quantize_append_kernel(QuantArgs a) {
   else quantize_append_body<G, TIERED, WINDOW, ROPE, 1>(a, slot_of_lds, vtile_lds);
 }
 
+// ------------------------------------------------------------------------------------------------
+// The 16-bit overlay rows of a long salient list (text-salient layers, Section III-B.1 / III-C.1), as a pass of their
+// own behind the block kernel: one wavefront per 32-slot tile of the overlay and tensor.  It gathers the tile's rows
+// through the salient list, transforms them exactly as the block kernel does (same butterflies, same roundings) and
+// stores K rows whole and the V tile through LDS as eight coalesced 1 KB pieces, instead of one 2-byte store per value
+// from whichever block a row happens to sit in.  Slots of the tile that are not being written (rows of earlier
+// appends, unused slots) keep their contents: unless every slot is new the tile is read into LDS first.
+// ------------------------------------------------------------------------------------------------
+template <bool ROPE>
+__global__ __launch_bounds__(256) void overlay_rows_kernel(QuantArgs a) {
+  __shared__ __attribute__((aligned(16))) uint32_t vtile_lds[4][2048];
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  const int bh = blockIdx.y, tensor = blockIdx.z;
+  const int s0 = (blockIdx.x * 4 + wave) * kTokBlock;
+  const int cnt = min(max(a.sal_cnt[bh], 0), a.S_cap);
+  if (s0 >= cnt) return;  // whole wavefront leaves; no block-wide barrier is used below
+  const int r = lane >> 2, j = lane & 3;
+  const int t_end = a.T_len + a.n_new;
+  const uint16_t *src = tensor == 0 ? a.k_new : a.v_new;
+  const bool rotate = (tensor == 0 ? a.rotate_k : a.rotate_v) != 0;
+  const float kappa_s = rotate ? quad_sign(j) * inv_sqrt128() : 1.0f;
+  const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
+
+  bool fresh[2];  // this lane's slot of half h holds a row of this append
+  u32x4 raw[2][4];
+  u32x4 rope_c[ROPE ? 2 : 1][2], rope_s[ROPE ? 2 : 1][2];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    const int slot = s0 + 16 * h + r;
+    const int t = slot < cnt ? sidx[slot] : -1;
+    fresh[h] = t >= a.T_len && t < t_end;
+    const int rel = min(max(t - a.T_len, 0), a.n_new - 1);  // other rows read a clamped (valid) address; nothing of them is stored
+    const uint16_t *row = src + ((size_t)bh * a.n_src + rel) * kD;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) raw[h][m] = *reinterpret_cast<const u32x4 *>(row + 32 * m + 8 * j);
+    if constexpr (ROPE) {
+      if (tensor == 0) {
+        const size_t at = (size_t)(bh / a.Hkv) * a.rope_stride + (size_t)rel * 64 + 8 * j;
+#pragma unroll
+        for (int mm = 0; mm < 2; ++mm) {
+          rope_c[h][mm] = *reinterpret_cast<const u32x4 *>(a.rope_cos + at + 32 * mm);
+          rope_s[h][mm] = *reinterpret_cast<const u32x4 *>(a.rope_sin + at + 32 * mm);
+        }
+      }
+    }
+  }
+  const unsigned long long n_fresh = __ballot(fresh[0]) | __ballot(fresh[1]);
+  if (n_fresh == 0ull) return;  // a tile of earlier rows
+  const bool all_fresh = __ballot(!fresh[0]) == 0ull && __ballot(!fresh[1]) == 0ull;
+  uint32_t *tile_out = reinterpret_cast<uint32_t *>(a.v_sal + (size_t)bh * a.S_cap * kD + (size_t)(s0 >> 5) * 4096);
+  if (tensor == 1 && !all_fresh) {
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+      *reinterpret_cast<u32x4 *>(vtile_lds[wave] + 256 * x + 4 * lane) =
+          *reinterpret_cast<const u32x4 *>(tile_out + 256 * x + 4 * lane);
+    wave_lds_sync();
+  }
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    float u[4][8];  // quad_sign(j) times the (rotated) row
+    if constexpr (ROPE) {
+      if (tensor == 0) rope_row_quad(raw[h], rope_c[h], rope_s[h]);
+    }
+    if (rotate) {
+      wht128_quad(raw[h], u, j);
+    } else {
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          u[m][2 * w] = half_bits_to_float(raw[h][m][w] & 0xFFFFu);
+          u[m][2 * w + 1] = half_bits_to_float(raw[h][m][w] >> 16);
+        }
+    }
+    if (tensor == 0) {
+      if (fresh[h]) {
+        uint16_t *dst = a.k_sal + ((size_t)bh * a.S_cap + s0 + 16 * h + r) * kD;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          u32x4 o;
+#pragma unroll
+          for (int w = 0; w < 4; ++w)
+            o[w] = pack_bf16x2(scaled_row_value(u[m][2 * w], kappa_s), scaled_row_value(u[m][2 * w + 1], kappa_s));
+          *reinterpret_cast<u32x4 *>(dst + 32 * m + 8 * j) = o;
+        }
+      }
+    } else if (fresh[h]) {
+      // in a tile the values of slots r and r + 16 of one channel are neighbours (see the recent-window tiles)
+      uint16_t *tile16 = reinterpret_cast<uint16_t *>(vtile_lds[wave]);
+      const int sq = r >> 2, sii = r & 3;
+#pragma unroll
+      for (int m = 0; m < 4; ++m)
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t pk = pack_bf16x2(scaled_row_value(u[m][2 * w], kappa_s), scaled_row_value(u[m][2 * w + 1], kappa_s));
+#pragma unroll
+          for (int c = 0; c < 2; ++c) {
+            const int e = 32 * m + 8 * j + 2 * w + c, nb = e >> 4, n = e & 15;
+            tile16[nb * 512 + (16 * sq + n) * 8 + 2 * sii + h] = (uint16_t)(c == 0 ? pk : pk >> 16);
+          }
+        }
+    }
+  }
+  if (tensor == 1) {
+    wave_lds_sync();
+#pragma unroll
+    for (int x = 0; x < 8; ++x)
+      *reinterpret_cast<u32x4 *>(tile_out + 256 * x + 4 * lane) =
+          *reinterpret_cast<const u32x4 *>(vtile_lds[wave] + 256 * x + 4 * lane);
+  }
+}
+
 template <int G>
 __global__ __launch_bounds__(64) void append_row_kernel(QuantArgs a) {
   __shared__ __attribute__((aligned(16))) uint8_t code_lds[kD];
@@ -569,6 +665,8 @@ static void launch_blocks(const QuantArgs &a, int B, int G, bool window, hipStre
 #undef AKVQ_LAUNCH_Q
 }
 
+static hipError_t launch_block_ranges(const QuantArgs &a, int B, int G, hipStream_t stream);
+
 hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t stream) {
   if (a.n_new == 1 && a.n_src == 1 && a.row_tier == nullptr) {  // the decode step: one plain row per (batch, kv-head)
     dim3 grid(B * a.Hkv, 2), block(64);
@@ -576,11 +674,25 @@ hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t 
     else hipLaunchKernelGGL(append_row_kernel<64>, grid, block, 0, stream, a);
     return hipGetLastError();
   }
-  // The instantiation with the tile path also stores salient V rows of tile-filling blocks as whole tiles: worth its
-  // extra registers when the salient lists are long (text-salient layers), not for a handful of pivots.
-  const bool dense_salient = a.S_cap > 64;
+  // Long salient lists (text-salient layers) get their overlay rows from a pass of their own behind the block kernel;
+  // a handful of pivots (and the rows of a tiered append, whose tiers the block kernel knows) are stored by the block
+  // kernel itself.
+  if (a.S_cap > 64 && a.row_tier == nullptr) {
+    QuantArgs blocks = a;
+    blocks.skip_overlay = 1;
+    hipError_t e = launch_block_ranges(blocks, B, G, stream);
+    if (e != hipSuccess) return e;
+    dim3 grid((a.S_cap / kTokBlock + 3) / 4, B * a.Hkv, 2), block(256);
+    if (a.rope_cos != nullptr) hipLaunchKernelGGL(overlay_rows_kernel<true>, grid, block, 0, stream, a);
+    else hipLaunchKernelGGL(overlay_rows_kernel<false>, grid, block, 0, stream, a);
+    return hipGetLastError();
+  }
+  return launch_block_ranges(a, B, G, stream);
+}
+
+hipError_t launch_block_ranges(const QuantArgs &a, int B, int G, hipStream_t stream) {
   if (a.win_len <= 0) {
-    launch_blocks(a, B, G, dense_salient, stream);
+    launch_blocks(a, B, G, false, stream);
     return hipGetLastError();
   }
   // Recent window: only the blocks that hold the last win_len new rows write ring slots.  A long append (prefill)
@@ -593,7 +705,7 @@ hipError_t launch_quantize_append(const QuantArgs &a, int B, int G, hipStream_t 
     QuantArgs head = a;
     head.n_blk = win_first_blk - a.first_blk;
     head.win_len = 0;
-    launch_blocks(head, B, G, dense_salient, stream);
+    launch_blocks(head, B, G, false, stream);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
