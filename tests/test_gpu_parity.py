@@ -111,6 +111,27 @@ def test_quantize_long_salient_lists(orc, T, every):
     assert_cache_equal(oc, gc, f"T={T} every={every} salient={n_sal}")
 
 
+def test_quantize_long_salient_list_in_pieces(orc):
+    """A long salient list filled over several appends: overlay tiles then hold rows of earlier appends next to the new
+    ones (and unused slots, pre-filled with a pattern), which the overlay pass must leave as they are."""
+    T = 900
+    w = synth.small("qlist_pieces", B=2, Hq=2, Hkv=2, T=T, G=64)
+    d = _np(synth.generate(w, seed=81))
+    mask = np.zeros((w.B, T), dtype=np.uint8)
+    mask[:, ::2] = 1
+    mask[:, 130:260] = 1
+    mask[1, 600:] = 0  # the batch elements differ
+    n_sal = int(mask.sum(axis=1).max())
+    oc, gc = make_pair(orc, w, fill=0x5A, t_cap=(T + 63) // 64 * 64, s_cap=(n_sal + 63) // 64 * 64)
+    oc.select_tsa(mask)
+    copy_salient_to_gpu(oc, gc)
+    cuts = [0, 33, 34, 100, 163, 164, 512, 899, 900]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        oc.quantize_append(d["k"][:, :, a:b], d["v"][:, :, a:b], 0.8)
+        akvq.quantize_append(gc, _dev(d["k"][:, :, a:b]), _dev(d["v"][:, :, a:b]), 0.8)
+        assert_cache_equal(oc, gc, f"rows {a}:{b}")
+
+
 def test_quantize_reciprocal_ties_over_scale_values(orc):
     """Rows built so that the stored scale is a chosen binary16 value s (extrema -s and 2s, clip 1) and the other
     elements sit on multiples of s/4: x/s + zero then lands exactly on .5 ties up to the rounding of 1/s, so the
