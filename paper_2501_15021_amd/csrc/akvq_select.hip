@@ -51,12 +51,13 @@ __global__ __launch_bounds__(256) void select_tsa_kernel(SelectArgs a) {
 }
 
 // ---- pivot scoring ---------------------------------------------------------------------------------------
-// Each workgroup (4 wavefronts) owns kScoreChunk consecutive keys of one (batch, head); a wavefront walks its quarter
-// in groups of 16 keys, with the next group's loads in flight while the current one goes through the matrix cores.
+// One query head per KV head: each workgroup (4 wavefronts) owns kScoreChunk consecutive keys of one (batch, head);
+// its wavefronts take the groups of 16 keys in turn, with the next groups' loads in flight while the current one goes
+// through the matrix cores.  (Several query heads per KV head: see the grouped-query kernels further down.)
 // Logits are kept in the base-2 domain (sm_scale * log2(e) folded into one multiply) so that exponentials are bare
 // v_exp_f32; both passes use the same domain, so the statistics carry over unchanged.
 constexpr int kGroupsPerWave = kScoreChunk / (4 * 16);
-constexpr int kKeyDepth = 1;  // key groups in flight ahead of the one being scored
+constexpr int kKeyDepth = 1;  // key groups in flight ahead of the one being scored in the second pass (deeper is slower)
 static_assert(kGroupsPerWave % (kKeyDepth + 1) == 0, "the scoring loop is unrolled over the key ring");
 
 // binary16 pair (packed) -> bfloat16 pair (packed), each rounded to nearest even
@@ -88,8 +89,9 @@ __device__ __forceinline__ void load_key_group(const uint16_t *k_rows, int t_fir
     g.raw[kc] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
 }
 
-// dot products of the W tail rows of one query head with 16 keys: acc[rb][i] = row 16*rb + 4*qd + i, key = mrow
-template <int NRB>
+// dot products of the W tail rows of one query head with 16 keys: acc[rb][i] = row 16*rb + 4*qd + i, key = mrow;
+// BY_ROW swaps the operands: acc[rb][i] = key 4*qd + i of the group, tail row 16*rb + mrow
+template <int NRB, bool BY_ROW = false>
 __device__ __forceinline__ void score_16keys(const u32x4 *q_lds, const KeyGroup &g, int mrow, int qd, f32x4 (&acc)[4]) {
   // The query operands live in LDS and are re-read for every key group: the offset is made opaque so the reads are
   // not hoisted out of the caller's loop into 64 registers (which would cost a wavefront of occupancy).
@@ -103,7 +105,8 @@ __device__ __forceinline__ void score_16keys(const u32x4 *q_lds, const KeyGroup 
     acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
-      acc[rb] = mfma_bf16(__builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), kb[kc], acc[rb]);
+      acc[rb] = BY_ROW ? mfma_bf16(kb[kc], __builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), acc[rb])
+                       : mfma_bf16(__builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), kb[kc], acc[rb]);
   }
 }
 // causal visibility of key t for tail row `row` (the row sits at position T-W+row); keys past the end are never seen
@@ -126,7 +129,73 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLazyRaise = 12.0f;  // a row reference is raised only for logits this far (base 2) above it
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }  // bare v_exp_f32
 
-// pass 1: per (b, hq, chunk): running max and sum of exponentials (base 2) of every tail row
+// ---- row statistics of the first pass, key-major ---------------------------------------------------------------
+// The products are taken with the keys as the first operand: acc[rb][i] = key 4*qd + i of the group against tail row
+// 16*rb + mrow, so a lane holds four keys of ONE tail row per row block, and a row's reference m and partial sum l
+// are one register each (shared with the three other lanes of the row) instead of four.
+// m is a reference, not the running maximum: it is raised only when a logit exceeds it by more than kLazyRaise (or at
+// the causal edge), so in the common case the sums just grow; otherwise the references are raised to the row maxima
+// of the group and the sums rescaled.
+struct RowStats {
+  float m[4], l[4];
+};
+template <int NRB>
+__device__ __forceinline__ void stats_raise_and_add(RowStats &s, const f32x4 (&acc)[4], float scale2, int t_first, int T,
+                                                    int W, int mrow, int qd) {
+  int t = t_first + 4 * qd;
+  asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    float sv[4];
+    bool seen[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      seen[i] = key_seen(t + i, 16 * rb + mrow, T, W);
+      sv[i] = seen[i] ? scale2 * acc[rb][i] : -INFINITY;
+    }
+    float top = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+    top = fmaxf(top, __shfl_xor(top, 16, kWave));
+    top = fmaxf(top, __shfl_xor(top, 32, kWave));
+    if (top > s.m[rb]) {  // uniform over the row's four lanes; a reference of -inf goes with a zero sum
+      s.l[rb] *= fast_exp2(s.m[rb] - top);
+      s.m[rb] = top;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (seen[i]) s.l[rb] += fast_exp2(sv[i] - s.m[rb]);
+  }
+}
+// a group every key of which is seen by every tail row
+template <int NRB>
+__device__ __forceinline__ void stats_add_group(RowStats &s, const f32x4 (&acc)[4], float scale2, int t_first, int T,
+                                                int W, int mrow, int qd) {
+  float x[4][4];
+  float top = -INFINITY;
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      x[rb][i] = __builtin_fmaf(acc[rb][i], scale2, -s.m[rb]);
+      top = fmaxf(top, x[rb][i]);
+    }
+  if (__ballot(!(top <= kLazyRaise)) == 0ull) {
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
+      s.l[rb] += (fast_exp2(x[rb][0]) + fast_exp2(x[rb][1])) + (fast_exp2(x[rb][2]) + fast_exp2(x[rb][3]));
+  } else {
+    stats_raise_and_add<NRB>(s, acc, scale2, t_first, T, W, mrow, qd);
+  }
+}
+// the row's four lanes share the reference: their sums add up (lanes of quarter 0 hold the result)
+__device__ __forceinline__ float stats_row_sum(float l) {
+  l += __shfl_xor(l, 16, kWave);
+  l += __shfl_xor(l, 32, kWave);
+  return l;
+}
+
+// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row
+constexpr int kStatsDepth = 3;  // key groups in flight ahead of the one being scored in the first pass
+static_assert(kGroupsPerWave % (kStatsDepth + 1) == 0, "the scoring loop is unrolled over the key ring");
 template <int NRB>
 __global__ __launch_bounds__(256, 4) void psa_row_stats_kernel(SelectArgs a) {  // 4 wavefronts per SIMD: at most 128 registers
   __shared__ float st_m[4][64], st_l[4][64];
@@ -139,81 +208,35 @@ __global__ __launch_bounds__(256, 4) void psa_row_stats_kernel(SelectArgs a) {  
   // the wavefronts take the chunk's groups of 16 keys in turn, so the workgroup walks its keys front to back in 16 KB
   // windows (a quarter of the chunk per wavefront, i.e. four distant streams per workgroup, is 3-4 % slower on HBM)
   const int t_wave = chunk * kScoreChunk + wave * 16;
-  // kKeyDepth groups of keys are in flight ahead of the one being scored (a ring of register buffers; loads are
+  // kStatsDepth groups of keys are in flight ahead of the one being scored (a ring of register buffers; loads are
   // unconditional with clamped addresses, so the wait counts the compiler derives stay exact).  The first keys are
   // requested before the query rows are staged, so the two latencies overlap.
-  KeyGroup ring[kKeyDepth + 1];
+  KeyGroup ring[kStatsDepth + 1];
 #pragma unroll
-  for (int p = 0; p < kKeyDepth; ++p) load_key_group(k_rows, t_wave + 64 * p, a.T, mrow, qd, ring[p]);
+  for (int p = 0; p < kStatsDepth; ++p) load_key_group(k_rows, t_wave + 64 * p, a.T, mrow, qd, ring[p]);
   stage_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, wave, mrow, qd, q_lds);
   __syncthreads();
-  float m[4][4], l[4][4];
+  RowStats st;  // of tail row 16*rb + mrow, over the keys 4*qd .. 4*qd + 3 of every group
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb)
+  for (int rb = 0; rb < 4; ++rb) { st.m[rb] = -INFINITY; st.l[rb] = 0.0f; }
+  for (int g0 = 0; g0 < kGroupsPerWave; g0 += kStatsDepth + 1)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) { m[rb][i] = -INFINITY; l[rb][i] = 0.0f; }
-#pragma unroll
-  for (int p = 0; p < kKeyDepth; ++p)
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) settle(ring[p].raw[kc]);
-  for (int g0 = 0; g0 < kGroupsPerWave; g0 += kKeyDepth + 1)
-#pragma unroll
-  for (int u = 0; u <= kKeyDepth; ++u) {
+  for (int u = 0; u <= kStatsDepth; ++u) {
     const int g = g0 + u;
     const int t_first = t_wave + 64 * g;
-    load_key_group(k_rows, t_wave + 64 * min(g + kKeyDepth, kGroupsPerWave - 1), a.T, mrow, qd,
-                   ring[(u + kKeyDepth) % (kKeyDepth + 1)]);
+    load_key_group(k_rows, t_wave + 64 * min(g + kStatsDepth, kGroupsPerWave - 1), a.T, mrow, qd,
+                   ring[(u + kStatsDepth) % (kStatsDepth + 1)]);
     if (t_first >= a.T) continue;  // uniform over the wavefront
-    const KeyGroup &cur = ring[u];
     f32x4 acc[4];
-    score_16keys<NRB>(q_lds, cur, mrow, qd, acc);
-    // m[rb][i] is a reference shared by the 16 lanes (keys) of a row, not the running maximum: it is raised only
-    // when a logit exceeds it by more than kLazyRaise, so in the common case (nothing masked, no such logit) the
-    // sums just grow.  Otherwise (first group, a new large logit, the causal edge) the references are raised to the
-    // row maxima of this group and the sums rescaled.
-    bool slow = group_has_masked(t_first, a.T, a.W);
-    float x[4][4];
-    if (!slow) {
-      float top = -INFINITY;
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          x[rb][i] = __builtin_fmaf(acc[rb][i], scale2, -m[rb][i]);
-          top = fmaxf(top, x[rb][i]);
-        }
-      slow = __ballot(!(top <= kLazyRaise)) != 0ull;
-    }
-    if (!slow) {
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) l[rb][i] += fast_exp2(x[rb][i]);
-    } else {
-      int t = t_first + mrow;
-      asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const bool seen = key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W);
-          const float sv = seen ? scale2 * acc[rb][i] : -INFINITY;
-          const float top = row_max16(sv);
-          if (top > m[rb][i]) {  // uniform over the row's lanes; a reference of -inf goes with a zero sum
-            l[rb][i] *= fast_exp2(m[rb][i] - top);
-            m[rb][i] = top;
-          }
-          if (seen) l[rb][i] += fast_exp2(sv - m[rb][i]);
-        }
-    }
+    score_16keys<NRB, true>(q_lds, ring[u], mrow, qd, acc);
+    if (!group_has_masked(t_first, a.T, a.W)) stats_add_group<NRB>(st, acc, scale2, t_first, a.T, a.W, mrow, qd);
+    else stats_raise_and_add<NRB>(st, acc, scale2, t_first, a.T, a.W, mrow, qd);
   }
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float lr = row_sum16(l[rb][i]);  // the row's lanes share the reference
-      if (mrow == 0) { st_m[wave][16 * rb + 4 * qd + i] = m[rb][i]; st_l[wave][16 * rb + 4 * qd + i] = lr; }
-    }
+  for (int rb = 0; rb < NRB; ++rb) {
+    const float lr = stats_row_sum(st.l[rb]);
+    if (qd == 0) { st_m[wave][16 * rb + mrow] = st.m[rb]; st_l[wave][16 * rb + mrow] = lr; }
+  }
   __syncthreads();
   if (threadIdx.x < a.W) {
     const int row = threadIdx.x;
@@ -420,10 +443,7 @@ __device__ __forceinline__ void score_block_group_by_row(const bf16x8 (&q)[NRB *
   }
 }
 
-// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel.
-// The products are taken key-major (score_block_group_by_row): a lane then holds four keys of ONE tail row per row
-// block, so a row's reference and partial sum are one register each (shared with the three other lanes of the row)
-// instead of four.
+// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel
 template <int NRB, int MAXIT>
 __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(SelectArgs a) {
   __shared__ u32x4 kbuf[2][kGqaItems * 64];
@@ -457,9 +477,9 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
   }
-  float m[4], l[4];  // of tail row 16*rb + mrow, over the keys 4*qd .. 4*qd + 3 of every group
+  RowStats st_row;  // of tail row 16*rb + mrow, over the keys 4*qd .. 4*qd + 3 of every group
 #pragma unroll
-  for (int rb = 0; rb < 4; ++rb) { m[rb] = -INFINITY; l[rb] = 0.0f; }
+  for (int rb = 0; rb < 4; ++rb) { st_row.m[rb] = -INFINITY; st_row.l[rb] = 0.0f; }
   __syncthreads();
   for (int j = 0; j < n_blk; ++j) {
     if constexpr (!kFeeder) {
@@ -468,50 +488,6 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
     }
     const u32x4 *buf = kbuf[j & 1];
     const int t_block = t_chunk + j * kGqaBlockKeys;
-    // A row reference is raised lazily, as in psa_row_stats_kernel: only when a logit exceeds it by more than
-    // kLazyRaise (or at the causal edge) are the references raised to the row maxima of the group and the sums rescaled.
-    auto raise_and_add = [&](const f32x4(&acc)[4], int t_first) {
-      int t = t_first + 4 * qd;
-      asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb) {
-        float sv[4];
-        bool seen[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          seen[i] = key_seen(t + i, 16 * rb + mrow, a.T, a.W);
-          sv[i] = seen[i] ? scale2 * acc[rb][i] : -INFINITY;
-        }
-        float top = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-        top = fmaxf(top, __shfl_xor(top, 16, kWave));
-        top = fmaxf(top, __shfl_xor(top, 32, kWave));
-        if (top > m[rb]) {  // uniform over the row's four lanes; a reference of -inf goes with a zero sum
-          l[rb] *= fast_exp2(m[rb] - top);
-          m[rb] = top;
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          if (seen[i]) l[rb] += fast_exp2(sv[i] - m[rb]);
-      }
-    };
-    auto add_group = [&](const f32x4(&cur)[4], int t_first) {
-      float x[4][4];
-      float top = -INFINITY;
-#pragma unroll
-      for (int rb = 0; rb < NRB; ++rb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          x[rb][i] = __builtin_fmaf(cur[rb][i], scale2, -m[rb]);
-          top = fmaxf(top, x[rb][i]);
-        }
-      if (__ballot(!(top <= kLazyRaise)) == 0ull) {
-#pragma unroll
-        for (int rb = 0; rb < NRB; ++rb)
-          l[rb] += (fast_exp2(x[rb][0]) + fast_exp2(x[rb][1])) + (fast_exp2(x[rb][2]) + fast_exp2(x[rb][3]));
-      } else {
-        raise_and_add(cur, t_first);
-      }
-    };
     if (t_block + kGqaBlockKeys - 1 <= a.T - a.W) {
       // Every key of the block is seen by every tail row (all but the last blocks of a context): no masks, and the
       // matrix products of group g + 1 are issued ahead of the exponentials of group g.  With two wavefronts per SIMD
@@ -525,10 +501,10 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
       for (int g = 0; g < kGqaBlockGroups; g += 2) {
         read_block_group(buf, min(g + 2, kGqaBlockGroups - 1), lane, kb_a);  // (past the last group: not used)
         products_of_group<NRB, true>(q, kb_b, acc_b);
-        add_group(acc_a, t_block + 16 * g);
+        stats_add_group<NRB>(st_row, acc_a, scale2, t_block + 16 * g, a.T, a.W, mrow, qd);
         read_block_group(buf, min(g + 3, kGqaBlockGroups - 1), lane, kb_b);
         products_of_group<NRB, true>(q, kb_a, acc_a);
-        add_group(acc_b, t_block + 16 * g + 16);
+        stats_add_group<NRB>(st_row, acc_b, scale2, t_block + 16 * g + 16, a.T, a.W, mrow, qd);
       }
     } else {
       for (int g = 0; g < kGqaBlockGroups; ++g) {
@@ -536,7 +512,7 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
         if (t_first >= a.T) break;  // uniform over the workgroup
         f32x4 acc[4];
         score_block_group_by_row<NRB>(q, buf, g, lane, acc);
-        raise_and_add(acc, t_first);
+        stats_raise_and_add<NRB>(st_row, acc, scale2, t_first, a.T, a.W, mrow, qd);
       }
     }
     __syncthreads();
@@ -544,12 +520,10 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
   // this wavefront saw every key of the chunk for its head: its statistics are the chunk's
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
-    float lr = l[rb];  // the row's four lanes share the reference
-    lr += __shfl_xor(lr, 16, kWave);
-    lr += __shfl_xor(lr, 32, kWave);
+    const float lr = stats_row_sum(st_row.l[rb]);
     if (qd == 0) {
       float *dst = a.row_stats + (((size_t)bhq * a.n_chunk + chunk) * a.W + 16 * rb + mrow) * 2;
-      dst[0] = m[rb];
+      dst[0] = st_row.m[rb];
       dst[1] = lr;
     }
   }
