@@ -661,7 +661,8 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
     if (n_blk > 0) flush_block(n_blk - 1, threadIdx.x, blockDim.x);
 }
 
-// inclusive prefix sum of one int per thread over the 256-thread workgroup, plus the workgroup total
+// inclusive prefix sum of one int per thread over a workgroup of NW wavefronts, plus the workgroup total
+template <int NW>
 __device__ __forceinline__ int block_inclusive_scan(int v, int *wave_tot, int &total) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -674,7 +675,7 @@ __device__ __forceinline__ int block_inclusive_scan(int v, int *wave_tot, int &t
   __syncthreads();
   int before = 0, tot = 0;
 #pragma unroll
-  for (int w = 0; w < 4; ++w) {
+  for (int w = 0; w < NW; ++w) {
     const int c = wave_tot[w];
     if (w < wave) before += c;
     tot += c;
@@ -688,16 +689,18 @@ __device__ __forceinline__ int block_inclusive_scan(int v, int *wave_tot, int &t
 constexpr int kTopkStageMax = 32768;  // keys (128 KB of LDS)
 constexpr int kTopkListMax = 256;     // selected positions ordered through LDS when k is at most this
 constexpr int kTopkCandMax = 512;     // candidates the short cut ranks among themselves
-template <bool STAGED>
-__global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
+constexpr int kTopkWideFrom = 8192, kTopkWideRows = 512, kTopkWideThreads = 1024;  // see launch_topk
+// NT threads per workgroup (256, or 1024 for long rows: the passes over the keys are what takes the time there)
+template <bool STAGED, int NT>
+__global__ __launch_bounds__(NT) void topk_kernel(SelectArgs a) {
   extern __shared__ float keys_lds[];
   __shared__ int hist[256];
-  __shared__ int wave_tot[4];
+  __shared__ int wave_tot[NT / 64];
   __shared__ uint32_t sh_prefix;
   __shared__ int sh_need;
   __shared__ int list_n;
   __shared__ int list[kTopkListMax];
-  __shared__ uint32_t thread_max[256];
+  __shared__ uint32_t thread_max[NT];
   __shared__ int cand_n;
   __shared__ uint32_t cand_key[kTopkCandMax];
   __shared__ int cand_pos[kTopkCandMax];
@@ -708,7 +711,7 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   const uint32_t lowest = a.skip_zero ? 1u : 0u;  // keys below this bit pattern (i.e. +0) are never selected
   if (STAGED) {
     uint32_t mine = 0u;  // largest key this thread staged (bit patterns of non-negative floats order like the floats)
-    for (int t = threadIdx.x; t < a.T; t += 256) {
+    for (int t = threadIdx.x; t < a.T; t += NT) {
       const float x = mass[t];
       keys_lds[t] = x;
       mine = max(mine, __float_as_uint(x));
@@ -717,21 +720,23 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
     thread_max[threadIdx.x] = mine;
     __syncthreads();
     if (k <= 128) {
-      // Short cut for the usual case (a few pivots out of thousands of keys): the k-th largest of the 256 per-thread
+      // Short cut for the usual case (a few pivots out of thousands of keys): the k-th largest of the per-thread
       // maxima is a lower bound of the k-th largest key, and few keys reach it.  They are collected and ranked among
       // themselves (key descending, position ascending: the order of the radix path).  Too many candidates (many equal
-      // keys): the radix passes below take over.  Every wavefront finds the bound for itself (four maxima per lane),
-      // bit by bit from the top: the largest x with at least k maxima >= x.
-      const uint32_t m0 = thread_max[lane], m1 = thread_max[lane + 64], m2 = thread_max[lane + 128],
-                     m3 = thread_max[lane + 192];
+      // keys): the radix passes below take over.  Every wavefront finds the bound for itself (NT / 64 maxima per
+      // lane), bit by bit from the top: the largest x with at least k maxima >= x.
+      uint32_t mx[NT / 64];
+#pragma unroll
+      for (int i = 0; i < NT / 64; ++i) mx[i] = thread_max[lane + 64 * i];
       uint32_t bound = 0u;
       for (int bit = 31; bit >= 0; --bit) {
         const uint32_t cand = bound | (1u << bit);
-        const int n_ge = __popcll(__ballot(m0 >= cand)) + __popcll(__ballot(m1 >= cand)) +
-                         __popcll(__ballot(m2 >= cand)) + __popcll(__ballot(m3 >= cand));
+        int n_ge = 0;
+#pragma unroll
+        for (int i = 0; i < NT / 64; ++i) n_ge += __popcll(__ballot(mx[i] >= cand));
         if (n_ge >= k) bound = cand;
       }
-      for (int t = threadIdx.x; t < a.T; t += 256) {
+      for (int t = threadIdx.x; t < a.T; t += NT) {
         const uint32_t bits = __float_as_uint(keys_lds[t]);
         if (bits >= bound && bits >= lowest) {
           const int at = atomicAdd(&cand_n, 1);
@@ -741,7 +746,7 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
       __syncthreads();
       const int n_cand = cand_n;
       if (n_cand <= kTopkCandMax) {  // uniform
-        for (int c = threadIdx.x; c < n_cand; c += 256) {
+        for (int c = threadIdx.x; c < n_cand; c += NT) {
           const uint32_t key = cand_key[c];
           const int pos = cand_pos[c];
           int beaten_by = 0;
@@ -768,10 +773,10 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   uint32_t prefix = 0;
   int need = k;
   for (int pass = 3; pass >= 0; --pass) {
-    hist[threadIdx.x] = 0;
+    if (threadIdx.x < 256) hist[threadIdx.x] = 0;
     __syncthreads();
     const uint32_t hi_mask = pass == 3 ? 0u : (0xFFFFFFFFu << (8 * (pass + 1)));
-    for (int t = threadIdx.x; t < a.T; t += 256) {
+    for (int t = threadIdx.x; t < a.T; t += NT) {
       const uint32_t bits = __float_as_uint(keys[t]);
       if ((bits & hi_mask) == (prefix & hi_mask)) {
         // the leading digits of the keys of a wavefront mostly coincide: one add for all of them then
@@ -788,11 +793,11 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
     __syncthreads();
     // thread i looks at bin 255-i: the prefix sum over threads is the count of candidates in bins >= that bin; the
     // digit of the k-th largest key is the first bin (from the top) where that count reaches `need`
-    const int bin = 255 - (int)threadIdx.x;
-    const int mine = hist[bin];
+    const int bin = 255 - (int)threadIdx.x;  // (threads past the 256 bins add nothing to the sums)
+    const int mine = bin >= 0 ? hist[bin] : 0;
     int total;
-    const int upto = block_inclusive_scan(mine, wave_tot, total);
-    if (upto >= need && upto - mine < need) {
+    const int upto = block_inclusive_scan<NT / 64>(mine, wave_tot, total);
+    if (bin >= 0 && upto >= need && upto - mine < need) {
       sh_prefix = prefix | ((uint32_t)bin << (8 * pass));
       sh_need = need - (upto - mine);
       if (pass == 0) hist[0] = mine;  // number of keys equal to the k-th largest (bin 0's own count is not needed again)
@@ -805,7 +810,7 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   const int n_equal = hist[0];
   if (STAGED && k <= kTopkListMax && n_equal == need) {
     // every key >= prefix is taken: gather their positions in any order, then order the short list by rank
-    for (int t = threadIdx.x; t < a.T; t += 256) {
+    for (int t = threadIdx.x; t < a.T; t += NT) {
       const uint32_t bits = __float_as_uint(keys[t]);
       if (bits >= prefix && bits >= lowest) list[atomicAdd(&list_n, 1)] = t;
     }
@@ -822,12 +827,12 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
   }
   // general case: each thread owns a contiguous run of positions, so two workgroup scans (equal keys, taken keys)
   // order the output
-  const int per = (a.T + 255) / 256;
+  const int per = (a.T + NT - 1) / NT;
   const int t0 = min((int)threadIdx.x * per, a.T), t1 = min(t0 + per, a.T);
   int n_eq = 0;
   for (int t = t0; t < t1; ++t) n_eq += __float_as_uint(keys[t]) == prefix;
   int tot_eq;
-  int eq_rank = block_inclusive_scan(n_eq, wave_tot, tot_eq) - n_eq;
+  int eq_rank = block_inclusive_scan<NT / 64>(n_eq, wave_tot, tot_eq) - n_eq;
   int n_take = 0;
   {
     int r = eq_rank;
@@ -837,7 +842,7 @@ __global__ __launch_bounds__(256) void topk_kernel(SelectArgs a) {
     }
   }
   int tot_take;
-  int pos = block_inclusive_scan(n_take, wave_tot, tot_take) - n_take;
+  int pos = block_inclusive_scan<NT / 64>(n_take, wave_tot, tot_take) - n_take;
   if (n_take > 0) {
     for (int t = t0; t < t1; ++t) {
       const uint32_t bits = __float_as_uint(keys[t]);
@@ -884,10 +889,34 @@ static hipError_t topk_allow_large_lds() {
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev >= 0 && dev < 64 && ((done.load(std::memory_order_acquire) >> dev) & 1ull)) return hipSuccess;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          (int)(kTopkStageMax * sizeof(float)));
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true, kTopkWideThreads>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTopkStageMax * sizeof(float)));
+  if (e == hipSuccess)
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(&topk_kernel<true, 256>),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kTopkStageMax * sizeof(float)));
   if (e == hipSuccess && dev >= 0 && dev < 64) done.fetch_or(1ull << dev, std::memory_order_release);
   return e;
+}
+
+// One workgroup per row of keys.  Few long rows (at most kTopkWideRows rows of kTopkWideFrom keys or more) get
+// workgroups of 1024 threads: the time goes into the passes over the keys then, and 256-thread workgroups would leave
+// most of the chip idle.  With many rows the small workgroups already fill it (and are 6 % faster at 2048 x 8192).
+static hipError_t launch_topk(const SelectArgs &k, hipStream_t stream) {
+  const dim3 grid(k.B * k.Hkv);
+  const bool wide = k.T >= kTopkWideFrom && (long)k.B * k.Hkv <= kTopkWideRows;
+  const size_t lds = k.T <= kTopkStageMax ? (size_t)k.T * sizeof(float) : 0;
+  if (lds > 48 * 1024) {
+    hipError_t e = topk_allow_large_lds();
+    if (e != hipSuccess) return e;
+  }
+  if (k.T > kTopkStageMax) {
+    if (wide) hipLaunchKernelGGL((topk_kernel<false, kTopkWideThreads>), grid, dim3(kTopkWideThreads), 0, stream, k);
+    else hipLaunchKernelGGL((topk_kernel<false, 256>), grid, dim3(256), 0, stream, k);
+  } else {
+    if (wide) hipLaunchKernelGGL((topk_kernel<true, kTopkWideThreads>), grid, dim3(kTopkWideThreads), lds, stream, k);
+    else hipLaunchKernelGGL((topk_kernel<true, 256>), grid, dim3(256), lds, stream, k);
+  }
+  return hipGetLastError();
 }
 
 hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream) {
@@ -895,17 +924,7 @@ hipError_t launch_select_massive(const SelectArgs &a, hipStream_t stream) {
   hipLaunchKernelGGL(massive_score_kernel, dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, a);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  if (a.T <= kTopkStageMax) {
-    const size_t lds = (size_t)a.T * sizeof(float);
-    if (lds > 48 * 1024) {
-      e = topk_allow_large_lds();
-      if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, a);
-  } else {
-    hipLaunchKernelGGL(topk_kernel<false>, dim3(a.B * a.Hkv), dim3(256), 0, stream, a);
-  }
-  return hipGetLastError();
+  return launch_topk(a, stream);
 }
 
 hipError_t launch_select_tsa(const SelectArgs &a, hipStream_t stream) {
@@ -963,16 +982,7 @@ hipError_t launch_select_psa(const SelectArgs &a, hipStream_t stream) {
     k.mass = a.mass_shared;
     k.mass_per_batch = 1;
   }
-  if (a.T <= kTopkStageMax) {
-    const size_t lds = (size_t)a.T * sizeof(float);
-    if (lds > 48 * 1024) {
-      e = topk_allow_large_lds();
-      if (e != hipSuccess) return e;
-    }
-    hipLaunchKernelGGL(topk_kernel<true>, dim3(a.B * a.Hkv), dim3(256), lds, stream, k);
-  } else
-    hipLaunchKernelGGL(topk_kernel<false>, dim3(a.B * a.Hkv), dim3(256), 0, stream, k);
-  return hipGetLastError();
+  return launch_topk(k, stream);
 }
 
 }  // namespace akvq
