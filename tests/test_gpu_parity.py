@@ -288,6 +288,14 @@ def test_select_psa_small(orc):
     check_psa(orc, w, 106, 8)
 
 
+@pytest.mark.parametrize("R,T", [(4, 2500), (5, 130), (6, 2049), (8, 4200), (2, 64)])
+def test_select_psa_grouped_heads(orc, R, T):
+    """W = 64 with several query heads per KV head: the kernels with a wavefront per head (a feeder wavefront below
+    eight heads, shared loading with eight); contexts of one block, of a chunk plus one key, of several chunks."""
+    w = synth.small(f"psa_gqa{R}", B=2, Hq=2 * R, Hkv=2, T=T, W=64, top_k=min(16, T), n_text_head=4, n_text_tail=1)
+    check_psa(orc, w, 4100 + 10 * R, w.top_k)
+
+
 def test_select_psa_longer_than_the_staged_topk(orc):
     """More than 32768 keys: 17 score chunks per head and the top-k that reads its keys from memory instead of LDS;
     top_k above the short-list limit takes the general ordering path as well."""

@@ -111,6 +111,38 @@ def test_rope_with_tiers_and_window(orc):
     _check_decode(orc, oc, gc, d["q"], np.array([w.T, w.T]), w, "tiered + window + rope", n_splits=(0, 2))
 
 
+@pytest.mark.parametrize("G", [128, 64])
+def test_rope_long_salient_list_with_window(orc, G):
+    """Pre-RoPE K, a salient list of several overlay tiles (every other token plus a dense run) and a recent window, in
+    pieces: the overlay rows come from the pass behind the block kernel, which applies the embedding itself, next to
+    ring stores of the windowed instantiation."""
+    T = 420
+    w = synth.small(f"rope_list{G}", B=2, Hq=2, Hkv=2, T=T, G=G, n_text_head=9, n_text_tail=6, top_k=5, W=16)
+    d = _np(synth.generate(w, seed=172))
+    mask = np.zeros((w.B, T), dtype=np.uint8)
+    mask[:, 1::2] = 1
+    mask[:, 96:170] = 1
+    n_sal = int(mask.sum(axis=1).max())
+    s_cap = (n_sal + 63) // 64 * 64
+    assert s_cap > 64
+    oc = orc.OracleCache(w.B, w.Hkv, G, 448, s_cap, fill=0)
+    gc = akvq.Cache(w.B, w.Hkv, G, 448, s_cap, fill=0)
+    oc.enable_window(64); gc.enable_window(64)
+    oc.select_tsa(mask)
+    gc.sal_idx.copy_(_dev(oc.sal_idx))
+    gc.counts().copy_(_dev(oc.sal_cnt))
+    pos = np.array([3, 50])[:, None] + np.arange(T)[None, :]
+    for lo, hi in ((0, 70), (70, 71), (71, 300), (300, 420)):
+        cos, sin = synth.rope_tables(pos[:, lo:hi])
+        k, v = d["k"][:, :, lo:hi], d["v"][:, :, lo:hi]
+        oc.quantize_append_tiered(orc.rope_rows(k, cos, sin), v, None, None, w.clip, 1.0)
+        akvq.quantize_append_tiered(gc, _dev(k), _dev(v), None, None, w.clip, 1.0, rope=(_dev(cos), _dev(sin)))
+        _assert_cache_equal(oc, gc, f"rows {lo}..{hi}")
+    rng = np.random.default_rng(4)
+    q = rng.standard_normal((w.B, 2, 128)).astype(np.float16)
+    _check_decode(orc, oc, gc, q, pos[:, T - 1] + 1, w, "long list + window + rope", per_batch=True)
+
+
 def test_rope_rejects_prerotated_inputs():
     gc = akvq.Cache(1, 1, 128, 64, 64)
     k = torch.zeros(1, 1, 4, 128, dtype=torch.float16, device="cuda")
