@@ -68,16 +68,6 @@ __device__ __forceinline__ bf16x8 rows8_as_bf16(u32x4 raw) {
   u32x4 r = {half2_to_bf16x2(raw[0]), half2_to_bf16x2(raw[1]), half2_to_bf16x2(raw[2]), half2_to_bf16x2(raw[3])};
   return __builtin_bit_cast(bf16x8, r);
 }
-__device__ __forceinline__ float row_max16(float v) {
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, kWave));
-  return v;
-}
-__device__ __forceinline__ float row_sum16(float v) {
-#pragma unroll
-  for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
-}
 
 struct KeyGroup {
   u32x4 raw[4];  // 16 keys x 128 channels as this lane's four 8-channel pieces (binary16)
@@ -398,22 +388,10 @@ __device__ __forceinline__ void load_query_rows(const uint16_t *q_head, int mrow
       q[rb * 4 + kc] = rows8_as_bf16(
           *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd));
 }
-template <int NRB>
-__device__ __forceinline__ void score_block_group(const bf16x8 (&q)[NRB * 4], const u32x4 *buf, int g, int lane,
-                                                  f32x4 (&acc)[4]) {
-  bf16x8 kb[4];
-#pragma unroll
-  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
-#pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) {
-    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) acc[rb] = mfma_bf16(q[rb * 4 + kc], kb[kc], acc[rb]);
-  }
-}
-
-// the two halves of the above on their own, for loops that read a group's keys one step ahead of its products;
-// BY_ROW swaps the operands: acc[rb][i] = key 4*qd + i of the group, tail row 16*rb + mrow
+// One group of 16 keys of a block against the head's rows: the keys' operands are read from LDS (read_block_group) and
+// multiplied (products_of_group) in two steps, so that loops can read a group ahead of its products.  Row-major:
+// acc[rb][i] = tail row 16*rb + 4*qd + i, key mrow; BY_ROW swaps the operands: acc[rb][i] = key 4*qd + i of the group,
+// tail row 16*rb + mrow.
 __device__ __forceinline__ void read_block_group(const u32x4 *buf, int g, int lane, bf16x8 (&kb)[4]) {
 #pragma unroll
   for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
@@ -428,19 +406,12 @@ __device__ __forceinline__ void products_of_group(const bf16x8 (&q)[NRB * 4], co
       acc[rb] = BY_ROW ? mfma_bf16(kb[kc], q[rb * 4 + kc], acc[rb]) : mfma_bf16(q[rb * 4 + kc], kb[kc], acc[rb]);
   }
 }
-// the same products with the operands swapped: acc[rb][i] = key 4*qd + i of the group, tail row 16*rb + mrow
-template <int NRB>
-__device__ __forceinline__ void score_block_group_by_row(const bf16x8 (&q)[NRB * 4], const u32x4 *buf, int g, int lane,
-                                                         f32x4 (&acc)[4]) {
+template <int NRB, bool BY_ROW>
+__device__ __forceinline__ void score_block_group(const bf16x8 (&q)[NRB * 4], const u32x4 *buf, int g, int lane,
+                                                  f32x4 (&acc)[4]) {
   bf16x8 kb[4];
-#pragma unroll
-  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
-#pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) {
-    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int kc = 0; kc < 4; ++kc) acc[rb] = mfma_bf16(kb[kc], q[rb * 4 + kc], acc[rb]);
-  }
+  read_block_group(buf, g, lane, kb);
+  products_of_group<NRB, BY_ROW>(q, kb, acc);
 }
 
 // pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel
@@ -511,7 +482,7 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
         const int t_first = t_block + 16 * g;
         if (t_first >= a.T) break;  // uniform over the workgroup
         f32x4 acc[4];
-        score_block_group_by_row<NRB>(q, buf, g, lane, acc);
+        score_block_group<NRB, true>(q, buf, g, lane, acc);
         stats_raise_and_add<NRB>(st_row, acc, scale2, t_first, a.T, a.W, mrow, qd);
       }
     }
@@ -639,7 +610,7 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
         float c = 0.0f;
         if (t_first < a.T) {  // uniform over the workgroup; groups past the end leave zeros in their slots
           f32x4 acc[4];
-          score_block_group<NRB>(q, buf, g, lane, acc);
+          score_block_group<NRB, false>(q, buf, g, lane, acc);
           float c0 = 0.0f, c1 = 0.0f;
           const int t = t_first + mrow;
 #pragma unroll
