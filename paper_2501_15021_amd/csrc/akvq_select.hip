@@ -79,9 +79,46 @@ __device__ __forceinline__ void load_key_group(const uint16_t *k_rows, int t_fir
     g.raw[kc] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
 }
 
-// dot products of the W tail rows of one query head with 16 keys: acc[rb][i] = row 16*rb + 4*qd + i, key = mrow;
-// BY_ROW swaps the operands: acc[rb][i] = key 4*qd + i of the group, tail row 16*rb + mrow
-template <int NRB, bool BY_ROW = false>
+// The same 16 keys as they come from memory line by line: load i covers keys 4i .. 4i+3 whole, lane l taking the
+// (l % 16)-th 16-byte piece of key 4i + l / 16, so every load is 1 KB of consecutive bytes (eight full cache lines, each
+// fetched by one instruction only) and can carry the non-temporal hint.
+__device__ __forceinline__ void load_key_lines(const uint16_t *k_rows, int t_first, int T, int lane, KeyGroup &g) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int t = min(t_first + 4 * i + (lane >> 4), T - 1);  // rows past the end repeat the last key; the causal mask removes them
+    g.raw[i] = stream_load(reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 8 * (lane & 15)));
+  }
+}
+// ... turned into matrix-core operands through the wavefront's own 4 KB of LDS (converted to bfloat16 on the way in):
+// piece p of key r sits at slot r * 16 + (p ^ r), which keeps both the writes (16 pieces of one key) and the reads (one
+// piece of 16 keys) free of bank conflicts.  Same wavefront on both sides; its LDS instructions complete in order.
+__device__ __forceinline__ void lines_to_operands(const KeyGroup &g, u32x4 *tile, int lane, bf16x8 (&kb)[4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int r = 4 * i + (lane >> 4), p = lane & 15;
+    tile[r * 16 + (p ^ r)] = __builtin_bit_cast(u32x4, rows8_as_bf16(g.raw[i]));
+  }
+  const int mrow = lane & 15, qd = lane >> 4;
+#pragma unroll
+  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, tile[mrow * 16 + ((4 * kc + qd) ^ mrow)]);
+}
+// products of such operands with the query rows in LDS, keys as the first operand: acc[rb][i] = key 4*qd + i of the
+// group, tail row 16*rb + mrow (the query operands are re-read per group behind an opaque offset, see score_16keys)
+template <int NRB>
+__device__ __forceinline__ void score_operands_by_row(const u32x4 *q_lds, const bf16x8 (&kb)[4], int mrow, int qd,
+                                                      f32x4 (&acc)[4]) {
+  uint32_t lane_off = (uint32_t)(qd * 16 + mrow);
+  asm volatile("" : "+v"(lane_off));
+#pragma unroll
+  for (int rb = 0; rb < NRB; ++rb) {
+    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kc = 0; kc < 4; ++kc)
+      acc[rb] = mfma_bf16(kb[kc], __builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), acc[rb]);
+  }
+}
+// dot products of the W tail rows of one query head with 16 keys: acc[rb][i] = row 16*rb + 4*qd + i, key = mrow
+template <int NRB>
 __device__ __forceinline__ void score_16keys(const u32x4 *q_lds, const KeyGroup &g, int mrow, int qd, f32x4 (&acc)[4]) {
   // The query operands live in LDS and are re-read for every key group: the offset is made opaque so the reads are
   // not hoisted out of the caller's loop into 64 registers (which would cost a wavefront of occupancy).
@@ -95,8 +132,7 @@ __device__ __forceinline__ void score_16keys(const u32x4 *q_lds, const KeyGroup 
     acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
-      acc[rb] = BY_ROW ? mfma_bf16(kb[kc], __builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), acc[rb])
-                       : mfma_bf16(__builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), kb[kc], acc[rb]);
+      acc[rb] = mfma_bf16(__builtin_bit_cast(bf16x8, q_lds[(rb * 4 + kc) * 64 + lane_off]), kb[kc], acc[rb]);
   }
 }
 // causal visibility of key t for tail row `row` (the row sits at position T-W+row); keys past the end are never seen
@@ -195,15 +231,18 @@ __global__ __launch_bounds__(256, 4) void psa_row_stats_kernel(SelectArgs a) {  
   const uint16_t *k_rows = a.k + ((size_t)b * a.Hkv + hkv) * a.T * kD;
   const float scale2 = a.sm_scale * kLog2e;
   __shared__ u32x4 q_lds[NRB * 4 * 64];
+  __shared__ u32x4 key_tile[4][256];
   // the wavefronts take the chunk's groups of 16 keys in turn, so the workgroup walks its keys front to back in 16 KB
   // windows (a quarter of the chunk per wavefront, i.e. four distant streams per workgroup, is 3-4 % slower on HBM)
   const int t_wave = chunk * kScoreChunk + wave * 16;
   // kStatsDepth groups of keys are in flight ahead of the one being scored (a ring of register buffers; loads are
   // unconditional with clamped addresses, so the wait counts the compiler derives stay exact).  The first keys are
-  // requested before the query rows are staged, so the two latencies overlap.
+  // requested before the query rows are staged, so the two latencies overlap.  The keys come line by line with the
+  // non-temporal hint and are turned into operands through LDS (2-4 % of the pass; the second pass would lose a
+  // workgroup per CU to the extra 16 KB and keeps its direct half-line loads).
   KeyGroup ring[kStatsDepth + 1];
 #pragma unroll
-  for (int p = 0; p < kStatsDepth; ++p) load_key_group(k_rows, t_wave + 64 * p, a.T, mrow, qd, ring[p]);
+  for (int p = 0; p < kStatsDepth; ++p) load_key_lines(k_rows, t_wave + 64 * p, a.T, lane, ring[p]);
   stage_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, wave, mrow, qd, q_lds);
   __syncthreads();
   RowStats st;  // of tail row 16*rb + mrow, over the keys 4*qd .. 4*qd + 3 of every group
@@ -214,11 +253,13 @@ __global__ __launch_bounds__(256, 4) void psa_row_stats_kernel(SelectArgs a) {  
   for (int u = 0; u <= kStatsDepth; ++u) {
     const int g = g0 + u;
     const int t_first = t_wave + 64 * g;
-    load_key_group(k_rows, t_wave + 64 * min(g + kStatsDepth, kGroupsPerWave - 1), a.T, mrow, qd,
+    load_key_lines(k_rows, t_wave + 64 * min(g + kStatsDepth, kGroupsPerWave - 1), a.T, lane,
                    ring[(u + kStatsDepth) % (kStatsDepth + 1)]);
     if (t_first >= a.T) continue;  // uniform over the wavefront
     f32x4 acc[4];
-    score_16keys<NRB, true>(q_lds, ring[u], mrow, qd, acc);
+    bf16x8 kb[4];
+    lines_to_operands(ring[u], key_tile[wave], lane, kb);
+    score_operands_by_row<NRB>(q_lds, kb, mrow, qd, acc);
     if (!group_has_masked(t_first, a.T, a.W)) stats_add_group<NRB>(st, acc, scale2, t_first, a.T, a.W, mrow, qd);
     else stats_raise_and_add<NRB>(st, acc, scale2, t_first, a.T, a.W, mrow, qd);
   }
