@@ -439,13 +439,14 @@ __device__ __forceinline__ void read_block_group(const u32x4 *buf, int g, int la
 }
 template <int NRB, bool BY_ROW>
 __device__ __forceinline__ void products_of_group(const bf16x8 (&q)[NRB * 4], const bf16x8 (&kb)[4], f32x4 (&acc)[4]) {
+  // channel step outermost: consecutive products belong to different row blocks, so none waits for the one before it
 #pragma unroll
-  for (int rb = 0; rb < NRB; ++rb) {
-    acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int rb = 0; rb < NRB; ++rb) acc[rb] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int kc = 0; kc < 4; ++kc)
+  for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+    for (int rb = 0; rb < NRB; ++rb)
       acc[rb] = BY_ROW ? mfma_bf16(kb[kc], q[rb * 4 + kc], acc[rb]) : mfma_bf16(q[rb * 4 + kc], kb[kc], acc[rb]);
-  }
 }
 template <int NRB, bool BY_ROW>
 __device__ __forceinline__ void score_block_group(const bf16x8 (&q)[NRB * 4], const u32x4 *buf, int g, int lane,
