@@ -157,7 +157,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 
 // ---- row statistics of the first pass, key-major ---------------------------------------------------------------
 // The products are taken with the keys as the first operand: acc[rb][i] = key 4*qd + i of the group against tail row
-// 16*rb + mrow, so a lane holds four keys of ONE tail row per row block, and a row's reference m and partial sum l
+// row0 + 16*rb + mrow, so a lane holds four keys of ONE tail row per row block, and a row's reference m and partial sum l
 // are one register each (shared with the three other lanes of the row) instead of four.
 // m is a reference, not the running maximum: it is raised only when a logit exceeds it by more than kLazyRaise (or at
 // the causal edge), so in the common case the sums just grow; otherwise the references are raised to the row maxima
@@ -167,7 +167,7 @@ struct RowStats {
 };
 template <int NRB>
 __device__ __forceinline__ void stats_raise_and_add(RowStats &s, const f32x4 (&acc)[4], float scale2, int t_first, int T,
-                                                    int W, int mrow, int qd) {
+                                                    int W, int mrow, int qd, int row0 = 0) {
   int t = t_first + 4 * qd;
   asm volatile("" : "+v"(t));  // keeps the masks from being precomputed ahead of the loop
 #pragma unroll
@@ -176,7 +176,7 @@ __device__ __forceinline__ void stats_raise_and_add(RowStats &s, const f32x4 (&a
     bool seen[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      seen[i] = key_seen(t + i, 16 * rb + mrow, T, W);
+      seen[i] = key_seen(t + i, row0 + 16 * rb + mrow, T, W);
       sv[i] = seen[i] ? scale2 * acc[rb][i] : -INFINITY;
     }
     float top = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
@@ -194,7 +194,7 @@ __device__ __forceinline__ void stats_raise_and_add(RowStats &s, const f32x4 (&a
 // a group every key of which is seen by every tail row
 template <int NRB>
 __device__ __forceinline__ void stats_add_group(RowStats &s, const f32x4 (&acc)[4], float scale2, int t_first, int T,
-                                                int W, int mrow, int qd) {
+                                                int W, int mrow, int qd, int row0 = 0) {
   float x[4][4];
   float top = -INFINITY;
 #pragma unroll
@@ -209,7 +209,7 @@ __device__ __forceinline__ void stats_add_group(RowStats &s, const f32x4 (&acc)[
     for (int rb = 0; rb < NRB; ++rb)
       s.l[rb] += (fast_exp2(x[rb][0]) + fast_exp2(x[rb][1])) + (fast_exp2(x[rb][2]) + fast_exp2(x[rb][3]));
   } else {
-    stats_raise_and_add<NRB>(s, acc, scale2, t_first, T, W, mrow, qd);
+    stats_raise_and_add<NRB>(s, acc, scale2, t_first, T, W, mrow, qd, row0);
   }
 }
 // the row's four lanes share the reference: their sums add up (lanes of quarter 0 hold the result)
@@ -375,25 +375,31 @@ __global__ __launch_bounds__(256, 4) void psa_mass_kernel(SelectArgs a) {  // re
 }
 
 // ---- pivot scoring with several query heads per KV head --------------------------------------------------------
-// One workgroup per (batch, kv-head, chunk of kScoreChunk keys) with one wavefront per query head of the group.  The
-// keys are read from HBM and converted to bfloat16 once for the whole group: the wavefronts share the work of bringing
-// blocks of 128 keys go through LDS (two buffers, laid out as matrix-core operands) and every head's wavefront scores
-// all of them against its own head, whose W tail rows it holds in registers as the other operand.  Per block: the keys
-// of the block after next are requested into registers, the next block's are converted and stored to LDS, the current
-// block is scored; one barrier per block orders the buffers.  With fewer than eight heads per KV head the keys are
-// brought in by a wavefront of their own (the feeder, which also adds up the column sums of the second pass): it
-// takes that work off the scoring wavefronts and evens out the SIMDs; with eight heads the scoring wavefronts share it.
-constexpr int kGqaBlockGroups = 8;                                // groups of 16 keys per block
-constexpr int kGqaBlockKeys = 16 * kGqaBlockGroups;               // 128
+// One workgroup per (batch, kv-head, chunk of kScoreChunk keys) with one or two wavefronts per query head of the group,
+// each holding all or half of the head's W = 64 tail rows in registers as one matrix operand.  The keys are read from
+// HBM and converted to bfloat16 once for the whole group: blocks of 64 keys go through LDS (two buffers, laid out as
+// matrix-core operands) and every scoring wavefront multiplies all of them with its rows.  Per block: the keys of the
+// block after next are requested into registers, the next block's are converted and stored to LDS, the current block
+// is scored; one barrier per block orders the buffers.  With fewer than eight heads per KV head the keys are brought
+// in by a wavefront of their own (the feeder, which also adds up the column sums of the second pass); with eight
+// heads the scoring wavefronts share that work.
+// The first pass runs two wavefronts per head (32 rows and under 128 registers each, four wavefronts per SIMD: 10 %
+// faster than one per head at about 200 registers and two per SIMD); the second pass one per head (with two, every
+// key operand is read from LDS twice for half the arithmetic each time: 17 % slower).
+constexpr int kGqaBlockGroups = 4;                                // groups of 16 keys per block
+constexpr int kGqaBlockKeys = 16 * kGqaBlockGroups;               // 64
 constexpr int kGqaBlocks = kScoreChunk / kGqaBlockKeys;           // blocks per chunk
 constexpr int kGqaItems = kGqaBlockGroups * 4;                    // 1 KB pieces (group, channel step) of a block
-constexpr int kGqaMaxWaves = 8;                                   // query heads per KV head
+constexpr int kGqaMaxHeads = 8;                                   // query heads per KV head
 constexpr int kGqaFeederItems = kGqaItems;                        // MAXIT of the kernels with a feeder wavefront
 static_assert(kScoreChunk % kGqaBlockKeys == 0, "a chunk is a whole number of blocks");
+static_assert(kGqaBlockGroups % 2 == 0, "the first pass walks a block two groups at a time");
+static_assert(kGqaItems % (2 * kGqaMaxHeads) == 0, "up to sixteen scoring wavefronts share a block's pieces evenly");
 
 // MAXIT: pieces of a block one wavefront brings in: pieces first, first + stride, ... (all of them for the feeder;
-// kGqaItems / heads per KV head for shared work, where only the last can fall past the block).  The loads are unconditional (a piece past the block re-reads the last one), so that they
-// stay in straight-line code and in flight together; only the LDS store is skipped.
+// kGqaItems / (scoring wavefronts) each when eight heads' scoring wavefronts share the work).  The loads are unconditional and in
+// straight-line code, so that they are in flight together (under per-piece branches the wait counts the compiler
+// inserts serialise them).
 template <int MAXIT>
 struct KeyStage {
   u32x4 raw[MAXIT];
@@ -403,7 +409,7 @@ __device__ __forceinline__ void request_block(const uint16_t *k_rows, int t_bloc
                                               int qd, KeyStage<MAXIT> &st) {
 #pragma unroll
   for (int it = 0; it < MAXIT; ++it) {
-    const int item = min(first + it * stride, kGqaItems - 1);  // uniform over the wavefront
+    const int item = first + it * stride;  // uniform over the wavefront
     const int g = item >> 2, kc = item & 3;
     const int t = min(t_block + 16 * g + mrow, T - 1);  // rows past the end repeat the last key; never scored unmasked
     st.raw[it] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
@@ -412,27 +418,24 @@ __device__ __forceinline__ void request_block(const uint16_t *k_rows, int t_bloc
 template <int MAXIT>
 __device__ __forceinline__ void deposit_block(const KeyStage<MAXIT> &st, u32x4 *buf, int first, int stride, int lane) {
 #pragma unroll
-  for (int it = 0; it < MAXIT; ++it) {
-    const int item = first + it * stride;
-    const u32x4 piece = __builtin_bit_cast(u32x4, rows8_as_bf16(st.raw[it]));
-    if (it + 1 < MAXIT || item < kGqaItems) buf[item * 64 + lane] = piece;
-  }
+  for (int it = 0; it < MAXIT; ++it)
+    buf[(first + it * stride) * 64 + lane] = __builtin_bit_cast(u32x4, rows8_as_bf16(st.raw[it]));
 }
-// the W tail rows of one query head as matrix-core operands in registers: q[rb * 4 + kc] is what this lane feeds for
-// row block rb and channel step kc
+// NRB row blocks of one query head, from row block rb0 on, as matrix-core operands in registers: q[rb * 4 + kc] is
+// what this lane feeds for row block rb0 + rb and channel step kc
 template <int NRB>
-__device__ __forceinline__ void load_query_rows(const uint16_t *q_head, int mrow, int qd, bf16x8 (&q)[NRB * 4]) {
+__device__ __forceinline__ void load_query_rows(const uint16_t *q_head, int rb0, int mrow, int qd, bf16x8 (&q)[NRB * 4]) {
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb)
 #pragma unroll
     for (int kc = 0; kc < 4; ++kc)
       q[rb * 4 + kc] = rows8_as_bf16(
-          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * rb + mrow) * kD + 32 * kc + 8 * qd));
+          *reinterpret_cast<const u32x4 *>(q_head + (size_t)(16 * (rb0 + rb) + mrow) * kD + 32 * kc + 8 * qd));
 }
-// One group of 16 keys of a block against the head's rows: the keys' operands are read from LDS (read_block_group) and
-// multiplied (products_of_group) in two steps, so that loops can read a group ahead of its products.  Row-major:
-// acc[rb][i] = tail row 16*rb + 4*qd + i, key mrow; BY_ROW swaps the operands: acc[rb][i] = key 4*qd + i of the group,
-// tail row 16*rb + mrow.
+// One group of 16 keys of a block against the wavefront's rows: the keys' operands are read from LDS
+// (read_block_group) and multiplied (products_of_group) in two steps, so that loops can read a group ahead of its
+// products.  Row-major: acc[rb][i] = row 16*rb + 4*qd + i of the wavefront's rows, key mrow; BY_ROW swaps the
+// operands: acc[rb][i] = key 4*qd + i of the group, row 16*rb + mrow.
 __device__ __forceinline__ void read_block_group(const u32x4 *buf, int g, int lane, bf16x8 (&kb)[4]) {
 #pragma unroll
   for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
@@ -456,22 +459,27 @@ __device__ __forceinline__ void score_block_group(const bf16x8 (&q)[NRB * 4], co
   products_of_group<NRB, BY_ROW>(q, kb, acc);
 }
 
-// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel
+// pass 1: per (b, hq, chunk): reference and sum of exponentials (base 2) of every tail row, as psa_row_stats_kernel.
+// NRB: row blocks per wavefront (4: one wavefront per head; 2: two).
 template <int NRB, int MAXIT>
-__global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(SelectArgs a) {
+__global__ __launch_bounds__(64 * kGqaMaxHeads * (4 / NRB)) void psa_row_stats_gqa_kernel(SelectArgs a) {
+  constexpr int kHeadWaves = 4 / NRB;                      // wavefronts per query head
+  constexpr int kMaxWaves = kGqaMaxHeads * kHeadWaves;     // scoring wavefronts of a workgroup, at most
   __shared__ u32x4 kbuf[2][kGqaItems * 64];
   const int chunk = blockIdx.x, bh = blockIdx.y;
   const int R = a.Hq / a.Hkv, b = bh / a.Hkv, hkv = bh % a.Hkv;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
-  const int bhq = b * a.Hq + hkv * R + wave;
+  const int n_score = R * kHeadWaves;                 // scoring wavefronts
+  const int head = wave / kHeadWaves, rb0 = (wave % kHeadWaves) * NRB;  // this wavefront's head and first row block
+  const int bhq = b * a.Hq + hkv * R + head;
   const uint16_t *k_rows = a.k + (size_t)bh * a.T * kD;
   const float scale2 = a.sm_scale * kLog2e;
   const int t_chunk = chunk * kScoreChunk;
   const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);  // blocks that hold keys
-  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than heads
-  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : R;
+  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than n_score
+  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : kMaxWaves;
   KeyStage<MAXIT> st;
-  if (kFeeder && wave == R) {  // the feeder: same barriers as the scoring wavefronts below
+  if (kFeeder && wave == n_score) {  // the feeder: same barriers as the scoring wavefronts below
     request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
@@ -485,12 +493,12 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
   }
   if constexpr (!kFeeder) request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
   bf16x8 q[NRB * 4];
-  load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, q);
+  load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, rb0, mrow, qd, q);
   if constexpr (!kFeeder) {
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
   }
-  RowStats st_row;  // of tail row 16*rb + mrow, over the keys 4*qd .. 4*qd + 3 of every group
+  RowStats st_row;  // of tail row 16*(rb0 + rb) + mrow, over the keys 4*qd .. 4*qd + 3 of every group
 #pragma unroll
   for (int rb = 0; rb < 4; ++rb) { st_row.m[rb] = -INFINITY; st_row.l[rb] = 0.0f; }
   __syncthreads();
@@ -502,22 +510,23 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
     const u32x4 *buf = kbuf[j & 1];
     const int t_block = t_chunk + j * kGqaBlockKeys;
     if (t_block + kGqaBlockKeys - 1 <= a.T - a.W) {
-      // Every key of the block is seen by every tail row (all but the last blocks of a context): no masks, and the
-      // matrix products of group g + 1 are issued ahead of the exponentials of group g.  With two wavefronts per SIMD
-      // the overlap of the two pipes has to come from inside a wavefront.
+      // Every key of the block is seen by every tail row (all but the last blocks of a context): no masks; keys are
+      // read from LDS one group ahead of their products, the products issued one group ahead of the exponentials.
       f32x4 acc_a[4], acc_b[4];
-      bf16x8 kb_a[4], kb_b[4];  // keys are read from LDS one step ahead of their products
+      bf16x8 kb_a[4], kb_b[4];
       read_block_group(buf, 0, lane, kb_a);
       read_block_group(buf, 1, lane, kb_b);
       products_of_group<NRB, true>(q, kb_a, acc_a);
-#pragma unroll 1
+#pragma unroll
       for (int g = 0; g < kGqaBlockGroups; g += 2) {
-        read_block_group(buf, min(g + 2, kGqaBlockGroups - 1), lane, kb_a);  // (past the last group: not used)
+        if (g + 2 < kGqaBlockGroups) read_block_group(buf, g + 2, lane, kb_a);
         products_of_group<NRB, true>(q, kb_b, acc_b);
-        stats_add_group<NRB>(st_row, acc_a, scale2, t_block + 16 * g, a.T, a.W, mrow, qd);
-        read_block_group(buf, min(g + 3, kGqaBlockGroups - 1), lane, kb_b);
-        products_of_group<NRB, true>(q, kb_a, acc_a);
-        stats_add_group<NRB>(st_row, acc_b, scale2, t_block + 16 * g + 16, a.T, a.W, mrow, qd);
+        stats_add_group<NRB>(st_row, acc_a, scale2, t_block + 16 * g, a.T, a.W, mrow, qd, 16 * rb0);
+        if (g + 2 < kGqaBlockGroups) {
+          read_block_group(buf, g + 3, lane, kb_b);
+          products_of_group<NRB, true>(q, kb_a, acc_a);
+        }
+        stats_add_group<NRB>(st_row, acc_b, scale2, t_block + 16 * g + 16, a.T, a.W, mrow, qd, 16 * rb0);
       }
     } else {
       for (int g = 0; g < kGqaBlockGroups; ++g) {
@@ -525,55 +534,57 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_row_stats_gqa_kernel(Se
         if (t_first >= a.T) break;  // uniform over the workgroup
         f32x4 acc[4];
         score_block_group<NRB, true>(q, buf, g, lane, acc);
-        stats_raise_and_add<NRB>(st_row, acc, scale2, t_first, a.T, a.W, mrow, qd);
+        stats_raise_and_add<NRB>(st_row, acc, scale2, t_first, a.T, a.W, mrow, qd, 16 * rb0);
       }
     }
     __syncthreads();
   }
-  // this wavefront saw every key of the chunk for its head: its statistics are the chunk's
+  // this wavefront saw every key of the chunk for its rows: its statistics are the chunk's
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
     const float lr = stats_row_sum(st_row.l[rb]);
     if (qd == 0) {
-      float *dst = a.row_stats + (((size_t)bhq * a.n_chunk + chunk) * a.W + 16 * rb + mrow) * 2;
+      float *dst = a.row_stats + (((size_t)bhq * a.n_chunk + chunk) * a.W + 16 * (rb0 + rb) + mrow) * 2;
       dst[0] = st_row.m[rb];
       dst[1] = lr;
     }
   }
 }
 
-// pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads (in head order) and the tail rows of 2^(s - m_row) / l_row
+// pass 2: per (b, hkv, chunk): mass[t] = sum over the group's heads and the tail rows of 2^(s - m_row) / l_row (added
+// up in wavefront order, i.e. head by head, lower rows first)
 template <int NRB, int MAXIT>
-__global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectArgs a) {
+__global__ __launch_bounds__(64 * kGqaMaxHeads * (4 / NRB)) void psa_mass_gqa_kernel(SelectArgs a) {
+  constexpr int kHeadWaves = 4 / NRB;                      // wavefronts per query head
+  constexpr int kMaxWaves = kGqaMaxHeads * kHeadWaves;     // scoring wavefronts of a workgroup, at most
   __shared__ u32x4 kbuf[2][kGqaItems * 64];
-  __shared__ float stat_m[kGqaMaxWaves][64], stat_il[kGqaMaxWaves][64];
-  // column sums of a block: one slot per (head, row quarter, key), each written by one lane; two copies, so that a
-  // block's slots are added up (fixed order) while the next block is being scored
-  __shared__ float col_lds[2][kGqaMaxWaves][4][kGqaBlockKeys];
+  __shared__ float stat_m[kGqaMaxHeads][64], stat_il[kGqaMaxHeads][64];
+  // column sums of a block: one slot per (scoring wavefront, row quarter, key), each written by one lane; two copies,
+  // so that a block's slots are added up (fixed order) while the next block is being scored
+  __shared__ float col_lds[2][kMaxWaves][4][kGqaBlockKeys];
   const int chunk = blockIdx.x, bh = blockIdx.y;
   const int R = a.Hq / a.Hkv, b = bh / a.Hkv, hkv = bh % a.Hkv;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, mrow = lane & 15, qd = lane >> 4;
-  const int bhq = b * a.Hq + hkv * R + wave;
+  const int n_score = R * kHeadWaves;
+  const int head = wave / kHeadWaves, rb0 = (wave % kHeadWaves) * NRB;
+  const int bhq = b * a.Hq + hkv * R + head;
   const uint16_t *k_rows = a.k + (size_t)bh * a.T * kD;
   const float scale2 = a.sm_scale * kLog2e;
   const int t_chunk = chunk * kScoreChunk;
   const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);
-  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than heads
-  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : R;
-  // adds up the slots of block j (all heads in head order, quarters pairwise) and stores the masses of its keys:
-  // key_first, key_first + key_step, ... of the block
-  auto flush_block = [&](int j, int key_first, int key_step) {
-    for (int key = key_first; key < kGqaBlockKeys; key += key_step) {
-      const int t = t_chunk + j * kGqaBlockKeys + key;
-      float sum = 0.0f;
-      for (int h = 0; h < R; ++h)
-        sum += (col_lds[j & 1][h][0][key] + col_lds[j & 1][h][1][key]) +
-               (col_lds[j & 1][h][2][key] + col_lds[j & 1][h][3][key]);
-      if (t < a.T) a.mass[(size_t)bh * a.T + t] = sum;
-    }
+  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than n_score
+  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : kMaxWaves;
+  // adds up the slots of key `key` of block j (scoring wavefronts in order, quarters pairwise) and stores its mass
+  auto flush_key = [&](int j, int key) {
+    const int t = t_chunk + j * kGqaBlockKeys + key;
+    float sum = 0.0f;
+    for (int w = 0; w < n_score; ++w)
+      sum += (col_lds[j & 1][w][0][key] + col_lds[j & 1][w][1][key]) +
+             (col_lds[j & 1][w][2][key] + col_lds[j & 1][w][3][key]);
+    if (t < a.T) a.mass[(size_t)bh * a.T + t] = sum;
   };
   KeyStage<MAXIT> st;
-  if (kFeeder && wave == R) {  // the feeder: same barriers as the scoring wavefronts below
+  if (kFeeder && wave == n_score) {  // the feeder: same barriers as the scoring wavefronts below
     request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
@@ -581,15 +592,16 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
     for (int j = 0; j < n_blk; ++j) {
       if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], first, stride, lane);
       if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
-      if (j > 0) flush_block(j - 1, lane, 64);
+      if (j > 0) flush_key(j - 1, lane);
       __syncthreads();
     }
-    if (n_blk > 0) flush_block(n_blk - 1, lane, 64);
+    flush_key(n_blk - 1, lane);
     return;
   }
   if constexpr (!kFeeder) request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
-  if (lane < a.W) {  // merge the chunk statistics of row `lane` of this wavefront's head
-    const float *src = a.row_stats + ((size_t)bhq * a.n_chunk * a.W + lane) * 2;
+  if (lane < 16 * NRB) {  // merge the chunk statistics of this wavefront's rows
+    const int row = 16 * rb0 + lane;
+    const float *src = a.row_stats + ((size_t)bhq * a.n_chunk * a.W + row) * 2;
     float mm = -INFINITY;
     for (int c = 0; c < a.n_chunk; ++c) mm = fmaxf(mm, src[(size_t)c * a.W * 2]);
     float ll = 0.0f;
@@ -597,37 +609,36 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
       const float mc = src[(size_t)c * a.W * 2];
       if (mc != -INFINITY) ll += src[(size_t)c * a.W * 2 + 1] * fast_exp2(mc - mm);
     }
-    stat_m[wave][lane] = mm;
-    stat_il[wave][lane] = 1.0f / ll;
+    stat_m[head][row] = mm;
+    stat_il[head][row] = 1.0f / ll;
   }
   bf16x8 q[NRB * 4];
-  load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, mrow, qd, q);
+  load_query_rows<NRB>(a.q_tail + (size_t)bhq * a.W * kD, rb0, mrow, qd, q);
   if constexpr (!kFeeder) {
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
   }
-  wave_lds_sync();  // the statistics were written by this wavefront
-  f32x4 rm[NRB], ril[NRB];  // rows 16*rb + 4*qd + i
+  wave_lds_sync();  // the statistics read below were written by this wavefront
+  f32x4 rm[NRB], ril[NRB];  // rows 16*(rb0 + rb) + 4*qd + i
 #pragma unroll
   for (int rb = 0; rb < NRB; ++rb) {
-    rm[rb] = *reinterpret_cast<const f32x4 *>(&stat_m[wave][16 * rb + 4 * qd]);
-    ril[rb] = *reinterpret_cast<const f32x4 *>(&stat_il[wave][16 * rb + 4 * qd]);
+    rm[rb] = *reinterpret_cast<const f32x4 *>(&stat_m[head][16 * (rb0 + rb) + 4 * qd]);
+    ril[rb] = *reinterpret_cast<const f32x4 *>(&stat_il[head][16 * (rb0 + rb) + 4 * qd]);
   }
   __syncthreads();
   for (int j = 0; j < n_blk; ++j) {
     if constexpr (!kFeeder) {
       if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], first, stride, lane);
       if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
-      if (j > 0) flush_block(j - 1, threadIdx.x, blockDim.x);
+      if (j > 0 && threadIdx.x < kGqaBlockKeys) flush_key(j - 1, threadIdx.x);
     }
     const u32x4 *buf = kbuf[j & 1];
     const int t_block = t_chunk + j * kGqaBlockKeys;
     if (t_block + kGqaBlockKeys - 1 <= a.T - a.W) {
-      // Every key of the block is seen by every tail row (all but the last blocks of a context): straight-line code, the
-      // matrix products of group g + 1 issued ahead of the exponentials of group g.  With two wavefronts per SIMD the
-      // overlap of the two pipes has to come from inside a wavefront.
+      // Every key of the block is seen by every tail row (all but the last blocks of a context): straight-line code,
+      // keys read from LDS one group ahead of their products, the products issued one group ahead of the exponentials.
       f32x4 acc[2][4];
-      bf16x8 kb[2][4];  // keys are read from LDS one step ahead of their products
+      bf16x8 kb[2][4];
       read_block_group(buf, 0, lane, kb[0]);
       read_block_group(buf, 1, lane, kb[1]);
       products_of_group<NRB, false>(q, kb[0], acc[0]);
@@ -660,7 +671,7 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
             float &cc = (rb & 1) ? c1 : c0;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
-              if (key_seen(t, 16 * rb + 4 * qd + i, a.T, a.W))
+              if (key_seen(t, 16 * (rb0 + rb) + 4 * qd + i, a.T, a.W))
                 cc = __builtin_fmaf(fast_exp2(__builtin_fmaf(acc[rb][i], scale2, -rm[rb][i])), ril[rb][i], cc);
           }
           c = c0 + c1;
@@ -671,7 +682,7 @@ __global__ __launch_bounds__(64 * kGqaMaxWaves) void psa_mass_gqa_kernel(SelectA
     __syncthreads();
   }
   if constexpr (!kFeeder)
-    if (n_blk > 0) flush_block(n_blk - 1, threadIdx.x, blockDim.x);
+    if (threadIdx.x < kGqaBlockKeys) flush_key(n_blk - 1, threadIdx.x);
 }
 
 // inclusive prefix sum of one int per thread over a workgroup of NW wavefronts, plus the workgroup total
@@ -959,19 +970,23 @@ __global__ __launch_bounds__(256) void sum_heads_kernel(SelectArgs a) {
 
 }  // namespace
 
-template <int NRB, int MAXIT>
+// FEEDER: fewer than eight heads per KV head (one more wavefront than scoring wavefronts)
+template <bool FEEDER>
 static void launch_psa_gqa_passes(const SelectArgs &a, hipStream_t stream) {
   const int R = a.Hq / a.Hkv;
-  const dim3 grid(a.n_chunk, a.B * a.Hkv), block(64 * (MAXIT == kGqaFeederItems ? R + 1 : R));
-  hipLaunchKernelGGL((psa_row_stats_gqa_kernel<NRB, MAXIT>), grid, block, 0, stream, a);
-  hipLaunchKernelGGL((psa_mass_gqa_kernel<NRB, MAXIT>), grid, block, 0, stream, a);
+  const dim3 grid(a.n_chunk, a.B * a.Hkv);
+  // first pass: two wavefronts per head; second pass: one
+  hipLaunchKernelGGL((psa_row_stats_gqa_kernel<2, FEEDER ? kGqaFeederItems : kGqaItems / (2 * kGqaMaxHeads)>), grid,
+                     dim3(64 * (2 * R + (FEEDER ? 1 : 0))), 0, stream, a);
+  hipLaunchKernelGGL((psa_mass_gqa_kernel<4, FEEDER ? kGqaFeederItems : kGqaItems / kGqaMaxHeads>), grid,
+                     dim3(64 * (R + (FEEDER ? 1 : 0))), 0, stream, a);
 }
 template <int NRB>
 static void launch_psa_passes(const SelectArgs &a, hipStream_t stream) {
   if constexpr (NRB == 4) {  // the grouped-query kernels exist for W = 64 only
     const int R = a.Hq / a.Hkv;
-    if (R == kGqaMaxWaves) return launch_psa_gqa_passes<NRB, kGqaItems / kGqaMaxWaves>(a, stream);
-    if (R >= 2 && R < kGqaMaxWaves) return launch_psa_gqa_passes<NRB, kGqaFeederItems>(a, stream);
+    if (R == kGqaMaxHeads) return launch_psa_gqa_passes<false>(a, stream);
+    if (R >= 2 && R < kGqaMaxHeads) return launch_psa_gqa_passes<true>(a, stream);
   }
   const dim3 block(256);
   hipLaunchKernelGGL(psa_row_stats_kernel<NRB>, dim3(a.n_chunk, a.B * a.Hq), block, 0, stream, a);
