@@ -381,8 +381,8 @@ __global__ __launch_bounds__(256, 4) void psa_mass_kernel(SelectArgs a) {  // re
 // matrix-core operands) and every scoring wavefront multiplies all of them with its rows.  Per block: the keys of the
 // block after next are requested into registers, the next block's are converted and stored to LDS, the current block
 // is scored; one barrier per block orders the buffers.  With fewer than eight heads per KV head the keys are brought
-// in by a wavefront of their own (the feeder, which also adds up the column sums of the second pass); with eight
-// heads the scoring wavefronts share that work.
+// in by wavefronts of their own (feeders: two in the first pass, one in the second, which also adds up the column
+// sums); with eight heads the scoring wavefronts share that work.
 // The first pass runs two wavefronts per head (32 rows and under 128 registers each, four wavefronts per SIMD: 10 %
 // faster than one per head at about 200 registers and two per SIMD); the second pass one per head (with two, every
 // key operand is read from LDS twice for half the arithmetic each time: 17 % slower).
@@ -391,7 +391,7 @@ constexpr int kGqaBlockKeys = 16 * kGqaBlockGroups;               // 64
 constexpr int kGqaBlocks = kScoreChunk / kGqaBlockKeys;           // blocks per chunk
 constexpr int kGqaItems = kGqaBlockGroups * 4;                    // 1 KB pieces (group, channel step) of a block
 constexpr int kGqaMaxHeads = 8;                                   // query heads per KV head
-constexpr int kGqaFeederItems = kGqaItems;                        // MAXIT of the kernels with a feeder wavefront
+constexpr int kGqaFeederItems = kGqaItems / 2;                    // MAXIT from this on: feeder wavefronts bring in the keys
 static_assert(kScoreChunk % kGqaBlockKeys == 0, "a chunk is a whole number of blocks");
 static_assert(kGqaBlockGroups % 2 == 0, "the first pass walks a block two groups at a time");
 static_assert(kGqaItems % (2 * kGqaMaxHeads) == 0, "up to sixteen scoring wavefronts share a block's pieces evenly");
@@ -476,10 +476,12 @@ __global__ __launch_bounds__(64 * kGqaMaxHeads * (4 / NRB)) void psa_row_stats_g
   const float scale2 = a.sm_scale * kLog2e;
   const int t_chunk = chunk * kScoreChunk;
   const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);  // blocks that hold keys
-  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than n_score
-  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : kMaxWaves;
+  // feeders (kGqaItems / MAXIT wavefronts behind the scoring ones) take consecutive pieces; without feeders the
+  // scoring wavefronts take pieces wave, wave + kMaxWaves, ...
+  constexpr bool kFeeder = MAXIT >= kGqaFeederItems;
+  const int first = kFeeder ? (wave - n_score) * MAXIT : wave, stride = kFeeder ? 1 : kMaxWaves;
   KeyStage<MAXIT> st;
-  if (kFeeder && wave == n_score) {  // the feeder: same barriers as the scoring wavefronts below
+  if (kFeeder && wave >= n_score) {  // a feeder: same barriers as the scoring wavefronts below
     request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
@@ -572,8 +574,10 @@ __global__ __launch_bounds__(64 * kGqaMaxHeads * (4 / NRB)) void psa_mass_gqa_ke
   const float scale2 = a.sm_scale * kLog2e;
   const int t_chunk = chunk * kScoreChunk;
   const int n_blk = min(kGqaBlocks, (a.T - t_chunk + kGqaBlockKeys - 1) / kGqaBlockKeys);
-  constexpr bool kFeeder = MAXIT == kGqaFeederItems;  // launched with one more wavefront than n_score
-  const int first = kFeeder ? 0 : wave, stride = kFeeder ? 1 : kMaxWaves;
+  // feeders (kGqaItems / MAXIT wavefronts behind the scoring ones) take consecutive pieces; without feeders the
+  // scoring wavefronts take pieces wave, wave + kMaxWaves, ...
+  constexpr bool kFeeder = MAXIT >= kGqaFeederItems;
+  const int first = kFeeder ? (wave - n_score) * MAXIT : wave, stride = kFeeder ? 1 : kMaxWaves;
   // adds up the slots of key `key` of block j (scoring wavefronts in order, quarters pairwise) and stores its mass
   auto flush_key = [&](int j, int key) {
     const int t = t_chunk + j * kGqaBlockKeys + key;
@@ -584,7 +588,7 @@ __global__ __launch_bounds__(64 * kGqaMaxHeads * (4 / NRB)) void psa_mass_gqa_ke
     if (t < a.T) a.mass[(size_t)bh * a.T + t] = sum;
   };
   KeyStage<MAXIT> st;
-  if (kFeeder && wave == n_score) {  // the feeder: same barriers as the scoring wavefronts below
+  if (kFeeder && wave >= n_score) {  // a feeder: same barriers as the scoring wavefronts below
     request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
@@ -970,15 +974,16 @@ __global__ __launch_bounds__(256) void sum_heads_kernel(SelectArgs a) {
 
 }  // namespace
 
-// FEEDER: fewer than eight heads per KV head (one more wavefront than scoring wavefronts)
+// FEEDER: fewer than eight heads per KV head (room for feeder wavefronts behind the scoring ones)
 template <bool FEEDER>
 static void launch_psa_gqa_passes(const SelectArgs &a, hipStream_t stream) {
   const int R = a.Hq / a.Hkv;
   const dim3 grid(a.n_chunk, a.B * a.Hkv);
-  // first pass: two wavefronts per head; second pass: one
-  hipLaunchKernelGGL((psa_row_stats_gqa_kernel<2, FEEDER ? kGqaFeederItems : kGqaItems / (2 * kGqaMaxHeads)>), grid,
-                     dim3(64 * (2 * R + (FEEDER ? 1 : 0))), 0, stream, a);
-  hipLaunchKernelGGL((psa_mass_gqa_kernel<4, FEEDER ? kGqaFeederItems : kGqaItems / kGqaMaxHeads>), grid,
+  // first pass: two wavefronts per head and two feeders (one feeder would be the slowest wavefront of the workgroup:
+  // about 240 vector instructions per block against 150 of a scoring wavefront); second pass: one per head, one feeder
+  hipLaunchKernelGGL((psa_row_stats_gqa_kernel<2, FEEDER ? kGqaItems / 2 : kGqaItems / (2 * kGqaMaxHeads)>), grid,
+                     dim3(64 * (2 * R + (FEEDER ? 2 : 0))), 0, stream, a);
+  hipLaunchKernelGGL((psa_mass_gqa_kernel<4, FEEDER ? kGqaItems : kGqaItems / kGqaMaxHeads>), grid,
                      dim3(64 * (R + (FEEDER ? 1 : 0))), 0, stream, a);
 }
 template <int NRB>
