@@ -263,6 +263,9 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   // Three tile buffers: while tile k is consumed, the loads of tiles k+1 and k+2 are in flight.  Loads are issued
   // unconditionally (the index is clamped to the wavefront's last tile) so that the number of outstanding loads is
   // the same on every path and the waits inside the loop count exactly two tiles of loads.
+  // the length of the salient list is asked for now and looked at after the stream (the append of a fused decode
+  // step does not change it): the 16-bit rows then cost one memory round trip, not three dependent ones
+  const int sal_cnt_early = a.sal_cnt[bh];
   const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
   const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
   auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
@@ -484,7 +487,8 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
       // only the token groups (16 slots) and blocks (32 slots) that hold rows are touched; the first block of value
       // rows and the row's validity are requested together with the key rows so that the phase costs one round trip
       const int n_grp = min(4, (cnt - unit * 64 + 15) >> 4), n_blk = min(2, (cnt - unit * 64 + 31) >> 5);
-      const bool lane_ok = (s_lane < cnt) && row_ok(s_lane);
+      const bool row_valid = row_ok(s_lane);  // fetched whatever cnt says (clamped address): no load behind a branch
+      const bool lane_ok = (s_lane < cnt) & row_valid;
       u32x4 vb0[8];
 #pragma unroll
       for (int nb = 0; nb < 8; ++nb)
@@ -538,8 +542,7 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
     }
   };
   {
-    int cnt = a.sal_cnt[bh];
-    cnt = min(max(cnt, 0), a.S_cap);
+    const int cnt = min(max(sal_cnt_early, 0), a.S_cap);
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
     bf16_units(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, cnt,
                [&](int s) { return sidx[min(s, a.S_cap - 1)] < a.t_win; });  // rows in the window are read there
@@ -920,6 +923,9 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     wave_lds_sync();
   };
   // three tile buffers, two tiles of loads in flight (see the MHA kernel)
+  // the length of the salient list is asked for now and looked at after the stream (the append of a fused decode
+  // step does not change it): the 16-bit rows then cost one memory round trip, not three dependent ones
+  const int sal_cnt_early = a.sal_cnt[bh];
   const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
   const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
   auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
@@ -967,7 +973,8 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
 #pragma unroll
       for (int tg = 0; tg < 2; ++tg) {
         const int s_lane = unit * 32 + 16 * tg + mrow;
-        lane_ok[tg] = (s_lane < cnt) && row_ok(s_lane);
+        const bool row_valid = row_ok(s_lane);  // fetched whatever cnt says (clamped address): no load behind a branch
+        lane_ok[tg] = (s_lane < cnt) & row_valid;
       }
       u32x4 vb_all[8];
 #pragma unroll
@@ -1022,8 +1029,7 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
     }
   };
   {
-    int cnt = a.sal_cnt[bh];
-    cnt = min(max(cnt, 0), a.S_cap);
+    const int cnt = min(max(sal_cnt_early, 0), a.S_cap);
     const int32_t *sidx = a.sal_idx + (size_t)bh * a.S_cap;
     bf16_units(a.k_sal + (size_t)bh * a.S_cap * kD, a.v_sal + (size_t)bh * a.S_cap * kD, cnt,
                [&](int s) { return sidx[min(s, a.S_cap - 1)] < a.t_win; });  // rows in the window are read there
