@@ -265,7 +265,10 @@ __device__ __forceinline__ void decode_mha_body(const DecodeArgs &a) {
   // the same on every path and the waits inside the loop count exactly two tiles of loads.
   // the length of the salient list is asked for now and looked at after the stream (the append of a fused decode
   // step does not change it): the 16-bit rows then cost one memory round trip, not three dependent ones
-  const int sal_cnt_early = a.sal_cnt[bh];
+  // (read through the constant address space: a scalar load, whose wait the compiler puts in front of the first use;
+  // as a vector load of a uniform address it would be moved to a scalar register, and waited for, right here)
+  const int sal_cnt_early = reinterpret_cast<const __attribute__((address_space(4))) int32_t *>(
+      reinterpret_cast<uintptr_t>(a.sal_cnt))[bh];
   const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
   const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
   auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
@@ -925,7 +928,10 @@ __global__ __launch_bounds__(64 * kWaves) void decode_gqa_kernel(DecodeArgs a) {
   // three tile buffers, two tiles of loads in flight (see the MHA kernel)
   // the length of the salient list is asked for now and looked at after the stream (the append of a fused decode
   // step does not change it): the 16-bit rows then cost one memory round trip, not three dependent ones
-  const int sal_cnt_early = a.sal_cnt[bh];
+  // (read through the constant address space: a scalar load, whose wait the compiler puts in front of the first use;
+  // as a vector load of a uniform address it would be moved to a scalar register, and waited for, right here)
+  const int sal_cnt_early = reinterpret_cast<const __attribute__((address_space(4))) int32_t *>(
+      reinterpret_cast<uintptr_t>(a.sal_cnt))[bh];
   const int n_mine = tile_begin + wave < tile_end ? (tile_end - tile_begin - wave + kWaves - 1) / kWaves : 0;
   const int last_tile = tile_begin + wave + kWaves * max(n_mine - 1, 0);
   auto tile_at = [&](int k) { return min(tile_begin + wave + kWaves * k, last_tile); };
