@@ -589,6 +589,9 @@ __global__ __launch_bounds__(64 * kGqaMaxHeads * (4 / NRB)) void psa_mass_gqa_ke
   };
   KeyStage<MAXIT> st;
   if (kFeeder && wave >= n_score) {  // a feeder: same barriers as the scoring wavefronts below
+    // the feeders share the keys of a block when its column sums are added up
+    constexpr int kFeederKeys = kFeeder ? kGqaBlockKeys * MAXIT / kGqaItems : kGqaBlockKeys;
+    const int first_key = (wave - n_score) * kFeederKeys;
     request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
     deposit_block(st, kbuf[0], first, stride, lane);
     request_block(k_rows, t_chunk + kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
@@ -596,10 +599,10 @@ __global__ __launch_bounds__(64 * kGqaMaxHeads * (4 / NRB)) void psa_mass_gqa_ke
     for (int j = 0; j < n_blk; ++j) {
       if (j + 1 < n_blk) deposit_block(st, kbuf[(j + 1) & 1], first, stride, lane);
       if (j + 2 < n_blk) request_block(k_rows, t_chunk + (j + 2) * kGqaBlockKeys, a.T, first, stride, mrow, qd, st);
-      if (j > 0) flush_key(j - 1, lane);
+      if (j > 0 && lane < kFeederKeys) flush_key(j - 1, first_key + lane);
       __syncthreads();
     }
-    flush_key(n_blk - 1, lane);
+    if (lane < kFeederKeys) flush_key(n_blk - 1, first_key + lane);
     return;
   }
   if constexpr (!kFeeder) request_block(k_rows, t_chunk, a.T, first, stride, mrow, qd, st);
@@ -983,6 +986,7 @@ static void launch_psa_gqa_passes(const SelectArgs &a, hipStream_t stream) {
   // about 240 vector instructions per block against 150 of a scoring wavefront); second pass: one per head, one feeder
   hipLaunchKernelGGL((psa_row_stats_gqa_kernel<2, FEEDER ? kGqaItems / 2 : kGqaItems / (2 * kGqaMaxHeads)>), grid,
                      dim3(64 * (2 * R + (FEEDER ? 2 : 0))), 0, stream, a);
+  // (two wavefronts per head and two feeders, measured: 692 against 645 us at cfg5)
   hipLaunchKernelGGL((psa_mass_gqa_kernel<4, FEEDER ? kGqaItems : kGqaItems / kGqaMaxHeads>), grid,
                      dim3(64 * (R + (FEEDER ? 1 : 0))), 0, stream, a);
 }
