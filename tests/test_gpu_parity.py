@@ -428,6 +428,9 @@ def test_no_rotation_mode(orc, Hq, Hkv, G):
     lse_tol = 2e-3 if Hq == Hkv else 6e-3
     run_decode_case(orc, w, d, "tsa", 6, n_splits=(1, 3), flags=allf, lse_tol=lse_tol)
     run_decode_case(orc, w, d, "psa", 6, n_splits=(2,), flags=akvq.K_PREROTATED | akvq.Q_PREROTATED, lse_tol=lse_tol)
+    # every row salient: the overlay rows come from the pass behind the block kernel, which must honour the flags too
+    run_decode_case(orc, w, d, "all", 6, n_splits=(1,), flags=allf, lse_tol=lse_tol)
+    run_decode_case(orc, w, d, "all", 6, n_splits=(2,), flags=akvq.V_PREROTATED, lse_tol=lse_tol)
 
 
 @pytest.mark.parametrize("mode,clip", [("tsa", 0.8), ("psa", 0.8), ("tsa", 1.0), ("psa", 1.0)])
