@@ -119,6 +119,45 @@ def decode_alone(w, akvq, synth, torch, np, warmup=20, timed=100, n_split=0):
             "buffer_sets": n_sets, "n_split": ns, "kv_tokens_per_s": w.B * w.T / (ms * 1e-3)}
 
 
+def prefill_alone(w, akvq, synth, torch, np, warmup=3, timed=20):
+    """akvq_select_salient (pivot selection) and akvq_quantize_append alone on one pivot-salient layer of workload w,
+    two input sets alternating; HIP events around `timed` calls of each."""
+    layer = 2 if w.tsa_layers else 0
+    t_cap = (w.T + 63) // 64 * 64
+    sets = []
+    for i in range(2):
+        d = synth.generate(w, layer=layer + 100 * i, device="cuda")
+        sets.append((d["q_tail"], d["k"], d["v"], akvq.Cache(w.B, w.Hkv, w.G, t_cap, w.s_cap(layer))))
+        del d
+
+    def timed_ms(fn):
+        for i in range(warmup):
+            fn(sets[i % 2])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(timed):
+            fn(sets[i % 2])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / timed
+
+    def select(s):
+        akvq.select_salient(s[3], akvq.MODE_PSA, q_tail=s[0], k=s[1], top_k=w.top_k, sm_scale=w.sm_scale)
+
+    def quantize(s):
+        s[3].T_len = 0
+        akvq.quantize_append(s[3], s[1], s[2], w.clip)
+
+    sel_ms, q_ms = timed_ms(select), timed_ms(quantize)
+    b = algorithmic_bytes(w, layer)
+    return {"workload": f"{w.name}: B={w.B} x Hq={w.Hq}/Hkv={w.Hkv} x T={w.T}, G={w.G}, PSA top-{w.top_k}",
+            "select_ms": round(sel_ms, 4), "select_GBps": round(b["select"] / (sel_ms * 1e-3) / 1e9, 1),
+            "quantize_ms": round(q_ms, 4), "quantize_GBps": round(b["quantize"] / (q_ms * 1e-3) / 1e9, 1),
+            "quantize_frac_of_hbm_peak": round(b["quantize"] / (q_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+            "calls_timed": timed}
+
+
 def stream_ceiling(akvq, torch, warmup=5, timed=40):
     """GB/s of the plain 128-bit streaming-read kernel over two 2 GiB buffers (alternating: no reuse in any cache),
     with the non-temporal load hint the decode kernels use and without it."""
@@ -738,6 +777,10 @@ def main():
         torch.cuda.empty_cache()
         for name in ("cfg3", "cfg5"):
             out["extra"]["rooflines"][f"decode_{name}"] = decode_alone(synth.WORKLOADS[name], akvq, synth, torch, np)
+            torch.cuda.empty_cache()
+        # the prefill configuration (write path + pivot selection at 16384 tokens) and the grouped-query one
+        for name in ("cfg4", "cfg5"):
+            out["extra"][f"prefill_{name}"] = prefill_alone(synth.WORKLOADS[name], akvq, synth, torch, np)
             torch.cuda.empty_cache()
         sc = stream_ceiling(akvq, torch)
         out["extra"]["stream_ceiling_GBps"] = sc["GBps"]
