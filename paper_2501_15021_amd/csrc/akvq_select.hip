@@ -754,17 +754,22 @@ __global__ __launch_bounds__(NT) void topk_kernel(SelectArgs a) {
       // Short cut for the usual case (a few pivots out of thousands of keys): the k-th largest of the per-thread
       // maxima is a lower bound of the k-th largest key, and few keys reach it.  They are collected and ranked among
       // themselves (key descending, position ascending: the order of the radix path).  Too many candidates (many equal
-      // keys): the radix passes below take over.  Every wavefront finds the bound for itself (NT / 64 maxima per
-      // lane), bit by bit from the top: the largest x with at least k maxima >= x.
-      uint32_t mx[NT / 64];
+      // keys): the radix passes below take over.  Every wavefront finds the bound for itself, bit by bit from the top:
+      // the largest x with at least k of 256 maxima >= x (four per lane; with more than 256 threads each is the
+      // largest of NT / 256 thread maxima, still 256 different keys).
+      uint32_t mx[4];
 #pragma unroll
-      for (int i = 0; i < NT / 64; ++i) mx[i] = thread_max[lane + 64 * i];
+      for (int i = 0; i < 4; ++i) {
+        uint32_t v = 0u;
+#pragma unroll
+        for (int jj = 0; jj < NT / 256; ++jj) v = max(v, thread_max[lane + 64 * i + 256 * jj]);
+        mx[i] = v;
+      }
       uint32_t bound = 0u;
       for (int bit = 31; bit >= 0; --bit) {
         const uint32_t cand = bound | (1u << bit);
-        int n_ge = 0;
-#pragma unroll
-        for (int i = 0; i < NT / 64; ++i) n_ge += __popcll(__ballot(mx[i] >= cand));
+        const int n_ge = __popcll(__ballot(mx[0] >= cand)) + __popcll(__ballot(mx[1] >= cand)) +
+                         __popcll(__ballot(mx[2] >= cand)) + __popcll(__ballot(mx[3] >= cand));
         if (n_ge >= k) bound = cand;
       }
       for (int t = threadIdx.x; t < a.T; t += NT) {
