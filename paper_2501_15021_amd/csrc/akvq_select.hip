@@ -51,9 +51,9 @@ __global__ __launch_bounds__(256) void select_tsa_kernel(SelectArgs a) {
 }
 
 // ---- pivot scoring ---------------------------------------------------------------------------------------
-// One query head per KV head: each workgroup (4 wavefronts) owns kScoreChunk consecutive keys of one (batch, head);
-// its wavefronts take the groups of 16 keys in turn, with the next groups' loads in flight while the current one goes
-// through the matrix cores.  (Several query heads per KV head: see the grouped-query kernels further down.)
+// Scoring windows of fewer than 64 rows (the kernels for W = 64 follow further down): each workgroup (4 wavefronts)
+// owns kScoreChunk consecutive keys of one (batch, query head); its wavefronts take the groups of 16 keys in turn,
+// with the next groups' loads in flight while the current one goes through the matrix cores.
 // Logits are kept in the base-2 domain (sm_scale * log2(e) folded into one multiply) so that exponentials are bare
 // v_exp_f32; both passes use the same domain, so the statistics carry over unchanged.
 constexpr int kGroupsPerWave = kScoreChunk / (4 * 16);
@@ -374,7 +374,8 @@ __global__ __launch_bounds__(256, 4) void psa_mass_kernel(SelectArgs a) {  // re
   }
 }
 
-// ---- pivot scoring with several query heads per KV head --------------------------------------------------------
+// ---- pivot scoring, W = 64: scoring wavefronts with their rows in registers, keys fed through LDS -----------------
+// (any number of query heads per KV head up to eight; the kernels above serve the other W)
 // One workgroup per (batch, kv-head, chunk of kScoreChunk keys) with one or two wavefronts per query head of the group,
 // each holding all or half of the head's W = 64 tail rows in registers as one matrix operand.  The keys are read from
 // HBM and converted to bfloat16 once for the whole group: blocks of 64 keys go through LDS (two buffers, laid out as
@@ -385,11 +386,13 @@ __global__ __launch_bounds__(256, 4) void psa_mass_kernel(SelectArgs a) {  // re
 // sums); with eight heads the scoring wavefronts share that work.
 // The first pass runs two wavefronts per head (32 rows and under 128 registers each, four wavefronts per SIMD: 10 %
 // faster than one per head at about 200 registers and two per SIMD); the second pass one per head (with two, every
-// key operand is read from LDS twice for half the arithmetic each time: 17 % slower).
+// key operand is read from LDS twice for half the arithmetic each time: 17 % slower), except with a single head.
+// The feeders read whole keys (1 KB of consecutive bytes per load, non-temporal); against the kernels above, whose
+// wavefronts load, convert and score their own keys, that is 2-7 % per pass with one head per KV head.
 constexpr int kGqaBlockGroups = 4;                                // groups of 16 keys per block
 constexpr int kGqaBlockKeys = 16 * kGqaBlockGroups;               // 64
 constexpr int kGqaBlocks = kScoreChunk / kGqaBlockKeys;           // blocks per chunk
-constexpr int kGqaItems = kGqaBlockGroups * 4;                    // 1 KB pieces (group, channel step) of a block
+constexpr int kGqaItems = kGqaBlockGroups * 4;                    // 1 KB pieces (four whole keys each) of a block
 constexpr int kGqaMaxHeads = 8;                                   // query heads per KV head
 constexpr int kGqaFeederItems = kGqaItems / 2;                    // MAXIT from this on: feeder wavefronts bring in the keys
 static_assert(kScoreChunk % kGqaBlockKeys == 0, "a chunk is a whole number of blocks");
@@ -407,19 +410,27 @@ struct KeyStage {
 template <int MAXIT>
 __device__ __forceinline__ void request_block(const uint16_t *k_rows, int t_block, int T, int first, int stride, int mrow,
                                               int qd, KeyStage<MAXIT> &st) {
+  // piece `item` of a block = keys 4*item .. 4*item + 3 whole: lane l takes the (l % 16)-th 16 bytes of key
+  // 4*item + l / 16, so a load is 1 KB of consecutive bytes and can carry the non-temporal hint (every key is read
+  // once per pass)
+  const int lane = qd * 16 + mrow;
 #pragma unroll
   for (int it = 0; it < MAXIT; ++it) {
     const int item = first + it * stride;  // uniform over the wavefront
-    const int g = item >> 2, kc = item & 3;
-    const int t = min(t_block + 16 * g + mrow, T - 1);  // rows past the end repeat the last key; never scored unmasked
-    st.raw[it] = *reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 32 * kc + 8 * qd);
+    const int t = min(t_block + 4 * item + (lane >> 4), T - 1);  // rows past the end repeat the last key; never scored unmasked
+    st.raw[it] = stream_load(reinterpret_cast<const u32x4 *>(k_rows + (size_t)t * kD + 8 * (lane & 15)));
   }
 }
 template <int MAXIT>
 __device__ __forceinline__ void deposit_block(const KeyStage<MAXIT> &st, u32x4 *buf, int first, int stride, int lane) {
+  // LDS layout of a block: key r of the block at r * 16 slots of 16 bytes, its piece p at slot p ^ (r % 16): the
+  // writes here (16 pieces of one key per 16 lanes) and the operand reads (one piece of 16 keys) are both free of
+  // bank conflicts
 #pragma unroll
-  for (int it = 0; it < MAXIT; ++it)
-    buf[(first + it * stride) * 64 + lane] = __builtin_bit_cast(u32x4, rows8_as_bf16(st.raw[it]));
+  for (int it = 0; it < MAXIT; ++it) {
+    const int r = 4 * (first + it * stride) + (lane >> 4), p = lane & 15;
+    buf[r * 16 + (p ^ (r & 15))] = __builtin_bit_cast(u32x4, rows8_as_bf16(st.raw[it]));
+  }
 }
 // NRB row blocks of one query head, from row block rb0 on, as matrix-core operands in registers: q[rb * 4 + kc] is
 // what this lane feeds for row block rb0 + rb and channel step kc
@@ -437,8 +448,9 @@ __device__ __forceinline__ void load_query_rows(const uint16_t *q_head, int rb0,
 // products.  Row-major: acc[rb][i] = row 16*rb + 4*qd + i of the wavefront's rows, key mrow; BY_ROW swaps the
 // operands: acc[rb][i] = key 4*qd + i of the group, row 16*rb + mrow.
 __device__ __forceinline__ void read_block_group(const u32x4 *buf, int g, int lane, bf16x8 (&kb)[4]) {
+  const int mrow = lane & 15, qd = lane >> 4;  // key 16*g + mrow of the block, channel pieces 4*kc + qd
 #pragma unroll
-  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(4 * g + kc) * 64 + lane]);
+  for (int kc = 0; kc < 4; ++kc) kb[kc] = __builtin_bit_cast(bf16x8, buf[(16 * g + mrow) * 16 + ((4 * kc + qd) ^ mrow)]);
 }
 template <int NRB, bool BY_ROW>
 __device__ __forceinline__ void products_of_group(const bf16x8 (&q)[NRB * 4], const bf16x8 (&kb)[4], f32x4 (&acc)[4]) {
@@ -991,16 +1003,21 @@ static void launch_psa_gqa_passes(const SelectArgs &a, hipStream_t stream) {
   // about 240 vector instructions per block against 150 of a scoring wavefront); second pass: one per head, one feeder
   hipLaunchKernelGGL((psa_row_stats_gqa_kernel<2, FEEDER ? kGqaItems / 2 : kGqaItems / (2 * kGqaMaxHeads)>), grid,
                      dim3(64 * (2 * R + (FEEDER ? 2 : 0))), 0, stream, a);
-  // (two wavefronts per head and two feeders, measured: 692 against 645 us at cfg5)
+  if (R == 1) {
+    // one head: a single scoring wavefront would leave the workgroup at two wavefronts; two of 32 rows and two feeders
+    hipLaunchKernelGGL((psa_mass_gqa_kernel<2, kGqaItems / 2>), grid, dim3(64 * 4), 0, stream, a);
+    return;
+  }
+  // (two wavefronts per head and two feeders, measured with seven heads: 692 against 645 us at cfg5)
   hipLaunchKernelGGL((psa_mass_gqa_kernel<4, FEEDER ? kGqaItems : kGqaItems / kGqaMaxHeads>), grid,
                      dim3(64 * (R + (FEEDER ? 1 : 0))), 0, stream, a);
 }
 template <int NRB>
 static void launch_psa_passes(const SelectArgs &a, hipStream_t stream) {
-  if constexpr (NRB == 4) {  // the grouped-query kernels exist for W = 64 only
+  if constexpr (NRB == 4) {  // the kernels with feeder wavefronts exist for W = 64 only
     const int R = a.Hq / a.Hkv;
     if (R == kGqaMaxHeads) return launch_psa_gqa_passes<false>(a, stream);
-    if (R >= 2 && R < kGqaMaxHeads) return launch_psa_gqa_passes<true>(a, stream);
+    if (R >= 1 && R < kGqaMaxHeads) return launch_psa_gqa_passes<true>(a, stream);
   }
   const dim3 block(256);
   hipLaunchKernelGGL(psa_row_stats_kernel<NRB>, dim3(a.n_chunk, a.B * a.Hq), block, 0, stream, a);
